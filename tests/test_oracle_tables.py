@@ -1,0 +1,139 @@
+"""Pins for the oracle's strategy enumerator and alpha-beta table builder.
+
+The paper names both steps but prints no formula, so the table model is this build's own
+reading ("parity unpinned" against the paper).  What is pinned here is the arithmetic:
+closed-form counts for the enumerator, and for the tables exact rational evaluation on
+power-of-two inputs, where every fp64 operation of the builder is exact.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from paper_2504_21411_amd import workloads
+
+
+@pytest.mark.parametrize("k", range(0, 8))
+def test_enumerator_closed_form_uncapped(oracle_mod, k):
+    N = 1 << k
+    d = oracle_mod.enumerate_strategies(N)
+    assert len(d) == 2 * (k + 1) ** 2
+    assert (d[:, 0] * d[:, 1] * d[:, 2] == N).all()
+    assert len({tuple(r) for r in d.tolist()}) == len(d)
+    assert not ((d[:, 3] == 1) & (d[:, 2] == 1)).any()        # nothing to shard over
+    key = [(r[1], r[0], r[3], r[4]) for r in d.tolist()]
+    assert key == sorted(key)                                  # tree order, ckpt fastest
+    assert set(d[:, 3].tolist()) <= {0, 1} and set(d[:, 4].tolist()) <= {0, 1}
+
+
+def test_enumerator_caps_give_the_benchmark_shapes(oracle_mod):
+    assert len(oracle_mod.enumerate_strategies(8, tp_max=4, sp_max=1)) == 12
+    assert len(oracle_mod.enumerate_strategies(32, tp_max=8, sp_max=4, tpsp_max=16)) == 44
+    assert len(oracle_mod.enumerate_strategies(64, sp_max=32)) == 96
+    assert len(oracle_mod.enumerate_strategies(8, sp_max=2)) == 24
+    d = oracle_mod.enumerate_strategies(32, tp_max=8, sp_max=4, tpsp_max=16)
+    assert d[:, 0].max() == 8 and d[:, 1].max() == 4 and (d[:, 0] * d[:, 1]).max() == 16
+    for i, cfg in enumerate(workloads.CONFIGS):
+        w = cfg() if i != 4 else workloads.config4(B=64)
+        assert len(oracle_mod.enumerate_strategies(**w.enum)) == w.S
+    with pytest.raises(ValueError):
+        oracle_mod.enumerate_strategies(12)
+
+
+def _exact_tables(desc, h, q, n, F, BW, binb, keep, M):
+    """Rational evaluation of the same model, no rounding anywhere."""
+    T, O = [], []
+    for tp, spd, dp, sdp, ckpt in desc.tolist():
+        t = Fraction(n, dp * spd)
+        P = 12 * h * h
+        flops = 3 * (24 * t * h * h + 4 * t * q * h)
+        if ckpt:
+            flops = flops * 4 / 3
+        comm = Fraction(0)
+        if tp > 1:
+            comm += 16 * t * h * Fraction(tp - 1, tp)
+        if dp > 1:
+            comm += 4 * Fraction(P, tp) * Fraction(dp - 1, dp) * (Fraction(3, 2) if sdp else 1)
+        if spd > 1:
+            comm += 8 * t * h * Fraction(spd - 1, spd)
+        T.append(1000 * (flops / (tp * F) + comm / BW))
+        mem = Fraction(16 * P, tp * (dp if sdp else 1)) + 68 * t * h / tp * (keep if ckpt else 1)
+        bins = -((-mem) // binb)
+        O.append(min(max(1, int(bins)), M + 1))
+    return T, O
+
+
+def test_table_builder_exact_on_power_of_two_inputs(oracle_mod):
+    desc = oracle_mod.enumerate_strategies(16)
+    h, q, n = 4096, 2048, 1 << 18
+    F, BW, binb, keep, M = 1 << 47, 1 << 37, 1 << 24, Fraction(1, 4), 4096
+    layer = np.array([[[h, q, n, 1.0, 1.0, 1.0]]], np.float64)
+    hw = np.array([F, BW, binb, 0.25], np.float64)
+    rmodel = np.array([[h, n]], np.float64)
+    T, O, R = oracle_mod.build_tables(desc, layer, hw, rmodel, M)
+    Tx, Ox = _exact_tables(desc, h, q, n, F, BW, binb, keep, M)
+    for s, d in enumerate(desc.tolist()):
+        want = np.float32(float(Tx[s]))
+        if d[4] == 0:
+            assert T[0, 0, s] == want, (s, d)                 # every step exact -> same bits
+        else:
+            assert abs(float(T[0, 0, s]) - float(want)) <= float(np.spacing(want))
+        assert O[0, 0, s] == Ox[s], (s, d)
+    # transition table: zero iff the (tp, sp, dp) layout agrees, value as defined otherwise
+    for i, a in enumerate(desc.tolist()):
+        for j, c in enumerate(desc.tolist()):
+            if a[:3] == c[:3]:
+                assert R[0, i, j] == 0.0
+            else:
+                gi, gj = a[2] * a[1], c[2] * c[1]
+                w = Fraction(1) if a[0] == c[0] else Fraction(1, 2)
+                x = 1000 * 2 * h * Fraction(n, gj) * (1 - w * Fraction(min(gi, gj), max(gi, gj))) / BW
+                assert R[0, i, j] == np.float32(float(x)), (i, j)
+    assert (R >= 0).all() and not np.array_equal(R[0], R[0].T)
+
+
+def test_table_builder_scales_and_clamps(oracle_mod):
+    desc = oracle_mod.enumerate_strategies(8)
+    base = np.array([[[4096.0, 4096.0, 2.0 ** 18, 1.0, 1.0, 1.0]]], np.float64)
+    hw = np.array([1.0e14, 1.0e11, 2.0 ** 24, 0.2], np.float64)
+    rm = np.array([[4096.0, 2.0 ** 18]], np.float64)
+    T1, O1, _ = oracle_mod.build_tables(desc, base, hw, rm, 1 << 20)
+    half = base.copy(); half[..., 3] = 0.5
+    T2, O2, _ = oracle_mod.build_tables(desc, half, hw, rm, 1 << 20)
+    assert np.array_equal(T2, (T1 * np.float32(0.5)).astype(np.float32))   # power-of-two scale
+    assert np.array_equal(O1, O2)
+    # recomputation: more time, less memory; sharding: less memory
+    d = desc.tolist()
+    for s in range(0, len(d), 2):
+        assert d[s][:4] == d[s + 1][:4] and d[s][4] == 0 and d[s + 1][4] == 1
+        assert T1[0, 0, s + 1] > T1[0, 0, s] and O1[0, 0, s + 1] <= O1[0, 0, s]
+    # clamp to M + 1 ("never fits") and floor of one bin
+    T3, O3, _ = oracle_mod.build_tables(desc, base, hw, rm, 4)
+    assert O3.max() == 5 and O3.min() >= 1
+    huge = hw.copy(); huge[2] = 1.0e30
+    _, O4, _ = oracle_mod.build_tables(desc, base, huge, rm, 4)
+    assert (O4 == 1).all()
+
+
+def test_workload_generators_are_deterministic_and_shaped():
+    a, b = workloads.config0(), workloads.config0()
+    assert np.array_equal(a.T, b.T) and np.array_equal(a.O, b.O) and np.array_equal(a.R, b.R)
+    assert a.relaxations() == 23 * 257 * 144
+    assert (np.diagonal(a.R[0]) == 0).all() and (a.T >= 1).all() and (a.T < 10).all()
+    assert (a.T[0, 0] == a.T[0, 5]).all()                       # identical layers
+    w1, w3 = workloads.config1(), workloads.config3()
+    assert w1.layer.shape == (64, 48, 6) and w3.layer.shape == (8, 128, 6)
+    assert w1.relaxations() == 64 * 47 * 2049 * 44 * 44
+    assert w3.relaxations() == 8 * 127 * 16385 * 96 * 96
+    assert set(w3.layer[:, 0, 1].tolist()) == {8192.0, 32768.0}
+    w2 = workloads.config2()
+    assert w2.T.shape == (256, 32, 44) and w2.K == 4 and w2.r_index.max() == 3
+    assert w2.relaxations() == 256 * 31 * 4097 * 44 * 44
+    w4 = workloads.config4()
+    assert w4.B == 2048 and w4.T.shape == (2048, 32, 24)
+    assert w4.budget.min() >= 1024 and w4.budget.max() < 2048
+    r = workloads.SplitMix64(5)
+    u = r.uniform(1000)
+    assert u.min() >= 0 and u.max() < 1 and u.dtype == np.float32
+    # SplitMix64 reference value: first output for seed 0 is the published test vector
+    assert int(workloads.SplitMix64(0).u64(1)[0]) == 0xE220A8397B1DCDAF
