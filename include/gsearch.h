@@ -1,0 +1,214 @@
+/*
+ * gsearch — batched per-layer parallel-strategy search on one MI355X (gfx950).
+ *
+ * The library solves, for a batch of independent instances, the problem the Galvatron
+ * search engine solves for every candidate (pipeline degree, stage split, micro-batch
+ * count): choose one hybrid-parallel strategy per Transformer layer so that the summed
+ * layer time plus strategy-switch time is smallest while the summed layer memory stays
+ * within the device budget (paper section 2, "Search Engine"; section 1, feature 2).
+ *
+ * One instance:  L layers, S strategies, budget of E bins (E <= M), tables
+ *   T[l][s]        time of layer l under strategy s         fp32, finite, >= +0
+ *   O[l][s]        memory of layer l under s, in bins       int32, >= 0 (> M: never fits)
+ *   R[k][si][sj]   cost of going from si (layer l-1) to sj (layer l), fp32 >= +0,
+ *                  +inf = forbidden; layer l uses matrix k = r_index[l]
+ * State C[l][e][s] = cheapest fp32 chain cost of layers 0..l that ends in strategy s and
+ * uses AT MOST e bins:
+ *   C[0][e][s]  = T[0][s] if e >= O[0][s] else +inf
+ *   C[l][e][sj] = ( min_si ( C[l-1][e-O[l][sj]][si] + R[k][si][sj] ) ) + T[l][sj]
+ *                 if e >= O[l][sj] else +inf            (two fp32 adds, in that order)
+ *   bp[l][e][sj] = lowest si attaining the min (0 if all candidates are +inf)
+ * Result per instance: min_s C[L-1][E][s] (lowest s on ties), the plan obtained by
+ * walking bp back from there, and over the batch the instance with the smallest cost
+ * (lowest instance index on ties).  An instance that fits no plan is a RESULT
+ * (cost +inf, indices -1), not an error.
+ *
+ * Conventions
+ *   - Every function returns GSEARCH_OK (0) or a negative gsearch_status code.  Nothing
+ *     throws or aborts across this boundary.
+ *   - Pointers named "device" are HIP device pointers owned by the caller (for example
+ *     torch tensors); pointers named "host" are ordinary host pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels
+ *     are enqueued on it and the call returns without waiting; outputs are valid once
+ *     the caller has synchronised that stream.
+ *   - A context is not thread-safe, and two solves on one context overlap in its
+ *     workspace: serialise them on one stream.
+ *   - Table contents live on the device, so they are checked there: a NaN, negative,
+ *     -0 or (for T) infinite entry, a negative O, a budget outside [0, M] or an r_index
+ *     outside [0, K) sets bits in the data-status word; the solve then still runs on
+ *     sanitised copies (memory-safe), reports every instance as infeasible, and
+ *     gsearch_data_status returns the bits.
+ */
+#ifndef GSEARCH_H
+#define GSEARCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GSEARCH_OK = 0,
+  GSEARCH_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, bad flag            */
+  GSEARCH_ERR_CAPACITY = -2,    /* shape exceeds what the context was created for       */
+  GSEARCH_ERR_NO_DEVICE = -3,   /* no usable GPU / bad device index                     */
+  GSEARCH_ERR_HIP = -4,         /* a HIP runtime call failed                            */
+  GSEARCH_ERR_NOT_SOLVED = -5,  /* backtrace / export asked before any solve            */
+  GSEARCH_ERR_NO_MEMORY = -6,   /* workspace allocation failed                          */
+  GSEARCH_ERR_UNSUPPORTED = -7  /* option needs a flag the context was not created with */
+} gsearch_status;
+
+/* gsearch_config.flags */
+#define GSEARCH_FLAG_KEEP_PLANES 0x1u    /* keep every C plane (needed by export / curve of
+                                            any layer); default keeps two ping-pong planes */
+#define GSEARCH_FLAG_FORCE_GENERIC 0x2u  /* always use the shape-agnostic forward kernel    */
+#define GSEARCH_FLAG_NO_BACKPOINTERS 0x4u /* min-only forward pass: no bp stream is written,
+                                            every C plane is kept instead and the backtrace
+                                            re-derives each argmin from the planes (same
+                                            plans, bit for bit)                             */
+
+/* bits of the data-status word */
+#define GSEARCH_DATA_BAD_T 0x1
+#define GSEARCH_DATA_BAD_R 0x2
+#define GSEARCH_DATA_BAD_O 0x4
+#define GSEARCH_DATA_BAD_BUDGET 0x8
+#define GSEARCH_DATA_BAD_RINDEX 0x10
+
+#define GSEARCH_MAX_S 1024 /* strategies per layer (bp is uint8 up to 256, uint16 above) */
+
+typedef struct gsearch_ctx gsearch_ctx; /* opaque, owned by the library */
+
+/* Capacity of a context.  The workspace (C planes, backpointer streams, sanitised
+ * tables) is allocated once at create time for these maxima; see
+ * gsearch_workspace_bytes. */
+typedef struct {
+  int32_t device; /* HIP device index                          */
+  int32_t max_B;  /* instances per solve                       */
+  int32_t max_L;  /* layers                                    */
+  int32_t max_S;  /* strategies, <= GSEARCH_MAX_S              */
+  int32_t max_M;  /* memory bins (budgets are 0..M)            */
+  int32_t max_K;  /* transition matrices in the pool           */
+  uint32_t flags; /* GSEARCH_FLAG_*                            */
+} gsearch_config;
+
+/* One batch.  All pointers are DEVICE pointers, row-major, densely packed. */
+typedef struct {
+  int32_t B, L, S, M, K;  /* uniform shape of the batch                            */
+  const float *T;         /* [B][L][S]                                             */
+  const int32_t *O;       /* [B][L][S]                                             */
+  const float *R;         /* [K][S][S]   R[k][si][sj], row = previous layer        */
+  const int32_t *r_index; /* [B][L]      matrix used INTO layer l; entry l=0 unused */
+  const int32_t *budget;  /* [B]         E_b, 0 <= E_b <= M                        */
+} gsearch_problem;
+
+/* Caller-allocated DEVICE outputs of a solve; any pointer may be NULL to skip it. */
+typedef struct {
+  float *best_cost;       /* [B]    min_s C[L-1][E_b][s]; +inf if infeasible        */
+  int32_t *best_s;        /* [B]    lowest s attaining it; -1 if infeasible         */
+  float *final_row;       /* [B][S] C[L-1][E_b][.]                                  */
+  int32_t *best_instance; /* [1]    argmin_b best_cost, lowest b; -1 if none        */
+} gsearch_result;
+
+/* Size in bytes of the device workspace gsearch_create would allocate for `cfg`
+ * (0 if cfg is NULL or invalid).  Pure host arithmetic; needs no GPU. */
+size_t gsearch_workspace_bytes(const gsearch_config *cfg);
+
+/* Create a context on cfg->device and allocate its workspace.
+ * Errors: INVALID_ARG (null, sizes < 1, max_S > GSEARCH_MAX_S), NO_DEVICE, NO_MEMORY. */
+int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out);
+
+/* Free the workspace and the context.  NULL is accepted.  The caller must have
+ * synchronised every stream that still runs work of this context. */
+int gsearch_destroy(gsearch_ctx *ctx);
+
+/* Forward dynamic program for the whole batch (recurrence above), per-instance final
+ * minimum and the minimum over instances.  Asynchronous on `stream`.
+ * Errors: INVALID_ARG (null problem/tables, shape < 1), CAPACITY, HIP. */
+int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *problem,
+                        const gsearch_result *result, void *stream);
+
+/* Plans of the most recent solve on this context.
+ *   instances  device [n] instance ids, or NULL for instances 0..n-1.  An id outside
+ *              [0, B) (for example best_instance == -1) yields plan = -1, mem_used = -1.
+ *   plan       device [n][L]: strategy per layer, all -1 for an infeasible instance
+ *   mem_used   device [n] or NULL: sum of O along the plan, -1 if infeasible
+ * The tables of the solved problem are read from the context's own copies, so the
+ * caller may already have released them.  Asynchronous on `stream`.
+ * Errors: INVALID_ARG, NOT_SOLVED, HIP. */
+int gsearch_backtrace(gsearch_ctx *ctx, const int32_t *instances, int32_t n, int32_t *plan,
+                      int32_t *mem_used, void *stream);
+
+/* Waits for `stream`, then copies the data-status word of the most recent solve to
+ * *host_bits (0 = tables were valid; else GSEARCH_DATA_* bits).  Errors: NOT_SOLVED, HIP. */
+int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits);
+
+/* Best cost for EVERY budget of the most recent solve (the last plane already holds
+ * it): curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf for E_b < e <= M.
+ * curve is device [B][M+1].  Paper section 1, feature 2 (adapting to hardware
+ * constraints): one solve answers every smaller device memory as well. */
+int gsearch_budget_curve(gsearch_ctx *ctx, float *curve, void *stream);
+
+/* Debug export of the most recent solve in canonical layout (needs KEEP_PLANES):
+ *   C  device [B][L][M+1][S] fp32, rows e > E_b are filled with +inf
+ *   bp device [B][L][M+1][S] int32, plane 0 and rows e > E_b are 0; NULL to skip (must be
+ *      NULL for a NO_BACKPOINTERS context).
+ * Errors: UNSUPPORTED without the flag, NOT_SOLVED, INVALID_ARG. */
+int gsearch_export_planes(gsearch_ctx *ctx, float *C, int32_t *bp, void *stream);
+
+/* ---- strategy enumeration (paper section 2: decision-tree model of the parallel
+ * configuration space with infeasible configurations discarded) -------------------
+ * Descriptor = 5 int32 (tp, sp, dp, sdp, ckpt): tensor, sequence and data degree
+ * (powers of two with tp*sp*dp == N), sharded-data flag (only when dp > 1) and
+ * recomputation flag.  Tree order: ascending (sp, tp, sdp, ckpt), ckpt fastest.
+ * Caps: tp <= tp_max, sp <= sp_max, tp*sp <= tpsp_max; a cap <= 0 means "none". */
+
+/* Number of strategies (host arithmetic, no GPU).  Negative status if N is not a power
+ * of two in [1, 2^30]. */
+int32_t gsearch_enumerate_count(int32_t N, int32_t tp_max, int32_t sp_max, int32_t tpsp_max);
+
+/* Device enumeration: writes min(count, cap) descriptors to desc (device [cap][5]) and
+ * the full count to count_out (device [1], may be NULL).  Asynchronous on `stream`. */
+int gsearch_enumerate(int32_t N, int32_t tp_max, int32_t sp_max, int32_t tpsp_max,
+                      int32_t *desc, int32_t cap, int32_t *count_out, void *stream);
+
+/* ---- cost tables (paper section 2: time and memory cost models per strategy) ------
+ * The paper prints no formula; this is an alpha-beta model evaluated in fp64, one
+ * rounding per operation, no fused multiply-add, rounded once to the output type.
+ *   layer  device [B][L] of gsearch_layer_model
+ *   hw     host pointer
+ *   rmodel device [K] of gsearch_reshard_model
+ * With t = tokens/(dp*sp), P = 12 hidden^2:
+ *   flops = 3 (24 t h^2 + 4 t seq h), x 4/3 under recomputation
+ *   comm  = [tp>1] 16 t h (tp-1)/tp + [dp>1] 4 (P/tp)(dp-1)/dp (x1.5 if sdp)
+ *           + [sp>1] 8 t h (sp-1)/sp
+ *   T     = fp32( time_scale * 1000 * (flops/(tp*flops_per_s) + comm/bytes_per_s) )
+ *   mem   = state_scale * 16 P/(tp*(sdp?dp:1)) + act_scale * (68 t h/tp) * (ckpt?ckpt_keep:1)
+ *   O     = min(max(1, ceil(mem/bin_bytes)), M+1)
+ *   R[k][si][sj] = 0 if (tp,sp,dp) agree, else
+ *           fp32( 1000 * 2 h (tokens/(dp_j sp_j)) (1 - w lo/hi) / bytes_per_s ),
+ *           lo/hi = min/max(dp_i sp_i, dp_j sp_j), w = 1 if tp_i == tp_j else 0.5
+ * Outputs T [B][L][S], O [B][L][S], R [K][S][S] are device buffers. */
+typedef struct {
+  double hidden, seq, tokens, time_scale, state_scale, act_scale;
+} gsearch_layer_model;
+typedef struct {
+  double flops_per_s, bytes_per_s, bin_bytes, ckpt_keep;
+} gsearch_hw_model;
+typedef struct {
+  double hidden, tokens;
+} gsearch_reshard_model;
+
+int gsearch_build_tables(int32_t B, int32_t L, int32_t S, int32_t M, int32_t K,
+                         const int32_t *desc, const gsearch_layer_model *layer,
+                         const gsearch_hw_model *hw, const gsearch_reshard_model *rmodel,
+                         float *T, int32_t *O, float *R, void *stream);
+
+/* Static description of an error code. */
+const char *gsearch_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSEARCH_H */

@@ -1,0 +1,510 @@
+// Kernels around the forward DP: input sanitising, layer-0 initialisation, final
+// reductions, backtrace, budget curve, debug export, strategy enumeration and the
+// alpha-beta cost-table builder.  All of them are small next to the forward pass.
+#include "gsearch_internal.h"
+
+namespace gs {
+
+#define GS_INF __builtin_huge_valf()
+
+// ----------------------------------------------------------------------------------------
+// Sanitised copies of the caller's tables (so that the hot kernels are memory-safe for
+// any input) and the data-status word.
+//   work item < B*L           : one (b,l) row of T and O, r_index[b][l], min_s O
+//   next K*SP*SP items        : one entry of the transposed transition pool
+//   next SP items             : the padding row behind the pool (read by the prefetch of
+//                               the register-tiled kernel, never used)
+//   last B items              : budgets
+// ----------------------------------------------------------------------------------------
+__global__ void k_prepare(const float *__restrict__ T, const int32_t *__restrict__ O,
+                          const float *__restrict__ R, const int32_t *__restrict__ r_index,
+                          const int32_t *__restrict__ budget, float *__restrict__ Tq,
+                          int32_t *__restrict__ Oq, float *__restrict__ Rt,
+                          int32_t *__restrict__ ridx, int32_t *__restrict__ budq,
+                          int32_t *__restrict__ minO, int32_t *__restrict__ status, int B, int L,
+                          int S, int M, int K, int SP) {
+  const long long nrow = (long long)B * L;
+  const long long nr = (long long)K * SP * SP + SP;
+  const long long total = nrow + nr + B;
+  int bad = 0;
+  for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < total;
+       w += (long long)gridDim.x * blockDim.x) {
+    if (w < nrow) {
+      const int l = (int)(w % L);
+      int mo = M + 1;
+      for (int s = 0; s < SP; ++s) {
+        float t = 0.0f;
+        int o = M + 1; // padding strategies never fit
+        if (s < S) {
+          t = T[w * S + s];
+          if (!(t >= 0.0f) || t == GS_INF || __builtin_signbit(t)) bad |= 0x1;
+          o = O[w * S + s];
+          if (o < 0) { bad |= 0x4; o = M + 1; }
+          if (o > M + 1) o = M + 1;
+          mo = o < mo ? o : mo;
+        }
+        Tq[w * SP + s] = t;
+        Oq[w * SP + s] = o;
+      }
+      minO[w] = mo;
+      int k = 0;
+      if (l > 0) {
+        k = r_index[w];
+        if (k < 0 || k >= K) { bad |= 0x10; k = 0; }
+      }
+      ridx[w] = k;
+    } else if (w < nrow + nr) {
+      const long long x = w - nrow;
+      float r = 0.0f;
+      if (x < (long long)K * SP * SP) {
+        const int i = (int)(x % SP);
+        const int j = (int)((x / SP) % SP);
+        const int k = (int)(x / ((long long)SP * SP));
+        if (i < S && j < S) {
+          r = R[((long long)k * S + i) * S + j];
+          if (!(r >= 0.0f) || __builtin_signbit(r)) bad |= 0x2;
+        }
+      }
+      Rt[x] = r;
+    } else {
+      const int b = (int)(w - nrow - nr);
+      int e = budget[b];
+      if (e < 0 || e > M) { bad |= 0x8; e = e < 0 ? 0 : M; }
+      budq[b] = e;
+    }
+  }
+  if (bad) atomicOr(status, bad);
+}
+
+__global__ void k_clear_status(int32_t *status) { *status = 0; }
+
+// Layer 0 has no predecessor: C[0][e][s] = T[0][s] if e >= O[0][s] else +inf.
+__global__ void k_init_layer0(float *__restrict__ plane, const float *__restrict__ Tq,
+                              const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
+                              int B, int L, int S, int SP, int pitch) {
+  const int b = blockIdx.x % B;
+  const int e = (blockIdx.x / B) * blockDim.x + threadIdx.x;
+  if (e > budget[b]) return;
+  for (int s = 0; s < S; ++s) {
+    const float t = Tq[(size_t)b * L * SP + s];
+    const int o = Oq[(size_t)b * L * SP + s];
+    plane[((size_t)b * S + s) * pitch + e] = (e >= o) ? t : GS_INF;
+  }
+}
+
+// Lexicographic (value, index) minimum across the 64 lanes of a wave.
+static __device__ __forceinline__ void wave_argmin(float &v, int &idx) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const float ov = __shfl_xor(v, d, 64);
+    const int oi = __shfl_xor(idx, d, 64);
+    if (ov < v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+  }
+}
+
+// One wave per instance: min_s C[L-1][E_b][s] with the lowest s on ties.
+__global__ void k_final_instance(const float *__restrict__ last,
+                                 const int32_t *__restrict__ budget,
+                                 const int32_t *__restrict__ status, float *__restrict__ ws_cost,
+                                 int32_t *__restrict__ ws_s, float *__restrict__ best_cost,
+                                 int32_t *__restrict__ best_s, float *__restrict__ final_row, int B,
+                                 int S, int pitch) {
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int E = budget[b];
+  const bool poisoned = *status != 0;
+  float m = GS_INF;
+  int arg = 0x7fffffff;
+  for (int s = lane; s < S; s += kWave) {
+    float v = last[((size_t)b * S + s) * pitch + E];
+    if (poisoned) v = GS_INF;
+    if (final_row) final_row[(size_t)b * S + s] = v;
+    if (v < m || arg == 0x7fffffff) {
+      if (v < m || arg == 0x7fffffff) { m = v; arg = s; }
+    }
+  }
+  wave_argmin(m, arg);
+  if (lane == 0) {
+    const int s = (m < GS_INF) ? arg : -1;
+    ws_cost[b] = m;
+    ws_s[b] = s;
+    if (best_cost) best_cost[b] = m;
+    if (best_s) best_s[b] = s;
+  }
+}
+
+// One block: argmin over instances, lowest instance on ties, -1 if none is feasible.
+__global__ void k_final_global(const float *__restrict__ ws_cost, int32_t *__restrict__ out,
+                               int B) {
+  __shared__ float sv[256 / kWave];
+  __shared__ int si[256 / kWave];
+  float m = GS_INF;
+  int arg = 0x7fffffff;
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    const float v = ws_cost[b];
+    if (v < m) { m = v; arg = b; }
+  }
+  wave_argmin(m, arg);
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = m; si[threadIdx.x >> 6] = arg; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < (int)(blockDim.x >> 6); ++w)
+      if (sv[w] < m || (sv[w] == m && si[w] < arg)) { m = sv[w]; arg = si[w]; }
+    *out = (m < GS_INF) ? arg : -1;
+  }
+}
+
+// Backtrace over stored backpointers: one thread per requested instance walks
+//   s <- best_s; e <- E_b; for l = L-1 .. 1: plan[l] = s; s' = bp[l][e][s]; e -= O[l][s]; s = s'
+template <typename BPT>
+__global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__restrict__ Oq,
+                               const int32_t *__restrict__ budget,
+                               const int32_t *__restrict__ ws_s,
+                               const int32_t *__restrict__ instances, int n,
+                               int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B,
+                               int L, int S, int SP, int pitch) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= n) return;
+  const int b = instances ? instances[q] : q;
+  int s = (b >= 0 && b < B) ? ws_s[b] : -1;
+  if (s < 0) {
+    for (int l = 0; l < L; ++l) plan[(size_t)q * L + l] = -1;
+    if (mem_used) mem_used[q] = -1;
+    return;
+  }
+  int e = budget[b];
+  int used = 0;
+  const size_t layer_stride = (size_t)B * S * pitch;
+  for (int l = L - 1; l >= 1; --l) {
+    plan[(size_t)q * L + l] = s;
+    const int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * S + s) * pitch + e];
+    const int o = Oq[((size_t)b * L + l) * SP + s];
+    used += o;
+    e -= o;
+    s = prev;
+  }
+  plan[(size_t)q * L] = s;
+  used += Oq[(size_t)b * L * SP + s];
+  if (mem_used) mem_used[q] = used;
+}
+
+// Backtrace without stored backpointers: one wave per requested instance re-derives every
+// argmin from the kept planes, argmin_si ( C[l-1][e-O][si] + R[si][s] ), lowest si on ties
+// (all +inf gives 0) - the same value the forward pass would have stored.
+__global__ void k_backtrace_planes(const float *__restrict__ planes,
+                                   const float *__restrict__ Rt, const int32_t *__restrict__ Oq,
+                                   const int32_t *__restrict__ ridx,
+                                   const int32_t *__restrict__ budget,
+                                   const int32_t *__restrict__ ws_s,
+                                   const int32_t *__restrict__ instances, int n,
+                                   int32_t *__restrict__ plan, int32_t *__restrict__ mem_used,
+                                   int B, int L, int S, int SP, int pitch) {
+  const int q = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int b = instances ? instances[q] : q;
+  int s = (b >= 0 && b < B) ? ws_s[b] : -1;
+  if (s < 0) {
+    for (int l = lane; l < L; l += kWave) plan[(size_t)q * L + l] = -1;
+    if (mem_used && lane == 0) mem_used[q] = -1;
+    return;
+  }
+  int e = budget[b];
+  int used = 0;
+  const size_t layer_stride = (size_t)B * S * pitch;
+  for (int l = L - 1; l >= 1; --l) {
+    if (lane == 0) plan[(size_t)q * L + l] = s;
+    const int o = Oq[((size_t)b * L + l) * SP + s];
+    used += o;
+    e -= o;
+    const float *prevp = planes + (size_t)(l - 1) * layer_stride + (size_t)b * S * pitch;
+    const float *rc = Rt + ((size_t)ridx[(size_t)b * L + l] * SP + s) * SP;
+    float m = GS_INF;
+    int arg = 0x7fffffff;
+    for (int i = lane; i < S; i += kWave) {
+      const float v = prevp[(size_t)i * pitch + e] + rc[i];
+      if (v < m || arg == 0x7fffffff) { m = v; arg = i; }
+    }
+    wave_argmin(m, arg);
+    s = arg;
+  }
+  if (lane == 0) {
+    plan[(size_t)q * L] = s;
+    used += Oq[(size_t)b * L * SP + s];
+    if (mem_used) mem_used[q] = used;
+  }
+}
+
+// curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf above.
+__global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__restrict__ budget,
+                               const int32_t *__restrict__ status, float *__restrict__ curve,
+                               int B, int S, int M, int pitch) {
+  const int b = blockIdx.x % B;
+  const int e = (blockIdx.x / B) * blockDim.x + threadIdx.x;
+  if (e > M) return;
+  float m = GS_INF;
+  if (e <= budget[b] && *status == 0)
+    for (int s = 0; s < S; ++s) {
+      const float v = last[((size_t)b * S + s) * pitch + e];
+      m = v < m ? v : m;
+    }
+  curve[(size_t)b * (M + 1) + e] = m;
+}
+
+// Canonical [b][l][e][s] export of the kept planes and backpointers (debug).
+template <typename BPT>
+__global__ void k_export(const float *__restrict__ planes, const BPT *__restrict__ bp,
+                         const int32_t *__restrict__ budget, float *__restrict__ C,
+                         int32_t *__restrict__ bpo, int B, int L, int S, int M, int pitch) {
+  const long long total = (long long)B * L * (M + 1) * S;
+  const size_t layer_stride = (size_t)B * S * pitch;
+  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
+       x += (long long)gridDim.x * blockDim.x) {
+    const int s = (int)(x % S);
+    const int e = (int)((x / S) % (M + 1));
+    const int l = (int)((x / ((long long)S * (M + 1))) % L);
+    const int b = (int)(x / ((long long)S * (M + 1) * L));
+    const bool in = e <= budget[b];
+    const size_t off = ((size_t)b * S + s) * pitch + e;
+    if (C) C[x] = in ? planes[(size_t)l * layer_stride + off] : GS_INF;
+    if (bpo) bpo[x] = (in && l > 0 && bp) ? (int32_t)bp[(size_t)(l - 1) * layer_stride + off] : 0;
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Strategy enumeration (paper section 2: decision tree over the parallel dimensions,
+// infeasible branches discarded).  Tree levels: sp, tp, (dp = N / (tp*sp)), sdp, ckpt.
+// One thread per leaf of the unpruned tree decides whether its leaf survives and, if so,
+// finds its position by counting the surviving leaves before it in tree order.
+// ----------------------------------------------------------------------------------------
+static __device__ __forceinline__ bool leaf_alive(int leaf, int k, int N, int tp_max, int sp_max,
+                                                  int tpsp_max, int *d) {
+  const int ckpt = leaf & 1, sdp = (leaf >> 1) & 1;
+  const int a = (leaf >> 2) % (k + 1); // log2 tp
+  const int c = (leaf >> 2) / (k + 1); // log2 sp
+  if (a + c > k) return false;
+  const int tp = 1 << a, sp = 1 << c, dp = N >> (a + c);
+  if (tp_max > 0 && tp > tp_max) return false;
+  if (sp_max > 0 && sp > sp_max) return false;
+  if (tpsp_max > 0 && tp * sp > tpsp_max) return false;
+  if (sdp && dp == 1) return false;
+  d[0] = tp; d[1] = sp; d[2] = dp; d[3] = sdp; d[4] = ckpt;
+  return true;
+}
+
+__global__ void k_enumerate(int N, int k, int tp_max, int sp_max, int tpsp_max,
+                            int32_t *__restrict__ desc, int cap, int32_t *__restrict__ count_out) {
+  const int leaves = (k + 1) * (k + 1) * 4;
+  int d[5], tmp[5];
+  for (int leaf = blockIdx.x * blockDim.x + threadIdx.x; leaf <= leaves;
+       leaf += gridDim.x * blockDim.x) {
+    // the extra work item leaf == leaves only counts (it yields the total)
+    const bool alive = leaf < leaves && leaf_alive(leaf, k, N, tp_max, sp_max, tpsp_max, d);
+    if (!alive && leaf != leaves) continue;
+    int rank = 0;
+    for (int u = 0; u < leaf; ++u) rank += leaf_alive(u, k, N, tp_max, sp_max, tpsp_max, tmp) ? 1 : 0;
+    if (leaf == leaves) {
+      if (count_out) *count_out = rank;
+    } else if (rank < cap) {
+      for (int x = 0; x < 5; ++x) desc[(size_t)rank * 5 + x] = d[x];
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Alpha-beta cost tables (paper section 2: time and memory cost models per strategy).
+// fp64, one rounding per operation in the order written (the file is compiled without
+// floating-point contraction), one final rounding to the output type.
+// ----------------------------------------------------------------------------------------
+__global__ void k_build_TO(int B, int L, int S, int M, const int32_t *__restrict__ desc,
+                           const double *__restrict__ layer, double F, double BW, double bin,
+                           double keep, float *__restrict__ T, int32_t *__restrict__ O) {
+  const long long total = (long long)B * L * S;
+  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
+       x += (long long)gridDim.x * blockDim.x) {
+    const int s = (int)(x % S);
+    const long long row = x / S;
+    const double *p = layer + row * 6;
+    const double h = p[0], q = p[1], n = p[2], tscale = p[3], sscale = p[4], ascale = p[5];
+    const int itp = desc[s * 5 + 0], isp = desc[s * 5 + 1], idp = desc[s * 5 + 2];
+    const int sdp = desc[s * 5 + 3], ckpt = desc[s * 5 + 4];
+    const double tp = itp, sp = isp, dp = idp;
+    const double t = n / (dp * sp);
+    const double hh = h * h;
+    const double P = 12.0 * hh;
+    double flops = 24.0 * t;
+    flops = flops * hh;
+    double attn = 4.0 * t;
+    attn = attn * q;
+    attn = attn * h;
+    flops = flops + attn;
+    flops = 3.0 * flops;
+    if (ckpt) {
+      flops = flops * 4.0;
+      flops = flops / 3.0;
+    }
+    double comm = 0.0;
+    if (itp > 1) {
+      double y = 16.0 * t;
+      y = y * h;
+      y = y * (tp - 1.0);
+      y = y / tp;
+      comm = comm + y;
+    }
+    if (idp > 1) {
+      double y = P / tp;
+      y = 4.0 * y;
+      y = y * (dp - 1.0);
+      y = y / dp;
+      if (sdp) y = y * 1.5;
+      comm = comm + y;
+    }
+    if (isp > 1) {
+      double y = 8.0 * t;
+      y = y * h;
+      y = y * (sp - 1.0);
+      y = y / sp;
+      comm = comm + y;
+    }
+    double sec = flops / (tp * F);
+    sec = sec + comm / BW;
+    double ms = tscale * 1000.0;
+    ms = ms * sec;
+    T[x] = (float)ms;
+
+    const double shard = sdp ? dp : 1.0;
+    double state = 16.0 * P;
+    state = state / (tp * shard);
+    state = sscale * state;
+    double act = 68.0 * t;
+    act = act * h;
+    act = act / tp;
+    if (ckpt) act = act * keep;
+    act = ascale * act;
+    const double bins = ceil((state + act) / bin);
+    int o;
+    if (!(bins >= 1.0)) o = 1;
+    else if (bins > (double)M + 1.0) o = M + 1;
+    else o = (int)bins;
+    O[x] = o;
+  }
+}
+
+__global__ void k_build_R(int S, int K, const int32_t *__restrict__ desc,
+                          const double *__restrict__ rmodel, double BW, float *__restrict__ R) {
+  const long long total = (long long)K * S * S;
+  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
+       x += (long long)gridDim.x * blockDim.x) {
+    const int j = (int)(x % S), i = (int)((x / S) % S), k = (int)(x / ((long long)S * S));
+    const int32_t *a = desc + i * 5, *c = desc + j * 5;
+    float r = 0.0f;
+    if (!(a[0] == c[0] && a[1] == c[1] && a[2] == c[2])) {
+      const double h = rmodel[k * 2], n = rmodel[k * 2 + 1];
+      const double gi = (double)a[2] * (double)a[1];
+      const double gj = (double)c[2] * (double)c[1];
+      const double lo = gi < gj ? gi : gj, hi = gi < gj ? gj : gi;
+      const double w = (a[0] == c[0]) ? 1.0 : 0.5;
+      double y = 2.0 * h;
+      y = y * (n / gj);
+      double keepfrac = w * lo;
+      keepfrac = keepfrac / hi;
+      y = y * (1.0 - keepfrac);
+      y = y / BW;
+      y = 1000.0 * y;
+      r = (float)y;
+    }
+    R[x] = r;
+  }
+}
+
+// ---- launchers -------------------------------------------------------------------------
+static unsigned blocks_for(long long items, int threads, long long cap = 65535) {
+  long long b = (items + threads - 1) / threads;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (unsigned)b;
+}
+
+void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
+                    const int32_t *r_index, const int32_t *budget, const Workspace &w,
+                    hipStream_t st) {
+  hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, w.status);
+  const long long items = (long long)s.B * s.L + (long long)s.K * s.SP * s.SP + s.SP + s.B;
+  hipLaunchKernelGGL(k_prepare, dim3(blocks_for(items, 256)), dim3(256), 0, st, T, O, R, r_index,
+                     budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B, s.L, s.S,
+                     s.M, s.K, s.SP);
+}
+
+void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st) {
+  const int per = (s.M + 1 + 255) / 256;
+  hipLaunchKernelGGL(k_init_layer0, dim3((unsigned)((size_t)per * s.B)), dim3(256), 0, st, plane0,
+                     w.Tq, w.Oq, w.budget, s.B, s.L, s.S, s.SP, s.pitch);
+}
+
+void launch_final(const Shape &s, const Workspace &w, const float *last_plane, float *best_cost,
+                  int32_t *best_s, float *final_row, int32_t *best_instance, hipStream_t st) {
+  hipLaunchKernelGGL(k_final_instance, dim3(s.B), dim3(kWave), 0, st, last_plane, w.budget,
+                     w.status, w.best_cost, w.best_s, best_cost, best_s, final_row, s.B, s.S,
+                     s.pitch);
+  if (best_instance)
+    hipLaunchKernelGGL(k_final_global, dim3(1), dim3(256), 0, st, w.best_cost, best_instance,
+                       s.B);
+}
+
+void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *instances, int n,
+                         int32_t *plan, int32_t *mem_used, hipStream_t st) {
+  const dim3 grid((n + 63) / 64), block(64);
+  if (s.bp16)
+    hipLaunchKernelGGL((k_backtrace_bp<uint16_t>), grid, block, 0, st, (const uint16_t *)w.bp,
+                       w.Oq, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S,
+                       s.SP, s.pitch);
+  else
+    hipLaunchKernelGGL((k_backtrace_bp<uint8_t>), grid, block, 0, st, (const uint8_t *)w.bp, w.Oq,
+                       w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S, s.SP,
+                       s.pitch);
+}
+
+void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *instances, int n,
+                             int32_t *plan, int32_t *mem_used, hipStream_t st) {
+  hipLaunchKernelGGL(k_backtrace_planes, dim3(n), dim3(kWave), 0, st, w.planes, w.Rt, w.Oq,
+                     w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S,
+                     s.SP, s.pitch);
+}
+
+void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_plane,
+                         float *curve, hipStream_t st) {
+  const int per = (s.M + 1 + 255) / 256;
+  hipLaunchKernelGGL(k_budget_curve, dim3((unsigned)((size_t)per * s.B)), dim3(256), 0, st,
+                     last_plane, w.budget, w.status, curve, s.B, s.S, s.M, s.pitch);
+}
+
+void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st) {
+  const long long total = (long long)s.B * s.L * (s.M + 1) * s.S;
+  const dim3 grid(blocks_for(total, 256, 1 << 20)), block(256);
+  if (s.bp16)
+    hipLaunchKernelGGL((k_export<uint16_t>), grid, block, 0, st, w.planes,
+                       (const uint16_t *)w.bp, w.budget, C, bp, s.B, s.L, s.S, s.M, s.pitch);
+  else
+    hipLaunchKernelGGL((k_export<uint8_t>), grid, block, 0, st, w.planes, (const uint8_t *)w.bp,
+                       w.budget, C, bp, s.B, s.L, s.S, s.M, s.pitch);
+}
+
+void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,
+                      int32_t *count_out, hipStream_t st) {
+  int k = 0;
+  while ((1 << k) < N) ++k;
+  const int leaves = (k + 1) * (k + 1) * 4 + 1;
+  hipLaunchKernelGGL(k_enumerate, dim3((leaves + 255) / 256), dim3(256), 0, st, N, k, tp_max,
+                     sp_max, tpsp_max, desc, cap, count_out);
+}
+
+void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,
+                         const double *layer, double flops_per_s, double bytes_per_s,
+                         double bin_bytes, double ckpt_keep, const double *rmodel, float *T,
+                         int32_t *O, float *R, hipStream_t st) {
+  hipLaunchKernelGGL(k_build_TO, dim3(blocks_for((long long)B * L * S, 256)), dim3(256), 0, st, B,
+                     L, S, M, desc, layer, flops_per_s, bytes_per_s, bin_bytes, ckpt_keep, T, O);
+  hipLaunchKernelGGL(k_build_R, dim3(blocks_for((long long)K * S * S, 256)), dim3(256), 0, st, S,
+                     K, desc, rmodel, bytes_per_s, R);
+}
+
+} // namespace gs

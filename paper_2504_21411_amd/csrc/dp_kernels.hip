@@ -1,0 +1,299 @@
+// Forward kernels of the per-layer strategy DP (paper section 2, "Search Engine"):
+//   C[l][e][sj] = ( min_si ( C[l-1][e-O[l][sj]][si] + R[si][sj] ) ) + T[l][sj]
+// One launch advances every instance of the batch by one layer front.
+//
+// Data layout: a C plane is [b][s][e] with the budget index e contiguous (pitch a
+// multiple of 64), so that a wavefront whose lanes are 64 consecutive budget rows reads
+// and writes 256 contiguous bytes per strategy row.
+//
+// Register-tiled "push" form (k_dp_push): a lane owns ONE source row e' of the previous
+// plane and keeps all S values C[l-1][e'][.] in VGPRs.  For each target strategy sj the
+// wave scans si with the transition column R[.][sj] as wave-uniform scalar operands, then
+// adds T and stores to row e' + O[l][sj].  Every C operand is read from HBM/L2 once and
+// reused S times from registers, so the kernel is bound by the vector ALU (one add and
+// the min/argmin bookkeeping per relaxation), not by LDS or HBM.  The shifted stores
+// stay coalesced because O[l][sj] is uniform across the wave.
+//
+// Rows e < O[l][sj] of the target cannot hold layer l under sj: they are set to +inf
+// (bp 0) by the wave that owns those rows, so that every row 0..E of the target plane is
+// written exactly once per launch and nothing stale survives from an earlier solve.
+#include "gsearch_internal.h"
+
+namespace gs {
+
+#define GS_INF __builtin_huge_valf()
+
+static __device__ __forceinline__ int wave_uniform(int v) {
+  return __builtin_amdgcn_readfirstlane(v);
+}
+
+// ---------------------------------------------------------------------------------------
+// Argmin scan of the register-tiled kernel, written as inline assembly.
+//
+// Per relaxation the vector ALU executes exactly four instructions,
+//     v = c + r;   keep = (v >= m);   m = keep ? m : v;   arg = keep ? arg : idx
+// ("v >= m keeps" is the strict-less-than update of the recurrence; NaN cannot occur
+// because inputs are validated non-negative and +inf only ever meets +inf).
+// Left to the compiler, the index selects get deferred and all S compare masks are parked
+// in scalar registers and spilled, so the schedule is fixed by hand here:
+//   * two independent chains (even candidates -> chain A, odd -> chain B) are interleaved
+//     so that, between a compare that writes a lane mask into scalar registers and the
+//     selects that read it, two other vector instructions always issue (gfx950 requires
+//     two wait states there; the last step of a block has no adds left and uses s_nop);
+//   * chain-local indices n (candidate 2n or 2n+1) stay below 64, so they are inline
+//     constants and never compete with the mask for the constant bus;
+//   * the eight transition values of the NEXT block are fetched by one scalar load issued
+//     at the top of the block and awaited at its end, after 32 vector instructions.
+// One block handles candidates 8q .. 8q+7; `r` holds their transition costs, `rn`
+// receives those of the following eight (the first eight of the next column after the
+// last block: the caller keeps one padding row behind the table for that).
+// ---------------------------------------------------------------------------------------
+typedef float float8_t __attribute__((ext_vector_type(8)));
+
+template <int Q>
+static __device__ __forceinline__ void argmin_block8(float &mA, int &argA, float &mB, int &argB,
+                                                     const float *c, const float8_t &r,
+                                                     float8_t &rn, const float *col) {
+  float tA0, tB0, tA1, tB1;
+  unsigned long long maskA;
+  asm volatile(
+      "s_load_dwordx8 %[rn], %[col], %[n0]*8+32\n\t"
+      "v_add_f32 %[tA0], %[r0], %[c0]\n\t"
+      "v_add_f32 %[tB0], %[r1], %[c1]\n\t"
+      // step 0
+      "v_cmp_ge_f32 %[mk], %[tA0], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB0], %[mB]\n\t"
+      "v_add_f32 %[tA1], %[r2], %[c2]\n\t"
+      "v_add_f32 %[tB1], %[r3], %[c3]\n\t"
+      "v_cndmask_b32 %[mA], %[tA0], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0], %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB0], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0], %[aB], vcc\n\t"
+      // step 1
+      "v_cmp_ge_f32 %[mk], %[tA1], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB1], %[mB]\n\t"
+      "v_add_f32 %[tA0], %[r4], %[c4]\n\t"
+      "v_add_f32 %[tB0], %[r5], %[c5]\n\t"
+      "v_cndmask_b32 %[mA], %[tA1], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0]+1, %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB1], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0]+1, %[aB], vcc\n\t"
+      // step 2
+      "v_cmp_ge_f32 %[mk], %[tA0], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB0], %[mB]\n\t"
+      "v_add_f32 %[tA1], %[r6], %[c6]\n\t"
+      "v_add_f32 %[tB1], %[r7], %[c7]\n\t"
+      "v_cndmask_b32 %[mA], %[tA0], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0]+2, %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB0], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0]+2, %[aB], vcc\n\t"
+      // step 3
+      "v_cmp_ge_f32 %[mk], %[tA1], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB1], %[mB]\n\t"
+      "s_nop 0\n\t"
+      "v_cndmask_b32 %[mA], %[tA1], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0]+3, %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB1], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0]+3, %[aB], vcc\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : [mA] "+v"(mA), [aA] "+v"(argA), [mB] "+v"(mB), [aB] "+v"(argB), [tA0] "=&v"(tA0),
+        [tB0] "=&v"(tB0), [tA1] "=&v"(tA1), [tB1] "=&v"(tB1), [mk] "=&s"(maskA),
+        [rn] "=&s"(rn)
+      : [col] "s"(col), [n0] "n"(4 * Q), [r0] "s"(r[0]), [r1] "s"(r[1]), [r2] "s"(r[2]),
+        [r3] "s"(r[3]), [r4] "s"(r[4]), [r5] "s"(r[5]), [r6] "s"(r[6]), [r7] "s"(r[7]),
+        [c0] "v"(c[8 * Q + 0]), [c1] "v"(c[8 * Q + 1]), [c2] "v"(c[8 * Q + 2]),
+        [c3] "v"(c[8 * Q + 3]), [c4] "v"(c[8 * Q + 4]), [c5] "v"(c[8 * Q + 5]),
+        [c6] "v"(c[8 * Q + 6]), [c7] "v"(c[8 * Q + 7])
+      : "vcc", "memory");
+}
+
+template <int Q, int NQ>
+struct ArgminBlocks {
+  static __device__ __forceinline__ void run(float &mA, int &argA, float &mB, int &argB,
+                                             const float *c, float8_t &r, const float *col) {
+    float8_t rn;
+    argmin_block8<Q>(mA, argA, mB, argB, c, r, rn, col);
+    r = rn;
+    ArgminBlocks<Q + 1, NQ>::run(mA, argA, mB, argB, c, r, col);
+  }
+};
+template <int NQ>
+struct ArgminBlocks<NQ, NQ> {
+  static __device__ __forceinline__ void run(float &, int &, float &, int &, const float *,
+                                             float8_t &, const float *) {}
+};
+
+// First eight transition values of a column, fetched and awaited (start of a tile).
+static __device__ __forceinline__ float8_t load_col_head(const float *col) {
+  float8_t r;
+  asm volatile("s_load_dwordx8 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(r) : "s"(col) : "memory");
+  return r;
+}
+
+// SP: padded strategy count (compile time).  WITH_BP: also track and store the argmin.
+template <int SP, bool WITH_BP>
+__global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
+    const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO, int B, int L, int S,
+    int l, int pitch) {
+  const int b = blockIdx.x % B;
+  const int wave = wave_uniform(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int tile_start = ((blockIdx.x / B) * (kRowsPerBlock / kWave) + wave) * kWave;
+  const int E = budget[b];
+  if (tile_start > E) return;
+
+  const int row = tile_start + lane;
+  const bool valid = row <= E;
+  const int bl = b * L + l;
+  // source rows above E - min_s O[l][s] feed no target row
+  const bool compute = tile_start <= E - minO[bl];
+  const size_t plane_off = (size_t)b * S * pitch;
+  const float *__restrict__ srcb = src + plane_off;
+  float *__restrict__ dstb = dst + plane_off;
+  uint8_t *__restrict__ bpb = WITH_BP ? bp + plane_off : nullptr;
+  const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
+  const float *__restrict__ trow = Tq + (size_t)bl * SP;
+  const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
+
+  float c[SP];
+  if (compute) {
+#pragma unroll
+    for (int i = 0; i < SP; ++i)
+      c[i] = (i < S && valid) ? srcb[(size_t)i * pitch + row] : GS_INF;
+  } else {
+#pragma unroll
+    for (int i = 0; i < SP; ++i) c[i] = GS_INF;
+  }
+
+  float8_t rcur;
+  if (WITH_BP && compute) rcur = load_col_head(rk);
+  for (int j = 0; j < S; ++j) {
+    const int o = orow[j];
+    const float t = trow[j];
+    if (compute) {
+      const float *__restrict__ rc = rk + (size_t)j * SP;
+      float m = GS_INF;
+      int arg = 0;
+      if (WITH_BP) {
+        float mB = GS_INF;
+        int argA = 0, argB = 0;
+        ArgminBlocks<0, SP / 8>::run(m, argA, mB, argB, c, rcur, rc);
+        // merge the chains: candidate 2*argA (even chain) against 2*argB+1 (odd chain),
+        // the strictly smaller value wins and equal values go to the lower candidate
+        const int candA = 2 * argA, candB = 2 * argB + 1;
+        const bool takeB = (mB < m) || (mB == m && candB < candA);
+        m = takeB ? mB : m;
+        arg = takeB ? candB : candA;
+      } else {
+#pragma unroll
+        for (int i = 0; i < SP; ++i) m = __builtin_fminf(m, c[i] + rc[i]);
+      }
+      const int eo = row + o;
+      if (valid && eo <= E) {
+        dstb[(size_t)j * pitch + eo] = m + t;
+        if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg;
+      }
+    }
+    if (tile_start < o) {
+      if (valid && row < o) {
+        dstb[(size_t)j * pitch + row] = GS_INF;
+        if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
+      }
+    }
+  }
+}
+
+// Shape-agnostic "pull" form: a lane owns one TARGET row e and, for each sj, scans the
+// previous plane at row e - O[l][sj] straight from global memory.  Any S up to the
+// library limit, uint8 or uint16 backpointers.  Slow (one load per relaxation); it is the
+// fallback for S above the register-tiled sizes and an independent second implementation.
+template <typename BPT, bool WITH_BP>
+__global__ __launch_bounds__(kRowsPerBlock) void k_dp_generic(
+    const float *__restrict__ src, float *__restrict__ dst, BPT *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, int B, int L, int S, int SP, int l, int pitch) {
+  const int b = blockIdx.x % B;
+  const int row = (blockIdx.x / B) * kRowsPerBlock + threadIdx.x;
+  const int E = budget[b];
+  if (row > E) return;
+  const int bl = b * L + l;
+  const size_t plane_off = (size_t)b * S * pitch;
+  const float *__restrict__ srcb = src + plane_off;
+  const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
+  for (int j = 0; j < S; ++j) {
+    const int o = Oq[(size_t)bl * SP + j];
+    float out = GS_INF;
+    int arg = 0;
+    if (row >= o) {
+      const int srow = row - o;
+      const float *__restrict__ rc = rk + (size_t)j * SP;
+      float m = GS_INF;
+      for (int i = 0; i < S; ++i) {
+        const float v = srcb[(size_t)i * pitch + srow] + rc[i];
+        if (v < m) { m = v; arg = i; }
+      }
+      out = m + Tq[(size_t)bl * SP + j];
+    }
+    dst[plane_off + (size_t)j * pitch + row] = out;
+    if (WITH_BP) bp[plane_off + (size_t)j * pitch + row] = (BPT)arg;
+  }
+}
+
+int tuned_sp_for(int S) {
+  static const int sizes[] = {8, 16, 24, 32, 48, 64, 96, 128};
+  for (int v : sizes)
+    if (S <= v) return v;
+  return 0;
+}
+
+template <int SP>
+static void launch_push(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                        void *bp_l, dim3 grid, hipStream_t st) {
+  if (bp_l)
+    hipLaunchKernelGGL((k_dp_push<SP, true>), grid, dim3(kRowsPerBlock), 0, st, src, dst,
+                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L,
+                       s.S, l, s.pitch);
+  else
+    hipLaunchKernelGGL((k_dp_push<SP, false>), grid, dim3(kRowsPerBlock), 0, st, src, dst,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
+                       s.L, s.S, l, s.pitch);
+}
+
+void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                     void *bp_l, bool force_generic, hipStream_t st) {
+  const int blocks_per_instance = (s.M + 1 + kRowsPerBlock - 1) / kRowsPerBlock;
+  const dim3 grid((unsigned)((size_t)blocks_per_instance * s.B));
+  const int tsp = tuned_sp_for(s.S);
+  if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16) {
+    switch (tsp) {
+      case 8: launch_push<8>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 16: launch_push<16>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 24: launch_push<24>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 32: launch_push<32>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 48: launch_push<48>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 64: launch_push<64>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 96: launch_push<96>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 128: launch_push<128>(s, w, l, src, dst, bp_l, grid, st); return;
+      default: break;
+    }
+  }
+  if (!bp_l) {
+    hipLaunchKernelGGL((k_dp_generic<uint8_t, false>), grid, dim3(kRowsPerBlock), 0, st, src,
+                       dst, (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L,
+                       s.S, s.SP, l, s.pitch);
+  } else if (s.bp16) {
+    hipLaunchKernelGGL((k_dp_generic<uint16_t, true>), grid, dim3(kRowsPerBlock), 0, st, src,
+                       dst, (uint16_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S,
+                       s.SP, l, s.pitch);
+  } else {
+    hipLaunchKernelGGL((k_dp_generic<uint8_t, true>), grid, dim3(kRowsPerBlock), 0, st, src,
+                       dst, (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S,
+                       s.SP, l, s.pitch);
+  }
+}
+
+} // namespace gs

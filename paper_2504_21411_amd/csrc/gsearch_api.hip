@@ -1,0 +1,294 @@
+// C ABI of libgsearch (see include/gsearch.h): argument checking, workspace layout and the
+// sequence of kernel launches.  No arithmetic of the method happens on the host.
+#include "../../include/gsearch.h"
+
+#include <new>
+
+#include "gsearch_internal.h"
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  size_t planes, bp, Tq, Oq, Rt, ridx, budget, minO, best_s, best_cost, status, total;
+  int nplanes;
+};
+
+gs::Shape make_shape(int B, int L, int S, int M, int K) {
+  gs::Shape s;
+  s.B = B; s.L = L; s.S = S; s.M = M; s.K = K;
+  const int tsp = gs::tuned_sp_for(S);
+  s.SP = tsp ? tsp : (int)align_up((size_t)S, 8);
+  s.pitch = (int)align_up((size_t)M + 1, 64);
+  s.bp16 = S > 256;
+  return s;
+}
+
+bool keeps_all_planes(uint32_t flags) {
+  return (flags & (GSEARCH_FLAG_KEEP_PLANES | GSEARCH_FLAG_NO_BACKPOINTERS)) != 0;
+}
+
+Layout make_layout(const gs::Shape &s, uint32_t flags) {
+  Layout y;
+  size_t off = 0;
+  auto take = [&off](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  y.nplanes = keeps_all_planes(flags) ? s.L : (s.L < 2 ? s.L : 2);
+  y.planes = take(sizeof(float) * gs::plane_elems(s) * (size_t)y.nplanes);
+  const bool want_bp = !(flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
+  y.bp = take(want_bp ? gs::plane_elems(s) * (size_t)(s.L - 1) * (s.bp16 ? 2 : 1) : 0);
+  y.Tq = take(sizeof(float) * (size_t)s.B * s.L * s.SP);
+  y.Oq = take(sizeof(int32_t) * (size_t)s.B * s.L * s.SP);
+  y.Rt = take(sizeof(float) * ((size_t)s.K * s.SP * s.SP + s.SP));
+  y.ridx = take(sizeof(int32_t) * (size_t)s.B * s.L);
+  y.budget = take(sizeof(int32_t) * (size_t)s.B);
+  y.minO = take(sizeof(int32_t) * (size_t)s.B * s.L);
+  y.best_s = take(sizeof(int32_t) * (size_t)s.B);
+  y.best_cost = take(sizeof(float) * (size_t)s.B);
+  y.status = take(sizeof(int32_t));
+  y.total = off;
+  return y;
+}
+
+bool config_ok(const gsearch_config *c) {
+  return c && c->max_B >= 1 && c->max_L >= 1 && c->max_S >= 1 && c->max_S <= GSEARCH_MAX_S &&
+         c->max_M >= 1 && c->max_K >= 1 && c->device >= 0 && c->max_B <= (1 << 20) &&
+         c->max_L <= (1 << 16) && c->max_M <= (1 << 24) && c->max_K <= (1 << 16) &&
+         (c->flags & ~(GSEARCH_FLAG_KEEP_PLANES | GSEARCH_FLAG_FORCE_GENERIC |
+                       GSEARCH_FLAG_NO_BACKPOINTERS)) == 0;
+}
+
+// Makes the context's device current for the duration of a call.
+struct DeviceScope {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceScope(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceScope() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+} // namespace
+
+struct gsearch_ctx {
+  gsearch_config cfg;
+  char *base = nullptr;
+  size_t bytes = 0;
+  bool solved = false;
+  gs::Shape shape{};
+  gs::Workspace ws{};
+  int last_plane = 0; // index of the plane that holds layer L-1
+};
+
+extern "C" {
+
+const char *gsearch_strerror(int status) {
+  switch (status) {
+    case GSEARCH_OK: return "ok";
+    case GSEARCH_ERR_INVALID_ARG: return "invalid argument";
+    case GSEARCH_ERR_CAPACITY: return "problem exceeds the capacity the context was created with";
+    case GSEARCH_ERR_NO_DEVICE: return "no usable GPU device";
+    case GSEARCH_ERR_HIP: return "HIP runtime error";
+    case GSEARCH_ERR_NOT_SOLVED: return "no solve has been issued on this context";
+    case GSEARCH_ERR_NO_MEMORY: return "out of device or host memory";
+    case GSEARCH_ERR_UNSUPPORTED: return "operation needs a flag the context was not created with";
+    default: return "unknown status";
+  }
+}
+
+size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
+  if (!config_ok(cfg)) return 0;
+  return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
+                     cfg->flags)
+      .total;
+}
+
+int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
+  if (!out) return GSEARCH_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!config_ok(cfg)) return GSEARCH_ERR_INVALID_ARG;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1 || cfg->device >= ndev) {
+    (void)hipGetLastError();
+    return GSEARCH_ERR_NO_DEVICE;
+  }
+  DeviceScope scope(cfg->device);
+  if (!scope.ok) return GSEARCH_ERR_NO_DEVICE;
+  gsearch_ctx *ctx = new (std::nothrow) gsearch_ctx;
+  if (!ctx) return GSEARCH_ERR_NO_MEMORY;
+  ctx->cfg = *cfg;
+  ctx->bytes = gsearch_workspace_bytes(cfg);
+  void *p = nullptr;
+  if (hipMalloc(&p, ctx->bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return GSEARCH_ERR_NO_MEMORY;
+  }
+  ctx->base = static_cast<char *>(p);
+  *out = ctx;
+  return GSEARCH_OK;
+}
+
+int gsearch_destroy(gsearch_ctx *ctx) {
+  if (!ctx) return GSEARCH_OK;
+  int rc = GSEARCH_OK;
+  {
+    DeviceScope scope(ctx->cfg.device);
+    if (ctx->base && hipFree(ctx->base) != hipSuccess) rc = GSEARCH_ERR_HIP;
+  }
+  delete ctx;
+  return rc;
+}
+
+int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result *r,
+                        void *stream) {
+  if (!ctx || !p || !r) return GSEARCH_ERR_INVALID_ARG;
+  if (p->B < 1 || p->L < 1 || p->S < 1 || p->M < 1 || p->K < 1 || !p->T || !p->O || !p->R ||
+      !p->r_index || !p->budget)
+    return GSEARCH_ERR_INVALID_ARG;
+  const gsearch_config &c = ctx->cfg;
+  if (p->B > c.max_B || p->L > c.max_L || p->S > c.max_S || p->M > c.max_M || p->K > c.max_K)
+    return GSEARCH_ERR_CAPACITY;
+  DeviceScope scope(c.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  const gs::Shape s = make_shape(p->B, p->L, p->S, p->M, p->K);
+  const Layout y = make_layout(s, c.flags);
+  if (y.total > ctx->bytes) return GSEARCH_ERR_CAPACITY;
+  gs::Workspace w;
+  char *base = ctx->base;
+  w.planes = reinterpret_cast<float *>(base + y.planes);
+  const bool with_bp = !(c.flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
+  w.bp = with_bp ? static_cast<void *>(base + y.bp) : nullptr;
+  w.Tq = reinterpret_cast<float *>(base + y.Tq);
+  w.Oq = reinterpret_cast<int32_t *>(base + y.Oq);
+  w.Rt = reinterpret_cast<float *>(base + y.Rt);
+  w.ridx = reinterpret_cast<int32_t *>(base + y.ridx);
+  w.budget = reinterpret_cast<int32_t *>(base + y.budget);
+  w.minO = reinterpret_cast<int32_t *>(base + y.minO);
+  w.best_s = reinterpret_cast<int32_t *>(base + y.best_s);
+  w.best_cost = reinterpret_cast<float *>(base + y.best_cost);
+  w.status = reinterpret_cast<int32_t *>(base + y.status);
+  ctx->solved = false;
+  ctx->shape = s;
+  ctx->ws = w;
+
+  const size_t pe = gs::plane_elems(s);
+  const bool keep = keeps_all_planes(c.flags);
+  const size_t bp_layer_bytes = pe * (s.bp16 ? 2 : 1);
+  const bool generic = (c.flags & GSEARCH_FLAG_FORCE_GENERIC) != 0;
+
+  gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w, st);
+  gs::launch_init_layer0(s, w, w.planes, st);
+  int cur = 0;
+  for (int l = 1; l < s.L; ++l) {
+    const int nxt = keep ? l : (cur ^ 1);
+    void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes : nullptr;
+    gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe, w.planes + (size_t)nxt * pe, bp_l,
+                        generic, st);
+    cur = nxt;
+  }
+  ctx->last_plane = cur;
+  gs::launch_final(s, w, w.planes + (size_t)cur * pe, r->best_cost, r->best_s, r->final_row,
+                   r->best_instance, st);
+  if (hipGetLastError() != hipSuccess) return GSEARCH_ERR_HIP;
+  ctx->solved = true;
+  return GSEARCH_OK;
+}
+
+int gsearch_backtrace(gsearch_ctx *ctx, const int32_t *instances, int32_t n, int32_t *plan,
+                      int32_t *mem_used, void *stream) {
+  if (!ctx || !plan || n < 1) return GSEARCH_ERR_INVALID_ARG;
+  if (!ctx->solved) return GSEARCH_ERR_NOT_SOLVED;
+  if (!instances && n > ctx->shape.B) return GSEARCH_ERR_INVALID_ARG;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (ctx->cfg.flags & GSEARCH_FLAG_NO_BACKPOINTERS)
+    gs::launch_backtrace_planes(ctx->shape, ctx->ws, instances, n, plan, mem_used, st);
+  else
+    gs::launch_backtrace_bp(ctx->shape, ctx->ws, instances, n, plan, mem_used, st);
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
+int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits) {
+  if (!ctx || !host_bits) return GSEARCH_ERR_INVALID_ARG;
+  if (!ctx->solved) return GSEARCH_ERR_NOT_SOLVED;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipStreamSynchronize(st) != hipSuccess) return GSEARCH_ERR_HIP;
+  if (hipMemcpy(host_bits, ctx->ws.status, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    return GSEARCH_ERR_HIP;
+  return GSEARCH_OK;
+}
+
+int gsearch_budget_curve(gsearch_ctx *ctx, float *curve, void *stream) {
+  if (!ctx || !curve) return GSEARCH_ERR_INVALID_ARG;
+  if (!ctx->solved) return GSEARCH_ERR_NOT_SOLVED;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  const float *last = ctx->ws.planes + (size_t)ctx->last_plane * gs::plane_elems(ctx->shape);
+  gs::launch_budget_curve(ctx->shape, ctx->ws, last, curve, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
+int gsearch_export_planes(gsearch_ctx *ctx, float *C, int32_t *bp, void *stream) {
+  if (!ctx || (!C && !bp)) return GSEARCH_ERR_INVALID_ARG;
+  if (!(ctx->cfg.flags & GSEARCH_FLAG_KEEP_PLANES)) return GSEARCH_ERR_UNSUPPORTED;
+  if (bp && (ctx->cfg.flags & GSEARCH_FLAG_NO_BACKPOINTERS)) return GSEARCH_ERR_INVALID_ARG;
+  if (!ctx->solved) return GSEARCH_ERR_NOT_SOLVED;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  gs::launch_export(ctx->shape, ctx->ws, C, bp, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
+int32_t gsearch_enumerate_count(int32_t N, int32_t tp_max, int32_t sp_max, int32_t tpsp_max) {
+  if (N < 1 || N > (1 << 30) || (N & (N - 1)) != 0) return GSEARCH_ERR_INVALID_ARG;
+  int32_t n = 0;
+  for (int64_t sp = 1; sp <= N; sp *= 2)
+    for (int64_t tp = 1; tp * sp <= N; tp *= 2) {
+      if ((sp_max > 0 && sp > sp_max) || (tp_max > 0 && tp > tp_max) ||
+          (tpsp_max > 0 && tp * sp > tpsp_max))
+        continue;
+      n += (N / (tp * sp) > 1) ? 4 : 2; // sdp needs dp > 1; ckpt doubles both
+    }
+  return n;
+}
+
+int gsearch_enumerate(int32_t N, int32_t tp_max, int32_t sp_max, int32_t tpsp_max, int32_t *desc,
+                      int32_t cap, int32_t *count_out, void *stream) {
+  if (N < 1 || N > (1 << 30) || (N & (N - 1)) != 0 || cap < 0 || (cap > 0 && !desc))
+    return GSEARCH_ERR_INVALID_ARG;
+  gs::launch_enumerate(N, tp_max, sp_max, tpsp_max, desc, cap, count_out,
+                       static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
+int gsearch_build_tables(int32_t B, int32_t L, int32_t S, int32_t M, int32_t K,
+                         const int32_t *desc, const gsearch_layer_model *layer,
+                         const gsearch_hw_model *hw, const gsearch_reshard_model *rmodel, float *T,
+                         int32_t *O, float *R, void *stream) {
+  if (B < 1 || L < 1 || S < 1 || M < 1 || K < 1 || !desc || !layer || !hw || !rmodel || !T ||
+      !O || !R)
+    return GSEARCH_ERR_INVALID_ARG;
+  if (!(hw->flops_per_s > 0.0) || !(hw->bytes_per_s > 0.0) || !(hw->bin_bytes > 0.0))
+    return GSEARCH_ERR_INVALID_ARG;
+  gs::launch_build_tables(B, L, S, M, K, desc, reinterpret_cast<const double *>(layer),
+                          hw->flops_per_s, hw->bytes_per_s, hw->bin_bytes, hw->ckpt_keep,
+                          reinterpret_cast<const double *>(rmodel), T, O, R,
+                          static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
+} // extern "C"

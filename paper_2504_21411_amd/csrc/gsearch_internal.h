@@ -1,0 +1,67 @@
+// Internal declarations shared by the HIP translation units of libgsearch (gfx950 only).
+// Nothing here is part of the C ABI; see include/gsearch.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace gs {
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kRowsPerBlock = 256; // budget rows handled by one workgroup (4 waves)
+
+// Shape of the batch being solved plus the padded pitches of the workspace copies.
+struct Shape {
+  int B, L, S, M, K;
+  int SP;    // pitch of one (b,l) row of Tq/Oq and of both dimensions of Rt
+  int pitch; // pitch (in elements) of one strategy row of a C plane / bp plane
+  int bp16;  // backpointers are uint16 (S > 256) instead of uint8
+};
+
+// Device pointers into the context's workspace.
+struct Workspace {
+  float *planes;     // [nplanes][B][S][pitch]   C planes, budget index contiguous
+  void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null)
+  float *Tq;         // [B][L][SP]   sanitised copy of T
+  int32_t *Oq;       // [B][L][SP]   sanitised copy of O, clamped to [0, M+1]
+  float *Rt;         // [K][SP][SP]  transposed copy: Rt[k][sj][si] = R[k][si][sj]
+  int32_t *ridx;     // [B][L]       clamped r_index (entry l=0 is 0)
+  int32_t *budget;   // [B]          clamped budgets
+  int32_t *minO;     // [B][L]       min_s Oq
+  int32_t *best_s;   // [B]          result of the final reduction (kept for backtrace)
+  float *best_cost;  // [B]
+  int32_t *status;   // [1]          data-status bits
+};
+
+inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; }
+
+// ---- launchers (all asynchronous on `st`) -------------------------------------------
+void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
+                    const int32_t *r_index, const int32_t *budget, const Workspace &w,
+                    hipStream_t st);
+void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);
+// One layer front of the recurrence: plane l-1 -> plane l (+ backpointers of layer l).
+void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                     void *bp_l, bool force_generic, hipStream_t st);
+void launch_final(const Shape &s, const Workspace &w, const float *last_plane,
+                  float *best_cost, int32_t *best_s, float *final_row, int32_t *best_instance,
+                  hipStream_t st);
+void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *instances, int n,
+                         int32_t *plan, int32_t *mem_used, hipStream_t st);
+void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *instances, int n,
+                             int32_t *plan, int32_t *mem_used, hipStream_t st);
+void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_plane,
+                         float *curve, hipStream_t st);
+void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st);
+void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,
+                      int32_t *count_out, hipStream_t st);
+void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,
+                         const double *layer, double flops_per_s, double bytes_per_s,
+                         double bin_bytes, double ckpt_keep, const double *rmodel, float *T,
+                         int32_t *O, float *R, hipStream_t st);
+
+// Register-tiled forward kernels exist for these padded strategy counts.
+int tuned_sp_for(int S); // smallest supported SP >= S, or 0 if S is too large
+
+} // namespace gs

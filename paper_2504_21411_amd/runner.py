@@ -1,0 +1,70 @@
+"""Drives the whole hot path for one workload through the C-ABI binding.
+
+enumerate strategies -> build cost tables (model workloads) -> batched DP -> final
+reductions -> backtrace.  Everything runs in libgsearch; this file only moves arrays
+between numpy and the GPU and orders the calls.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding
+from .workloads import Workload
+
+
+class DeviceWorkload:
+    """A workload's inputs resident in HBM (uploaded once, reused by every step)."""
+
+    def __init__(self, w: Workload, device="cuda"):
+        import torch
+        self.w = w
+        self.device = torch.device(device)
+        t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(self.device, dtype=dt)
+        self.r_index = t(w.r_index, torch.int32)
+        self.budget = t(w.budget, torch.int32)
+        if w.kind == "tables":
+            self.T, self.O, self.R = t(w.T, torch.float32), t(w.O, torch.int32), t(w.R, torch.float32)
+            self.layer = self.rmodel = None
+        else:
+            self.T = self.O = self.R = None
+            self.layer = t(w.layer, torch.float64)
+            self.rmodel = t(w.rmodel, torch.float64)
+        self.desc = None
+
+
+def make_context(w: Workload, flags=0, device=0) -> binding.GSearch:
+    return binding.GSearch(w.B, w.L, w.S, w.M, w.K, flags=flags, device=device)
+
+
+def run_step(ctx: binding.GSearch, dw: DeviceWorkload, backtrace="best", stream=None):
+    """One pass of the hot path.  Returns device tensors; nothing is synchronised here."""
+    w = dw.w
+    out = {}
+    if w.kind == "model":
+        desc, count = binding.gsearch_enumerate(device=dw.device, stream=stream, **w.enum)
+        T, O, R = binding.gsearch_build_tables(desc, dw.layer, w.hw, dw.rmodel, w.M, stream=stream)
+        out.update(desc=desc, count=count, T=T, O=O, R=R)
+    else:
+        T, O, R = dw.T, dw.O, dw.R
+    res = ctx.gsearch_solve_batch(T, O, R, dw.r_index, dw.budget, w.M, stream=stream)
+    out.update(res)
+    if backtrace == "best":
+        out.update(ctx.gsearch_backtrace(res["best_instance"], 1, stream=stream))
+    elif backtrace == "all":
+        out.update(ctx.gsearch_backtrace(None, w.B, stream=stream))
+    return out
+
+
+def to_numpy(out: dict) -> dict:
+    import torch
+    torch.cuda.synchronize()
+    return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
+
+
+def solve_workload(w: Workload, flags=0, backtrace="all") -> dict:
+    """Convenience: upload, run one step, download everything as numpy."""
+    dw = DeviceWorkload(w)
+    with make_context(w, flags=flags) as ctx:
+        out = to_numpy(run_step(ctx, dw, backtrace=backtrace))
+        out["data_status"] = ctx.gsearch_data_status()
+    return out

@@ -1,0 +1,107 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, sizes its workspace, counts strategies, and reports a missing device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2504_21411_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2504_21411_amd import build
+        build.build()
+    return binding.load_library()
+
+
+def _has_gpu():
+    import torch
+    return torch.cuda.is_available()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "gsearch.h")).read()
+    declared = set(re.findall(r"\b(gsearch_[a-z_]+)\s*\(", header))
+    declared -= {"gsearch_ctx"}
+    assert {"gsearch_create", "gsearch_solve_batch", "gsearch_backtrace",
+            "gsearch_destroy"} <= declared
+    from paper_2504_21411_amd import binding
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_and_codes(lib):
+    from paper_2504_21411_amd import binding
+    assert binding.strerror(0) == "ok"
+    seen = {binding.strerror(c) for c in range(-7, 1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert binding.strerror(-99) == "unknown status"
+
+
+def test_workspace_bytes_is_host_arithmetic(lib):
+    from paper_2504_21411_amd import binding as b
+    assert b.gsearch_workspace_bytes(0, 1, 1, 1) == 0
+    assert b.gsearch_workspace_bytes(1, 1, 2000, 1) == 0          # S above the library limit
+    small = b.gsearch_workspace_bytes(1, 24, 12, 256)
+    # two ping-pong planes + 23 uint8 backpointer planes of 12 x 320 elements, plus tables
+    assert small >= 2 * 12 * 320 * 4 + 23 * 12 * 320
+    assert small < 1 << 20
+    keep = b.gsearch_workspace_bytes(1, 24, 12, 256, flags=b.GSEARCH_FLAG_KEEP_PLANES)
+    assert keep > small
+    nobp = b.gsearch_workspace_bytes(8, 128, 96, 16384, flags=b.GSEARCH_FLAG_NO_BACKPOINTERS)
+    withbp = b.gsearch_workspace_bytes(8, 128, 96, 16384)
+    assert 6.0e9 < nobp < 7.0e9 and 1.6e9 < withbp < 1.8e9
+    big16 = b.gsearch_workspace_bytes(1, 40, 257, 1000)
+    big8 = b.gsearch_workspace_bytes(1, 40, 256, 1000)
+    assert big16 > big8 * 1.5                                      # uint16 backpointers
+
+
+def test_enumerate_count_matches_oracle(lib, oracle_mod):
+    from paper_2504_21411_amd import binding as b
+    for k in range(0, 9):
+        for caps in [(0, 0, 0), (8, 4, 16), (4, 1, 0), (0, 2, 0), (0, 32, 0), (2, 2, 2)]:
+            n = b.gsearch_enumerate_count(1 << k, *caps)
+            assert n == len(oracle_mod.enumerate_strategies(1 << k, *caps))
+    with pytest.raises(b.GSearchError):
+        b.gsearch_enumerate_count(12)
+
+
+def test_create_reports_argument_errors_and_missing_device(lib):
+    from paper_2504_21411_amd import binding as b
+    ctx = ctypes.c_void_p()
+    assert lib.gsearch_create(None, ctypes.byref(ctx)) == b.GSEARCH_ERR_INVALID_ARG
+    bad = b.gsearch_config(0, 0, 1, 1, 1, 1, 0)
+    assert lib.gsearch_create(ctypes.byref(bad), ctypes.byref(ctx)) == b.GSEARCH_ERR_INVALID_ARG
+    badflag = b.gsearch_config(0, 1, 1, 1, 1, 1, 0x80)
+    assert lib.gsearch_create(ctypes.byref(badflag), ctypes.byref(ctx)) == b.GSEARCH_ERR_INVALID_ARG
+    ok = b.gsearch_config(0, 1, 2, 2, 4, 1, 0)
+    assert lib.gsearch_create(ctypes.byref(ok), None) == b.GSEARCH_ERR_INVALID_ARG
+    if not _has_gpu():
+        assert lib.gsearch_create(ctypes.byref(ok), ctypes.byref(ctx)) == b.GSEARCH_ERR_NO_DEVICE
+        assert not ctx.value
+        with pytest.raises(b.GSearchError) as ei:
+            b.GSearch(1, 2, 2, 4)
+        assert ei.value.code == b.GSEARCH_ERR_NO_DEVICE
+    assert lib.gsearch_destroy(None) == b.GSEARCH_OK
+    assert lib.gsearch_solve_batch(None, None, None, None) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_backtrace(None, None, 1, None, None, None) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_build_tables(0, 1, 1, 1, 1, None, None, None, None, None, None, None,
+                                    None) == b.GSEARCH_ERR_INVALID_ARG
+
+
+def test_product_package_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2504_21411_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "liboracle" not in text, f

@@ -1,0 +1,324 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit.
+
+Costs, final rows, argmins, plans, memory use and the best instance must be identical;
+with kept planes the whole C and backpointer tables are compared too.  All inputs are
+seeded and synthetic.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from golden_io import read_example
+from paper_2504_21411_amd import workloads
+from paper_2504_21411_amd.workloads import Workload, random_tables
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 1)
+
+
+@pytest.fixture(scope="module")
+def gs():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2504_21411_amd import binding, runner
+    binding.load_library()          # fails loudly if libgsearch.so is missing
+    return binding, runner
+
+
+def bits(a):
+    return np.ascontiguousarray(a, np.float32).view(np.uint32)
+
+
+def assert_same(got, ref, w, what=""):
+    tag = f"{w.name} {what}"
+    assert got["data_status"] == 0, tag
+    assert np.array_equal(bits(got["best_cost"]), bits(ref["best_cost"])), tag
+    assert np.array_equal(got["best_s"], ref["best_s"]), tag
+    assert np.array_equal(bits(got["final_row"]), bits(ref["final_row"])), tag
+    assert int(got["best_instance"][0]) == ref["best_instance"], tag
+    if "plan" in got and got["plan"].shape == ref["plan"].shape:
+        assert np.array_equal(got["plan"], ref["plan"]), tag
+        assert np.array_equal(got["mem_used"], ref["mem_used"]), tag
+
+
+def oracle_batch(oracle_mod, w, T=None, O=None, R=None):
+    return oracle_mod.solve_batch(w.T if T is None else T, w.O if O is None else O,
+                                  w.R if R is None else R, w.r_index, w.budget, threads=THREADS)
+
+
+MODES = {"bp": 0, "generic": 0x2, "nobp": 0x4, "nobp_generic": 0x6}
+
+SHAPES = [
+    # B, L, S,  M,   K   (S spans every register-tile size class, M spans tile tails)
+    (3, 5, 1, 70, 1), (2, 6, 7, 63, 2), (4, 4, 8, 64, 1), (2, 7, 12, 65, 3),
+    (3, 5, 16, 300, 1), (2, 4, 24, 1000, 2), (2, 5, 33, 257, 1), (3, 4, 44, 511, 4),
+    (2, 3, 64, 320, 1), (2, 3, 65, 200, 2), (2, 3, 96, 260, 1), (1, 3, 100, 130, 1),
+    (2, 3, 128, 129, 2), (5, 1, 9, 40, 1), (1, 2, 2, 1, 1),
+]
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "B%dL%dS%dM%dK%d" % s)
+def test_random_tables_match_oracle(gs, oracle_mod, shape, mode):
+    _, runner = gs
+    B, L, S, M, K = shape
+    rng = workloads.SplitMix64(hash(shape) & 0xFFFF)
+    budget = rng.randint(0, M, B).astype(np.int32)
+    budget[0] = M
+    w = random_tables("rand", B, L, S, M, K=K, seed=sum(shape), budget=budget)
+    got = runner.solve_workload(w, flags=MODES[mode])
+    assert_same(got, oracle_batch(oracle_mod, w), w, mode)
+
+
+@pytest.mark.parametrize("mode", ["bp", "generic", "nobp"])
+def test_whole_planes_and_backpointers(gs, oracle_mod, mode):
+    binding, runner = gs
+    w = random_tables("planes", 3, 6, 44, 333, K=2, seed=11,
+                      budget=np.array([333, 100, 257], np.int32))
+    w.O[0, 2, 5] = 0
+    w.O[1, 3, :] = np.minimum(w.O[1, 3, :], 3)
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
+        out = runner.run_step(ctx, dw, backtrace="all")
+        C, bp = ctx.gsearch_export_planes(want_bp=(mode != "nobp"))
+        curve = ctx.gsearch_budget_curve()
+        out = runner.to_numpy(out)
+        C, curve = C.cpu().numpy(), curve.cpu().numpy()
+        bp = bp.cpu().numpy() if bp is not None else None
+    for b in range(w.B):
+        E = int(w.budget[b])
+        ref = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True,
+                               want_curve=True)
+        assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(ref["C"])), (mode, b)
+        if bp is not None:
+            assert np.array_equal(bp[b, :, :E + 1, :], ref["bp"].astype(np.int32)), (mode, b)
+        assert np.array_equal(bits(curve[b, :E + 1]), bits(ref["curve"]))
+        assert np.isinf(curve[b, E + 1:]).all()
+        assert np.array_equal(out["plan"][b], ref["plan"])
+
+
+@pytest.mark.parametrize("mode", ["bp", "generic", "nobp"])
+@pytest.mark.parametrize("name", ["worked_example_a.txt", "worked_example_b.txt"])
+def test_hand_worked_examples_on_gpu(gs, name, mode):
+    _, runner = gs
+    ex = read_example(name)
+    for r in ex["results"]:
+        w = Workload("golden", 1, ex["L"], ex["S"], ex["E_max"], ex["K"],
+                     np.array([r["E"]], np.int32), ex["r_index"][None, :].copy(), "tables",
+                     T=ex["T"][None], O=ex["O"][None], R=ex["R"])
+        got = runner.solve_workload(w, flags=MODES[mode])
+        assert bits(got["best_cost"])[0] == bits(r["best_cost"])
+        assert got["best_s"][0] == r["best_s"] and got["mem_used"][0] == r["mem_used"]
+        assert list(got["plan"][0]) == r["plan"]
+
+
+@pytest.mark.parametrize("mode", ["bp", "generic", "nobp"])
+def test_edge_cases(gs, oracle_mod, mode):
+    _, runner = gs
+    flags = MODES[mode]
+    # ties everywhere: integer tables, many equal candidates
+    w = random_tables("ties", 4, 8, 24, 200, K=2, seed=21, o_hi=6, integer=True)
+    assert_same(runner.solve_workload(w, flags), oracle_batch(oracle_mod, w), w, "ties")
+    # all-equal tables: every argmin must be 0
+    w = random_tables("equal", 2, 5, 12, 70, seed=22)
+    w.T[:] = 1.0; w.O[:] = 1; w.R[:] = 0.0
+    got = runner.solve_workload(w, flags)
+    assert_same(got, oracle_batch(oracle_mod, w), w, "equal")
+    assert (got["plan"] == 0).all()
+    # zero-memory strategies, strategies that never fit, forbidden transitions
+    w = random_tables("mixed", 3, 6, 16, 90, K=2, seed=23, o_hi=20)
+    w.O[:, :, 3] = 0
+    w.O[:, 2, 5] = 91
+    w.O[1, 4, :] = 10 ** 9
+    w.R[0, 3, :] = np.inf
+    w.R[1, :, 7] = np.inf
+    got = runner.solve_workload(w, flags)
+    ref = oracle_batch(oracle_mod, w)
+    assert_same(got, ref, w, "mixed")
+    assert np.isinf(ref["best_cost"][1]) and got["best_s"][1] == -1 and (got["plan"][1] == -1).all()
+    # budget 0, and a batch where nothing fits
+    w = random_tables("zero", 3, 4, 8, 64, seed=24, budget=np.zeros(3, np.int32))
+    got = runner.solve_workload(w, flags)
+    assert_same(got, oracle_batch(oracle_mod, w), w, "zero")
+    assert int(got["best_instance"][0]) == -1 and np.isinf(got["best_cost"]).all()
+    w.O[:] = 0
+    assert_same(runner.solve_workload(w, flags), oracle_batch(oracle_mod, w), w, "zero-fit")
+
+
+def test_uint16_backpointers_above_256_strategies(gs, oracle_mod):
+    _, runner = gs
+    w = random_tables("wide", 2, 3, 300, 90, seed=31, budget=np.array([90, 41], np.int32))
+    # make high indices win so that values above 255 must survive the store
+    w.T[:, :, :280] += np.float32(50.0)
+    got = runner.solve_workload(w, 0)
+    ref = oracle_batch(oracle_mod, w)
+    assert_same(got, ref, w, "uint16")
+    assert ref["plan"].max() > 255
+    assert_same(runner.solve_workload(w, 0x4), ref, w, "uint16 nobp")
+
+
+def test_backtrace_instance_lists_and_capacity_errors(gs, oracle_mod):
+    import torch
+    binding, runner = gs
+    w = random_tables("list", 6, 5, 12, 100, seed=41,
+                      budget=np.array([100, 3, 50, 77, 100, 20], np.int32))
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w) as ctx:
+        with pytest.raises(binding.GSearchError) as ei:
+            ctx.gsearch_backtrace(None, 1)
+        assert ei.value.code == binding.GSEARCH_ERR_NOT_SOLVED
+        runner.run_step(ctx, dw, backtrace=None)
+        ids = torch.tensor([4, -1, 0, 99, 2, 1], dtype=torch.int32, device="cuda")
+        out = runner.to_numpy(ctx.gsearch_backtrace(ids))
+        for q, b in enumerate([4, -1, 0, 99, 2, 1]):
+            if 0 <= b < 6:
+                assert np.array_equal(out["plan"][q], ref["plan"][b])
+                assert out["mem_used"][q] == ref["mem_used"][b]
+            else:
+                assert (out["plan"][q] == -1).all() and out["mem_used"][q] == -1
+        big = random_tables("big", 7, 5, 12, 100, seed=42)
+        with pytest.raises(binding.GSearchError) as ei:
+            runner.run_step(ctx, runner.DeviceWorkload(big))
+        assert ei.value.code == binding.GSEARCH_ERR_CAPACITY
+        with pytest.raises(binding.GSearchError) as ei:
+            ctx.gsearch_export_planes()
+        assert ei.value.code == binding.GSEARCH_ERR_UNSUPPORTED
+    # a context may be reused for smaller problems; results do not depend on what ran before
+    small = random_tables("small", 2, 3, 7, 40, seed=43)
+    with runner.make_context(w) as ctx:
+        runner.run_step(ctx, dw, backtrace="all")
+        got = runner.to_numpy(runner.run_step(ctx, runner.DeviceWorkload(small), backtrace="all"))
+        got["data_status"] = ctx.gsearch_data_status()
+    assert_same(got, oracle_batch(oracle_mod, small), small, "reuse")
+
+
+def test_bad_table_contents_are_flagged_not_fatal(gs):
+    binding, runner = gs
+    base = random_tables("bad", 2, 4, 12, 80, K=2, seed=51)
+
+    def status_of(mut):
+        w = random_tables("bad", 2, 4, 12, 80, K=2, seed=51)
+        mut(w)
+        out = runner.solve_workload(w)
+        assert np.isinf(out["best_cost"]).all() and (out["best_s"] == -1).all()
+        assert int(out["best_instance"][0]) == -1 and (out["plan"] == -1).all()
+        return out["data_status"]
+
+    def set_(arr, idx, v):
+        arr[idx] = v
+    assert runner.solve_workload(base)["data_status"] == 0
+    assert status_of(lambda w: set_(w.T, (0, 1, 2), np.nan)) == binding.GSEARCH_DATA_BAD_T
+    assert status_of(lambda w: set_(w.T, (1, 0, 0), -1.0)) == binding.GSEARCH_DATA_BAD_T
+    assert status_of(lambda w: set_(w.T, (1, 0, 0), -0.0)) == binding.GSEARCH_DATA_BAD_T
+    assert status_of(lambda w: set_(w.T, (1, 3, 11), np.inf)) == binding.GSEARCH_DATA_BAD_T
+    assert status_of(lambda w: set_(w.R, (1, 2, 3), np.nan)) == binding.GSEARCH_DATA_BAD_R
+    assert status_of(lambda w: set_(w.R, (0, 0, 0), -2.0)) == binding.GSEARCH_DATA_BAD_R
+    assert status_of(lambda w: set_(w.O, (0, 2, 2), -5)) == binding.GSEARCH_DATA_BAD_O
+    assert status_of(lambda w: set_(w.budget, 1, 81)) == binding.GSEARCH_DATA_BAD_BUDGET
+    assert status_of(lambda w: set_(w.budget, 0, -1)) == binding.GSEARCH_DATA_BAD_BUDGET
+    assert status_of(lambda w: set_(w.r_index, (1, 2), 2)) == binding.GSEARCH_DATA_BAD_RINDEX
+    ignored = random_tables("bad", 2, 4, 12, 80, K=2, seed=51)
+    ignored.r_index[0, 0] = 7                                     # entry l=0 is never read
+    out = runner.solve_workload(ignored)
+    assert out["data_status"] == 0
+    assert np.array_equal(out["best_cost"], runner.solve_workload(base)["best_cost"])
+    both = status_of(lambda w: (set_(w.T, (0, 0, 0), np.nan), set_(w.O, (0, 0, 0), -1)))
+    assert both == binding.GSEARCH_DATA_BAD_T | binding.GSEARCH_DATA_BAD_O
+
+
+def test_enumerator_and_table_builder_match_oracle(gs, oracle_mod):
+    import torch
+    binding, _ = gs
+    for N, caps in [(1, (0, 0, 0)), (8, (4, 1, 0)), (8, (0, 2, 0)), (32, (8, 4, 16)),
+                    (64, (0, 32, 0)), (256, (0, 0, 0)), (1 << 12, (64, 8, 0))]:
+        desc, count = binding.gsearch_enumerate(N, *caps)
+        ref = oracle_mod.enumerate_strategies(N, *caps)
+        assert int(count.cpu()[0]) == len(ref)
+        assert np.array_equal(desc.cpu().numpy(), ref)
+    for cfg in (workloads.config1(), workloads.config3()):
+        desc, _ = binding.gsearch_enumerate(**cfg.enum)
+        dl = torch.from_numpy(cfg.layer).cuda()
+        dr = torch.from_numpy(cfg.rmodel).cuda()
+        T, O, R = binding.gsearch_build_tables(desc, dl, cfg.hw, dr, cfg.M)
+        Tr, Or, Rr = oracle_mod.build_tables(desc.cpu().numpy(), cfg.layer, cfg.hw, cfg.rmodel, cfg.M)
+        assert np.array_equal(bits(T.cpu().numpy()), bits(Tr))
+        assert np.array_equal(O.cpu().numpy(), Or)
+        assert np.array_equal(bits(R.cpu().numpy()), bits(Rr))
+    # scales, clamping to M+1 and the one-bin floor
+    rng = workloads.SplitMix64(61)
+    layer = np.zeros((3, 4, 6))
+    layer[..., 0] = 1000.0 + 9000.0 * rng.uniform(12).reshape(3, 4)
+    layer[..., 1] = 2048.0
+    layer[..., 2] = 65536.0
+    layer[..., 3:] = 0.25 + rng.uniform(36).reshape(3, 4, 3)
+    rm = np.array([[4096.0, 65536.0], [7000.0, 1.0e6]])
+    desc, _ = binding.gsearch_enumerate(16)
+    for binb in (1.0e3, 1.0e7, 1.0e12):
+        hw = np.array([3.0e14, 4.0e11, binb, 0.3])
+        T, O, R = binding.gsearch_build_tables(desc, torch.from_numpy(layer).cuda(), hw,
+                                               torch.from_numpy(rm).cuda(), 500)
+        Tr, Or, Rr = oracle_mod.build_tables(desc.cpu().numpy(), layer, hw, rm, 500)
+        assert np.array_equal(bits(T.cpu().numpy()), bits(Tr))
+        assert np.array_equal(O.cpu().numpy(), Or)
+        assert np.array_equal(bits(R.cpu().numpy()), bits(Rr))
+
+
+def test_repeated_solves_are_bit_identical(gs):
+    _, runner = gs
+    w = random_tables("repeat", 8, 12, 44, 700, K=2, seed=71)
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w) as ctx:
+        runs = [runner.to_numpy(runner.run_step(ctx, dw, backtrace="all")) for _ in range(3)]
+    for r in runs[1:]:
+        for k in ("best_cost", "best_s", "final_row", "plan", "mem_used", "best_instance"):
+            assert np.array_equal(runs[0][k], r[k], equal_nan=True), k
+
+
+# ------------------------------------------------------------------ the five configurations
+def _run_config(gs, oracle_mod, i, flags, backtrace="all"):
+    """Full-size configuration in the launch configuration bench.py times."""
+    _, runner = gs
+    w = workloads.get_config(i)
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w, flags=flags) as ctx:
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace=backtrace))
+        got["data_status"] = ctx.gsearch_data_status()
+    if w.kind == "model":
+        desc = oracle_mod.enumerate_strategies(**w.enum)
+        T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
+        assert np.array_equal(got["desc"], desc)
+        assert np.array_equal(bits(got["T"]), bits(T)) and np.array_equal(got["O"], O)
+        assert np.array_equal(bits(got["R"]), bits(R))
+        ref = oracle_batch(oracle_mod, w, T, O, R)
+    else:
+        ref = oracle_batch(oracle_mod, w)
+    assert_same(got, ref, w, f"flags={flags}")
+    assert np.isfinite(ref["best_cost"]).any()
+    return got, ref
+
+
+@pytest.mark.parametrize("mode", ["bp", "nobp"])
+@pytest.mark.parametrize("i", [0, 1, 2, 4])
+def test_config_full_size(gs, oracle_mod, i, mode):
+    _run_config(gs, oracle_mod, i, MODES[mode])
+
+
+@pytest.mark.timeout(600)
+def test_config3_large_dense_full_size(gs, oracle_mod):
+    """L=128, S=96, M=16384, B=8: the oracle needs about half a minute per instance."""
+    _, runner = gs
+    w = workloads.get_config(3)
+    desc = oracle_mod.enumerate_strategies(**w.enum)
+    T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
+    ref = oracle_batch(oracle_mod, w, T, O, R)
+    dw = runner.DeviceWorkload(w)
+    for flags in (0, 0x4):
+        with runner.make_context(w, flags=flags) as ctx:
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+            got["data_status"] = ctx.gsearch_data_status()
+        assert np.array_equal(bits(got["T"]), bits(T)) and np.array_equal(got["O"], O)
+        assert_same(got, ref, w, f"flags={flags}")
+    assert np.isfinite(ref["best_cost"]).all()
