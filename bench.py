@@ -1,0 +1,147 @@
+"""Benchmark of the batched strategy-search DP on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--mode bp|nobp]
+
+A step is one pass of the whole hot path over one batch whose inputs are already resident
+in HBM: strategy enumeration, cost-table builder (model workloads), batched forward DP,
+final reductions and the backtrace of the best instance.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Vector-ALU peak for the instructions this path uses (plain fp32 add / compare / select,
+# one result per lane per issue, no packed or fused forms):
+# 256 CUs x 4 SIMDs x 16 lanes per clock x 2.4 GHz.  The published 157.3 TFLOP/s is the
+# same machine counting a packed (x2) fused multiply-add (x2) on every lane.
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Algorithmic vector operations per relaxation: add + compare + two selects with the
+# argmin; add + half of a three-input minimum without it.
+OPS_PER_RELAX = {"bp": 4.0, "nobp": 1.5}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
+# copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(w, cfg_index, target_relax=9.0e9):
+    """The oracle as it stands, single-threaded, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    if w.kind == "model":
+        desc = oracle.enumerate_strategies(**w.enum)
+        T, O, R = oracle.build_tables(desc, w.layer[:1], w.hw, w.rmodel, w.M)
+    else:
+        T, O, R = w.T[:1], w.O[:1], w.R
+    E = int(w.budget[0])
+    per_layer = (E + 1) * w.S * w.S
+    Ls = int(max(2, min(w.L, 1 + target_relax // per_layer)))
+    t0 = time.perf_counter()
+    oracle.solve(T[0][:Ls], O[0][:Ls], R, w.r_index[0][:Ls], E)
+    dt = time.perf_counter() - t0
+    relax = (Ls - 1) * per_layer
+    return {"value": relax / dt / 1e9, "unit": "Grelax/s", "cores": 1, "kind": "oracle",
+            "sample": f"instance 0 of cfg{cfg_index}, first {Ls} of {w.L} layers, "
+                      f"{relax / 1e9:.2f} G relaxations in {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--mode", choices=["bp", "nobp"], default="bp")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", default="", help="comma list of extra modes to time, e.g. nobp")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (the batch would shard over "
+                 "GPUs by instance; no multi-GPU path exists). Use --gpus 1.")
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    from paper_2504_21411_amd import binding, runner, workloads
+    binding.load_library()
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_per_launch": int(src.numel() * 4),
+                          "launches": 5}))
+        return
+
+    w = workloads.get_config(args.config)
+    dw = runner.DeviceWorkload(w)
+    relax = w.relaxations()
+
+    def time_mode(mode):
+        flags = binding.GSEARCH_FLAG_NO_BACKPOINTERS if mode == "nobp" else 0
+        with runner.make_context(w, flags=flags) as ctx:
+            ctx.gsearch_set_profiling(True)
+            for _ in range(args.warmup):
+                runner.run_step(ctx, dw, backtrace="best")
+            torch.cuda.synchronize()
+            fwd = []
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                out = runner.run_step(ctx, dw, backtrace="best")
+                fwd.append(ctx.gsearch_forward_ms())      # waits for this step's forward pass
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            assert ctx.gsearch_data_status() == 0
+            best = int(out["best_instance"].cpu()[0])
+        ms_step = dt * 1e3 / args.steps
+        fwd_ms = sum(fwd) / len(fwd)
+        launches = w.L - 1
+        ops = OPS_PER_RELAX[mode] * relax / launches           # per launch
+        achieved = ops / (fwd_ms * 1e-3 / launches) / 1e12
+        return {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
+                "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
+                "forward_grelax_per_s": relax / (fwd_ms * 1e-3) / 1e9,
+                "kernel_avg_us": fwd_ms * 1e3 / launches,
+                "roofline": {"bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TLANEOPS,
+                             "unit": "Tlaneop/s", "frac": achieved / ALU_PEAK_TLANEOPS,
+                             "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode)),
+                             "kernel": "k_dp_push", "ops_per_relaxation": OPS_PER_RELAX[mode]},
+                "best_instance": best}
+
+    main_res = time_mode(args.mode)
+    extra = [time_mode(m) for m in args.also.split(",") if m and m != args.mode]
+
+    line = {
+        "metric": "G DP relaxations/sec (min-plus updates) + batch search latency, 1 MI355X",
+        "value": main_res["grelax_per_s"], "unit": "Grelax/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {w.name}: B={w.B} L={w.L} S={w.S} "
+                               f"M={w.M}", "mode": args.mode,
+                   "relaxations_per_step": relax},
+        "search_latency_ms": main_res["ms_per_step"],
+        "forward_ms": main_res["forward_ms"],
+        "forward_grelax_per_s": main_res["forward_grelax_per_s"],
+        "kernel_avg_us": main_res["kernel_avg_us"],
+        "roofline": main_res["roofline"],
+    }
+    if extra:
+        line["other_modes"] = extra
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, args.config)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

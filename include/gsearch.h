@@ -144,6 +144,15 @@ int gsearch_backtrace(gsearch_ctx *ctx, const int32_t *instances, int32_t n, int
  * *host_bits (0 = tables were valid; else GSEARCH_DATA_* bits).  Errors: NOT_SOLVED, HIP. */
 int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits);
 
+/* Measurement aid.  With profiling enabled, every later solve records one HIP event on
+ * its stream just before the first forward-DP launch (layer 1) and one just after the
+ * last (layer L-1).  gsearch_forward_ms waits for the second event of the most recent
+ * solve and returns the elapsed milliseconds between the two in *host_ms, i.e. the time
+ * of the L-1 layer-front launches including the gaps between them.
+ * Errors: NOT_SOLVED (no profiled solve yet, or L == 1), HIP. */
+int gsearch_set_profiling(gsearch_ctx *ctx, int enable);
+int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
+
 /* Best cost for EVERY budget of the most recent solve (the last plane already holds
  * it): curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf for E_b < e <= M.
  * curve is device [B][M+1].  Paper section 1, feature 2 (adapting to hardware

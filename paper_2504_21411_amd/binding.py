@@ -36,6 +36,7 @@ EXPORTS = [
     "gsearch_workspace_bytes", "gsearch_create", "gsearch_destroy", "gsearch_solve_batch",
     "gsearch_backtrace", "gsearch_data_status", "gsearch_budget_curve", "gsearch_export_planes",
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
+    "gsearch_set_profiling", "gsearch_forward_ms",
 ]
 
 
@@ -95,6 +96,10 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_backtrace.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.gsearch_data_status.restype = ctypes.c_int
     lib.gsearch_data_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.gsearch_set_profiling.restype = ctypes.c_int
+    lib.gsearch_set_profiling.argtypes = [vp, ctypes.c_int]
+    lib.gsearch_forward_ms.restype = ctypes.c_int
+    lib.gsearch_forward_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.gsearch_budget_curve.restype = ctypes.c_int
     lib.gsearch_budget_curve.argtypes = [vp, vp, vp]
     lib.gsearch_export_planes.restype = ctypes.c_int
@@ -264,6 +269,15 @@ class GSearch:
         _check(self._lib.gsearch_data_status(self._ctx, _stream(stream), ctypes.byref(bits)),
                "gsearch_data_status")
         return int(bits.value)
+
+    def gsearch_set_profiling(self, enable: bool):
+        _check(self._lib.gsearch_set_profiling(self._ctx, int(bool(enable))),
+               "gsearch_set_profiling")
+
+    def gsearch_forward_ms(self) -> float:
+        ms = ctypes.c_float(0.0)
+        _check(self._lib.gsearch_forward_ms(self._ctx, ctypes.byref(ms)), "gsearch_forward_ms")
+        return float(ms.value)
 
     def gsearch_budget_curve(self, stream=None):
         import torch

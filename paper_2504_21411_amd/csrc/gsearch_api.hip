@@ -86,6 +86,9 @@ struct gsearch_ctx {
   gs::Shape shape{};
   gs::Workspace ws{};
   int last_plane = 0; // index of the plane that holds layer L-1
+  bool profiling = false;
+  bool timed = false; // the most recent solve recorded both events
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr;
 };
 
 extern "C" {
@@ -142,6 +145,8 @@ int gsearch_destroy(gsearch_ctx *ctx) {
   int rc = GSEARCH_OK;
   {
     DeviceScope scope(ctx->cfg.device);
+    if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
+    if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
     if (ctx->base && hipFree(ctx->base) != hipSuccess) rc = GSEARCH_ERR_HIP;
   }
   delete ctx;
@@ -190,12 +195,19 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w, st);
   gs::launch_init_layer0(s, w, w.planes, st);
   int cur = 0;
+  ctx->timed = false;
+  const bool timing = ctx->profiling && s.L > 1;
+  if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
   for (int l = 1; l < s.L; ++l) {
     const int nxt = keep ? l : (cur ^ 1);
     void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes : nullptr;
     gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe, w.planes + (size_t)nxt * pe, bp_l,
                         generic, st);
     cur = nxt;
+  }
+  if (timing) {
+    if (hipEventRecord(ctx->ev_end, st) != hipSuccess) return GSEARCH_ERR_HIP;
+    ctx->timed = true;
   }
   ctx->last_plane = cur;
   gs::launch_final(s, w, w.planes + (size_t)cur * pe, r->best_cost, r->best_s, r->final_row,
@@ -228,6 +240,34 @@ int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (hipStreamSynchronize(st) != hipSuccess) return GSEARCH_ERR_HIP;
   if (hipMemcpy(host_bits, ctx->ws.status, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+    return GSEARCH_ERR_HIP;
+  return GSEARCH_OK;
+}
+
+int gsearch_set_profiling(gsearch_ctx *ctx, int enable) {
+  if (!ctx) return GSEARCH_ERR_INVALID_ARG;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  if (enable && !ctx->ev_begin) {
+    if (hipEventCreate(&ctx->ev_begin) != hipSuccess) return GSEARCH_ERR_HIP;
+    if (hipEventCreate(&ctx->ev_end) != hipSuccess) {
+      (void)hipEventDestroy(ctx->ev_begin);
+      ctx->ev_begin = nullptr;
+      return GSEARCH_ERR_HIP;
+    }
+  }
+  ctx->profiling = enable != 0;
+  if (!enable) ctx->timed = false;
+  return GSEARCH_OK;
+}
+
+int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms) {
+  if (!ctx || !host_ms) return GSEARCH_ERR_INVALID_ARG;
+  if (!ctx->solved || !ctx->timed) return GSEARCH_ERR_NOT_SOLVED;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  if (hipEventSynchronize(ctx->ev_end) != hipSuccess) return GSEARCH_ERR_HIP;
+  if (hipEventElapsedTime(host_ms, ctx->ev_begin, ctx->ev_end) != hipSuccess)
     return GSEARCH_ERR_HIP;
   return GSEARCH_OK;
 }
