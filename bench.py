@@ -28,7 +28,7 @@ ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 OPS_PER_RELAX = {"bp": 4.0, "nobp": 1.5}
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {(3, "bp"): 113.9e6, (3, "nobp"): 101.3e6}
 
 
 def cpu_baseline(w, cfg_index, target_relax=9.0e9):
