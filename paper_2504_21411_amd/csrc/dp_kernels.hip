@@ -17,6 +17,8 @@
 // Rows e < O[l][sj] of the target cannot hold layer l under sj: they are set to +inf
 // (bp 0) by the wave that owns those rows, so that every row 0..E of the target plane is
 // written exactly once per launch and nothing stale survives from an earlier solve.
+#include <stdlib.h>
+
 #include "gsearch_internal.h"
 
 namespace gs {
@@ -137,13 +139,24 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
     const int32_t *__restrict__ budget, const int32_t *__restrict__ minO, int B, int L, int S,
-    int l, int pitch) {
+    int l, int pitch, int jsplit) {
+  // blockIdx.x = (row_block * jsplit + js) * B + b: consecutive workgroups belong to
+  // different instances, so the hardware's round-robin over the eight XCDs spreads every
+  // instance's tables over the same XCD's L2 only when B is a multiple of 8, and spreads
+  // the load evenly in every case.
   const int b = blockIdx.x % B;
+  const int rest = blockIdx.x / B;
+  const int js = rest % jsplit;
   const int wave = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int tile_start = ((blockIdx.x / B) * (kRowsPerBlock / kWave) + wave) * kWave;
+  const int tile_start = ((rest / jsplit) * (int)(blockDim.x >> 6) + wave) * kWave;
   const int E = budget[b];
   if (tile_start > E) return;
+  // this workgroup's slice of target strategies
+  const int jper = (S + jsplit - 1) / jsplit;
+  const int jbeg = js * jper;
+  const int jend = jbeg + jper < S ? jbeg + jper : S;
+  if (jbeg >= jend) return;
 
   const int row = tile_start + lane;
   const bool valid = row <= E;
@@ -169,8 +182,8 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
   }
 
   float8_t rcur;
-  if (WITH_BP && compute) rcur = load_col_head(rk);
-  for (int j = 0; j < S; ++j) {
+  if (WITH_BP && compute) rcur = load_col_head(rk + (size_t)jbeg * SP);
+  for (int j = jbeg; j < jend; ++j) {
     const int o = orow[j];
     const float t = trow[j];
     if (compute) {
@@ -250,17 +263,48 @@ int tuned_sp_for(int S) {
   return 0;
 }
 
+// Launch shape of the register-tiled kernel.  Work is cut into (64-row tile) x (slice of
+// target strategies) pieces, one per wave; slicing the strategies costs a repeated load
+// of the tile's source values but multiplies the number of waves, which is what hides
+// the scalar-load latency when a batch has few tiles (8 instances x 257 tiles fill the
+// 1024 SIMDs only twice).  GSEARCH_JSPLIT / GSEARCH_WAVES_PER_BLOCK override the
+// heuristic (debugging and tuning aid).
+struct PushTuning {
+  int jsplit = 0, waves_per_block = 0;
+  PushTuning() {
+    if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
+    if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
+  }
+};
+
+static void push_launch_shape(const Shape &s, int &jsplit, int &wpb) {
+  static const PushTuning tune;
+  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
+  wpb = tune.waves_per_block >= 1 && tune.waves_per_block <= 4 ? tune.waves_per_block : 4;
+  jsplit = tune.jsplit;
+  if (jsplit < 1) {
+    jsplit = 1;
+    while (tiles * jsplit < 4096 && jsplit < 8 && s.S / (jsplit * 2) >= 8) jsplit *= 2;
+  }
+  if (jsplit > s.S) jsplit = s.S;
+}
+
 template <int SP>
 static void launch_push(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
-                        void *bp_l, dim3 grid, hipStream_t st) {
+                        void *bp_l, hipStream_t st) {
+  int jsplit, wpb;
+  push_launch_shape(s, jsplit, wpb);
+  const int rows = wpb * kWave;
+  const long long row_blocks = (s.M + 1 + rows - 1) / rows;
+  const dim3 grid((unsigned)(row_blocks * jsplit * s.B)), block(rows);
   if (bp_l)
-    hipLaunchKernelGGL((k_dp_push<SP, true>), grid, dim3(kRowsPerBlock), 0, st, src, dst,
-                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L,
-                       s.S, l, s.pitch);
+    hipLaunchKernelGGL((k_dp_push<SP, true>), grid, block, 0, st, src, dst, (uint8_t *)bp_l,
+                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L, s.S, l, s.pitch,
+                       jsplit);
   else
-    hipLaunchKernelGGL((k_dp_push<SP, false>), grid, dim3(kRowsPerBlock), 0, st, src, dst,
+    hipLaunchKernelGGL((k_dp_push<SP, false>), grid, block, 0, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
-                       s.L, s.S, l, s.pitch);
+                       s.L, s.S, l, s.pitch, jsplit);
 }
 
 void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
@@ -270,14 +314,14 @@ void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src
   const int tsp = tuned_sp_for(s.S);
   if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16) {
     switch (tsp) {
-      case 8: launch_push<8>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 16: launch_push<16>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 24: launch_push<24>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 32: launch_push<32>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 48: launch_push<48>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 64: launch_push<64>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 96: launch_push<96>(s, w, l, src, dst, bp_l, grid, st); return;
-      case 128: launch_push<128>(s, w, l, src, dst, bp_l, grid, st); return;
+      case 8: launch_push<8>(s, w, l, src, dst, bp_l, st); return;
+      case 16: launch_push<16>(s, w, l, src, dst, bp_l, st); return;
+      case 24: launch_push<24>(s, w, l, src, dst, bp_l, st); return;
+      case 32: launch_push<32>(s, w, l, src, dst, bp_l, st); return;
+      case 48: launch_push<48>(s, w, l, src, dst, bp_l, st); return;
+      case 64: launch_push<64>(s, w, l, src, dst, bp_l, st); return;
+      case 96: launch_push<96>(s, w, l, src, dst, bp_l, st); return;
+      case 128: launch_push<128>(s, w, l, src, dst, bp_l, st); return;
       default: break;
     }
   }
