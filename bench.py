@@ -23,9 +23,20 @@ if ROOT not in sys.path:
 # 256 CUs x 4 SIMDs x 16 lanes per clock x 2.4 GHz.  The published 157.3 TFLOP/s is the
 # same machine counting a packed (x2) fused multiply-add (x2) on every lane.
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# Algorithmic vector operations per relaxation: add + compare + two selects with the
-# argmin; add + half of a three-input minimum without it.
-OPS_PER_RELAX = {"bp": 4.0, "nobp": 1.5}
+def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
+    """Vector-ALU instructions per relaxation that the kernel's algorithm needs.
+
+    min only: one add and half of a three-input minimum.  Flat argmin (push and generic
+    kernels): add, compare, two selects.  Two-level argmin (tile kernel): per chunk of
+    eight candidates eight adds, four minimum instructions, one compare and two selects
+    (15/8), plus the second look at one chunk per target state (8 adds, 8 compares,
+    8 selects = 24 per S relaxations).
+    """
+    if mode == "nobp":
+        return 1.5
+    if kernel == "k_dp_tile":
+        return 15.0 / 8.0 + 24.0 / S
+    return 4.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
 MEASURED_TRAFFIC_BYTES = {(3, "bp"): 113.9e6, (3, "nobp"): 101.3e6}
@@ -103,10 +114,12 @@ def main():
             dt = time.perf_counter() - t0
             assert ctx.gsearch_data_status() == 0
             best = int(out["best_instance"].cpu()[0])
+            kernel = ctx.gsearch_forward_kernel()
         ms_step = dt * 1e3 / args.steps
         fwd_ms = sum(fwd) / len(fwd)
         launches = w.L - 1
-        ops = OPS_PER_RELAX[mode] * relax / launches           # per launch
+        opr = ops_per_relaxation(kernel, mode, w.S)
+        ops = opr * relax / launches                            # per launch
         achieved = ops / (fwd_ms * 1e-3 / launches) / 1e12
         return {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
                 "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
@@ -115,7 +128,7 @@ def main():
                 "roofline": {"bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TLANEOPS,
                              "unit": "Tlaneop/s", "frac": achieved / ALU_PEAK_TLANEOPS,
                              "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode)),
-                             "kernel": "k_dp_push", "ops_per_relaxation": OPS_PER_RELAX[mode]},
+                             "kernel": kernel, "ops_per_relaxation": opr},
                 "best_instance": best}
 
     main_res = time_mode(args.mode)

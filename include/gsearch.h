@@ -69,6 +69,11 @@ typedef enum {
                                             re-derives each argmin from the planes (same
                                             plans, bit for bit)                             */
 
+#define GSEARCH_FLAG_FORCE_PUSH 0x8u      /* testing/tuning: always the register-tiled push
+                                            kernel (flat four-instruction argmin)          */
+#define GSEARCH_FLAG_FORCE_TILE 0x10u     /* testing/tuning: always the LDS-staged kernel
+                                            with the two-level argmin                      */
+
 /* bits of the data-status word */
 #define GSEARCH_DATA_BAD_T 0x1
 #define GSEARCH_DATA_BAD_R 0x2
@@ -152,6 +157,9 @@ int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits);
  * Errors: NOT_SOLVED (no profiled solve yet, or L == 1), HIP. */
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable);
 int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
+/* Name of the forward kernel the most recent solve launched for its layer fronts
+ * ("k_dp_push", "k_dp_tile" or "k_dp_generic"; "" before any solve).  Static string. */
+const char *gsearch_forward_kernel(gsearch_ctx *ctx);
 
 /* Best cost for EVERY budget of the most recent solve (the last plane already holds
  * it): curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf for E_b < e <= M.

@@ -25,6 +25,8 @@ GSEARCH_ERR_UNSUPPORTED = -7
 GSEARCH_FLAG_KEEP_PLANES = 0x1
 GSEARCH_FLAG_FORCE_GENERIC = 0x2
 GSEARCH_FLAG_NO_BACKPOINTERS = 0x4
+GSEARCH_FLAG_FORCE_PUSH = 0x8
+GSEARCH_FLAG_FORCE_TILE = 0x10
 
 GSEARCH_DATA_BAD_T = 0x1
 GSEARCH_DATA_BAD_R = 0x2
@@ -36,7 +38,7 @@ EXPORTS = [
     "gsearch_workspace_bytes", "gsearch_create", "gsearch_destroy", "gsearch_solve_batch",
     "gsearch_backtrace", "gsearch_data_status", "gsearch_budget_curve", "gsearch_export_planes",
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
-    "gsearch_set_profiling", "gsearch_forward_ms",
+    "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
 ]
 
 
@@ -100,6 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_set_profiling.argtypes = [vp, ctypes.c_int]
     lib.gsearch_forward_ms.restype = ctypes.c_int
     lib.gsearch_forward_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+    lib.gsearch_forward_kernel.restype = ctypes.c_char_p
+    lib.gsearch_forward_kernel.argtypes = [vp]
     lib.gsearch_budget_curve.restype = ctypes.c_int
     lib.gsearch_budget_curve.argtypes = [vp, vp, vp]
     lib.gsearch_export_planes.restype = ctypes.c_int
@@ -278,6 +282,9 @@ class GSearch:
         ms = ctypes.c_float(0.0)
         _check(self._lib.gsearch_forward_ms(self._ctx, ctypes.byref(ms)), "gsearch_forward_ms")
         return float(ms.value)
+
+    def gsearch_forward_kernel(self) -> str:
+        return self._lib.gsearch_forward_kernel(self._ctx).decode()
 
     def gsearch_budget_curve(self, stream=None):
         import torch

@@ -219,6 +219,129 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// LDS-staged tile kernel with a two-level argmin.
+//
+// One workgroup owns one 64-row tile of source rows; its waves split the target
+// strategies among themselves.  The tile C[l-1][rows][0..S) is fetched from HBM once,
+// cooperatively, into LDS ([si][64 rows], so that lane r always hits bank r mod 32), and
+// every wave then copies it into registers.
+//
+// Argmin in two levels, which cuts the vector work per relaxation from four instructions
+// to a little over two while producing the same index as the strict-"<" scan:
+//   level 1  the si candidates are taken in chunks of eight; a chunk costs eight adds and
+//            four (three-input) minimum instructions and yields the chunk minimum cm;
+//            "cm < m" (strict) updates the running minimum m and the chunk number g, so
+//            that g ends as the FIRST chunk that attains the overall minimum;
+//   level 2  only chunk g is looked at again: its eight sums are rebuilt from the LDS tile
+//            and the transition column (same operands, same fp32 add, hence the same
+//            bits) and the lowest k with sum == m is the argmin 8g + k.
+// If every candidate is +inf, m stays +inf, g stays 0 and level 2 returns index 0, which
+// is what the scan gives.
+// ---------------------------------------------------------------------------------------
+template <int SP, int NW, bool WITH_BP>
+__global__ __launch_bounds__(NW *kWave) void k_dp_tile(
+    const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO, int B, int L, int S,
+    int l, int pitch) {
+  extern __shared__ float tile[]; // [SP][64]
+  const int b = blockIdx.x % B;
+  const int tile_start = (int)(blockIdx.x / B) * kWave;
+  const int js = wave_uniform(threadIdx.x >> 6);
+  constexpr int nw = NW; // waves per workgroup = slices of the target strategies
+  const int lane = threadIdx.x & 63;
+  const int E = budget[b];
+  if (tile_start > E) return; // whole workgroup
+
+  const int row = tile_start + lane;
+  const bool valid = row <= E;
+  const int bl = b * L + l;
+  const bool compute = tile_start <= E - minO[bl]; // uniform over the workgroup
+  const size_t plane_off = (size_t)b * S * pitch;
+  const float *__restrict__ srcb = src + plane_off;
+  float *__restrict__ dstb = dst + plane_off;
+  uint8_t *__restrict__ bpb = WITH_BP ? bp + plane_off : nullptr;
+  const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
+  const float *__restrict__ trow = Tq + (size_t)bl * SP;
+  const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
+
+  float c[SP];
+  if (compute) {
+    // every wave fetches SP/NW strategy rows of the tile: all loads first, then the LDS
+    // writes, so that the loads are in flight together
+    float stage[SP / NW];
+#pragma unroll
+    for (int u = 0; u < SP / NW; ++u) {
+      const int i = u * NW + js;
+      stage[u] = (i < S && valid) ? srcb[(size_t)i * pitch + row] : GS_INF;
+    }
+#pragma unroll
+    for (int u = 0; u < SP / NW; ++u) tile[(u * NW + js) * kWave + lane] = stage[u];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < SP; ++i) c[i] = tile[i * kWave + lane];
+  } else {
+#pragma unroll
+    for (int i = 0; i < SP; ++i) c[i] = GS_INF;
+  }
+
+  const int jper = (S + nw - 1) / nw;
+  const int jbeg = js * jper;
+  const int jend = jbeg + jper < S ? jbeg + jper : S;
+  for (int j = jbeg; j < jend; ++j) {
+    const int o = orow[j];
+    const float t = trow[j];
+    if (compute) {
+      const float *__restrict__ rc = rk + (size_t)j * SP;
+      float m = GS_INF;
+      int g = 0;
+#pragma unroll
+      for (int q = 0; q < SP / 8; ++q) {
+        const float8_t r = *reinterpret_cast<const float8_t *>(rc + 8 * q);
+        float cm = __builtin_fminf(c[8 * q] + r[0], c[8 * q + 1] + r[1]);
+#pragma unroll
+        for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[8 * q + k] + r[k]);
+        if (WITH_BP) {
+          const bool lt = cm < m;
+          m = lt ? cm : m;
+          g = lt ? q : g;
+        } else {
+          m = __builtin_fminf(m, cm);
+        }
+      }
+      int arg = 0;
+      if (WITH_BP) {
+        const float *__restrict__ rg = rc + 8 * g;      // per-lane slice of the column
+        const float *tg = tile + (8 * g) * kWave + lane; // per-lane slice of the tile
+        const float4 ra = *reinterpret_cast<const float4 *>(rg);
+        const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
+        const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+        arg = 8 * g;
+#pragma unroll
+        for (int k = 7; k >= 1; --k) {
+          const float v = tg[k * kWave] + rr[k];
+          arg = (v == m) ? 8 * g + k : arg;
+        }
+        const float v0 = tg[0] + rr[0];
+        arg = (v0 == m) ? 8 * g : arg;
+      }
+      const int eo = row + o;
+      if (valid && eo <= E) {
+        dstb[(size_t)j * pitch + eo] = m + t;
+        if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg;
+      }
+    }
+    if (tile_start < o) {
+      if (valid && row < o) {
+        dstb[(size_t)j * pitch + row] = GS_INF;
+        if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
+      }
+    }
+  }
+}
+
 // Shape-agnostic "pull" form: a lane owns one TARGET row e and, for each sj, scans the
 // previous plane at row e - O[l][sj] straight from global memory.  Any S up to the
 // library limit, uint8 or uint16 backpointers.  Slow (one load per relaxation); it is the
@@ -270,15 +393,20 @@ int tuned_sp_for(int S) {
 // 1024 SIMDs only twice).  GSEARCH_JSPLIT / GSEARCH_WAVES_PER_BLOCK override the
 // heuristic (debugging and tuning aid).
 struct PushTuning {
-  int jsplit = 0, waves_per_block = 0;
+  int jsplit = 0, waves_per_block = 0, kernel = 0;
   PushTuning() {
     if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
     if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
+    if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile
   }
 };
+static const PushTuning &tuning() {
+  static const PushTuning t;
+  return t;
+}
 
 static void push_launch_shape(const Shape &s, int &jsplit, int &wpb) {
-  static const PushTuning tune;
+  const PushTuning &tune = tuning();
   const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
   wpb = tune.waves_per_block >= 1 && tune.waves_per_block <= 4 ? tune.waves_per_block : 4;
   jsplit = tune.jsplit;
@@ -287,6 +415,30 @@ static void push_launch_shape(const Shape &s, int &jsplit, int &wpb) {
     while (tiles * jsplit < 4096 && jsplit < 8 && s.S / (jsplit * 2) >= 8) jsplit *= 2;
   }
   if (jsplit > s.S) jsplit = s.S;
+}
+
+template <int SP, int NW>
+static void launch_tile_nw(const Shape &s, const Workspace &w, int l, const float *src,
+                           float *dst, void *bp_l, hipStream_t st) {
+  const long long tiles = (s.M + 1 + kWave - 1) / kWave;
+  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
+  const size_t lds = sizeof(float) * SP * kWave;
+  if (bp_l)
+    hipLaunchKernelGGL((k_dp_tile<SP, NW, true>), grid, block, lds, st, src, dst,
+                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L,
+                       s.S, l, s.pitch);
+  else
+    hipLaunchKernelGGL((k_dp_tile<SP, NW, false>), grid, block, lds, st, src, dst,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
+                       s.L, s.S, l, s.pitch);
+}
+
+template <int SP>
+static void launch_tile(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                        void *bp_l, int waves, hipStream_t st) {
+  if (waves >= 4) launch_tile_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
+  else if (waves >= 2) launch_tile_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
+  else launch_tile_nw<SP, 1>(s, w, l, src, dst, bp_l, st);
 }
 
 template <int SP>
@@ -307,21 +459,46 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
                        s.L, s.S, l, s.pitch, jsplit);
 }
 
-void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
-                     void *bp_l, bool force_generic, hipStream_t st) {
+const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,
+                            float *dst, void *bp_l, ForwardKernel which, hipStream_t st) {
+  const bool force_generic = which == ForwardKernel::Generic;
   const int blocks_per_instance = (s.M + 1 + kRowsPerBlock - 1) / kRowsPerBlock;
   const dim3 grid((unsigned)((size_t)blocks_per_instance * s.B));
   const int tsp = tuned_sp_for(s.S);
+  // Which register-tiled kernel: measured on MI355X, the LDS-staged two-level kernel wins
+  // from 48 padded strategies up when backpointers are wanted (its argmin costs about 2.3
+  // instead of 4 vector instructions per relaxation) and for 48..64 without them; the
+  // plain push kernel wins for small S (few chunks, relatively more fixed work per tile)
+  // and for the min-only pass at S >= 96.  The context flags (or GSEARCH_KERNEL=1|2) force one.
+  bool use_tile = bp_l ? tsp >= 48 : (tsp >= 48 && tsp <= 64);
+  if (tuning().kernel == 1 || which == ForwardKernel::Push) use_tile = false;
+  if (tuning().kernel == 2 || which == ForwardKernel::Tile) use_tile = true;
+  if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16 && use_tile) {
+    int waves = tuning().jsplit;
+    if (waves < 1 || waves > 4) waves = 4;
+    if (waves > s.S) waves = s.S;
+    switch (tsp) {
+      case 8: launch_tile<8>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 16: launch_tile<16>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 24: launch_tile<24>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 32: launch_tile<32>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 48: launch_tile<48>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 64: launch_tile<64>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 96: launch_tile<96>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      case 128: launch_tile<128>(s, w, l, src, dst, bp_l, waves, st); return "k_dp_tile";
+      default: break;
+    }
+  }
   if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16) {
     switch (tsp) {
-      case 8: launch_push<8>(s, w, l, src, dst, bp_l, st); return;
-      case 16: launch_push<16>(s, w, l, src, dst, bp_l, st); return;
-      case 24: launch_push<24>(s, w, l, src, dst, bp_l, st); return;
-      case 32: launch_push<32>(s, w, l, src, dst, bp_l, st); return;
-      case 48: launch_push<48>(s, w, l, src, dst, bp_l, st); return;
-      case 64: launch_push<64>(s, w, l, src, dst, bp_l, st); return;
-      case 96: launch_push<96>(s, w, l, src, dst, bp_l, st); return;
-      case 128: launch_push<128>(s, w, l, src, dst, bp_l, st); return;
+      case 8: launch_push<8>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 16: launch_push<16>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 24: launch_push<24>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 32: launch_push<32>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 48: launch_push<48>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 64: launch_push<64>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 96: launch_push<96>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
+      case 128: launch_push<128>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
       default: break;
     }
   }
@@ -338,6 +515,7 @@ void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src
                        dst, (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S,
                        s.SP, l, s.pitch);
   }
+  return "k_dp_generic";
 }
 
 } // namespace gs

@@ -59,7 +59,8 @@ bool config_ok(const gsearch_config *c) {
          c->max_M >= 1 && c->max_K >= 1 && c->device >= 0 && c->max_B <= (1 << 20) &&
          c->max_L <= (1 << 16) && c->max_M <= (1 << 24) && c->max_K <= (1 << 16) &&
          (c->flags & ~(GSEARCH_FLAG_KEEP_PLANES | GSEARCH_FLAG_FORCE_GENERIC |
-                       GSEARCH_FLAG_NO_BACKPOINTERS)) == 0;
+                       GSEARCH_FLAG_NO_BACKPOINTERS | GSEARCH_FLAG_FORCE_PUSH |
+                       GSEARCH_FLAG_FORCE_TILE)) == 0;
 }
 
 // Makes the context's device current for the duration of a call.
@@ -89,6 +90,7 @@ struct gsearch_ctx {
   bool profiling = false;
   bool timed = false; // the most recent solve recorded both events
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+  const char *forward_kernel = ""; // kernel used by the most recent solve's layer fronts
 };
 
 extern "C" {
@@ -190,7 +192,10 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   const size_t pe = gs::plane_elems(s);
   const bool keep = keeps_all_planes(c.flags);
   const size_t bp_layer_bytes = pe * (s.bp16 ? 2 : 1);
-  const bool generic = (c.flags & GSEARCH_FLAG_FORCE_GENERIC) != 0;
+  gs::ForwardKernel which = gs::ForwardKernel::Auto;
+  if (c.flags & GSEARCH_FLAG_FORCE_GENERIC) which = gs::ForwardKernel::Generic;
+  else if (c.flags & GSEARCH_FLAG_FORCE_PUSH) which = gs::ForwardKernel::Push;
+  else if (c.flags & GSEARCH_FLAG_FORCE_TILE) which = gs::ForwardKernel::Tile;
 
   gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w, st);
   gs::launch_init_layer0(s, w, w.planes, st);
@@ -201,8 +206,8 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   for (int l = 1; l < s.L; ++l) {
     const int nxt = keep ? l : (cur ^ 1);
     void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes : nullptr;
-    gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe, w.planes + (size_t)nxt * pe, bp_l,
-                        generic, st);
+    ctx->forward_kernel = gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe, w.planes + (size_t)nxt * pe, bp_l,
+                        which, st);
     cur = nxt;
   }
   if (timing) {
@@ -242,6 +247,10 @@ int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits) {
   if (hipMemcpy(host_bits, ctx->ws.status, sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
     return GSEARCH_ERR_HIP;
   return GSEARCH_OK;
+}
+
+const char *gsearch_forward_kernel(gsearch_ctx *ctx) {
+  return (ctx && ctx->solved) ? ctx->forward_kernel : "";
 }
 
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable) {

@@ -41,9 +41,12 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
                     const int32_t *r_index, const int32_t *budget, const Workspace &w,
                     hipStream_t st);
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);
+// Forward-kernel choice: Auto picks by shape; the others force one implementation.
+enum class ForwardKernel { Auto, Generic, Push, Tile };
 // One layer front of the recurrence: plane l-1 -> plane l (+ backpointers of layer l).
-void launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
-                     void *bp_l, bool force_generic, hipStream_t st);
+// Returns the name of the kernel it launched.
+const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,
+                            float *dst, void *bp_l, ForwardKernel which, hipStream_t st);
 void launch_final(const Shape &s, const Workspace &w, const float *last_plane,
                   float *best_cost, int32_t *best_s, float *final_row, int32_t *best_instance,
                   hipStream_t st);

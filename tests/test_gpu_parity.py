@@ -48,7 +48,8 @@ def oracle_batch(oracle_mod, w, T=None, O=None, R=None):
                                   w.R if R is None else R, w.r_index, w.budget, threads=THREADS)
 
 
-MODES = {"bp": 0, "generic": 0x2, "nobp": 0x4, "nobp_generic": 0x6}
+MODES = {"bp": 0, "generic": 0x2, "nobp": 0x4, "nobp_generic": 0x6,
+         "bp_push": 0x8, "bp_tile": 0x10, "nobp_push": 0xC, "nobp_tile": 0x14}
 
 SHAPES = [
     # B, L, S,  M,   K   (S spans every register-tile size class, M spans tile tails)
@@ -72,7 +73,7 @@ def test_random_tables_match_oracle(gs, oracle_mod, shape, mode):
     assert_same(got, oracle_batch(oracle_mod, w), w, mode)
 
 
-@pytest.mark.parametrize("mode", ["bp", "generic", "nobp"])
+@pytest.mark.parametrize("mode", ["bp_push", "bp_tile", "generic", "nobp_push", "nobp_tile"])
 def test_whole_planes_and_backpointers(gs, oracle_mod, mode):
     binding, runner = gs
     w = random_tables("planes", 3, 6, 44, 333, K=2, seed=11,
@@ -82,7 +83,7 @@ def test_whole_planes_and_backpointers(gs, oracle_mod, mode):
     dw = runner.DeviceWorkload(w)
     with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
         out = runner.run_step(ctx, dw, backtrace="all")
-        C, bp = ctx.gsearch_export_planes(want_bp=(mode != "nobp"))
+        C, bp = ctx.gsearch_export_planes(want_bp=not mode.startswith("nobp"))
         curve = ctx.gsearch_budget_curve()
         out = runner.to_numpy(out)
         C, curve = C.cpu().numpy(), curve.cpu().numpy()
@@ -99,7 +100,7 @@ def test_whole_planes_and_backpointers(gs, oracle_mod, mode):
         assert np.array_equal(out["plan"][b], ref["plan"])
 
 
-@pytest.mark.parametrize("mode", ["bp", "generic", "nobp"])
+@pytest.mark.parametrize("mode", ["bp_push", "bp_tile", "generic", "nobp"])
 @pytest.mark.parametrize("name", ["worked_example_a.txt", "worked_example_b.txt"])
 def test_hand_worked_examples_on_gpu(gs, name, mode):
     _, runner = gs
@@ -114,7 +115,7 @@ def test_hand_worked_examples_on_gpu(gs, name, mode):
         assert list(got["plan"][0]) == r["plan"]
 
 
-@pytest.mark.parametrize("mode", ["bp", "generic", "nobp"])
+@pytest.mark.parametrize("mode", ["bp_push", "bp_tile", "generic", "nobp_push", "nobp_tile"])
 def test_edge_cases(gs, oracle_mod, mode):
     _, runner = gs
     flags = MODES[mode]
