@@ -9,52 +9,60 @@ namespace gs {
 
 // ----------------------------------------------------------------------------------------
 // Sanitised copies of the caller's tables (so that the hot kernels are memory-safe for
-// any input) and the data-status word.
-//   work item < B*L           : one (b,l) row of T and O, r_index[b][l], min_s O
-//   next K*SP*SP items        : one entry of the transposed transition pool
-//   next SP items             : the padding row behind the pool (read by the prefetch of
-//                               the register-tiled kernel, never used)
-//   last B items              : budgets
+// any input) and the data-status word.  One wave per work item group:
+//   wave < B*L            : one (b,l) row of T and O (lanes = strategies), r_index[b][l],
+//                           min_s O by a wave reduction
+//   remaining waves       : 64 consecutive entries each of the transposed transition pool
+//                           (incl. the padding row behind it, which the push kernel's
+//                           prefetch reads but never uses), then the budgets
 // ----------------------------------------------------------------------------------------
-__global__ void k_prepare(const float *__restrict__ T, const int32_t *__restrict__ O,
-                          const float *__restrict__ R, const int32_t *__restrict__ r_index,
-                          const int32_t *__restrict__ budget, float *__restrict__ Tq,
-                          int32_t *__restrict__ Oq, float *__restrict__ Rt,
-                          int32_t *__restrict__ ridx, int32_t *__restrict__ budq,
-                          int32_t *__restrict__ minO, int32_t *__restrict__ status, int B, int L,
-                          int S, int M, int K, int SP) {
+__global__ __launch_bounds__(256) void k_prepare(
+    const float *__restrict__ T, const int32_t *__restrict__ O, const float *__restrict__ R,
+    const int32_t *__restrict__ r_index, const int32_t *__restrict__ budget,
+    float *__restrict__ Tq, int32_t *__restrict__ Oq, float *__restrict__ Rt,
+    int32_t *__restrict__ ridx, int32_t *__restrict__ budq, int32_t *__restrict__ minO,
+    int32_t *__restrict__ status, int B, int L, int S, int M, int K, int SP) {
   const long long nrow = (long long)B * L;
   const long long nr = (long long)K * SP * SP + SP;
-  const long long total = nrow + nr + B;
+  const long long nr_waves = (nr + kWave - 1) / kWave;
+  const long long nb_waves = ((long long)B + kWave - 1) / kWave;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int lane = threadIdx.x & 63;
   int bad = 0;
-  for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < total;
-       w += (long long)gridDim.x * blockDim.x) {
-    if (w < nrow) {
-      const int l = (int)(w % L);
-      int mo = M + 1;
-      for (int s = 0; s < SP; ++s) {
-        float t = 0.0f;
-        int o = M + 1; // padding strategies never fit
-        if (s < S) {
-          t = T[w * S + s];
-          if (!(t >= 0.0f) || t == GS_INF || __builtin_signbit(t)) bad |= 0x1;
-          o = O[w * S + s];
-          if (o < 0) { bad |= 0x4; o = M + 1; }
-          if (o > M + 1) o = M + 1;
-          mo = o < mo ? o : mo;
-        }
-        Tq[w * SP + s] = t;
-        Oq[w * SP + s] = o;
+  if (wave < nrow) {
+    const int l = (int)(wave % L);
+    int mo = M + 1;
+    for (int s = lane; s < SP; s += kWave) {
+      float t = 0.0f;
+      int o = M + 1; // padding strategies never fit
+      if (s < S) {
+        t = T[wave * S + s];
+        if (!(t >= 0.0f) || t == GS_INF || __builtin_signbit(t)) bad |= 0x1;
+        o = O[wave * S + s];
+        if (o < 0) { bad |= 0x4; o = M + 1; }
+        if (o > M + 1) o = M + 1;
+        mo = o < mo ? o : mo;
       }
-      minO[w] = mo;
+      Tq[wave * SP + s] = t;
+      Oq[wave * SP + s] = o;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      const int other = __shfl_xor(mo, d, 64);
+      mo = other < mo ? other : mo;
+    }
+    if (lane == 0) {
+      minO[wave] = mo;
       int k = 0;
       if (l > 0) {
-        k = r_index[w];
+        k = r_index[wave];
         if (k < 0 || k >= K) { bad |= 0x10; k = 0; }
       }
-      ridx[w] = k;
-    } else if (w < nrow + nr) {
-      const long long x = w - nrow;
+      ridx[wave] = k;
+    }
+  } else if (wave < nrow + nr_waves) {
+    const long long x = (wave - nrow) * kWave + lane;
+    if (x < nr) {
       float r = 0.0f;
       if (x < (long long)K * SP * SP) {
         const int i = (int)(x % SP);
@@ -66,8 +74,10 @@ __global__ void k_prepare(const float *__restrict__ T, const int32_t *__restrict
         }
       }
       Rt[x] = r;
-    } else {
-      const int b = (int)(w - nrow - nr);
+    }
+  } else if (wave < nrow + nr_waves + nb_waves) {
+    const long long b = (wave - nrow - nr_waves) * kWave + lane;
+    if (b < B) {
       int e = budget[b];
       if (e < 0 || e > M) { bad |= 0x8; e = e < 0 ? 0 : M; }
       budq[b] = e;
@@ -119,9 +129,7 @@ __global__ void k_final_instance(const float *__restrict__ last,
     float v = last[((size_t)b * S + s) * pitch + E];
     if (poisoned) v = GS_INF;
     if (final_row) final_row[(size_t)b * S + s] = v;
-    if (v < m || arg == 0x7fffffff) {
-      if (v < m || arg == 0x7fffffff) { m = v; arg = s; }
-    }
+    if (v < m || arg == 0x7fffffff) { m = v; arg = s; }
   }
   wave_argmin(m, arg);
   if (lane == 0) {
@@ -291,23 +299,47 @@ static __device__ __forceinline__ bool leaf_alive(int leaf, int k, int N, int tp
   return true;
 }
 
-__global__ void k_enumerate(int N, int k, int tp_max, int sp_max, int tpsp_max,
-                            int32_t *__restrict__ desc, int cap, int32_t *__restrict__ count_out) {
+// Single workgroup of 1024 threads; the unpruned tree has at most 31*31*4 = 3844 leaves, so
+// every thread owns up to four consecutive leaves and the ranks come from one block-wide
+// exclusive scan of the survivor counts.
+__global__ __launch_bounds__(1024) void k_enumerate(int N, int k, int tp_max, int sp_max,
+                                                    int tpsp_max, int32_t *__restrict__ desc,
+                                                    int cap, int32_t *__restrict__ count_out) {
+  __shared__ int wave_sum[16];
   const int leaves = (k + 1) * (k + 1) * 4;
-  int d[5], tmp[5];
-  for (int leaf = blockIdx.x * blockDim.x + threadIdx.x; leaf <= leaves;
-       leaf += gridDim.x * blockDim.x) {
-    // the extra work item leaf == leaves only counts (it yields the total)
-    const bool alive = leaf < leaves && leaf_alive(leaf, k, N, tp_max, sp_max, tpsp_max, d);
-    if (!alive && leaf != leaves) continue;
-    int rank = 0;
-    for (int u = 0; u < leaf; ++u) rank += leaf_alive(u, k, N, tp_max, sp_max, tpsp_max, tmp) ? 1 : 0;
-    if (leaf == leaves) {
-      if (count_out) *count_out = rank;
-    } else if (rank < cap) {
-      for (int x = 0; x < 5; ++x) desc[(size_t)rank * 5 + x] = d[x];
-    }
+  const int first = threadIdx.x * 4;
+  int d[4][5];
+  bool alive[4];
+  int mine = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    alive[u] = first + u < leaves && leaf_alive(first + u, k, N, tp_max, sp_max, tpsp_max, d[u]);
+    mine += alive[u] ? 1 : 0;
   }
+  // inclusive scan inside the wave, then across the 16 waves
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int v = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += v;
+  }
+  if (lane == 63) wave_sum[wv] = incl;
+  __syncthreads();
+  int base = 0, total = 0;
+  for (int x = 0; x < 16; ++x) {
+    if (x < wv) base += wave_sum[x];
+    total += wave_sum[x];
+  }
+  int rank = base + incl - mine;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (alive[u]) {
+      if (rank < cap)
+        for (int x = 0; x < 5; ++x) desc[(size_t)rank * 5 + x] = d[u][x];
+      ++rank;
+    }
+  if (threadIdx.x == 0 && count_out) *count_out = total;
 }
 
 // ----------------------------------------------------------------------------------------
@@ -428,10 +460,11 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
                     const int32_t *r_index, const int32_t *budget, const Workspace &w,
                     hipStream_t st) {
   hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, w.status);
-  const long long items = (long long)s.B * s.L + (long long)s.K * s.SP * s.SP + s.SP + s.B;
-  hipLaunchKernelGGL(k_prepare, dim3(blocks_for(items, 256)), dim3(256), 0, st, T, O, R, r_index,
-                     budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B, s.L, s.S,
-                     s.M, s.K, s.SP);
+  const long long nr = (long long)s.K * s.SP * s.SP + s.SP;
+  const long long waves = (long long)s.B * s.L + (nr + kWave - 1) / kWave + (s.B + kWave - 1) / kWave;
+  hipLaunchKernelGGL(k_prepare, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, T, O, R,
+                     r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B,
+                     s.L, s.S, s.M, s.K, s.SP);
 }
 
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st) {
@@ -492,9 +525,8 @@ void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc
                       int32_t *count_out, hipStream_t st) {
   int k = 0;
   while ((1 << k) < N) ++k;
-  const int leaves = (k + 1) * (k + 1) * 4 + 1;
-  hipLaunchKernelGGL(k_enumerate, dim3((leaves + 255) / 256), dim3(256), 0, st, N, k, tp_max,
-                     sp_max, tpsp_max, desc, cap, count_out);
+  hipLaunchKernelGGL(k_enumerate, dim3(1), dim3(1024), 0, st, N, k, tp_max, sp_max, tpsp_max,
+                     desc, cap, count_out);
 }
 
 void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,

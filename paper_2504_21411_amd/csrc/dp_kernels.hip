@@ -379,6 +379,113 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_generic(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Whole forward pass of a SMALL instance in one launch (latency path).
+//
+// One workgroup per instance runs layer 0 .. L-1 back to back; the two ping-pong planes
+// live in LDS ([s][e], pitch a multiple of 64), so a layer front costs one workgroup
+// barrier instead of a kernel launch.  Threads are laid out as (budget row e) x (group of
+// target strategies): all lanes of a wave share sj, so R, T and O stay wave-uniform scalar
+// operands, and the LDS reads prev[si][e - O] are conflict-free (consecutive lanes,
+// consecutive addresses).  Flat strict-"<" scan; backpointers go to HBM as in the other
+// kernels.  The last plane (or every plane when all are kept) is copied to the HBM
+// workspace so that the final reductions, the budget curve and the plane-based backtrace
+// read what they always read.
+// ---------------------------------------------------------------------------------------
+template <typename BPT>
+__global__ __launch_bounds__(1024) void k_dp_small(
+    float *__restrict__ planes, BPT *__restrict__ bp, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const float *__restrict__ Rt,
+    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget, int B, int L, int S,
+    int SP, int pitch, int keep_all, int last_plane) {
+  extern __shared__ float lds[]; // two planes of S * pitch floats
+  const int b = blockIdx.x;
+  const int E = budget[b];
+  const int rows64 = (E + 1 + kWave - 1) / kWave * kWave; // threads along e
+  const int groups = (int)blockDim.x / rows64;             // >= 1 by the launch condition
+  const int e = (int)threadIdx.x % rows64;
+  const int jg = (int)threadIdx.x / rows64;
+  const bool active = jg < groups && e <= E;
+  const size_t plane_elems_all = (size_t)B * S * pitch;
+  const size_t plane_off = (size_t)b * S * pitch;
+  float *cur = lds;
+  float *nxt = lds + (size_t)S * pitch;
+
+  if (active)
+    for (int s = jg; s < S; s += groups) {
+      const float v = (e >= Oq[(size_t)b * L * SP + s]) ? Tq[(size_t)b * L * SP + s] : GS_INF;
+      cur[s * pitch + e] = v;
+      if (keep_all || L == 1) planes[plane_off + (size_t)s * pitch + e] = v;
+    }
+  for (int l = 1; l < L; ++l) {
+    __syncthreads();
+    const int bl = b * L + l;
+    const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
+    float *gplane = planes + (keep_all ? (size_t)l * plane_elems_all : (size_t)last_plane * plane_elems_all) + plane_off;
+    const bool to_global = keep_all || l == L - 1;
+    if (active)
+      for (int j = jg; j < S; j += groups) {
+        const int o = Oq[(size_t)bl * SP + j];
+        float out = GS_INF;
+        int arg = 0;
+        if (e >= o) {
+          const float *__restrict__ rc = rk + (size_t)j * SP;
+          const float *src = cur + (e - o);
+          float m = GS_INF;
+          // eight candidates at a time: the LDS reads and the scalar load of the eight
+          // transition values are issued together, then the strict-"<" scan runs
+          for (int i0 = 0; i0 < S; i0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = (i0 + k < S) ? src[(i0 + k) * pitch] : GS_INF;
+            const float8_t r = *reinterpret_cast<const float8_t *>(rc + i0);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const float t = v[k] + r[k];
+              if (t < m) { m = t; arg = i0 + k; }
+            }
+          }
+          out = m + Tq[(size_t)bl * SP + j];
+        }
+        nxt[j * pitch + e] = out;
+        if (to_global) gplane[(size_t)j * pitch + e] = out;
+        if (bp) bp[(size_t)(l - 1) * plane_elems_all + plane_off + (size_t)j * pitch + e] = (BPT)arg;
+      }
+    float *t = cur; cur = nxt; nxt = t;
+  }
+}
+
+// The latency path applies when an instance's budget rows fit one workgroup, its two planes
+// fit LDS, and the batch is too small to fill the GPU through the per-layer kernels anyway.
+bool small_path_applies(const Shape &s) {
+  if (s.M + 1 > 1024) return false;
+  if ((size_t)2 * s.S * s.pitch * sizeof(float) > (size_t)96 * 1024) return false;
+  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
+  return tiles <= 2048;
+}
+
+void launch_dp_small(const Shape &s, const Workspace &w, bool keep_all, int last_plane,
+                     hipStream_t st) {
+  const size_t lds = (size_t)2 * s.S * s.pitch * sizeof(float);
+  const int rows64 = (s.M + 1 + kWave - 1) / kWave * kWave;
+  int threads = (1024 / rows64) * rows64; // whole groups of target strategies
+  const int useful = ((s.S < 1024 / rows64) ? s.S : 1024 / rows64) * rows64;
+  if (useful < threads) threads = useful;
+  if (s.bp16) {
+    (void)hipFuncSetAttribute((const void *)k_dp_small<uint16_t>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((k_dp_small<uint16_t>), dim3(s.B), dim3(threads), lds, st, w.planes,
+                       (uint16_t *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, s.SP,
+                       s.pitch, keep_all ? 1 : 0, last_plane);
+  } else {
+    (void)hipFuncSetAttribute((const void *)k_dp_small<uint8_t>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((k_dp_small<uint8_t>), dim3(s.B), dim3(threads), lds, st, w.planes,
+                       (uint8_t *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, s.SP,
+                       s.pitch, keep_all ? 1 : 0, last_plane);
+  }
+}
+
 int tuned_sp_for(int S) {
   static const int sizes[] = {8, 16, 24, 32, 48, 64, 96, 128};
   for (int v : sizes)

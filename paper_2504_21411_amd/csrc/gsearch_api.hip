@@ -198,17 +198,26 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   else if (c.flags & GSEARCH_FLAG_FORCE_TILE) which = gs::ForwardKernel::Tile;
 
   gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w, st);
-  gs::launch_init_layer0(s, w, w.planes, st);
   int cur = 0;
   ctx->timed = false;
   const bool timing = ctx->profiling && s.L > 1;
-  if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
-  for (int l = 1; l < s.L; ++l) {
-    const int nxt = keep ? l : (cur ^ 1);
-    void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes : nullptr;
-    ctx->forward_kernel = gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe, w.planes + (size_t)nxt * pe, bp_l,
-                        which, st);
-    cur = nxt;
+  if (which == gs::ForwardKernel::Auto && gs::small_path_applies(s)) {
+    // latency path: layer 0 and every layer front in one launch, planes in LDS
+    cur = keep ? s.L - 1 : ((s.L - 1) & 1);
+    if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
+    gs::launch_dp_small(s, w, keep, cur, st);
+    ctx->forward_kernel = "k_dp_small";
+  } else {
+    gs::launch_init_layer0(s, w, w.planes, st);
+    if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
+    for (int l = 1; l < s.L; ++l) {
+      const int nxt = keep ? l : (cur ^ 1);
+      void *bp_l =
+          with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes : nullptr;
+      ctx->forward_kernel = gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe,
+                                                w.planes + (size_t)nxt * pe, bp_l, which, st);
+      cur = nxt;
+    }
   }
   if (timing) {
     if (hipEventRecord(ctx->ev_end, st) != hipSuccess) return GSEARCH_ERR_HIP;
