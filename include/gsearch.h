@@ -167,6 +167,22 @@ const char *gsearch_forward_kernel(gsearch_ctx *ctx);
  * constraints): one solve answers every smaller device memory as well. */
 int gsearch_budget_curve(gsearch_ctx *ctx, float *curve, void *stream);
 
+/* Pipeline-aware outer reduction over the most recent solve (paper abstract and section 2:
+ * pipeline parallelism is one of the searched dimensions; the paper gives no formula, this
+ * is the synchronous-pipeline reading).  A candidate g = (pipeline degree, stage split,
+ * micro-batch count m) owns the solved instances group_members[group_offsets[g] ..
+ * group_offsets[g+1]), one per stage; their optima t are per-micro-batch stage times and
+ *     group_cost[g] = (t_0 + t_1 + ...) + (m - 1) * max t          (fp32, in that order)
+ * +inf if any member is infeasible or not a valid instance id.  best_group = argmin,
+ * lowest g on ties, -1 if none is feasible (NULL to skip).
+ *   group_offsets device [G+1], group_members device [n_members], group_micro device [G],
+ *   group_cost device [G], best_group device [1].  Asynchronous on `stream`.
+ * Errors: INVALID_ARG, NOT_SOLVED, HIP. */
+int gsearch_pipeline_reduce(gsearch_ctx *ctx, int32_t G, const int32_t *group_offsets,
+                            const int32_t *group_members, int32_t n_members,
+                            const int32_t *group_micro, float *group_cost, int32_t *best_group,
+                            void *stream);
+
 /* Debug export of the most recent solve in canonical layout (needs KEEP_PLANES):
  *   C  device [B][L][M+1][S] fp32, rows e > E_b are filled with +inf
  *   bp device [B][L][M+1][S] int32, plane 0 and rows e > E_b are 0; NULL to skip (must be

@@ -192,3 +192,20 @@ def build_tables(desc, layer, hw, rmodel, M):
     if rc != 0:
         raise ValueError(f"oracle_build_tables failed with code {rc}")
     return T, O, R
+
+
+def pipeline_reduce(stage_cost, group_offsets, group_members, group_micro):
+    """Pipeline-aware outer reduction.  Returns (group_cost [G] fp32, best_group)."""
+    lib = _load()
+    stage_cost = _f32(stage_cost)
+    group_offsets, group_members, group_micro = _i32(group_offsets), _i32(group_members), _i32(group_micro)
+    G = group_micro.shape[0]
+    cost = np.zeros(G, np.float32)
+    best = np.zeros(1, np.int32)
+    rc = lib.oracle_pipeline_reduce(
+        ctypes.c_int32(stage_cost.shape[0]), ctypes.c_int32(G), _p(stage_cost, ctypes.c_float),
+        _p(group_offsets, ctypes.c_int32), _p(group_members, ctypes.c_int32),
+        _p(group_micro, ctypes.c_int32), _p(cost, ctypes.c_float), _p(best, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError("oracle_pipeline_reduce: bad arguments")
+    return cost, int(best[0])

@@ -39,6 +39,7 @@ EXPORTS = [
     "gsearch_backtrace", "gsearch_data_status", "gsearch_budget_curve", "gsearch_export_planes",
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
+    "gsearch_pipeline_reduce",
 ]
 
 
@@ -104,6 +105,8 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_forward_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.gsearch_forward_kernel.restype = ctypes.c_char_p
     lib.gsearch_forward_kernel.argtypes = [vp]
+    lib.gsearch_pipeline_reduce.restype = ctypes.c_int
+    lib.gsearch_pipeline_reduce.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
     lib.gsearch_budget_curve.restype = ctypes.c_int
     lib.gsearch_budget_curve.argtypes = [vp, vp, vp]
     lib.gsearch_export_planes.restype = ctypes.c_int
@@ -285,6 +288,21 @@ class GSearch:
 
     def gsearch_forward_kernel(self) -> str:
         return self._lib.gsearch_forward_kernel(self._ctx).decode()
+
+    def gsearch_pipeline_reduce(self, group_offsets, group_members, group_micro, stream=None):
+        """int32 device tensors (CSR offsets [G+1], member ids, micro-batch counts [G]).
+        Returns (group_cost fp32 [G], best_group int32 [1]) on the GPU."""
+        import torch
+        G = int(group_micro.numel())
+        dev = group_micro.device
+        cost = torch.empty(G, dtype=torch.float32, device=dev)
+        best = torch.empty(1, dtype=torch.int32, device=dev)
+        _check(self._lib.gsearch_pipeline_reduce(
+            self._ctx, G, _ptr(group_offsets, torch.int32, "group_offsets"),
+            _ptr(group_members, torch.int32, "group_members"), int(group_members.numel()),
+            _ptr(group_micro, torch.int32, "group_micro"), _ptr(cost), _ptr(best),
+            _stream(stream)), "gsearch_pipeline_reduce")
+        return cost, best
 
     def gsearch_budget_curve(self, stream=None):
         import torch

@@ -242,6 +242,37 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
   }
 }
 
+// Pipeline-aware outer reduction: one thread per candidate (pipeline degree, stage split,
+// micro-batch count).  cost = (t_0 + ... + t_{pp-1}) + (m - 1) * max t, in fp32: the sum
+// left to right over the members as listed, the product rounded, then one add; +inf as
+// soon as a member is infeasible or not a valid instance id.  Offsets are clamped to the
+// member list so that a corrupt offset table cannot read outside it.
+__global__ void k_pipeline_groups(const float *__restrict__ stage_cost, int B, int G,
+                                  const int32_t *__restrict__ offsets,
+                                  const int32_t *__restrict__ members, int n_members,
+                                  const int32_t *__restrict__ micro, float *__restrict__ cost) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= G) return;
+  int lo = offsets[g], hi = offsets[g + 1];
+  const int m = micro[g];
+  bool ok = lo >= 0 && hi <= n_members && hi > lo && m >= 1;
+  float sum = 0.0f, mx = 0.0f;
+  for (int x = lo; ok && x < hi; ++x) {
+    const int b = members[x];
+    if (b < 0 || b >= B) { ok = false; break; }
+    const float t = stage_cost[b];
+    if (t == GS_INF) { ok = false; break; }
+    sum = (x == lo) ? t : sum + t;
+    mx = t > mx ? t : mx;
+  }
+  float out = GS_INF;
+  if (ok) {
+    const float bubble = (float)(m - 1) * mx;
+    out = sum + bubble;
+  }
+  cost[g] = out;
+}
+
 // curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf above.
 __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__restrict__ budget,
                                const int32_t *__restrict__ status, float *__restrict__ curve,
@@ -501,6 +532,15 @@ void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *
   hipLaunchKernelGGL(k_backtrace_planes, dim3(n), dim3(kWave), 0, st, w.planes, w.Rt, w.Oq,
                      w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S,
                      s.SP, s.pitch);
+}
+
+void launch_pipeline_reduce(const Shape &s, const Workspace &w, int G, const int32_t *offsets,
+                            const int32_t *members, int n_members, const int32_t *micro,
+                            float *group_cost, int32_t *best_group, hipStream_t st) {
+  hipLaunchKernelGGL(k_pipeline_groups, dim3((G + 255) / 256), dim3(256), 0, st, w.best_cost,
+                     s.B, G, offsets, members, n_members, micro, group_cost);
+  if (best_group)
+    hipLaunchKernelGGL(k_final_global, dim3(1), dim3(256), 0, st, group_cost, best_group, G);
 }
 
 void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_plane,

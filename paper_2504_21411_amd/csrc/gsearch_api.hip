@@ -300,6 +300,22 @@ int gsearch_budget_curve(gsearch_ctx *ctx, float *curve, void *stream) {
   return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
 }
 
+int gsearch_pipeline_reduce(gsearch_ctx *ctx, int32_t G, const int32_t *group_offsets,
+                            const int32_t *group_members, int32_t n_members,
+                            const int32_t *group_micro, float *group_cost, int32_t *best_group,
+                            void *stream) {
+  if (!ctx || G < 1 || n_members < 1 || !group_offsets || !group_members || !group_micro ||
+      !group_cost)
+    return GSEARCH_ERR_INVALID_ARG;
+  if (!ctx->solved) return GSEARCH_ERR_NOT_SOLVED;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_HIP;
+  gs::launch_pipeline_reduce(ctx->shape, ctx->ws, G, group_offsets, group_members, n_members,
+                             group_micro, group_cost, best_group,
+                             static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
 int gsearch_export_planes(gsearch_ctx *ctx, float *C, int32_t *bp, void *stream) {
   if (!ctx || (!C && !bp)) return GSEARCH_ERR_INVALID_ARG;
   if (!(ctx->cfg.flags & GSEARCH_FLAG_KEEP_PLANES)) return GSEARCH_ERR_UNSUPPORTED;

@@ -58,6 +58,9 @@ void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *inst
                          int32_t *plan, int32_t *mem_used, hipStream_t st);
 void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *instances, int n,
                              int32_t *plan, int32_t *mem_used, hipStream_t st);
+void launch_pipeline_reduce(const Shape &s, const Workspace &w, int G, const int32_t *offsets,
+                            const int32_t *members, int n_members, const int32_t *micro,
+                            float *group_cost, int32_t *best_group, hipStream_t st);
 void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_plane,
                          float *curve, hipStream_t st);
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st);

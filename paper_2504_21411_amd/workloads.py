@@ -214,6 +214,34 @@ def pipeline_instances(limit=2048, pps=(1, 2, 4, 8, 16), splits_per_pp=3, max_mi
     return a[:, 0], a[:, 1], a[:, 2], a[:, 3]
 
 
+def pipeline_groups(pp, split, stage, micro):
+    """Complete candidates (pp, split, micro) of an instance list, as CSR.
+
+    A candidate is complete when all its pp stages are present; members are listed in
+    stage order.  Returns int32 arrays (offsets [G+1], members, micro [G]) plus the
+    (pp, split) of every group.
+    """
+    index = {}
+    for b in range(len(pp)):
+        index[(int(pp[b]), int(split[b]), int(micro[b]), int(stage[b]))] = b
+    offsets, members, gm, gkey = [0], [], [], []
+    seen = set()
+    for b in range(len(pp)):
+        key = (int(pp[b]), int(split[b]), int(micro[b]))
+        if key in seen:
+            continue
+        seen.add(key)
+        ids = [index.get(key + (st,)) for st in range(key[0])]
+        if any(i is None for i in ids):
+            continue
+        members.extend(ids)
+        offsets.append(len(members))
+        gm.append(key[2])
+        gkey.append(key[:2])
+    return (np.asarray(offsets, np.int32), np.asarray(members, np.int32),
+            np.asarray(gm, np.int32), np.asarray(gkey, np.int32))
+
+
 def config4(B=2048) -> Workload:
     """Full outer search: B pipeline-stage instances, L=32, S=24, M=2048, seed 4."""
     L, S, M = 32, 24, 2048
@@ -235,7 +263,8 @@ def config4(B=2048) -> Workload:
     return Workload("cfg4_outer_search", B, L, S, M, 1, budget, np.zeros((B, L), np.int32),
                     "tables", T=np.ascontiguousarray(T), O=np.ascontiguousarray(O.astype(np.int32)),
                     R=R, enum=dict(N=8, tp_max=0, sp_max=2, tpsp_max=0),
-                    meta=dict(pp=pp, split=split, stage=stage, micro=micro))
+                    meta=dict(pp=pp, split=split, stage=stage, micro=micro,
+                              groups=pipeline_groups(pp, split, stage, micro)))
 
 
 CONFIGS = [config0, config1, config2, config3, config4]

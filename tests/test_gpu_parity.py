@@ -323,3 +323,34 @@ def test_config3_large_dense_full_size(gs, oracle_mod):
         assert np.array_equal(bits(got["T"]), bits(T)) and np.array_equal(got["O"], O)
         assert_same(got, ref, w, f"flags={flags}")
     assert np.isfinite(ref["best_cost"]).all()
+
+
+def test_pipeline_aware_reduction(gs, oracle_mod):
+    """Outer reduction over (pipeline degree, split, micro-batch) candidates of a reduced
+    outer-search batch, then the plans of the winning candidate's stages."""
+    import torch
+    binding, runner = gs
+    w = workloads.config4(B=704)                    # pp 1, 2 and part of pp 4
+    off, mem, mic, _ = w.meta["groups"]
+    w.budget[5] = 3                                  # one infeasible stage instance
+    ref = oracle_batch(oracle_mod, w)
+    assert np.isinf(ref["best_cost"][5])
+    want_cost, want_best = oracle_mod.pipeline_reduce(ref["best_cost"], off, mem, mic)
+    dw = runner.DeviceWorkload(w)
+    t32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, np.int32)).cuda()
+    with runner.make_context(w) as ctx:
+        with pytest.raises(binding.GSearchError) as ei:
+            ctx.gsearch_pipeline_reduce(t32(off), t32(mem), t32(mic))
+        assert ei.value.code == binding.GSEARCH_ERR_NOT_SOLVED
+        runner.run_step(ctx, dw, backtrace=None)
+        cost, best = ctx.gsearch_pipeline_reduce(t32(off), t32(mem), t32(mic))
+        cost, best = cost.cpu().numpy(), int(best.cpu()[0])
+        assert np.array_equal(bits(cost), bits(want_cost)) and best == want_best
+        assert np.isinf(cost).any() and np.isfinite(cost).any()
+        members = t32(mem[off[best]:off[best + 1]])
+        plans = runner.to_numpy(ctx.gsearch_backtrace(members))
+        assert np.array_equal(plans["plan"], ref["plan"][mem[off[best]:off[best + 1]]])
+        # corrupt offsets must not read outside the member list: the candidate is infeasible
+        bad = off.copy(); bad[3] = 10 ** 6
+        cost2, _ = ctx.gsearch_pipeline_reduce(t32(bad), t32(mem), t32(mic))
+        assert np.isinf(cost2.cpu().numpy()[2:4]).all()
