@@ -132,6 +132,55 @@ static __device__ __forceinline__ float8_t load_col_head(const float *col) {
   return r;
 }
 
+// ---------------------------------------------------------------------------------------
+// Level 1 of the two-level argmin (and the whole scan of the min-only pass), left to the
+// compiler: per chunk of eight candidates eight adds and four minimum instructions give
+// the chunk minimum cm; WITH_ARG then updates (m, g) with a strict "<", so that g ends as
+// the first chunk attaining the minimum.  The transition values are fetched sixteen at a
+// time (one wide scalar load per two chunks), which halves the number of scalar-load
+// waits compared with one load per chunk.  (A hand-scheduled variant that requested the
+// next chunk at the top of an eight-candidate block and waited at its end was slower: it
+// doubles the number of requests and its 12 vector instructions do not cover a
+// scalar-cache hit.)
+// ---------------------------------------------------------------------------------------
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+template <bool WITH_ARG>
+static __device__ __forceinline__ void chunk_update(float &m, int &g, float cm, int q) {
+  if (WITH_ARG) {
+    const bool lt = cm < m;
+    m = lt ? cm : m;
+    g = lt ? q : g;
+  } else {
+    m = __builtin_fminf(m, cm);
+  }
+}
+
+template <int SP, bool WITH_ARG>
+static __device__ __forceinline__ void scan_chunks(float &m, int &g, const float (&c)[SP],
+                                                   const float *__restrict__ rc) {
+#pragma unroll
+  for (int p = 0; p < SP / 16; ++p) {
+    const float16_t r = *reinterpret_cast<const float16_t *>(rc + 16 * p);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int q = 2 * p + h;
+      float cm = __builtin_fminf(c[8 * q] + r[8 * h], c[8 * q + 1] + r[8 * h + 1]);
+#pragma unroll
+      for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[8 * q + k] + r[8 * h + k]);
+      chunk_update<WITH_ARG>(m, g, cm, q);
+    }
+  }
+  if (SP % 16 != 0) { // one last chunk of eight (SP = 8 or 24)
+    constexpr int q = SP / 8 - 1;
+    const float8_t r = *reinterpret_cast<const float8_t *>(rc + 8 * q);
+    float cm = __builtin_fminf(c[8 * q] + r[0], c[8 * q + 1] + r[1]);
+#pragma unroll
+    for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[8 * q + k] + r[k]);
+    chunk_update<WITH_ARG>(m, g, cm, q);
+  }
+}
+
 // SP: padded strategy count (compile time).  WITH_BP: also track and store the argmin.
 template <int SP, bool WITH_BP>
 __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
@@ -201,8 +250,8 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
         m = takeB ? mB : m;
         arg = takeB ? candB : candA;
       } else {
-#pragma unroll
-        for (int i = 0; i < SP; ++i) m = __builtin_fminf(m, c[i] + rc[i]);
+        int unused = 0;
+        scan_chunks<SP, false>(m, unused, c, rc);
       }
       const int eo = row + o;
       if (valid && eo <= E) {
@@ -297,20 +346,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
       const float *__restrict__ rc = rk + (size_t)j * SP;
       float m = GS_INF;
       int g = 0;
-#pragma unroll
-      for (int q = 0; q < SP / 8; ++q) {
-        const float8_t r = *reinterpret_cast<const float8_t *>(rc + 8 * q);
-        float cm = __builtin_fminf(c[8 * q] + r[0], c[8 * q + 1] + r[1]);
-#pragma unroll
-        for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[8 * q + k] + r[k]);
-        if (WITH_BP) {
-          const bool lt = cm < m;
-          m = lt ? cm : m;
-          g = lt ? q : g;
-        } else {
-          m = __builtin_fminf(m, cm);
-        }
-      }
+      scan_chunks<SP, WITH_BP>(m, g, c, rc);
       int arg = 0;
       if (WITH_BP) {
         const float *__restrict__ rg = rc + 8 * g;      // per-lane slice of the column
