@@ -39,7 +39,7 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     return 4.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {(3, "bp"): 113.9e6, (3, "nobp"): 101.3e6}
+MEASURED_TRAFFIC_BYTES = {(3, "bp"): 114.5e6, (3, "nobp"): 101.3e6}
 
 
 def cpu_baseline(w, cfg_index, target_relax=9.0e9):
