@@ -42,7 +42,7 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
 MEASURED_TRAFFIC_BYTES = {(3, "bp"): 114.5e6, (3, "nobp"): 101.3e6}
 
 
-def cpu_baseline(w, cfg_index, target_relax=9.0e9):
+def cpu_baseline(w, cfg_index, target_relax=3.0e10):
     """The oracle as it stands, single-threaded, on a bounded sample of the same workload."""
     import numpy as np
     import oracle

@@ -109,19 +109,81 @@ static __device__ __forceinline__ void argmin_block8(float &mA, int &argA, float
       : "vcc", "memory");
 }
 
-template <int Q, int NQ>
+// Same eight-candidate block without the scalar prefetch: used for all but the last of the
+// RU row groups that share one set of transition values.
+template <int Q>
+static __device__ __forceinline__ void argmin_block8_shared(float &mA, int &argA, float &mB,
+                                                            int &argB, const float *c,
+                                                            const float8_t &r) {
+  float tA0, tB0, tA1, tB1;
+  unsigned long long maskA;
+  asm volatile(
+      "v_add_f32 %[tA0], %[r0], %[c0]\n\t"
+      "v_add_f32 %[tB0], %[r1], %[c1]\n\t"
+      "v_cmp_ge_f32 %[mk], %[tA0], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB0], %[mB]\n\t"
+      "v_add_f32 %[tA1], %[r2], %[c2]\n\t"
+      "v_add_f32 %[tB1], %[r3], %[c3]\n\t"
+      "v_cndmask_b32 %[mA], %[tA0], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0], %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB0], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0], %[aB], vcc\n\t"
+      "v_cmp_ge_f32 %[mk], %[tA1], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB1], %[mB]\n\t"
+      "v_add_f32 %[tA0], %[r4], %[c4]\n\t"
+      "v_add_f32 %[tB0], %[r5], %[c5]\n\t"
+      "v_cndmask_b32 %[mA], %[tA1], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0]+1, %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB1], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0]+1, %[aB], vcc\n\t"
+      "v_cmp_ge_f32 %[mk], %[tA0], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB0], %[mB]\n\t"
+      "v_add_f32 %[tA1], %[r6], %[c6]\n\t"
+      "v_add_f32 %[tB1], %[r7], %[c7]\n\t"
+      "v_cndmask_b32 %[mA], %[tA0], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0]+2, %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB0], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0]+2, %[aB], vcc\n\t"
+      "v_cmp_ge_f32 %[mk], %[tA1], %[mA]\n\t"
+      "v_cmp_ge_f32 vcc, %[tB1], %[mB]\n\t"
+      "s_nop 0\n\t"
+      "v_cndmask_b32 %[mA], %[tA1], %[mA], %[mk]\n\t"
+      "v_cndmask_b32 %[aA], %[n0]+3, %[aA], %[mk]\n\t"
+      "v_cndmask_b32 %[mB], %[tB1], %[mB], vcc\n\t"
+      "v_cndmask_b32 %[aB], %[n0]+3, %[aB], vcc"
+      : [mA] "+v"(mA), [aA] "+v"(argA), [mB] "+v"(mB), [aB] "+v"(argB), [tA0] "=&v"(tA0),
+        [tB0] "=&v"(tB0), [tA1] "=&v"(tA1), [tB1] "=&v"(tB1), [mk] "=&s"(maskA)
+      : [n0] "n"(4 * Q), [r0] "s"(r[0]), [r1] "s"(r[1]), [r2] "s"(r[2]), [r3] "s"(r[3]),
+        [r4] "s"(r[4]), [r5] "s"(r[5]), [r6] "s"(r[6]), [r7] "s"(r[7]),
+        [c0] "v"(c[8 * Q + 0]), [c1] "v"(c[8 * Q + 1]), [c2] "v"(c[8 * Q + 2]),
+        [c3] "v"(c[8 * Q + 3]), [c4] "v"(c[8 * Q + 4]), [c5] "v"(c[8 * Q + 5]),
+        [c6] "v"(c[8 * Q + 6]), [c7] "v"(c[8 * Q + 7])
+      : "vcc");
+}
+
+// Running state of one lane's scan: the two chains of the flat argmin.
+struct ArgminState {
+  float mA, mB;
+  int argA, argB;
+};
+
+template <int Q, int NQ, int RU, int SP>
 struct ArgminBlocks {
-  static __device__ __forceinline__ void run(float &mA, int &argA, float &mB, int &argB,
-                                             const float *c, float8_t &r, const float *col) {
+  static __device__ __forceinline__ void run(ArgminState (&st)[RU], const float (&c)[RU][SP],
+                                             float8_t &r, const float *col) {
     float8_t rn;
-    argmin_block8<Q>(mA, argA, mB, argB, c, r, rn, col);
+#pragma unroll
+    for (int u = 0; u < RU - 1; ++u)
+      argmin_block8_shared<Q>(st[u].mA, st[u].argA, st[u].mB, st[u].argB, c[u], r);
+    argmin_block8<Q>(st[RU - 1].mA, st[RU - 1].argA, st[RU - 1].mB, st[RU - 1].argB, c[RU - 1],
+                     r, rn, col);
     r = rn;
-    ArgminBlocks<Q + 1, NQ>::run(mA, argA, mB, argB, c, r, col);
+    ArgminBlocks<Q + 1, NQ, RU, SP>::run(st, c, r, col);
   }
 };
-template <int NQ>
-struct ArgminBlocks<NQ, NQ> {
-  static __device__ __forceinline__ void run(float &, int &, float &, int &, const float *,
+template <int NQ, int RU, int SP>
+struct ArgminBlocks<NQ, NQ, RU, SP> {
+  static __device__ __forceinline__ void run(ArgminState (&)[RU], const float (&)[RU][SP],
                                              float8_t &, const float *) {}
 };
 
@@ -181,8 +243,11 @@ static __device__ __forceinline__ void scan_chunks(float &m, int &g, const float
   }
 }
 
-// SP: padded strategy count (compile time).  WITH_BP: also track and store the argmin.
-template <int SP, bool WITH_BP>
+// SP: padded strategy count (compile time).  RU: groups of 64 budget rows per wave (a lane
+// owns rows r, r+64, ...): with few strategies the per-column work of one row group is too
+// short to amortise the scalar loads, the loop and the stores' address arithmetic, so
+// several row groups share them.  WITH_BP: also track and store the argmin.
+template <int SP, int RU, bool WITH_BP>
 __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
@@ -190,15 +255,14 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const int32_t *__restrict__ budget, const int32_t *__restrict__ minO, int B, int L, int S,
     int l, int pitch, int jsplit) {
   // blockIdx.x = (row_block * jsplit + js) * B + b: consecutive workgroups belong to
-  // different instances, so the hardware's round-robin over the eight XCDs spreads every
-  // instance's tables over the same XCD's L2 only when B is a multiple of 8, and spreads
-  // the load evenly in every case.
+  // different instances, so the round-robin of workgroups over the eight XCDs spreads
+  // every instance (and ragged budgets) evenly over the chip.
   const int b = blockIdx.x % B;
   const int rest = blockIdx.x / B;
   const int js = rest % jsplit;
   const int wave = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int tile_start = ((rest / jsplit) * (int)(blockDim.x >> 6) + wave) * kWave;
+  const int tile_start = ((rest / jsplit) * (int)(blockDim.x >> 6) + wave) * (kWave * RU);
   const int E = budget[b];
   if (tile_start > E) return;
   // this workgroup's slice of target strategies
@@ -207,8 +271,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
   const int jend = jbeg + jper < S ? jbeg + jper : S;
   if (jbeg >= jend) return;
 
-  const int row = tile_start + lane;
-  const bool valid = row <= E;
+  const int row0 = tile_start + lane;
   const int bl = b * L + l;
   // source rows above E - min_s O[l][s] feed no target row
   const bool compute = tile_start <= E - minO[bl];
@@ -220,14 +283,13 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
   const float *__restrict__ trow = Tq + (size_t)bl * SP;
   const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
 
-  float c[SP];
-  if (compute) {
+  float c[RU][SP];
+#pragma unroll
+  for (int u = 0; u < RU; ++u) {
+    const int row = row0 + u * kWave;
 #pragma unroll
     for (int i = 0; i < SP; ++i)
-      c[i] = (i < S && valid) ? srcb[(size_t)i * pitch + row] : GS_INF;
-  } else {
-#pragma unroll
-    for (int i = 0; i < SP; ++i) c[i] = GS_INF;
+      c[u][i] = (compute && i < S && row <= E) ? srcb[(size_t)i * pitch + row] : GS_INF;
   }
 
   float8_t rcur;
@@ -237,32 +299,48 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const float t = trow[j];
     if (compute) {
       const float *__restrict__ rc = rk + (size_t)j * SP;
-      float m = GS_INF;
-      int arg = 0;
+      float m[RU];
+      int arg[RU];
       if (WITH_BP) {
-        float mB = GS_INF;
-        int argA = 0, argB = 0;
-        ArgminBlocks<0, SP / 8>::run(m, argA, mB, argB, c, rcur, rc);
-        // merge the chains: candidate 2*argA (even chain) against 2*argB+1 (odd chain),
-        // the strictly smaller value wins and equal values go to the lower candidate
-        const int candA = 2 * argA, candB = 2 * argB + 1;
-        const bool takeB = (mB < m) || (mB == m && candB < candA);
-        m = takeB ? mB : m;
-        arg = takeB ? candB : candA;
+        ArgminState st[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) st[u] = ArgminState{GS_INF, GS_INF, 0, 0};
+        ArgminBlocks<0, SP / 8, RU, SP>::run(st, c, rcur, rc);
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          // merge the chains: candidate 2*argA (even chain) against 2*argB+1 (odd chain),
+          // the strictly smaller value wins and equal values go to the lower candidate
+          const int candA = 2 * st[u].argA, candB = 2 * st[u].argB + 1;
+          const bool takeB = (st[u].mB < st[u].mA) || (st[u].mB == st[u].mA && candB < candA);
+          m[u] = takeB ? st[u].mB : st[u].mA;
+          arg[u] = takeB ? candB : candA;
+        }
       } else {
-        int unused = 0;
-        scan_chunks<SP, false>(m, unused, c, rc);
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          m[u] = GS_INF;
+          arg[u] = 0;
+          scan_chunks<SP, false>(m[u], arg[u], c[u], rc);
+        }
       }
-      const int eo = row + o;
-      if (valid && eo <= E) {
-        dstb[(size_t)j * pitch + eo] = m + t;
-        if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg;
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const int row = row0 + u * kWave;
+        const int eo = row + o;
+        if (row <= E && eo <= E) {
+          dstb[(size_t)j * pitch + eo] = m[u] + t;
+          if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg[u];
+        }
       }
     }
     if (tile_start < o) {
-      if (valid && row < o) {
-        dstb[(size_t)j * pitch + row] = GS_INF;
-        if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const int row = row0 + u * kWave;
+        if (row <= E && row < o) {
+          dstb[(size_t)j * pitch + row] = GS_INF;
+          if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
+        }
       }
     }
   }
@@ -536,11 +614,12 @@ int tuned_sp_for(int S) {
 // 1024 SIMDs only twice).  GSEARCH_JSPLIT / GSEARCH_WAVES_PER_BLOCK override the
 // heuristic (debugging and tuning aid).
 struct PushTuning {
-  int jsplit = 0, waves_per_block = 0, kernel = 0;
+  int jsplit = 0, waves_per_block = 0, kernel = 0, row_groups = 0;
   PushTuning() {
     if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
     if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
     if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile
+    if (const char *e = getenv("GSEARCH_ROW_GROUPS")) row_groups = atoi(e);
   }
 };
 static const PushTuning &tuning() {
@@ -584,22 +663,42 @@ static void launch_tile(const Shape &s, const Workspace &w, int l, const float *
   else launch_tile_nw<SP, 1>(s, w, l, src, dst, bp_l, st);
 }
 
+template <int SP, int RU>
+static void launch_push_ru(const Shape &s, const Workspace &w, int l, const float *src,
+                           float *dst, void *bp_l, int jsplit, int wpb, hipStream_t st) {
+  const int rows = wpb * kWave * RU;
+  const long long row_blocks = (s.M + 1 + rows - 1) / rows;
+  const dim3 grid((unsigned)(row_blocks * jsplit * s.B)), block(wpb * kWave);
+  if (bp_l)
+    hipLaunchKernelGGL((k_dp_push<SP, RU, true>), grid, block, 0, st, src, dst, (uint8_t *)bp_l,
+                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L, s.S, l, s.pitch,
+                       jsplit);
+  else
+    hipLaunchKernelGGL((k_dp_push<SP, RU, false>), grid, block, 0, st, src, dst,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
+                       s.L, s.S, l, s.pitch, jsplit);
+}
+
 template <int SP>
 static void launch_push(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                         void *bp_l, hipStream_t st) {
   int jsplit, wpb;
   push_launch_shape(s, jsplit, wpb);
-  const int rows = wpb * kWave;
-  const long long row_blocks = (s.M + 1 + rows - 1) / rows;
-  const dim3 grid((unsigned)(row_blocks * jsplit * s.B)), block(rows);
-  if (bp_l)
-    hipLaunchKernelGGL((k_dp_push<SP, true>), grid, block, 0, st, src, dst, (uint8_t *)bp_l,
-                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L, s.S, l, s.pitch,
-                       jsplit);
-  else
-    hipLaunchKernelGGL((k_dp_push<SP, false>), grid, block, 0, st, src, dst,
-                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
-                       s.L, s.S, l, s.pitch, jsplit);
+  // Row groups per wave.  Measured: they pay only for the min-only pass (5 % on the outer
+  // search batch), where the shared scalar loads and loop overhead are a large part of a
+  // short column; the flat argmin is bound by its own instruction count either way and
+  // loses occupancy to the extra registers.  Used while the batch still yields at least
+  // eight waves per SIMD.  GSEARCH_ROW_GROUPS overrides.
+  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B * jsplit;
+  int ru = tuning().row_groups;
+  if (ru < 1) ru = bp_l ? 1 : (tiles >= 4 * 8192 ? 4 : (tiles >= 2 * 8192 ? 2 : 1));
+  if constexpr (SP <= 24) {
+    if (ru >= 4) return launch_push_ru<SP, 4>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
+  }
+  if constexpr (SP <= 48) {
+    if (ru >= 2) return launch_push_ru<SP, 2>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
+  }
+  launch_push_ru<SP, 1>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
 }
 
 const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,
