@@ -88,6 +88,21 @@ __global__ __launch_bounds__(256) void k_prepare(
 
 __global__ void k_clear_status(int32_t *status) { *status = 0; }
 
+// lowsum[b][l] = min(M+1, sum_{l' <= l} min_s O[l'][s]): a plan of layers 0..l needs at
+// least that many bins, so C[l][e][.] is +inf for every e below it.  The forward kernels
+// use it to fill those rows without computing them.  One thread per instance.
+__global__ void k_prefix_min_memory(const int32_t *__restrict__ minO,
+                                    int32_t *__restrict__ lowsum, int B, int L, int M) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int acc = 0;
+  for (int l = 0; l < L; ++l) {
+    acc += minO[(size_t)b * L + l];
+    if (acc > M + 1) acc = M + 1;
+    lowsum[(size_t)b * L + l] = acc;
+  }
+}
+
 // Layer 0 has no predecessor: C[0][e][s] = T[0][s] if e >= O[0][s] else +inf.
 __global__ void k_init_layer0(float *__restrict__ plane, const float *__restrict__ Tq,
                               const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
@@ -496,6 +511,8 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
   hipLaunchKernelGGL(k_prepare, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, T, O, R,
                      r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B,
                      s.L, s.S, s.M, s.K, s.SP);
+  hipLaunchKernelGGL(k_prefix_min_memory, dim3((s.B + 63) / 64), dim3(64), 0, st, w.minO,
+                     w.lowsum, s.B, s.L, s.M);
 }
 
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st) {

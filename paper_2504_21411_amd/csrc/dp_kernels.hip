@@ -252,7 +252,8 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO, int B, int L, int S,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ lowsum, int B, int L, int S,
     int l, int pitch, int jsplit) {
   // blockIdx.x = (row_block * jsplit + js) * B + b: consecutive workgroups belong to
   // different instances, so the round-robin of workgroups over the eight XCDs spreads
@@ -273,8 +274,11 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
 
   const int row0 = tile_start + lane;
   const int bl = b * L + l;
-  // source rows above E - min_s O[l][s] feed no target row
-  const bool compute = tile_start <= E - minO[bl];
+  // source rows above E - min_s O[l][s] feed no target row; source rows below `low`, the
+  // least memory any plan of layers 0..l-1 needs, hold +inf only, so their targets are
+  // filled with +inf by the row owners below instead of being computed
+  const int low = lowsum[bl - 1];
+  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave * RU > low;
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
@@ -327,17 +331,17 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
       for (int u = 0; u < RU; ++u) {
         const int row = row0 + u * kWave;
         const int eo = row + o;
-        if (row <= E && eo <= E) {
+        if (row >= low && eo <= E) {
           dstb[(size_t)j * pitch + eo] = m[u] + t;
           if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg[u];
         }
       }
     }
-    if (tile_start < o) {
+    if (tile_start < o + low) {
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
         const int row = row0 + u * kWave;
-        if (row <= E && row < o) {
+        if (row <= E && row < o + low) {
           dstb[(size_t)j * pitch + row] = GS_INF;
           if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
         }
@@ -371,7 +375,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
     const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO, int B, int L, int S,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ lowsum, int B, int L, int S,
     int l, int pitch) {
   extern __shared__ float tile[]; // [SP][64]
   const int b = blockIdx.x % B;
@@ -385,7 +390,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   const int row = tile_start + lane;
   const bool valid = row <= E;
   const int bl = b * L + l;
-  const bool compute = tile_start <= E - minO[bl]; // uniform over the workgroup
+  const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
+  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave > low; // uniform
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
@@ -442,13 +448,13 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
         arg = (v0 == m) ? 8 * g : arg;
       }
       const int eo = row + o;
-      if (valid && eo <= E) {
+      if (row >= low && eo <= E) {
         dstb[(size_t)j * pitch + eo] = m + t;
         if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg;
       }
     }
-    if (tile_start < o) {
-      if (valid && row < o) {
+    if (tile_start < o + low) {
+      if (valid && row < o + low) {
         dstb[(size_t)j * pitch + row] = GS_INF;
         if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
       }
@@ -647,11 +653,11 @@ static void launch_tile_nw(const Shape &s, const Workspace &w, int l, const floa
   const size_t lds = sizeof(float) * SP * kWave;
   if (bp_l)
     hipLaunchKernelGGL((k_dp_tile<SP, NW, true>), grid, block, lds, st, src, dst,
-                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L,
+                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
                        s.S, l, s.pitch);
   else
     hipLaunchKernelGGL((k_dp_tile<SP, NW, false>), grid, block, lds, st, src, dst,
-                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
                        s.L, s.S, l, s.pitch);
 }
 
@@ -671,11 +677,11 @@ static void launch_push_ru(const Shape &s, const Workspace &w, int l, const floa
   const dim3 grid((unsigned)(row_blocks * jsplit * s.B)), block(wpb * kWave);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_push<SP, RU, true>), grid, block, 0, st, src, dst, (uint8_t *)bp_l,
-                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B, s.L, s.S, l, s.pitch,
+                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, l, s.pitch,
                        jsplit);
   else
     hipLaunchKernelGGL((k_dp_push<SP, RU, false>), grid, block, 0, st, src, dst,
-                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, s.B,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
                        s.L, s.S, l, s.pitch, jsplit);
 }
 

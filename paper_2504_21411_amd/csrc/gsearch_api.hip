@@ -11,7 +11,7 @@ namespace {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t planes, bp, Tq, Oq, Rt, ridx, budget, minO, best_s, best_cost, status, total;
+  size_t planes, bp, Tq, Oq, Rt, ridx, budget, minO, lowsum, best_s, best_cost, status, total;
   int nplanes;
 };
 
@@ -47,6 +47,7 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.ridx = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.budget = take(sizeof(int32_t) * (size_t)s.B);
   y.minO = take(sizeof(int32_t) * (size_t)s.B * s.L);
+  y.lowsum = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.best_s = take(sizeof(int32_t) * (size_t)s.B);
   y.best_cost = take(sizeof(float) * (size_t)s.B);
   y.status = take(sizeof(int32_t));
@@ -182,6 +183,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   w.ridx = reinterpret_cast<int32_t *>(base + y.ridx);
   w.budget = reinterpret_cast<int32_t *>(base + y.budget);
   w.minO = reinterpret_cast<int32_t *>(base + y.minO);
+  w.lowsum = reinterpret_cast<int32_t *>(base + y.lowsum);
   w.best_s = reinterpret_cast<int32_t *>(base + y.best_s);
   w.best_cost = reinterpret_cast<float *>(base + y.best_cost);
   w.status = reinterpret_cast<int32_t *>(base + y.status);

@@ -29,6 +29,8 @@ struct Workspace {
   int32_t *ridx;     // [B][L]       clamped r_index (entry l=0 is 0)
   int32_t *budget;   // [B]          clamped budgets
   int32_t *minO;     // [B][L]       min_s Oq
+  int32_t *lowsum;   // [B][L]       sum over layers 0..l of minO, clamped to M+1: budget rows
+                     //              below it cannot hold any plan of layers 0..l (all +inf)
   int32_t *best_s;   // [B]          result of the final reduction (kept for backtrace)
   float *best_cost;  // [B]
   int32_t *status;   // [1]          data-status bits
