@@ -115,11 +115,22 @@ def main():
             assert ctx.gsearch_data_status() == 0
             best = int(out["best_instance"].cpu()[0])
             kernel = ctx.gsearch_forward_kernel()
+            # Share of the (layer, budget row) pairs the forward kernels really computed:
+            # rows below the prefix sum of the per-layer minimum memory are filled with
+            # +inf without being computed (64-row tile granularity).  Reporting only.
+            import numpy as np
+            O = (out["O"] if "O" in out else dw.O).cpu().numpy().astype(np.int64)
+            low = np.minimum(np.cumsum(np.minimum(O.min(axis=2), w.M + 1), axis=1), w.M + 1)
+            rows = w.budget.astype(np.int64)[:, None] + 1
+            skipped = np.minimum(low[:, :-1] // 64 * 64, rows)
+            executed = float((rows - skipped).sum()) / float((rows * (w.L - 1)).sum())
+            if kernel not in ("k_dp_push", "k_dp_tile"):
+                executed = 1.0
         ms_step = dt * 1e3 / args.steps
         fwd_ms = sum(fwd) / len(fwd)
         launches = w.L - 1
         opr = ops_per_relaxation(kernel, mode, w.S)
-        ops = opr * relax / launches                            # per launch
+        ops = opr * relax * executed / launches                 # executed, per launch
         achieved = ops / (fwd_ms * 1e-3 / launches) / 1e12
         return {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
                 "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
@@ -128,7 +139,8 @@ def main():
                 "roofline": {"bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TLANEOPS,
                              "unit": "Tlaneop/s", "frac": achieved / ALU_PEAK_TLANEOPS,
                              "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode)),
-                             "kernel": kernel, "ops_per_relaxation": opr},
+                             "kernel": kernel, "ops_per_relaxation": opr,
+                             "executed_fraction_of_nominal_relaxations": executed},
                 "best_instance": best}
 
     main_res = time_mode(args.mode)
