@@ -354,3 +354,30 @@ def test_pipeline_aware_reduction(gs, oracle_mod):
         bad = off.copy(); bad[3] = 10 ** 6
         cost2, _ = ctx.gsearch_pipeline_reduce(t32(bad), t32(mem), t32(mic))
         assert np.isinf(cost2.cpu().numpy()[2:4]).all()
+
+
+def test_random_shape_sweep(gs, oracle_mod):
+    """Forty seeded random shapes (strategy counts around every register-tile size, ragged
+    budgets, zero-memory and never-fitting strategies, forbidden transitions), each through
+    the automatic kernel choice and one forced variant."""
+    _, runner = gs
+    rng = workloads.SplitMix64(2024)
+    variants = [0x8, 0x10, 0x2, 0xC, 0x14, 0x4]
+    for case in range(40):
+        v = rng.randint(0, 10 ** 6, 8)
+        S = [1, 2, 7, 8, 9, 15, 16, 17, 23, 24, 25, 31, 33, 47, 48, 49, 63, 64, 65, 95, 96, 97,
+             127, 128, 129][int(v[0]) % 25]
+        B, L, M, K = 1 + int(v[1]) % 5, 1 + int(v[2]) % 6, 1 + int(v[3]) % 700, 1 + int(v[4]) % 3
+        budget = rng.randint(0, M, B).astype(np.int32)
+        w = random_tables(f"sweep{case}", B, L, S, M, K=K, seed=5000 + case, budget=budget,
+                          o_hi=max(1, M // max(1, L - 1)), integer=(case % 4 == 0))
+        if case % 3 == 0:
+            w.O[int(v[5]) % B, int(v[6]) % L, int(v[7]) % S] = 0
+        if case % 5 == 0:
+            w.O[:, int(v[5]) % L, int(v[6]) % S] = M + 7
+        if case % 7 == 0:
+            w.R[int(v[5]) % K, int(v[6]) % S, :] = np.inf
+        ref = oracle_batch(oracle_mod, w)
+        assert_same(runner.solve_workload(w, 0), ref, w, "auto")
+        flags = variants[case % len(variants)]
+        assert_same(runner.solve_workload(w, flags), ref, w, f"flags={flags:#x}")
