@@ -238,6 +238,39 @@ int gsearch_build_tables(int32_t B, int32_t L, int32_t S, int32_t M, int32_t K,
                          const gsearch_hw_model *hw, const gsearch_reshard_model *rmodel,
                          float *T, int32_t *O, float *R, void *stream);
 
+/* ---- profile-driven cost tables (paper section 2, "Profiler": measured per-layer compute
+ * time and memory and measured inter-device bandwidth at different group sizes are what
+ * the cost models are built from; the paper prints no formula, this is this library's
+ * reading).  Same conventions as gsearch_build_tables; R is not touched.
+ *   layer_type device [B][L]   index into profile
+ *   profile    device [Y]      per layer type: forward ms per 1000 tokens at tp = 1,
+ *                              parameter bytes, activation bytes per token
+ *   bandwidth  device [NB]     measured collective bandwidth (bytes/s) of a group of 2^g
+ *                              devices, entry g (entry 0 unused)
+ *   par        host
+ * With t = tokens/(dp*sp):
+ *   comp    = 3 * fwd_ms * (t/1000) / tp, x 4/3 under recomputation
+ *   tp_comm = [tp>1] 1000 * (4 act t (tp-1)/tp) / bandwidth[log2 tp]
+ *   dp_comm = [dp>1] 1000 * (2 (param/tp) (dp-1)/dp (x1.5 if sdp)) / bandwidth[log2 dp]
+ *   sp_comm = [sp>1] 1000 * (2 act t (sp-1)/sp) / bandwidth[log2 sp]
+ *   T = fp32( ((comp + tp_comm) + (1 - overlap) * dp_comm) + sp_comm )
+ *   mem = state_factor * param / (tp*(sdp?dp:1)) + (act t / tp) * (ckpt ? ckpt_keep : 1)
+ *   O = min(max(1, ceil(mem/bin_bytes)), M+1)
+ * A layer type outside [0, Y) or a degree beyond the bandwidth table gives T = +inf and
+ * O = M+1 (the solve then flags the table as invalid). */
+typedef struct {
+  double fwd_ms_per_ktoken, param_bytes, act_bytes_per_token;
+} gsearch_layer_profile;
+typedef struct {
+  double tokens, overlap, bin_bytes, ckpt_keep, state_factor;
+} gsearch_profile_params;
+
+int gsearch_build_tables_profiled(int32_t B, int32_t L, int32_t S, int32_t M, int32_t Y,
+                                  int32_t NB, const int32_t *desc, const int32_t *layer_type,
+                                  const gsearch_layer_profile *profile, const double *bandwidth,
+                                  const gsearch_profile_params *par, float *T, int32_t *O,
+                                  void *stream);
+
 /* Static description of an error code. */
 const char *gsearch_strerror(int status);
 

@@ -209,3 +209,24 @@ def pipeline_reduce(stage_cost, group_offsets, group_members, group_micro):
     if rc != 0:
         raise ValueError("oracle_pipeline_reduce: bad arguments")
     return cost, int(best[0])
+
+
+def build_tables_profiled(desc, layer_type, profile, bw, par, M):
+    """Profile-driven tables.  desc [S][5]; layer_type [B][L]; profile [Y][3]; bw [NB]; par [5]."""
+    lib = _load()
+    desc, layer_type = _i32(desc), _i32(layer_type)
+    profile = np.ascontiguousarray(profile, dtype=np.float64)
+    bw = np.ascontiguousarray(bw, dtype=np.float64)
+    par = np.ascontiguousarray(par, dtype=np.float64)
+    B, L = layer_type.shape
+    S = desc.shape[0]
+    T = np.zeros((B, L, S), np.float32)
+    O = np.zeros((B, L, S), np.int32)
+    rc = lib.oracle_build_tables_profiled(
+        ctypes.c_int32(B), ctypes.c_int32(L), ctypes.c_int32(S), ctypes.c_int32(int(M)),
+        ctypes.c_int32(profile.shape[0]), ctypes.c_int32(bw.shape[0]), _p(desc, ctypes.c_int32),
+        _p(layer_type, ctypes.c_int32), _p(profile, ctypes.c_double), _p(bw, ctypes.c_double),
+        _p(par, ctypes.c_double), _p(T, ctypes.c_float), _p(O, ctypes.c_int32))
+    if rc != 0:
+        raise ValueError(f"oracle_build_tables_profiled failed with code {rc}")
+    return T, O

@@ -373,3 +373,99 @@ int oracle_build_tables(int32_t B, int32_t L, int32_t S, int32_t M, int32_t K,
     }
     return ORACLE_OK;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Profile-driven cost tables (paper section 2, "Profiler" and "Search Engine": measured
+ * per-layer compute time and memory and measured inter-device bandwidth at different
+ * group sizes feed the cost models; section 3 step 3).  The paper prints no formula; this
+ * reading is this build's own ("parity unpinned" against the paper).  fp64, one rounding
+ * per operation in the order written, one final rounding.
+ *
+ *   layer_type [B][L]      index into profile
+ *   profile    [Y][3]      { fwd_ms_per_1000_tokens at tp = 1, param_bytes, act_bytes_per_token }
+ *   bw         [NB]        measured collective bandwidth in bytes/s for a group of 2^g devices
+ *                          (entry g; entry 0 unused)
+ *   par        [5]         { tokens, overlap in [0,1], bin_bytes, ckpt_keep, state_factor }
+ * With t = tokens / (dp * sp):
+ *   comp    = 3 * fwd_ms * (t / 1000) / tp, times 4/3 under recomputation
+ *   tp_comm = [tp>1] 1000 * (4 * act * t * (tp-1)/tp) / bw[log2 tp]
+ *   dp_comm = [dp>1] 1000 * (2 * (param/tp) * (dp-1)/dp * (sdp ? 1.5 : 1)) / bw[log2 dp]
+ *   sp_comm = [sp>1] 1000 * (2 * act * t * (sp-1)/sp) / bw[log2 sp]
+ *   T = fp32( ((comp + tp_comm) + (1 - overlap) * dp_comm) + sp_comm )
+ *   mem = state_factor * param / (tp * (sdp ? dp : 1)) + (act * t / tp) * (ckpt ? ckpt_keep : 1)
+ *   O = min(max(1, ceil(mem / bin_bytes)), M + 1)
+ * ---------------------------------------------------------------------------------------- */
+static int ilog2_i32(int32_t v) { int g = 0; while ((1 << g) < v) ++g; return g; }
+
+int oracle_build_tables_profiled(int32_t B, int32_t L, int32_t S, int32_t M, int32_t Y,
+                                 int32_t NB, const int32_t *desc, const int32_t *layer_type,
+                                 const double *profile, const double *bw, const double *par,
+                                 float *T, int32_t *O)
+{
+    if (B < 1 || L < 1 || S < 1 || M < 1 || Y < 1 || NB < 1 || !desc || !layer_type ||
+        !profile || !bw || !par || !T || !O)
+        return ORACLE_BAD_ARG;
+    const double tokens = par[0], overlap = par[1], bin = par[2], keep = par[3], sf = par[4];
+    for (int64_t x = 0; x < (int64_t)B * L; ++x) {
+        const int32_t y = layer_type[x];
+        if (y < 0 || y >= Y) return ORACLE_BAD_ARG;
+        const double fwd = profile[(size_t)y * 3], param = profile[(size_t)y * 3 + 1];
+        const double act = profile[(size_t)y * 3 + 2];
+        for (int32_t s = 0; s < S; ++s) {
+            const int32_t *d = desc + (size_t)s * 5;
+            const double tp = d[0], sp = d[1], dp = d[2];
+            const int gt = ilog2_i32(d[0]), gs = ilog2_i32(d[1]), gd = ilog2_i32(d[2]);
+            if (gt >= NB || gs >= NB || gd >= NB) return ORACLE_BAD_ARG;
+            const double t = tokens / (dp * sp);
+            double comp = t / 1000.0;
+            comp = fwd * comp;
+            comp = 3.0 * comp;
+            comp = comp / tp;
+            if (d[4]) { comp = comp * 4.0; comp = comp / 3.0; }
+            double tpc = 0.0, dpc = 0.0, spc = 0.0;
+            if (d[0] > 1) {
+                double v = 4.0 * act;
+                v = v * t;
+                v = v * (tp - 1.0);
+                v = v / tp;
+                v = 1000.0 * v;
+                tpc = v / bw[gt];
+            }
+            if (d[2] > 1) {
+                double v = param / tp;
+                v = 2.0 * v;
+                v = v * (dp - 1.0);
+                v = v / dp;
+                if (d[3]) v = v * 1.5;
+                v = 1000.0 * v;
+                dpc = v / bw[gd];
+            }
+            if (d[1] > 1) {
+                double v = 2.0 * act;
+                v = v * t;
+                v = v * (sp - 1.0);
+                v = v / sp;
+                v = 1000.0 * v;
+                spc = v / bw[gs];
+            }
+            double ms = comp + tpc;
+            ms = ms + (1.0 - overlap) * dpc;
+            ms = ms + spc;
+            T[(size_t)x * S + s] = (float)ms;
+
+            const double shard = d[3] ? dp : 1.0;
+            double state = sf * param;
+            state = state / (tp * shard);
+            double a = act * t;
+            a = a / tp;
+            if (d[4]) a = a * keep;
+            const double bins = ceil((state + a) / bin);
+            int32_t o;
+            if (!(bins >= 1.0)) o = 1;
+            else if (bins > (double)M + 1.0) o = M + 1;
+            else o = (int32_t)bins;
+            O[(size_t)x * S + s] = o;
+        }
+    }
+    return ORACLE_OK;
+}

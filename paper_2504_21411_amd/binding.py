@@ -39,7 +39,7 @@ EXPORTS = [
     "gsearch_backtrace", "gsearch_data_status", "gsearch_budget_curve", "gsearch_export_planes",
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
-    "gsearch_pipeline_reduce",
+    "gsearch_pipeline_reduce", "gsearch_build_tables_profiled",
 ]
 
 
@@ -64,6 +64,12 @@ class gsearch_result(ctypes.Structure):
 class gsearch_hw_model(ctypes.Structure):
     _fields_ = [("flops_per_s", ctypes.c_double), ("bytes_per_s", ctypes.c_double),
                 ("bin_bytes", ctypes.c_double), ("ckpt_keep", ctypes.c_double)]
+
+
+class gsearch_profile_params(ctypes.Structure):
+    _fields_ = [("tokens", ctypes.c_double), ("overlap", ctypes.c_double),
+                ("bin_bytes", ctypes.c_double), ("ckpt_keep", ctypes.c_double),
+                ("state_factor", ctypes.c_double)]
 
 
 class GSearchError(RuntimeError):
@@ -118,6 +124,10 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_build_tables.restype = ctypes.c_int
     lib.gsearch_build_tables.argtypes = [i32, i32, i32, i32, i32, vp, vp,
                                          ctypes.POINTER(gsearch_hw_model), vp, vp, vp, vp, vp]
+    lib.gsearch_build_tables_profiled.restype = ctypes.c_int
+    lib.gsearch_build_tables_profiled.argtypes = [i32, i32, i32, i32, i32, i32, vp, vp, vp, vp,
+                                                  ctypes.POINTER(gsearch_profile_params), vp, vp,
+                                                  vp]
     lib.gsearch_strerror.restype = ctypes.c_char_p
     lib.gsearch_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -194,6 +204,25 @@ def gsearch_build_tables(desc, layer, hw, rmodel, M, stream=None):
         ctypes.byref(hwm), _ptr(rmodel, torch.float64, "rmodel"), _ptr(T), _ptr(O), _ptr(R),
         _stream(stream)), "gsearch_build_tables")
     return T, O, R
+
+
+def gsearch_build_tables_profiled(desc, layer_type, profile, bandwidth, par, M, stream=None):
+    """desc int32 [S][5], layer_type int32 [B][L], profile fp64 [Y][3], bandwidth fp64 [NB] on
+    the GPU; par = (tokens, overlap, bin_bytes, ckpt_keep, state_factor).
+    Returns device tensors T [B][L][S] fp32 and O [B][L][S] int32."""
+    import torch
+    B, L = layer_type.shape
+    S = desc.shape[0]
+    dev = layer_type.device
+    T = torch.empty((B, L, S), dtype=torch.float32, device=dev)
+    O = torch.empty((B, L, S), dtype=torch.int32, device=dev)
+    pp = gsearch_profile_params(*[float(x) for x in par])
+    _check(load_library().gsearch_build_tables_profiled(
+        B, L, S, int(M), int(profile.shape[0]), int(bandwidth.numel()),
+        _ptr(desc, torch.int32, "desc"), _ptr(layer_type, torch.int32, "layer_type"),
+        _ptr(profile, torch.float64, "profile"), _ptr(bandwidth, torch.float64, "bandwidth"),
+        ctypes.byref(pp), _ptr(T), _ptr(O), _stream(stream)), "gsearch_build_tables_profiled")
+    return T, O
 
 
 class GSearch:

@@ -467,6 +467,91 @@ __global__ void k_build_TO(int B, int L, int S, int M, const int32_t *__restrict
   }
 }
 
+// Profile-driven tables: measured per-layer-type compute time and memory plus measured
+// collective bandwidth per group size (see include/gsearch.h for the formula).  fp64, one
+// rounding per operation in the order written.  A layer type outside [0, Y) or a degree
+// whose log2 is not covered by the bandwidth table yields T = +inf, O = M+1 (never fits).
+__global__ void k_build_TO_profiled(int B, int L, int S, int M, int Y, int NB,
+                                    const int32_t *__restrict__ desc,
+                                    const int32_t *__restrict__ layer_type,
+                                    const double *__restrict__ profile,
+                                    const double *__restrict__ bw, double tokens, double overlap,
+                                    double bin, double keep, double sf, float *__restrict__ T,
+                                    int32_t *__restrict__ O) {
+  const long long total = (long long)B * L * S;
+  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
+       x += (long long)gridDim.x * blockDim.x) {
+    const int s = (int)(x % S);
+    const long long row = x / S;
+    const int y = layer_type[row];
+    const int itp = desc[s * 5 + 0], isp = desc[s * 5 + 1], idp = desc[s * 5 + 2];
+    const int sdp = desc[s * 5 + 3], ckpt = desc[s * 5 + 4];
+    int gt = 0, gs = 0, gd = 0;
+    while ((1 << gt) < itp) ++gt;
+    while ((1 << gs) < isp) ++gs;
+    while ((1 << gd) < idp) ++gd;
+    if (y < 0 || y >= Y || gt >= NB || gs >= NB || gd >= NB) {
+      T[x] = GS_INF;
+      O[x] = M + 1;
+      continue;
+    }
+    const double fwd = profile[y * 3], param = profile[y * 3 + 1], act = profile[y * 3 + 2];
+    const double tp = itp, sp = isp, dp = idp;
+    const double t = tokens / (dp * sp);
+    double comp = t / 1000.0;
+    comp = fwd * comp;
+    comp = 3.0 * comp;
+    comp = comp / tp;
+    if (ckpt) {
+      comp = comp * 4.0;
+      comp = comp / 3.0;
+    }
+    double tpc = 0.0, dpc = 0.0, spc = 0.0;
+    if (itp > 1) {
+      double v = 4.0 * act;
+      v = v * t;
+      v = v * (tp - 1.0);
+      v = v / tp;
+      v = 1000.0 * v;
+      tpc = v / bw[gt];
+    }
+    if (idp > 1) {
+      double v = param / tp;
+      v = 2.0 * v;
+      v = v * (dp - 1.0);
+      v = v / dp;
+      if (sdp) v = v * 1.5;
+      v = 1000.0 * v;
+      dpc = v / bw[gd];
+    }
+    if (isp > 1) {
+      double v = 2.0 * act;
+      v = v * t;
+      v = v * (sp - 1.0);
+      v = v / sp;
+      v = 1000.0 * v;
+      spc = v / bw[gs];
+    }
+    double ms = comp + tpc;
+    ms = ms + (1.0 - overlap) * dpc;
+    ms = ms + spc;
+    T[x] = (float)ms;
+
+    const double shard = sdp ? dp : 1.0;
+    double state = sf * param;
+    state = state / (tp * shard);
+    double a = act * t;
+    a = a / tp;
+    if (ckpt) a = a * keep;
+    const double bins = ceil((state + a) / bin);
+    int o;
+    if (!(bins >= 1.0)) o = 1;
+    else if (bins > (double)M + 1.0) o = M + 1;
+    else o = (int)bins;
+    O[x] = o;
+  }
+}
+
 __global__ void k_build_R(int S, int K, const int32_t *__restrict__ desc,
                           const double *__restrict__ rmodel, double BW, float *__restrict__ R) {
   const long long total = (long long)K * S * S;
@@ -584,6 +669,15 @@ void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc
   while ((1 << k) < N) ++k;
   hipLaunchKernelGGL(k_enumerate, dim3(1), dim3(1024), 0, st, N, k, tp_max, sp_max, tpsp_max,
                      desc, cap, count_out);
+}
+
+void launch_build_tables_profiled(int B, int L, int S, int M, int Y, int NB, const int32_t *desc,
+                                  const int32_t *layer_type, const double *profile,
+                                  const double *bw, double tokens, double overlap, double bin,
+                                  double keep, double sf, float *T, int32_t *O, hipStream_t st) {
+  hipLaunchKernelGGL(k_build_TO_profiled, dim3(blocks_for((long long)B * L * S, 256)), dim3(256),
+                     0, st, B, L, S, M, Y, NB, desc, layer_type, profile, bw, tokens, overlap, bin,
+                     keep, sf, T, O);
 }
 
 void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,

@@ -367,4 +367,22 @@ int gsearch_build_tables(int32_t B, int32_t L, int32_t S, int32_t M, int32_t K,
   return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
 }
 
+int gsearch_build_tables_profiled(int32_t B, int32_t L, int32_t S, int32_t M, int32_t Y,
+                                  int32_t NB, const int32_t *desc, const int32_t *layer_type,
+                                  const gsearch_layer_profile *profile, const double *bandwidth,
+                                  const gsearch_profile_params *par, float *T, int32_t *O,
+                                  void *stream) {
+  if (B < 1 || L < 1 || S < 1 || M < 1 || Y < 1 || NB < 1 || !desc || !layer_type || !profile ||
+      !bandwidth || !par || !T || !O)
+    return GSEARCH_ERR_INVALID_ARG;
+  if (!(par->tokens > 0.0) || !(par->bin_bytes > 0.0) || !(par->overlap >= 0.0) ||
+      !(par->overlap <= 1.0))
+    return GSEARCH_ERR_INVALID_ARG;
+  gs::launch_build_tables_profiled(B, L, S, M, Y, NB, desc, layer_type,
+                                   reinterpret_cast<const double *>(profile), bandwidth,
+                                   par->tokens, par->overlap, par->bin_bytes, par->ckpt_keep,
+                                   par->state_factor, T, O, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
+}
+
 } // extern "C"

@@ -68,6 +68,10 @@ void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_p
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st);
 void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,
                       int32_t *count_out, hipStream_t st);
+void launch_build_tables_profiled(int B, int L, int S, int M, int Y, int NB, const int32_t *desc,
+                                  const int32_t *layer_type, const double *profile,
+                                  const double *bw, double tokens, double overlap, double bin,
+                                  double keep, double sf, float *T, int32_t *O, hipStream_t st);
 void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,
                          const double *layer, double flops_per_s, double bytes_per_s,
                          double bin_bytes, double ckpt_keep, const double *rmodel, float *T,

@@ -267,6 +267,31 @@ def config4(B=2048) -> Workload:
                               groups=pipeline_groups(pp, split, stage, micro)))
 
 
+def load_profile_dump(path, M):
+    """Read a profiler-dump-shaped JSON file into the arrays the profiled table builder takes.
+
+    Returns (type_names, profile fp64 [Y][3], bandwidth fp64 [NB], par fp64 [5]) with
+    par = (tokens, overlap, bin_bytes, ckpt_keep, state_factor), bin_bytes = device_bytes / M.
+    Only reshapes the file's numbers; no cost-model arithmetic happens here.
+    """
+    import json
+    with open(path) as fh:
+        d = json.load(fh)
+    names = sorted(d["layer_types"])
+    profile = np.asarray([[d["layer_types"][n]["fwd_ms_per_ktoken"],
+                           d["layer_types"][n]["param_bytes"],
+                           d["layer_types"][n]["act_bytes_per_token"]] for n in names], np.float64)
+    sizes = {int(k): float(v) for k, v in d["allreduce_bandwidth_bytes_per_s"].items()}
+    nb = max(sizes).bit_length()
+    bw = np.full(nb, min(sizes.values()), np.float64)
+    for g in range(1, nb):
+        if (1 << g) in sizes:
+            bw[g] = sizes[1 << g]
+    par = np.asarray([d["tokens_per_step"], d["overlap"], d["device_bytes"] / M, d["ckpt_keep"],
+                      d["state_factor"]], np.float64)
+    return names, profile, bw, par
+
+
 CONFIGS = [config0, config1, config2, config3, config4]
 
 

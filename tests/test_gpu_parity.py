@@ -381,3 +381,32 @@ def test_random_shape_sweep(gs, oracle_mod):
         assert_same(runner.solve_workload(w, 0), ref, w, "auto")
         flags = variants[case % len(variants)]
         assert_same(runner.solve_workload(w, flags), ref, w, f"flags={flags:#x}")
+
+
+def test_profiled_table_builder_matches_oracle_and_solves(gs, oracle_mod):
+    """Tables built on the GPU from a profiler-dump-shaped file equal the oracle's bit for
+    bit, and a solve on them matches the oracle's solve."""
+    import torch
+    binding, runner = gs
+    path = os.path.join(os.path.dirname(__file__), "data", "profile_dump_example.json")
+    M, B, L = 4096, 6, 20
+    names, profile, bw, par = workloads.load_profile_dump(path, M)
+    rng = workloads.SplitMix64(77)
+    ltype = rng.randint(0, len(names) - 1, B * L).astype(np.int32).reshape(B, L)
+    desc, _ = binding.gsearch_enumerate(32, 8, 4, 16)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    T, O = binding.gsearch_build_tables_profiled(desc, dev(ltype), dev(profile), dev(bw), par, M)
+    Tr, Or = oracle_mod.build_tables_profiled(desc.cpu().numpy(), ltype, profile, bw, par, M)
+    assert np.array_equal(bits(T.cpu().numpy()), bits(Tr)) and np.array_equal(O.cpu().numpy(), Or)
+    S = desc.shape[0]
+    base = random_tables("prof", B, L, S, M, K=1, seed=78)
+    w = Workload("profiled", B, L, S, M, 1, np.full(B, M, np.int32), np.zeros((B, L), np.int32),
+                 "tables", T=Tr, O=Or, R=base.R)
+    got = runner.solve_workload(w)
+    ref = oracle_batch(oracle_mod, w)
+    assert_same(got, ref, w, "profiled")
+    assert np.isfinite(ref["best_cost"]).all() and len(np.unique(ref["plan"])) > 1
+    # a layer type outside the profile poisons the table, and the solve reports it
+    bad = ltype.copy(); bad[2, 3] = 9
+    T2, O2 = binding.gsearch_build_tables_profiled(desc, dev(bad), dev(profile), dev(bw), par, M)
+    assert np.isinf(T2.cpu().numpy()[2, 3]).all() and (O2.cpu().numpy()[2, 3] == M + 1).all()

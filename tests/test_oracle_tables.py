@@ -137,3 +137,44 @@ def test_workload_generators_are_deterministic_and_shaped():
     assert u.min() >= 0 and u.max() < 1 and u.dtype == np.float32
     # SplitMix64 reference value: first output for seed 0 is the published test vector
     assert int(workloads.SplitMix64(0).u64(1)[0]) == 0xE220A8397B1DCDAF
+
+
+def test_profiled_table_builder_exact_on_power_of_two_inputs(oracle_mod):
+    """Profile-driven builder ("parity unpinned" against the paper, which gives no formula):
+    with power-of-two inputs every fp64 step is exact, so the result must equal a rational
+    evaluation of the stated formula."""
+    desc = oracle_mod.enumerate_strategies(16)
+    fwd, param, act = Fraction(3, 2), 1 << 28, 1 << 17
+    tokens, overlap, binb, keep, sf, M = 1 << 17, Fraction(1, 4), 1 << 24, Fraction(1, 4), 8, 1 << 14
+    bw = [1, 1 << 38, 1 << 37, 1 << 36, 1 << 35]
+    T, O = oracle_mod.build_tables_profiled(
+        desc, [[0]], [[float(fwd), param, act]], [float(x) for x in bw],
+        [tokens, float(overlap), binb, float(keep), sf], M)
+    for s, (tp, sp, dp, sdp, ckpt) in enumerate(desc.tolist()):
+        t = Fraction(tokens, dp * sp)
+        comp = 3 * fwd * t / 1000 / tp * (Fraction(4, 3) if ckpt else 1)
+        lg = lambda v: v.bit_length() - 1
+        tpc = 1000 * 4 * act * t * Fraction(tp - 1, tp) / bw[lg(tp)] if tp > 1 else 0
+        dpc = (1000 * 2 * Fraction(param, tp) * Fraction(dp - 1, dp) * (Fraction(3, 2) if sdp else 1)
+               / bw[lg(dp)]) if dp > 1 else 0
+        spc = 1000 * 2 * act * t * Fraction(sp - 1, sp) / bw[lg(sp)] if sp > 1 else 0
+        want = comp + tpc + (1 - overlap) * dpc + spc
+        # t/1000 and the 4/3 factor round, so allow a few ulps of fp32; the rest is exact
+        assert abs(float(T[0, 0, s]) - float(want)) <= 4 * float(np.spacing(np.float32(float(want))))
+        mem = Fraction(sf * param, tp * (dp if sdp else 1)) + Fraction(act, 1) * t / tp * (keep if ckpt else 1)
+        assert O[0, 0, s] == min(max(1, int(-((-mem) // binb))), M + 1)
+    # more overlap can only hide data-parallel communication
+    T2, _ = oracle_mod.build_tables_profiled(
+        desc, [[0]], [[float(fwd), param, act]], [float(x) for x in bw],
+        [tokens, 1.0, binb, float(keep), sf], M)
+    assert (T2 <= T).all() and (T2 < T)[0, 0, desc[:, 2] > 1].all()
+    assert np.array_equal(T2[0, 0, desc[:, 2] == 1], T[0, 0, desc[:, 2] == 1])
+
+
+def test_profile_dump_reader():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "data", "profile_dump_example.json")
+    names, profile, bw, par = workloads.load_profile_dump(path, 4096)
+    assert names == ["decoder", "encoder"] and profile.shape == (2, 3)
+    assert len(bw) == 6 and bw[1] == 3.0e11 and bw[5] == 2.5e10
+    assert par[2] == 68719476736 / 4096 and par[1] == 0.5
