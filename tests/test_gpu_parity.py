@@ -410,3 +410,26 @@ def test_profiled_table_builder_matches_oracle_and_solves(gs, oracle_mod):
     bad = ltype.copy(); bad[2, 3] = 9
     T2, O2 = binding.gsearch_build_tables_profiled(desc, dev(bad), dev(profile), dev(bw), par, M)
     assert np.isinf(T2.cpu().numpy()[2, 3]).all() and (O2.cpu().numpy()[2, 3] == M + 1).all()
+
+
+def test_profiling_entry_points(gs):
+    binding, runner = gs
+    w = random_tables("timing", 4, 6, 96, 2000, seed=91)       # too large for the one-launch path
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w) as ctx:
+        assert ctx.gsearch_forward_kernel() == ""
+        runner.run_step(ctx, dw, backtrace=None)
+        with pytest.raises(binding.GSearchError) as ei:
+            ctx.gsearch_forward_ms()                            # profiling was off
+        assert ei.value.code == binding.GSEARCH_ERR_NOT_SOLVED
+        ctx.gsearch_set_profiling(True)
+        runner.run_step(ctx, dw, backtrace=None)
+        assert 0.0 < ctx.gsearch_forward_ms() < 1000.0
+        assert ctx.gsearch_forward_kernel() == "k_dp_tile"
+    small = random_tables("timing_small", 1, 5, 12, 100, seed=92)
+    with runner.make_context(small) as ctx:
+        runner.run_step(ctx, runner.DeviceWorkload(small), backtrace=None)
+        assert ctx.gsearch_forward_kernel() == "k_dp_small"
+    with runner.make_context(w, flags=binding.GSEARCH_FLAG_FORCE_GENERIC) as ctx:
+        runner.run_step(ctx, dw, backtrace=None)
+        assert ctx.gsearch_forward_kernel() == "k_dp_generic"
