@@ -115,6 +115,7 @@ def main():
             assert ctx.gsearch_data_status() == 0
             best = int(out["best_instance"].cpu()[0])
             kernel = ctx.gsearch_forward_kernel()
+            groups = max(1, ctx.gsearch_instance_groups())
             # Share of the (layer, budget row) pairs the forward kernels really computed:
             # rows below the prefix sum of the per-layer minimum memory are filled with
             # +inf without being computed (64-row tile granularity).  Reporting only.
@@ -128,10 +129,14 @@ def main():
                 executed = 1.0
         ms_step = dt * 1e3 / args.steps
         fwd_ms = sum(fwd) / len(fwd)
+        # The batch runs as `groups` chains of L-1 launches side by side (one stream each);
+        # every chain spans the forward time, so a launch lasts fwd/(L-1) on average and
+        # works on 1/groups of a layer front while the other chains' launches share the chip.
         launches = w.L - 1
         opr = ops_per_relaxation(kernel, mode, w.S)
-        ops = opr * relax * executed / launches                 # executed, per launch
-        achieved = ops / (fwd_ms * 1e-3 / launches) / 1e12
+        ops = opr * relax * executed / launches / groups        # executed, per launch
+        per_launch = ops / (fwd_ms * 1e-3 / launches) / 1e12
+        achieved = per_launch * groups                          # all concurrent launches
         return {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
                 "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
                 "forward_grelax_per_s": relax / (fwd_ms * 1e-3) / 1e9,
@@ -140,6 +145,8 @@ def main():
                              "unit": "Tlaneop/s", "frac": achieved / ALU_PEAK_TLANEOPS,
                              "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode)),
                              "kernel": kernel, "ops_per_relaxation": opr,
+                             "concurrent_launches": groups,
+                             "achieved_per_launch": per_launch,
                              "executed_fraction_of_nominal_relaxations": executed},
                 "best_instance": best}
 

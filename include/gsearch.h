@@ -149,6 +149,19 @@ int gsearch_backtrace(gsearch_ctx *ctx, const int32_t *instances, int32_t n, int
  * *host_bits (0 = tables were valid; else GSEARCH_DATA_* bits).  Errors: NOT_SOLVED, HIP. */
 int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits);
 
+/* Tuning.  The instances of a batch are independent, so a solve may cut the batch into
+ * `groups` contiguous groups whose chains of layer-front launches run side by side: the
+ * first on the caller's stream, the others on streams the context owns (default priority,
+ * created on first use), forked from and joined back into the caller's stream with events,
+ * so that work queued on the caller's stream after the solve still sees every result.
+ * Results do not depend on the number of groups.  groups = 0 restores the default (chosen
+ * from the batch shape); values above 8 or above B are clamped.  Applies to later solves.
+ * Errors: INVALID_ARG (null context, negative count). */
+int gsearch_set_instance_groups(gsearch_ctx *ctx, int groups);
+/* Number of groups the most recent solve ran side by side (1 for the one-launch path of
+ * small instances; 0 before any solve or for a null context). */
+int gsearch_instance_groups(gsearch_ctx *ctx);
+
 /* Measurement aid.  With profiling enabled, every later solve records one HIP event on
  * its stream just before the first forward-DP launch (layer 1) and one just after the
  * last (layer L-1).  gsearch_forward_ms waits for the second event of the most recent

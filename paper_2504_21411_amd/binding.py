@@ -39,7 +39,8 @@ EXPORTS = [
     "gsearch_backtrace", "gsearch_data_status", "gsearch_budget_curve", "gsearch_export_planes",
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
-    "gsearch_pipeline_reduce", "gsearch_build_tables_profiled",
+    "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
+    "gsearch_instance_groups",
 ]
 
 
@@ -107,6 +108,10 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_data_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
     lib.gsearch_set_profiling.restype = ctypes.c_int
     lib.gsearch_set_profiling.argtypes = [vp, ctypes.c_int]
+    lib.gsearch_set_instance_groups.restype = ctypes.c_int
+    lib.gsearch_set_instance_groups.argtypes = [vp, ctypes.c_int]
+    lib.gsearch_instance_groups.restype = ctypes.c_int
+    lib.gsearch_instance_groups.argtypes = [vp]
     lib.gsearch_forward_ms.restype = ctypes.c_int
     lib.gsearch_forward_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.gsearch_forward_kernel.restype = ctypes.c_char_p
@@ -309,6 +314,13 @@ class GSearch:
     def gsearch_set_profiling(self, enable: bool):
         _check(self._lib.gsearch_set_profiling(self._ctx, int(bool(enable))),
                "gsearch_set_profiling")
+
+    def gsearch_set_instance_groups(self, groups: int):
+        _check(self._lib.gsearch_set_instance_groups(self._ctx, int(groups)),
+               "gsearch_set_instance_groups")
+
+    def gsearch_instance_groups(self) -> int:
+        return int(self._lib.gsearch_instance_groups(self._ctx))
 
     def gsearch_forward_ms(self) -> float:
         ms = ctypes.c_float(0.0)

@@ -377,12 +377,16 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
     const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
     const int32_t *__restrict__ lowsum, int B, int L, int S,
-    int l, int pitch) {
+    int l, int pitch, int csplit) {
   extern __shared__ float tile[]; // [SP][64]
-  const int b = blockIdx.x % B;
-  const int tile_start = (int)(blockIdx.x / B) * kWave;
+  // blockIdx = ((tile * B) + b) * csplit + h: csplit workgroups share one tile and take
+  // 1/csplit of the target strategies each (finer units fill the last round of workgroups)
+  const int h = blockIdx.x % csplit;
+  const int bt = blockIdx.x / csplit;
+  const int b = bt % B;
+  const int tile_start = (bt / B) * kWave;
   const int js = wave_uniform(threadIdx.x >> 6);
-  constexpr int nw = NW; // waves per workgroup = slices of the target strategies
+  const int nw = NW * csplit; // slices of the target strategies
   const int lane = threadIdx.x & 63;
   const int E = budget[b];
   if (tile_start > E) return; // whole workgroup
@@ -421,7 +425,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   }
 
   const int jper = (S + nw - 1) / nw;
-  const int jbeg = js * jper;
+  const int jbeg = (h * NW + js) * jper;
   const int jend = jbeg + jper < S ? jbeg + jper : S;
   for (int j = jbeg; j < jend; ++j) {
     const int o = orow[j];
@@ -620,12 +624,13 @@ int tuned_sp_for(int S) {
 // 1024 SIMDs only twice).  GSEARCH_JSPLIT / GSEARCH_WAVES_PER_BLOCK override the
 // heuristic (debugging and tuning aid).
 struct PushTuning {
-  int jsplit = 0, waves_per_block = 0, kernel = 0, row_groups = 0;
+  int jsplit = 0, waves_per_block = 0, kernel = 0, row_groups = 0, col_split = 0;
   PushTuning() {
     if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
     if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
     if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile
     if (const char *e = getenv("GSEARCH_ROW_GROUPS")) row_groups = atoi(e);
+    if (const char *e = getenv("GSEARCH_COL_SPLIT")) col_split = atoi(e);
   }
 };
 static const PushTuning &tuning() {
@@ -635,6 +640,8 @@ static const PushTuning &tuning() {
 
 static void push_launch_shape(const Shape &s, int &jsplit, int &wpb) {
   const PushTuning &tune = tuning();
+  // tiles of this launch alone, also when other groups of the batch run beside it on
+  // parallel streams: measured, the finer split is what lets the groups interleave
   const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
   wpb = tune.waves_per_block >= 1 && tune.waves_per_block <= 4 ? tune.waves_per_block : 4;
   jsplit = tune.jsplit;
@@ -649,16 +656,19 @@ template <int SP, int NW>
 static void launch_tile_nw(const Shape &s, const Workspace &w, int l, const float *src,
                            float *dst, void *bp_l, hipStream_t st) {
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
-  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
+  int csplit = tuning().col_split;
+  if (csplit < 1) csplit = 1;
+  while (csplit > 1 && s.S / (NW * csplit) < 1) csplit /= 2;
+  const dim3 grid((unsigned)(tiles * s.B * csplit)), block(NW * kWave);
   const size_t lds = sizeof(float) * SP * kWave;
   if (bp_l)
     hipLaunchKernelGGL((k_dp_tile<SP, NW, true>), grid, block, lds, st, src, dst,
                        (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
-                       s.S, l, s.pitch);
+                       s.S, l, s.pitch, csplit);
   else
     hipLaunchKernelGGL((k_dp_tile<SP, NW, false>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
-                       s.L, s.S, l, s.pitch);
+                       s.L, s.S, l, s.pitch, csplit);
 }
 
 template <int SP>
@@ -695,7 +705,7 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
   // short column; the flat argmin is bound by its own instruction count either way and
   // loses occupancy to the extra registers.  Used while the batch still yields at least
   // eight waves per SIMD.  GSEARCH_ROW_GROUPS overrides.
-  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B * jsplit;
+  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.Bc * jsplit;
   int ru = tuning().row_groups;
   if (ru < 1) ru = bp_l ? 1 : (tiles >= 4 * 8192 ? 4 : (tiles >= 2 * 8192 ? 2 : 1));
   if constexpr (SP <= 24) {

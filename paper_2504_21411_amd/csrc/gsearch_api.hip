@@ -2,6 +2,7 @@
 // sequence of kernel launches.  No arithmetic of the method happens on the host.
 #include "../../include/gsearch.h"
 
+#include <cstdlib>
 #include <new>
 
 #include "gsearch_internal.h"
@@ -22,6 +23,7 @@ gs::Shape make_shape(int B, int L, int S, int M, int K) {
   s.SP = tsp ? tsp : (int)align_up((size_t)S, 8);
   s.pitch = (int)align_up((size_t)M + 1, 64);
   s.bp16 = S > 256;
+  s.Bc = B;
   return s;
 }
 
@@ -92,7 +94,68 @@ struct gsearch_ctx {
   bool timed = false; // the most recent solve recorded both events
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
   const char *forward_kernel = ""; // kernel used by the most recent solve's layer fronts
+  // Instances are independent, so the batch is cut into groups whose chains of layer
+  // fronts run side by side: group 0 on the caller's stream, the others on these streams
+  // (default priority), forked and joined with events.  While one group's launch drains,
+  // the workgroups of another fill the compute units, and launch gaps overlap.
+  static constexpr int kMaxSide = 7;
+  hipStream_t side[kMaxSide] = {};
+  hipEvent_t ev_fork = nullptr, ev_join[kMaxSide] = {};
+  int n_side = 0;
+  int groups = 0; // 0 = choose from the shape
+  int groups_used = 0; // by the most recent solve
 };
+
+namespace {
+
+// Number of instance groups for a batch (GSEARCH_STREAMS overrides).  Measured on MI355X:
+// two groups pay as soon as a layer front is worth about half a billion relaxations (8 to
+// 16 % on the large batches: a front there is a few rounds of long workgroups, and the
+// second chain fills the tail of each round and the gap between launches); more than two
+// add little, and fronts of a few microseconds lose to the fork and join.
+int group_count(const gs::Shape &s, int requested) {
+  static const int env = [] {
+    const char *e = getenv("GSEARCH_STREAMS");
+    return e ? atoi(e) : 0;
+  }();
+  const double front = (double)s.B * (s.M + 1) * s.S * s.S;
+  int g = requested >= 1 ? requested : env >= 1 ? env : (front >= 5.0e8 ? 2 : 1);
+  if (g > gsearch_ctx::kMaxSide + 1) g = gsearch_ctx::kMaxSide + 1;
+  return g < s.B ? g : s.B;
+}
+
+// Side streams and events are made on first use and live as long as the context.
+bool ensure_side_streams(gsearch_ctx *ctx, int n) {
+  if (!ctx->ev_fork &&
+      hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess)
+    return false;
+  while (ctx->n_side < n) {
+    const int i = ctx->n_side;
+    if (hipStreamCreateWithFlags(&ctx->side[i], hipStreamNonBlocking) != hipSuccess) return false;
+    if (hipEventCreateWithFlags(&ctx->ev_join[i], hipEventDisableTiming) != hipSuccess) {
+      (void)hipStreamDestroy(ctx->side[i]);
+      ctx->side[i] = nullptr;
+      return false;
+    }
+    ctx->n_side = i + 1;
+  }
+  return true;
+}
+
+// View of instances [b0, b0 + nb) of a workspace: the same kernels run on it as a batch
+// of nb instances.  Plane and backpointer bases are offset by the caller.
+gs::Workspace group_view(const gs::Shape &s, const gs::Workspace &w, int b0) {
+  gs::Workspace g = w;
+  g.Tq = w.Tq + (size_t)b0 * s.L * s.SP;
+  g.Oq = w.Oq + (size_t)b0 * s.L * s.SP;
+  g.ridx = w.ridx + (size_t)b0 * s.L;
+  g.budget = w.budget + b0;
+  g.minO = w.minO + (size_t)b0 * s.L;
+  g.lowsum = w.lowsum + (size_t)b0 * s.L;
+  return g;
+}
+
+} // namespace
 
 extern "C" {
 
@@ -150,6 +213,12 @@ int gsearch_destroy(gsearch_ctx *ctx) {
     DeviceScope scope(ctx->cfg.device);
     if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
     if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    for (int i = 0; i < ctx->n_side; ++i) {
+      (void)hipStreamSynchronize(ctx->side[i]);
+      (void)hipEventDestroy(ctx->ev_join[i]);
+      (void)hipStreamDestroy(ctx->side[i]);
+    }
     if (ctx->base && hipFree(ctx->base) != hipSuccess) rc = GSEARCH_ERR_HIP;
   }
   delete ctx;
@@ -209,17 +278,45 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
     gs::launch_dp_small(s, w, keep, cur, st);
     ctx->forward_kernel = "k_dp_small";
+    ctx->groups_used = 1;
   } else {
     gs::launch_init_layer0(s, w, w.planes, st);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
-    for (int l = 1; l < s.L; ++l) {
-      const int nxt = keep ? l : (cur ^ 1);
-      void *bp_l =
-          with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes : nullptr;
-      ctx->forward_kernel = gs::launch_dp_layer(s, w, l, w.planes + (size_t)cur * pe,
-                                                w.planes + (size_t)nxt * pe, bp_l, which, st);
-      cur = nxt;
+    const int groups = s.L > 1 ? group_count(s, ctx->groups) : 1;
+    ctx->groups_used = groups;
+    if (groups > 1) {
+      if (!ensure_side_streams(ctx, groups - 1)) return GSEARCH_ERR_HIP;
+      if (hipEventRecord(ctx->ev_fork, st) != hipSuccess) return GSEARCH_ERR_HIP;
     }
+    const size_t inst_elems = (size_t)s.S * s.pitch; // one instance's share of a plane
+    int last = 0;
+    for (int g = groups - 1; g >= 0; --g) { // the caller's stream (group 0) is fed last
+      const int b0 = (int)((long long)s.B * g / groups);
+      const int b1 = (int)((long long)s.B * (g + 1) / groups);
+      gs::Shape sg = s;
+      sg.B = b1 - b0;
+      const gs::Workspace wg = group_view(s, w, b0);
+      hipStream_t sst = g == 0 ? st : ctx->side[g - 1];
+      if (g > 0 && hipStreamWaitEvent(sst, ctx->ev_fork, 0) != hipSuccess) return GSEARCH_ERR_HIP;
+      int c2 = 0;
+      for (int l = 1; l < s.L; ++l) {
+        const int nxt = keep ? l : (c2 ^ 1);
+        void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes +
+                                   (size_t)b0 * inst_elems * (s.bp16 ? 2 : 1)
+                             : nullptr;
+        ctx->forward_kernel = gs::launch_dp_layer(
+            sg, wg, l, w.planes + (size_t)c2 * pe + (size_t)b0 * inst_elems,
+            w.planes + (size_t)nxt * pe + (size_t)b0 * inst_elems, bp_l, which, sst);
+        c2 = nxt;
+      }
+      last = c2;
+      if (g > 0) {
+        if (hipEventRecord(ctx->ev_join[g - 1], sst) != hipSuccess) return GSEARCH_ERR_HIP;
+      }
+    }
+    for (int g = 1; g < groups; ++g)
+      if (hipStreamWaitEvent(st, ctx->ev_join[g - 1], 0) != hipSuccess) return GSEARCH_ERR_HIP;
+    cur = last;
   }
   if (timing) {
     if (hipEventRecord(ctx->ev_end, st) != hipSuccess) return GSEARCH_ERR_HIP;
@@ -263,6 +360,14 @@ int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits) {
 const char *gsearch_forward_kernel(gsearch_ctx *ctx) {
   return (ctx && ctx->solved) ? ctx->forward_kernel : "";
 }
+
+int gsearch_set_instance_groups(gsearch_ctx *ctx, int groups) {
+  if (!ctx || groups < 0) return GSEARCH_ERR_INVALID_ARG;
+  ctx->groups = groups;
+  return GSEARCH_OK;
+}
+
+int gsearch_instance_groups(gsearch_ctx *ctx) { return (ctx && ctx->solved) ? ctx->groups_used : 0; }
 
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable) {
   if (!ctx) return GSEARCH_ERR_INVALID_ARG;

@@ -17,6 +17,8 @@ struct Shape {
   int SP;    // pitch of one (b,l) row of Tq/Oq and of both dimensions of Rt
   int pitch; // pitch (in elements) of one strategy row of a C plane / bp plane
   int bp16;  // backpointers are uint16 (S > 256) instead of uint8
+  int Bc;    // instances in flight at the same time (>= B when this shape is one group of
+             // a batch whose groups run on parallel streams); launch heuristics only
 };
 
 // Device pointers into the context's workspace.

@@ -433,3 +433,31 @@ def test_profiling_entry_points(gs):
     with runner.make_context(w, flags=binding.GSEARCH_FLAG_FORCE_GENERIC) as ctx:
         runner.run_step(ctx, dw, backtrace=None)
         assert ctx.gsearch_forward_kernel() == "k_dp_generic"
+
+
+@pytest.mark.parametrize("mode", ["bp_push", "bp_tile", "generic", "nobp_push", "nobp_tile"])
+def test_instance_groups_on_parallel_streams(gs, oracle_mod, mode):
+    """The batch cut into 1..8 groups (ragged sizes, more groups than instances) on the
+    context's own streams: same bits as the oracle each time, also when one context
+    changes the group count from solve to solve and keeps planes."""
+    binding, runner = gs
+    B = 7
+    budget = np.array([900, 64, 511, 0, 900, 333, 700], np.int32)
+    w = random_tables("groups", B, 9, 44, 900, K=3, seed=123, budget=budget)
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
+        for groups in (3, 1, 8, 2, 5, 0, 7):
+            ctx.gsearch_set_instance_groups(groups)
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert_same(got, ref, w, f"{mode} groups={groups}")
+            assert ctx.gsearch_instance_groups() == (min(groups, B) if groups else 1)
+            C, _ = ctx.gsearch_export_planes(want_bp=False)
+            C = C.cpu().numpy()
+            for b in (0, 3, 6):
+                E = int(w.budget[b])
+                one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True)
+                assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (groups, b)
+        with pytest.raises(binding.GSearchError):
+            ctx.gsearch_set_instance_groups(-1)
