@@ -377,16 +377,12 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
     const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
     const int32_t *__restrict__ lowsum, int B, int L, int S,
-    int l, int pitch, int csplit) {
+    int l, int pitch) {
   extern __shared__ float tile[]; // [SP][64]
-  // blockIdx = ((tile * B) + b) * csplit + h: csplit workgroups share one tile and take
-  // 1/csplit of the target strategies each (finer units fill the last round of workgroups)
-  const int h = blockIdx.x % csplit;
-  const int bt = blockIdx.x / csplit;
-  const int b = bt % B;
-  const int tile_start = (bt / B) * kWave;
+  const int b = blockIdx.x % B;
+  const int tile_start = (int)(blockIdx.x / B) * kWave;
   const int js = wave_uniform(threadIdx.x >> 6);
-  const int nw = NW * csplit; // slices of the target strategies
+  constexpr int nw = NW; // waves per workgroup = slices of the target strategies
   const int lane = threadIdx.x & 63;
   const int E = budget[b];
   if (tile_start > E) return; // whole workgroup
@@ -425,7 +421,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   }
 
   const int jper = (S + nw - 1) / nw;
-  const int jbeg = (h * NW + js) * jper;
+  const int jbeg = js * jper;
   const int jend = jbeg + jper < S ? jbeg + jper : S;
   for (int j = jbeg; j < jend; ++j) {
     const int o = orow[j];
@@ -624,13 +620,12 @@ int tuned_sp_for(int S) {
 // 1024 SIMDs only twice).  GSEARCH_JSPLIT / GSEARCH_WAVES_PER_BLOCK override the
 // heuristic (debugging and tuning aid).
 struct PushTuning {
-  int jsplit = 0, waves_per_block = 0, kernel = 0, row_groups = 0, col_split = 0;
+  int jsplit = 0, waves_per_block = 0, kernel = 0, row_groups = 0;
   PushTuning() {
     if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
     if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
     if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile
     if (const char *e = getenv("GSEARCH_ROW_GROUPS")) row_groups = atoi(e);
-    if (const char *e = getenv("GSEARCH_COL_SPLIT")) col_split = atoi(e);
   }
 };
 static const PushTuning &tuning() {
@@ -656,19 +651,16 @@ template <int SP, int NW>
 static void launch_tile_nw(const Shape &s, const Workspace &w, int l, const float *src,
                            float *dst, void *bp_l, hipStream_t st) {
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
-  int csplit = tuning().col_split;
-  if (csplit < 1) csplit = 1;
-  while (csplit > 1 && s.S / (NW * csplit) < 1) csplit /= 2;
-  const dim3 grid((unsigned)(tiles * s.B * csplit)), block(NW * kWave);
+  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
   const size_t lds = sizeof(float) * SP * kWave;
   if (bp_l)
     hipLaunchKernelGGL((k_dp_tile<SP, NW, true>), grid, block, lds, st, src, dst,
                        (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
-                       s.S, l, s.pitch, csplit);
+                       s.S, l, s.pitch);
   else
     hipLaunchKernelGGL((k_dp_tile<SP, NW, false>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
-                       s.L, s.S, l, s.pitch, csplit);
+                       s.L, s.S, l, s.pitch);
 }
 
 template <int SP>
