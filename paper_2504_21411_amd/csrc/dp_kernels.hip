@@ -423,6 +423,31 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   const int jper = (S + nw - 1) / nw;
   const int jbeg = js * jper;
   const int jend = jbeg + jper < S ? jbeg + jper : S;
+  // Level 2 of a column: which of the eight candidates of chunk g attains m.  The eight
+  // transition values differ from lane to lane, so they come through the vector memory
+  // path (two 16-byte loads per lane), the eight previous-plane values from the LDS tile.
+  struct Column {
+    float4 ra, rb;
+    float m, t;
+    int g, j, o;
+  };
+  auto finish = [&](const Column &d) {
+    const float *tg = tile + (8 * d.g) * kWave + lane; // per-lane slice of the tile
+    const float rr[8] = {d.ra.x, d.ra.y, d.ra.z, d.ra.w, d.rb.x, d.rb.y, d.rb.z, d.rb.w};
+    int arg = 8 * d.g;
+#pragma unroll
+    for (int k = 7; k >= 1; --k) {
+      const float v = tg[k * kWave] + rr[k];
+      arg = (v == d.m) ? 8 * d.g + k : arg;
+    }
+    const float v0 = tg[0] + rr[0];
+    arg = (v0 == d.m) ? 8 * d.g : arg;
+    const int eo = row + d.o;
+    if (row >= low && eo <= E) {
+      dstb[(size_t)d.j * pitch + eo] = d.m + d.t;
+      bpb[(size_t)d.j * pitch + eo] = (uint8_t)arg;
+    }
+  };
   for (int j = jbeg; j < jend; ++j) {
     const int o = orow[j];
     const float t = trow[j];
@@ -431,26 +456,16 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
       float m = GS_INF;
       int g = 0;
       scan_chunks<SP, WITH_BP>(m, g, c, rc);
-      int arg = 0;
-      if (WITH_BP) {
-        const float *__restrict__ rg = rc + 8 * g;      // per-lane slice of the column
-        const float *tg = tile + (8 * g) * kWave + lane; // per-lane slice of the tile
-        const float4 ra = *reinterpret_cast<const float4 *>(rg);
-        const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
-        const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
-        arg = 8 * g;
-#pragma unroll
-        for (int k = 7; k >= 1; --k) {
-          const float v = tg[k * kWave] + rr[k];
-          arg = (v == m) ? 8 * g + k : arg;
-        }
-        const float v0 = tg[0] + rr[0];
-        arg = (v0 == m) ? 8 * g : arg;
-      }
-      const int eo = row + o;
-      if (row >= low && eo <= E) {
-        dstb[(size_t)j * pitch + eo] = m + t;
-        if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg;
+      if constexpr (WITH_BP) {
+        const float *__restrict__ rg = rc + 8 * g; // per-lane slice of the column
+        Column d;
+        d.ra = *reinterpret_cast<const float4 *>(rg);
+        d.rb = *reinterpret_cast<const float4 *>(rg + 4);
+        d.m = m; d.t = t; d.g = g; d.j = j; d.o = o;
+        finish(d);
+      } else {
+        const int eo = row + o;
+        if (row >= low && eo <= E) dstb[(size_t)j * pitch + eo] = m + t;
       }
     }
     if (tile_start < o + low) {
