@@ -218,9 +218,14 @@ static __device__ __forceinline__ void chunk_update(float &m, int &g, float cm, 
   }
 }
 
-template <int SP, bool WITH_ARG>
+// SA (a multiple of 4, SP - 8 < SA <= SP): candidates SA .. SP-1 are padding, +inf by
+// construction, and can never be the strict minimum, so the last chunk may stop after
+// four of them (saves four adds and two minimum instructions per column when the
+// strategy count is 4 mod 8, as with the paper's 44).
+template <int SP, bool WITH_ARG, int SA = SP>
 static __device__ __forceinline__ void scan_chunks(float &m, int &g, const float (&c)[SP],
                                                    const float *__restrict__ rc) {
+  static_assert(SA % 4 == 0 && SA <= SP && SA > SP - 8, "SA trims at most half a chunk");
 #pragma unroll
   for (int p = 0; p < SP / 16; ++p) {
     const float16_t r = *reinterpret_cast<const float16_t *>(rc + 16 * p);
@@ -229,7 +234,8 @@ static __device__ __forceinline__ void scan_chunks(float &m, int &g, const float
       const int q = 2 * p + h;
       float cm = __builtin_fminf(c[8 * q] + r[8 * h], c[8 * q + 1] + r[8 * h + 1]);
 #pragma unroll
-      for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[8 * q + k] + r[8 * h + k]);
+      for (int k = 2; k < 8; ++k)
+        if (8 * q + k < SA) cm = __builtin_fminf(cm, c[8 * q + k] + r[8 * h + k]);
       chunk_update<WITH_ARG>(m, g, cm, q);
     }
   }
@@ -238,7 +244,8 @@ static __device__ __forceinline__ void scan_chunks(float &m, int &g, const float
     const float8_t r = *reinterpret_cast<const float8_t *>(rc + 8 * q);
     float cm = __builtin_fminf(c[8 * q] + r[0], c[8 * q + 1] + r[1]);
 #pragma unroll
-    for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[8 * q + k] + r[k]);
+    for (int k = 2; k < 8; ++k)
+      if (8 * q + k < SA) cm = __builtin_fminf(cm, c[8 * q + k] + r[k]);
     chunk_update<WITH_ARG>(m, g, cm, q);
   }
 }
@@ -370,7 +377,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
 // If every candidate is +inf, m stays +inf, g stays 0 and level 2 returns index 0, which
 // is what the scan gives.
 // ---------------------------------------------------------------------------------------
-template <int SP, int NW, bool WITH_BP>
+template <int SP, int NW, bool WITH_BP, int SA>
 __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
     const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
@@ -455,7 +462,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
       const float *__restrict__ rc = rk + (size_t)j * SP;
       float m = GS_INF;
       int g = 0;
-      scan_chunks<SP, WITH_BP>(m, g, c, rc);
+      scan_chunks<SP, WITH_BP, SA>(m, g, c, rc);
       if constexpr (WITH_BP) {
         const float *__restrict__ rg = rc + 8 * g; // per-lane slice of the column
         Column d;
@@ -662,20 +669,30 @@ static void push_launch_shape(const Shape &s, int &jsplit, int &wpb) {
   if (jsplit > s.S) jsplit = s.S;
 }
 
-template <int SP, int NW>
-static void launch_tile_nw(const Shape &s, const Workspace &w, int l, const float *src,
+template <int SP, int NW, int SA>
+static void launch_tile_sa(const Shape &s, const Workspace &w, int l, const float *src,
                            float *dst, void *bp_l, hipStream_t st) {
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
   const size_t lds = sizeof(float) * SP * kWave;
   if (bp_l)
-    hipLaunchKernelGGL((k_dp_tile<SP, NW, true>), grid, block, lds, st, src, dst,
+    hipLaunchKernelGGL((k_dp_tile<SP, NW, true, SA>), grid, block, lds, st, src, dst,
                        (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
                        s.S, l, s.pitch);
   else
-    hipLaunchKernelGGL((k_dp_tile<SP, NW, false>), grid, block, lds, st, src, dst,
+    hipLaunchKernelGGL((k_dp_tile<SP, NW, false, SA>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
                        s.L, s.S, l, s.pitch);
+}
+
+template <int SP, int NW>
+static void launch_tile_nw(const Shape &s, const Workspace &w, int l, const float *src,
+                           float *dst, void *bp_l, hipStream_t st) {
+  // the half-chunk variant exists for 48 padded strategies (S = 41..44) only
+  if constexpr (SP == 48) {
+    if (s.S <= SP - 4) return launch_tile_sa<SP, NW, SP - 4>(s, w, l, src, dst, bp_l, st);
+  }
+  launch_tile_sa<SP, NW, SP>(s, w, l, src, dst, bp_l, st);
 }
 
 template <int SP>

@@ -57,6 +57,7 @@ SHAPES = [
     (3, 5, 16, 300, 1), (2, 4, 24, 1000, 2), (2, 5, 33, 257, 1), (3, 4, 44, 511, 4),
     (2, 3, 64, 320, 1), (2, 3, 65, 200, 2), (2, 3, 96, 260, 1), (1, 3, 100, 130, 1),
     (2, 3, 128, 129, 2), (5, 1, 9, 40, 1), (1, 2, 2, 1, 1),
+    (2, 4, 41, 200, 1), (2, 3, 45, 130, 2),   # either side of the half-chunk variant (41..44)
 ]
 
 
