@@ -261,16 +261,21 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
     const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
     const int32_t *__restrict__ lowsum, int B, int L, int S,
-    int l, int pitch, int jsplit) {
-  // blockIdx.x = (row_block * jsplit + js) * B + b: consecutive workgroups belong to
-  // different instances, so the round-robin of workgroups over the eight XCDs spreads
-  // every instance (and ragged budgets) evenly over the chip.
-  const int b = blockIdx.x % B;
-  const int rest = blockIdx.x / B;
-  const int js = rest % jsplit;
+    int l, int pitch, int jsplit, int nblk) {
+  // Work item p = row_block * B + b (nblk of them): consecutive items belong to different
+  // instances, so every instance (and ragged budgets) spreads evenly over the chip.  The
+  // hardware deals consecutive workgroups round-robin to the eight XCDs, each with its own
+  // L2, and the jsplit workgroups that share one item read the same source rows: they are
+  // numbered so that they land on the same XCD and the rows are fetched into one L2 only,
+  //   blockIdx.x = ((p / 8) * jsplit + js) * 8 + p % 8.
+  const int q = blockIdx.x >> 3;
+  const int js = q % jsplit;
+  const int p = (q / jsplit) * 8 + (int)(blockIdx.x & 7);
+  if (p >= nblk) return;
+  const int b = p % B;
   const int wave = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int tile_start = ((rest / jsplit) * (int)(blockDim.x >> 6) + wave) * (kWave * RU);
+  const int tile_start = ((p / B) * (int)(blockDim.x >> 6) + wave) * (kWave * RU);
   const int E = budget[b];
   if (tile_start > E) return;
   // this workgroup's slice of target strategies
@@ -708,15 +713,16 @@ static void launch_push_ru(const Shape &s, const Workspace &w, int l, const floa
                            float *dst, void *bp_l, int jsplit, int wpb, hipStream_t st) {
   const int rows = wpb * kWave * RU;
   const long long row_blocks = (s.M + 1 + rows - 1) / rows;
-  const dim3 grid((unsigned)(row_blocks * jsplit * s.B)), block(wpb * kWave);
+  const long long nblk = row_blocks * s.B;
+  const dim3 grid((unsigned)((nblk + 7) / 8 * 8 * jsplit)), block(wpb * kWave);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_push<SP, RU, true>), grid, block, 0, st, src, dst, (uint8_t *)bp_l,
                        w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, l, s.pitch,
-                       jsplit);
+                       jsplit, (int)nblk);
   else
     hipLaunchKernelGGL((k_dp_push<SP, RU, false>), grid, block, 0, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
-                       s.L, s.S, l, s.pitch, jsplit);
+                       s.L, s.S, l, s.pitch, jsplit, (int)nblk);
 }
 
 template <int SP>
