@@ -80,6 +80,10 @@ typedef enum {
 #define GSEARCH_DATA_BAD_O 0x4
 #define GSEARCH_DATA_BAD_BUDGET 0x8
 #define GSEARCH_DATA_BAD_RINDEX 0x10
+#define GSEARCH_DATA_BAD_RCLASS 0x20 /* r_class is not a valid partition, has more than
+                                        GSEARCH_MAX_CLASSES classes, or R differs inside one */
+
+#define GSEARCH_MAX_CLASSES 32 /* transition classes a solve can exploit (see r_class) */
 
 #define GSEARCH_MAX_S 1024 /* strategies per layer (bp is uint8 up to 256, uint16 above) */
 
@@ -106,6 +110,20 @@ typedef struct {
   const float *R;         /* [K][S][S]   R[k][si][sj], row = previous layer        */
   const int32_t *r_index; /* [B][L]      matrix used INTO layer l; entry l=0 unused */
   const int32_t *budget;  /* [B]         E_b, 0 <= E_b <= M                        */
+  const int32_t *r_class; /* [S] or NULL.  Optional promise about R that lets the solve do
+                             less work for bit-identical results: strategies are grouped
+                             into contiguous classes (r_class[0] = 0, each entry equal to
+                             its predecessor or one more, at most GSEARCH_MAX_CLASSES
+                             classes), and R depends on the strategies only through their
+                             classes, i.e. rows si, si' of one class are equal in every
+                             matrix of the pool and so are columns sj, sj' of one class.
+                             That is the case when the transition cost is a resharding
+                             cost between parallel layouts and several strategies share a
+                             layout (they differ in recomputation or parameter sharding
+                             only); gsearch_layout_classes derives it from descriptors.
+                             The promise is checked on the device: a violation sets
+                             GSEARCH_DATA_BAD_RCLASS and the solve reports every instance
+                             as infeasible.  NULL: no assumption.                        */
 } gsearch_problem;
 
 /* Caller-allocated DEVICE outputs of a solve; any pointer may be NULL to skip it. */
@@ -209,6 +227,15 @@ int gsearch_export_planes(gsearch_ctx *ctx, float *C, int32_t *bp, void *stream)
  * (powers of two with tp*sp*dp == N), sharded-data flag (only when dp > 1) and
  * recomputation flag.  Tree order: ascending (sp, tp, sdp, ckpt), ckpt fastest.
  * Caps: tp <= tp_max, sp <= sp_max, tp*sp <= tpsp_max; a cap <= 0 means "none". */
+
+/* Transition classes of an enumerated strategy set: r_class[s] (device [S]) counts the
+ * changes of the layout (tp, sp, dp) along desc[0..s], so strategies that follow each other
+ * with the same layout share a class; count_out (device [1], may be NULL) receives the
+ * number of classes.  Feed r_class to gsearch_problem when R was built from the same
+ * descriptors by gsearch_build_tables (its R depends on the layouts only).
+ * Asynchronous on `stream`.  Errors: INVALID_ARG (null pointers, S outside 1..GSEARCH_MAX_S). */
+int gsearch_layout_classes(const int32_t *desc, int32_t S, int32_t *r_class, int32_t *count_out,
+                           void *stream);
 
 /* Number of strategies (host arithmetic, no GPU).  Negative status if N is not a power
  * of two in [1, 2^30]. */

@@ -33,6 +33,8 @@ GSEARCH_DATA_BAD_R = 0x2
 GSEARCH_DATA_BAD_O = 0x4
 GSEARCH_DATA_BAD_BUDGET = 0x8
 GSEARCH_DATA_BAD_RINDEX = 0x10
+GSEARCH_DATA_BAD_RCLASS = 0x20
+GSEARCH_MAX_CLASSES = 32
 
 EXPORTS = [
     "gsearch_workspace_bytes", "gsearch_create", "gsearch_destroy", "gsearch_solve_batch",
@@ -40,7 +42,7 @@ EXPORTS = [
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
     "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
-    "gsearch_instance_groups",
+    "gsearch_instance_groups", "gsearch_layout_classes",
 ]
 
 
@@ -54,7 +56,7 @@ class gsearch_problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("L", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("M", ctypes.c_int32), ("K", ctypes.c_int32), ("T", ctypes.c_void_p),
                 ("O", ctypes.c_void_p), ("R", ctypes.c_void_p), ("r_index", ctypes.c_void_p),
-                ("budget", ctypes.c_void_p)]
+                ("budget", ctypes.c_void_p), ("r_class", ctypes.c_void_p)]
 
 
 class gsearch_result(ctypes.Structure):
@@ -112,6 +114,8 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_set_instance_groups.argtypes = [vp, ctypes.c_int]
     lib.gsearch_instance_groups.restype = ctypes.c_int
     lib.gsearch_instance_groups.argtypes = [vp]
+    lib.gsearch_layout_classes.restype = ctypes.c_int
+    lib.gsearch_layout_classes.argtypes = [vp, i32, vp, vp, vp]
     lib.gsearch_forward_ms.restype = ctypes.c_int
     lib.gsearch_forward_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
     lib.gsearch_forward_kernel.restype = ctypes.c_char_p
@@ -191,6 +195,18 @@ def gsearch_enumerate(N, tp_max=0, sp_max=0, tpsp_max=0, device="cuda", stream=N
     return desc, count
 
 
+def gsearch_layout_classes(desc, stream=None):
+    """desc int32 [S][5] on the GPU -> (r_class int32 [S], count int32 [1]) on the GPU."""
+    import torch
+    S = desc.shape[0]
+    r_class = torch.empty(S, dtype=torch.int32, device=desc.device)
+    count = torch.empty(1, dtype=torch.int32, device=desc.device)
+    _check(load_library().gsearch_layout_classes(_ptr(desc, torch.int32, "desc"), S,
+                                                 _ptr(r_class), _ptr(count), _stream(stream)),
+           "gsearch_layout_classes")
+    return r_class, count
+
+
 def gsearch_build_tables(desc, layer, hw, rmodel, M, stream=None):
     """desc int32 [S][5], layer fp64 [B][L][6], rmodel fp64 [K][2] on the GPU; hw 4 floats.
 
@@ -261,14 +277,16 @@ class GSearch:
             pass
 
     def gsearch_solve_batch(self, T, O, R, r_index, budget, M, want_final_row=True, stream=None,
-                            out=None):
+                            out=None, r_class=None):
         """T fp32 [B][L][S], O int32 [B][L][S], R fp32 [K][S][S], r_index int32 [B][L],
-        budget int32 [B], all on the GPU.  Returns a dict of device tensors (asynchronous)."""
+        budget int32 [B], optional r_class int32 [S], all on the GPU.  Returns a dict of
+        device tensors (asynchronous)."""
         import torch
         B, L, S = T.shape
         K = R.shape[0]
         if tuple(O.shape) != (B, L, S) or tuple(R.shape) != (K, S, S) or \
-                tuple(r_index.shape) != (B, L) or tuple(budget.shape) != (B,):
+                tuple(r_index.shape) != (B, L) or tuple(budget.shape) != (B,) or \
+                (r_class is not None and tuple(r_class.shape) != (S,)):
             raise ValueError("table shapes do not agree")
         dev = T.device
         if out is None:
@@ -280,7 +298,8 @@ class GSearch:
         prob = gsearch_problem(B, L, S, int(M), K, _ptr(T, torch.float32, "T"),
                                _ptr(O, torch.int32, "O"), _ptr(R, torch.float32, "R"),
                                _ptr(r_index, torch.int32, "r_index"),
-                               _ptr(budget, torch.int32, "budget"))
+                               _ptr(budget, torch.int32, "budget"),
+                               _ptr(r_class, torch.int32, "r_class"))
         res = gsearch_result(_ptr(out["best_cost"]), _ptr(out["best_s"]),
                              _ptr(out.get("final_row")), _ptr(out["best_instance"]))
         _check(self._lib.gsearch_solve_batch(self._ctx, ctypes.byref(prob), ctypes.byref(res),

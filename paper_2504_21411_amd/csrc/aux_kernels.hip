@@ -88,6 +88,108 @@ __global__ __launch_bounds__(256) void k_prepare(
 
 __global__ void k_clear_status(int32_t *status) { *status = 0; }
 
+// ----------------------------------------------------------------------------------------
+// Transition classes.  The caller's r_class[S] promises that R depends on the strategies
+// only through contiguous classes.  Block 0 checks the partition itself (starts at 0, steps
+// of 0 or 1, at most kMaxClasses classes) and writes its run table; every block checks a
+// share of the table entries against their left and upper neighbours of the same class,
+// which together imply that R is constant on every (class, class) block.  A bad partition
+// is replaced by the single class {0..S-1} so that whatever reads the run table stays in
+// bounds; the status bit makes the solve report every instance as infeasible anyway.
+// ----------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_prepare_classes(
+    const int32_t *__restrict__ r_class, const float *__restrict__ Rt,
+    int32_t *__restrict__ cmeta, int32_t *__restrict__ cstart, int32_t *__restrict__ cls,
+    int32_t *__restrict__ status, int S, int SP, int K) {
+  __shared__ int s_bad, s_maxlen;
+  int bad = 0;
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) { s_bad = 0; s_maxlen = 0; }
+    __syncthreads();
+    int pbad = 0;
+    for (int i = threadIdx.x; i < S; i += blockDim.x) {
+      const int c = r_class[i];
+      const int prev = i ? r_class[i - 1] : 0;
+      if (i == 0 ? c != 0 : (c != prev && c != prev + 1)) pbad = 1;
+      if (c < 0 || c >= kMaxClasses) pbad = 1;
+    }
+    if (pbad) atomicOr(&s_bad, 1);
+    __syncthreads();
+    const bool ok = s_bad == 0;
+    const int nc = ok ? r_class[S - 1] + 1 : 1;
+    for (int c = threadIdx.x; c <= kMaxClasses; c += blockDim.x) cstart[c] = c == 0 ? 0 : S;
+    __syncthreads();
+    for (int i = threadIdx.x; i < SP; i += blockDim.x) {
+      const int c = (ok && i < S) ? r_class[i] : 0;
+      cls[i] = c;
+      if (ok && i > 0 && i < S && c != r_class[i - 1]) cstart[c] = i;
+    }
+    __syncthreads();
+    // longest class: thread c looks at its own run
+    for (int c = threadIdx.x; c < nc; c += blockDim.x)
+      atomicMax(&s_maxlen, (c + 1 < nc ? cstart[c + 1] : S) - cstart[c]);
+    __syncthreads();
+    if (threadIdx.x == 0) { cmeta[0] = nc; cmeta[1] = s_maxlen; }
+    if (!ok) bad = 0x20;
+  }
+  // R constant inside classes: compare with the left (si-1) and upper (sj-1) neighbour
+  const long long total = (long long)K * S * S;
+  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
+       x += (long long)gridDim.x * blockDim.x) {
+    const int i = (int)(x % S);
+    const int j = (int)((x / S) % S);
+    const long long k = x / ((long long)S * S);
+    const float *m = Rt + k * SP * SP;
+    const uint32_t v = __float_as_uint(m[(size_t)j * SP + i]);
+    if (i > 0 && r_class[i] == r_class[i - 1] && v != __float_as_uint(m[(size_t)j * SP + i - 1]))
+      bad = 0x20;
+    if (j > 0 && r_class[j] == r_class[j - 1] && v != __float_as_uint(m[(size_t)(j - 1) * SP + i]))
+      bad = 0x20;
+  }
+  if (bad) atomicOr(status, bad);
+}
+
+// Rc[k][cj][ci] = Rt[k][first strategy of cj][first strategy of ci], +inf for padding classes.
+__global__ __launch_bounds__(256) void k_build_Rc(const float *__restrict__ Rt,
+                                                  const int32_t *__restrict__ cmeta,
+                                                  const int32_t *__restrict__ cstart,
+                                                  float *__restrict__ Rc, int SP, int K) {
+  const int nc = cmeta[0];
+  const long long total = (long long)K * kMaxClasses * kMaxClasses;
+  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
+       x += (long long)gridDim.x * blockDim.x) {
+    const int ci = (int)(x % kMaxClasses);
+    const int cj = (int)((x / kMaxClasses) % kMaxClasses);
+    const long long k = x / (kMaxClasses * kMaxClasses);
+    float r = GS_INF;
+    if (ci < nc && cj < nc) r = Rt[k * SP * SP + (size_t)cstart[cj] * SP + cstart[ci]];
+    Rc[x] = r;
+  }
+}
+
+// r_class[s] = number of layout changes along desc[0..s] (one block, serial prefix over S
+// <= 1024 entries by a scan in shared memory).
+__global__ __launch_bounds__(1024) void k_layout_classes(const int32_t *__restrict__ desc, int S,
+                                                         int32_t *__restrict__ r_class,
+                                                         int32_t *__restrict__ count_out) {
+  __shared__ int flag[1024];
+  const int s = threadIdx.x;
+  int f = 0;
+  if (s > 0 && s < S)
+    f = desc[5 * s] != desc[5 * (s - 1)] || desc[5 * s + 1] != desc[5 * (s - 1) + 1] ||
+        desc[5 * s + 2] != desc[5 * (s - 1) + 2];
+  flag[s] = f;
+  __syncthreads();
+  for (int d = 1; d < 1024; d <<= 1) { // inclusive scan
+    const int add = s >= d ? flag[s - d] : 0;
+    __syncthreads();
+    flag[s] += add;
+    __syncthreads();
+  }
+  if (s < S) r_class[s] = flag[s];
+  if (s == S - 1 && count_out) *count_out = flag[s] + 1;
+}
+
 // lowsum[b][l] = min(M+1, sum_{l' <= l} min_s O[l'][s]): a plan of layers 0..l needs at
 // least that many bins, so C[l][e][.] is +inf for every e below it.  The forward kernels
 // use it to fill those rows without computing them.  One thread per instance.
@@ -598,6 +700,21 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
                      s.L, s.S, s.M, s.K, s.SP);
   hipLaunchKernelGGL(k_prefix_min_memory, dim3((s.B + 63) / 64), dim3(64), 0, st, w.minO,
                      w.lowsum, s.B, s.L, s.M);
+}
+
+void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
+                            hipStream_t st) {
+  const long long total = (long long)s.K * s.S * s.S;
+  hipLaunchKernelGGL(k_prepare_classes, dim3(blocks_for(total, 256, 4096)), dim3(256), 0, st,
+                     r_class, w.Rt, w.cmeta, w.cstart, w.cls, w.status, s.S, s.SP, s.K);
+  const long long nrc = (long long)s.K * kMaxClasses * kMaxClasses;
+  hipLaunchKernelGGL(k_build_Rc, dim3(blocks_for(nrc, 256, 4096)), dim3(256), 0, st, w.Rt,
+                     w.cmeta, w.cstart, w.Rc, s.SP, s.K);
+}
+
+void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
+                           hipStream_t st) {
+  hipLaunchKernelGGL(k_layout_classes, dim3(1), dim3(1024), 0, st, desc, S, r_class, count_out);
 }
 
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st) {

@@ -489,6 +489,163 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Class kernel: the transition table depends on the strategies only through nc <= 32
+// contiguous classes (checked on the device beforehand), R[si][sj] = Rc[class si][class sj].
+// Then, for a source row,
+//     min_si (C[si] + R[si][sj]) = min_ci ( (min_{si in ci} C[si]) + Rc[ci][cj] )
+// bit for bit, because the fp32 add is monotone: one minimum per class (S operations) and
+// nc relaxations per target CLASS replace S relaxations per target strategy, and every
+// strategy of a target class shares the result before its own T and O are applied.  The
+// lowest-index rule survives: classes are ascending index ranges, so the first class that
+// attains the minimum (strict "<" scan) holds the lowest strategy attaining it, and that
+// strategy is found by rebuilding the sums of this one class from the LDS tile (several of
+// its members may round to the same sum, so the member with the smallest C need not be it).
+//
+// One workgroup per 64-row tile, NW waves.  Tile HBM -> LDS once; the class minima are
+// formed by LDS float-minimum atomics while the rows arrive (cmin[class][lane]), then every
+// wave keeps all of them in registers and takes every NW-th target class.
+// ---------------------------------------------------------------------------------------
+template <int SP, int NW, bool WITH_BP>
+__global__ __launch_bounds__(NW *kWave) void k_dp_class(
+    const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
+    const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int S,
+    int l, int pitch) {
+  constexpr int NC = kMaxClasses;
+  extern __shared__ float lds[];
+  float *tile = lds;                    // [SP][64]
+  float *cmin = tile + SP * kWave;      // [NC][64]
+  float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
+  int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1]
+  const int b = blockIdx.x % B;
+  const int tile_start = (int)(blockIdx.x / B) * kWave;
+  const int js = wave_uniform(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int E = budget[b];
+  if (tile_start > E) return; // whole workgroup
+
+  const int row = tile_start + lane;
+  const bool valid = row <= E;
+  const int bl = b * L + l;
+  const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
+  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave > low; // uniform
+  const size_t plane_off = (size_t)b * S * pitch;
+  const float *__restrict__ srcb = src + plane_off;
+  float *__restrict__ dstb = dst + plane_off;
+  uint8_t *__restrict__ bpb = WITH_BP ? bp + plane_off : nullptr;
+  const float *__restrict__ rck = Rc + (size_t)ridx[bl] * NC * NC;
+  const float *__restrict__ trow = Tq + (size_t)bl * SP;
+  const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
+  const int nc = cmeta[0];
+  const int maxlen = cmeta[1];
+
+  float cmv[NC];
+  if (compute) {
+    float stage[SP / NW];
+#pragma unroll
+    for (int u = 0; u < SP / NW; ++u) {
+      const int i = u * NW + js;
+      stage[u] = (i < S && valid) ? srcb[(size_t)i * pitch + row] : GS_INF;
+    }
+    for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
+    for (int x = threadIdx.x; x < NC * NC; x += NW * kWave) rc_lds[x] = rck[x];
+    if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+#pragma unroll
+    for (int u = 0; u < SP / NW; ++u) tile[(u * NW + js) * kWave + lane] = stage[u];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < SP / NW; ++u) {
+      const int c = cls[u * NW + js]; // wave-uniform
+      __hip_atomic_fetch_min(&cmin[c * kWave + lane], stage[u], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    __syncthreads();
+    // only the chunks of eight classes that exist are kept (the rest is never read)
+#pragma unroll
+    for (int q = 0; q < NC / 8; ++q) {
+      if (8 * q < nc) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) cmv[8 * q + k] = cmin[(8 * q + k) * kWave + lane];
+      }
+    }
+  }
+
+  const bool rows_on = valid && row >= low; // source rows whose targets are computed
+  for (int cj = js; cj < nc; cj += NW) {
+    float m = GS_INF;
+    int arg = 0;
+    if (compute) {
+      const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
+      // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
+      int g = 0;
+#pragma unroll
+      for (int q = 0; q < NC / 8; ++q) {
+        if (8 * q < nc) {
+          const float8_t r = *reinterpret_cast<const float8_t *>(rc + 8 * q);
+          float cm = __builtin_fminf(cmv[8 * q] + r[0], cmv[8 * q + 1] + r[1]);
+#pragma unroll
+          for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[k]);
+          chunk_update<true>(m, g, cm, q);
+        }
+      }
+      // level 1b: first class of chunk g attaining it (operands re-read from LDS: g varies
+      // from lane to lane)
+      int ca = 8 * g;
+      {
+        const float *cg = cmin + (8 * g) * kWave + lane;
+        const float *rg = rc_lds + cj * NC + 8 * g;
+        const float4 ra = *reinterpret_cast<const float4 *>(rg);
+        const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
+        const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+#pragma unroll
+        for (int k = 7; k >= 0; --k) { // descending: the lowest matching class wins
+          const float v = cg[k * kWave] + rr[k];
+          ca = (v == m) ? 8 * g + k : ca;
+        }
+      }
+      if (WITH_BP) {
+        // level 2: lowest member of class ca whose sum equals m (descending scan, last hit
+        // wins); several members can round to the same sum
+        const int lo = cs_lds[ca], hi = cs_lds[ca + 1];
+        const float rr = rc_lds[cj * NC + ca];
+        for (int d = maxlen - 1; d >= 0; --d) {
+          // past the end of a short class the last member is simply looked at again
+          const int i = lo + d < hi ? lo + d : hi - 1;
+          const float v = tile[i * kWave + lane] + rr;
+          arg = (v == m) ? i : arg;
+        }
+      }
+    }
+    // Every strategy of the target class gets the same (m, arg), shifted by its own O and
+    // with its own T added.  All offsets are 32-bit element offsets from the instance's
+    // plane (the launcher admits the kernel only when S * pitch fits), so the per-strategy
+    // bookkeeping stays on the scalar side and costs a handful of instructions.
+    const int jlo = cstart[cj], jhi = cstart[cj + 1];
+    uint32_t joff = (uint32_t)jlo * (uint32_t)pitch;
+    for (int j = jlo; j < jhi; ++j, joff += (uint32_t)pitch) {
+      const int o = orow[j];
+      if (compute) {
+        if (rows_on && row <= E - o) {
+          const uint32_t at = joff + (uint32_t)o + (uint32_t)row;
+          dstb[at] = m + trow[j];
+          if (WITH_BP) bpb[at] = (uint8_t)arg;
+        }
+      }
+      if (tile_start < o + low) { // uniform and rare: only the tiles around row `low`
+        if (valid && row < o + low) {
+          const uint32_t at = joff + (uint32_t)row;
+          dstb[at] = GS_INF;
+          if (WITH_BP) bpb[at] = 0;
+        }
+      }
+    }
+  }
+}
+
 // Shape-agnostic "pull" form: a lane owns one TARGET row e and, for each sj, scans the
 // previous plane at row e - O[l][sj] straight from global memory.  Any S up to the
 // library limit, uint8 or uint16 backpointers.  Slow (one load per relaxation); it is the
@@ -745,6 +902,55 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
     if (ru >= 2) return launch_push_ru<SP, 2>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
   }
   launch_push_ru<SP, 1>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
+}
+
+bool class_path_applies(const Shape &s) {
+  const int tsp = tuned_sp_for(s.S);
+  // the kernel addresses an instance's plane with 32-bit element offsets
+  return tsp >= 16 && tsp == s.SP && !s.bp16 && (size_t)s.S * s.pitch < ((size_t)1 << 31);
+}
+
+template <int SP, int NW>
+static void launch_class_nw(const Shape &s, const Workspace &w, int l, const float *src,
+                            float *dst, void *bp_l, hipStream_t st) {
+  const long long tiles = (s.M + 1 + kWave - 1) / kWave;
+  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
+  const size_t lds = sizeof(float) * (SP * kWave + kMaxClasses * kWave + kMaxClasses * kMaxClasses) +
+                     sizeof(int) * (kMaxClasses + 1);
+  if (bp_l)
+    hipLaunchKernelGGL((k_dp_class<SP, NW, true>), grid, block, lds, st, src, dst, (uint8_t *)bp_l,
+                       w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
+                       w.lowsum, s.B, s.L, s.S, l, s.pitch);
+  else
+    hipLaunchKernelGGL((k_dp_class<SP, NW, false>), grid, block, lds, st, src, dst,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                       w.budget, w.minO, w.lowsum, s.B, s.L, s.S, l, s.pitch);
+}
+
+template <int SP>
+static void launch_class(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                         void *bp_l, hipStream_t st) {
+  int waves = tuning().jsplit;
+  if (waves < 1 || waves > 8) waves = 4;
+  if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
+  else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
+  else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
+  else launch_class_nw<SP, 1>(s, w, l, src, dst, bp_l, st);
+}
+
+const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
+                            float *dst, void *bp_l, hipStream_t st) {
+  switch (s.SP) {
+    case 16: launch_class<16>(s, w, l, src, dst, bp_l, st); break;
+    case 24: launch_class<24>(s, w, l, src, dst, bp_l, st); break;
+    case 32: launch_class<32>(s, w, l, src, dst, bp_l, st); break;
+    case 48: launch_class<48>(s, w, l, src, dst, bp_l, st); break;
+    case 64: launch_class<64>(s, w, l, src, dst, bp_l, st); break;
+    case 96: launch_class<96>(s, w, l, src, dst, bp_l, st); break;
+    case 128: launch_class<128>(s, w, l, src, dst, bp_l, st); break;
+    default: break; // class_path_applies() admits no other pitch
+  }
+  return "k_dp_class";
 }
 
 const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,

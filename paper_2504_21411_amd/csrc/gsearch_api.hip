@@ -12,7 +12,8 @@ namespace {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t planes, bp, Tq, Oq, Rt, ridx, budget, minO, lowsum, best_s, best_cost, status, total;
+  size_t planes, bp, Tq, Oq, Rt, ridx, budget, minO, lowsum, best_s, best_cost, status, cmeta,
+      cstart, cls, Rc, total;
   int nplanes;
 };
 
@@ -53,6 +54,10 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.best_s = take(sizeof(int32_t) * (size_t)s.B);
   y.best_cost = take(sizeof(float) * (size_t)s.B);
   y.status = take(sizeof(int32_t));
+  y.cmeta = take(sizeof(int32_t) * 2);
+  y.cstart = take(sizeof(int32_t) * (gs::kMaxClasses + 1));
+  y.cls = take(sizeof(int32_t) * (size_t)s.SP);
+  y.Rc = take(sizeof(float) * (size_t)s.K * gs::kMaxClasses * gs::kMaxClasses);
   y.total = off;
   return y;
 }
@@ -256,6 +261,10 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   w.best_s = reinterpret_cast<int32_t *>(base + y.best_s);
   w.best_cost = reinterpret_cast<float *>(base + y.best_cost);
   w.status = reinterpret_cast<int32_t *>(base + y.status);
+  w.cmeta = reinterpret_cast<int32_t *>(base + y.cmeta);
+  w.cstart = reinterpret_cast<int32_t *>(base + y.cstart);
+  w.cls = reinterpret_cast<int32_t *>(base + y.cls);
+  w.Rc = reinterpret_cast<float *>(base + y.Rc);
   ctx->solved = false;
   ctx->shape = s;
   ctx->ws = w;
@@ -269,10 +278,15 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   else if (c.flags & GSEARCH_FLAG_FORCE_TILE) which = gs::ForwardKernel::Tile;
 
   gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w, st);
+  // Transition classes: checked whenever the caller states them, exploited by the class
+  // kernel when no particular kernel is forced and the shape has a register-tiled size.
+  if (p->r_class && s.L > 1) gs::launch_prepare_classes(s, p->r_class, w, st);
+  const bool use_classes =
+      p->r_class && s.L > 1 && which == gs::ForwardKernel::Auto && gs::class_path_applies(s);
   int cur = 0;
   ctx->timed = false;
   const bool timing = ctx->profiling && s.L > 1;
-  if (which == gs::ForwardKernel::Auto && gs::small_path_applies(s)) {
+  if (which == gs::ForwardKernel::Auto && !use_classes && gs::small_path_applies(s)) {
     // latency path: layer 0 and every layer front in one launch, planes in LDS
     cur = keep ? s.L - 1 : ((s.L - 1) & 1);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
@@ -304,9 +318,11 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
         void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes +
                                    (size_t)b0 * inst_elems * (s.bp16 ? 2 : 1)
                              : nullptr;
-        ctx->forward_kernel = gs::launch_dp_layer(
-            sg, wg, l, w.planes + (size_t)c2 * pe + (size_t)b0 * inst_elems,
-            w.planes + (size_t)nxt * pe + (size_t)b0 * inst_elems, bp_l, which, sst);
+        const float *src_l = w.planes + (size_t)c2 * pe + (size_t)b0 * inst_elems;
+        float *dst_l = w.planes + (size_t)nxt * pe + (size_t)b0 * inst_elems;
+        ctx->forward_kernel = use_classes
+                                  ? gs::launch_dp_class(sg, wg, l, src_l, dst_l, bp_l, sst)
+                                  : gs::launch_dp_layer(sg, wg, l, src_l, dst_l, bp_l, which, sst);
         c2 = nxt;
       }
       last = c2;
@@ -445,6 +461,14 @@ int32_t gsearch_enumerate_count(int32_t N, int32_t tp_max, int32_t sp_max, int32
       n += (N / (tp * sp) > 1) ? 4 : 2; // sdp needs dp > 1; ckpt doubles both
     }
   return n;
+}
+
+int gsearch_layout_classes(const int32_t *desc, int32_t S, int32_t *r_class, int32_t *count_out,
+                           void *stream) {
+  if (!desc || !r_class || S < 1 || S > GSEARCH_MAX_S) return GSEARCH_ERR_INVALID_ARG;
+  gs::launch_layout_classes(desc, S, r_class, count_out, static_cast<hipStream_t>(stream));
+  if (hipGetLastError() != hipSuccess) return GSEARCH_ERR_HIP;
+  return GSEARCH_OK;
 }
 
 int gsearch_enumerate(int32_t N, int32_t tp_max, int32_t sp_max, int32_t tpsp_max, int32_t *desc,

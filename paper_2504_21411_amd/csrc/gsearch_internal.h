@@ -10,6 +10,7 @@ namespace gs {
 
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kRowsPerBlock = 256; // budget rows handled by one workgroup (4 waves)
+constexpr int kMaxClasses = 32;    // transition classes the class kernel keeps in registers
 
 // Shape of the batch being solved plus the padded pitches of the workspace copies.
 struct Shape {
@@ -36,6 +37,12 @@ struct Workspace {
   int32_t *best_s;   // [B]          result of the final reduction (kept for backtrace)
   float *best_cost;  // [B]
   int32_t *status;   // [1]          data-status bits
+  // Transition classes (only meaningful when the caller gave r_class):
+  int32_t *cmeta;    // [2]          number of classes, longest class
+  int32_t *cstart;   // [kMaxClasses+1]  first strategy of class c; S for c >= number of classes
+  int32_t *cls;      // [SP]         class of strategy s (0 for the padding)
+  float *Rc;         // [K][kMaxClasses][kMaxClasses]  Rc[k][cj][ci] = R between the classes'
+                     //              first strategies, +inf for padding classes
 };
 
 inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; }
@@ -44,6 +51,17 @@ inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; 
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
                     const int32_t *r_index, const int32_t *budget, const Workspace &w,
                     hipStream_t st);
+// Validates r_class and R against each other (status bit on violation) and fills
+// cmeta / cstart / cls / Rc; with an invalid partition it installs the one-class partition,
+// so that the class kernel stays memory-safe.  Must follow launch_prepare on the stream.
+void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
+                            hipStream_t st);
+bool class_path_applies(const Shape &s);
+// One layer front with the class kernel (same contract as launch_dp_layer).
+const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
+                            float *dst, void *bp_l, hipStream_t st);
+void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
+                           hipStream_t st);
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);
 // Forward-kernel choice: Auto picks by shape; the others force one implementation.
 enum class ForwardKernel { Auto, Generic, Push, Tile };

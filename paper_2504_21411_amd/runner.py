@@ -36,17 +36,26 @@ def make_context(w: Workload, flags=0, device=0) -> binding.GSearch:
     return binding.GSearch(w.B, w.L, w.S, w.M, w.K, flags=flags, device=device)
 
 
-def run_step(ctx: binding.GSearch, dw: DeviceWorkload, backtrace="best", stream=None):
-    """One pass of the hot path.  Returns device tensors; nothing is synchronised here."""
+def run_step(ctx: binding.GSearch, dw: DeviceWorkload, backtrace="best", stream=None,
+             classes=True, r_class=None):
+    """One pass of the hot path.  Returns device tensors; nothing is synchronised here.
+
+    Model workloads build R from the strategy layouts, so the layout classes of the
+    enumerated strategies are handed to the solve (classes=False withholds them).  Table
+    workloads pass r_class only when the caller supplies one."""
     w = dw.w
     out = {}
     if w.kind == "model":
         desc, count = binding.gsearch_enumerate(device=dw.device, stream=stream, **w.enum)
         T, O, R = binding.gsearch_build_tables(desc, dw.layer, w.hw, dw.rmodel, w.M, stream=stream)
         out.update(desc=desc, count=count, T=T, O=O, R=R)
+        if classes and r_class is None:
+            r_class, n_class = binding.gsearch_layout_classes(desc, stream=stream)
+            out.update(r_class=r_class, n_class=n_class)
     else:
         T, O, R = dw.T, dw.O, dw.R
-    res = ctx.gsearch_solve_batch(T, O, R, dw.r_index, dw.budget, w.M, stream=stream)
+    res = ctx.gsearch_solve_batch(T, O, R, dw.r_index, dw.budget, w.M, stream=stream,
+                                  r_class=r_class if classes else None)
     out.update(res)
     if backtrace == "best":
         out.update(ctx.gsearch_backtrace(res["best_instance"], 1, stream=stream))
@@ -61,10 +70,15 @@ def to_numpy(out: dict) -> dict:
     return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
 
 
-def solve_workload(w: Workload, flags=0, backtrace="all") -> dict:
-    """Convenience: upload, run one step, download everything as numpy."""
+def solve_workload(w: Workload, flags=0, backtrace="all", classes=True, r_class=None) -> dict:
+    """Convenience: upload, run one step, download everything as numpy.  r_class: optional
+    numpy int32 [S] for table workloads."""
+    import torch
     dw = DeviceWorkload(w)
+    if r_class is not None:
+        r_class = torch.from_numpy(np.ascontiguousarray(r_class, np.int32)).to(dw.device)
     with make_context(w, flags=flags) as ctx:
-        out = to_numpy(run_step(ctx, dw, backtrace=backtrace))
+        out = to_numpy(run_step(ctx, dw, backtrace=backtrace, classes=classes, r_class=r_class))
         out["data_status"] = ctx.gsearch_data_status()
+        out["forward_kernel"] = ctx.gsearch_forward_kernel()
     return out

@@ -124,6 +124,34 @@ def random_tables(name, B, L, S, M, K=1, seed=0, o_hi=None, budget=None, identic
                     T=np.ascontiguousarray(T), O=np.ascontiguousarray(O), R=R)
 
 
+def class_tables(name, B, L, S, M, sizes, K=1, seed=0, budget=None, coarse=False):
+    """Random tables whose transition matrices depend on the strategies only through
+    contiguous classes of the given sizes (sum(sizes) == S).  Returns (workload, r_class).
+
+    coarse=True draws T from 1024 + k * 2^-13 (k in 0..7, neighbouring fp32 values) and the
+    class transition values from {0, 4096, 8192}: adding 4096 or more drops the low bits of
+    the sum, so different candidates of a class often ROUND to the same sum; that is the
+    case in which the member with the smallest previous cost is not the lowest-index
+    argmin."""
+    sizes = [int(x) for x in sizes]
+    assert sum(sizes) == S and all(x >= 1 for x in sizes)
+    w = random_tables(name, B, L, S, M, K=K, seed=seed, budget=budget)
+    rng = SplitMix64(seed + 7919)
+    r_class = np.repeat(np.arange(len(sizes), dtype=np.int32), sizes)
+    nc = len(sizes)
+    if coarse:
+        w.T = (np.float32(1024.0) + rng.randint(0, 7, w.T.size).astype(np.float32)
+               * np.float32(2.0 ** -13)).reshape(w.T.shape).astype(np.float32)
+        Rc = (rng.randint(0, 2, K * nc * nc).astype(np.float32) * np.float32(4096.0))
+    else:
+        Rc = rng.uniform_range(0.0, 2.0, K * nc * nc)
+    Rc = Rc.reshape(K, nc, nc).astype(np.float32)
+    for k in range(K):
+        np.fill_diagonal(Rc[k], 0.0)
+    w.R = np.ascontiguousarray(Rc[:, r_class][:, :, r_class])
+    return w, r_class
+
+
 # --------------------------------------------------------------------------------------
 # The five benchmark configurations (zero-based numbering).
 # --------------------------------------------------------------------------------------

@@ -462,3 +462,134 @@ def test_instance_groups_on_parallel_streams(gs, oracle_mod, mode):
                 assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (groups, b)
         with pytest.raises(binding.GSearchError):
             ctx.gsearch_set_instance_groups(-1)
+
+
+# ------------------------------------------------------------------ transition classes
+CLASS_CASES = [
+    # S, class sizes, K, M, coarse
+    (16, [4, 4, 4, 4], 1, 200, False), (24, [1] * 24, 2, 130, False), (24, [24], 1, 90, True),
+    (44, [4] * 11, 1, 300, True), (44, [2, 6, 1, 1, 9, 5, 4, 4, 4, 8], 3, 257, True),
+    (64, [2] * 32, 1, 129, False), (96, [4, 4, 4, 4, 4, 4, 2] * 3 + [4, 4, 4, 2, 4], 1, 260, True),
+    (100, [25, 25, 25, 25], 2, 100, True), (128, [4] * 32, 1, 70, False),
+    (13, [6, 7], 1, 140, True),
+]
+
+
+@pytest.mark.parametrize("mode", ["bp", "nobp"])
+@pytest.mark.parametrize("case", CLASS_CASES, ids=lambda c: "S%dnc%dK%d" % (c[0], len(c[1]), c[2]))
+def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode):
+    """R constant on (class, class) blocks, stated through r_class: the class kernel must
+    give the oracle's bits (the oracle knows nothing of classes), whole planes and
+    backpointers included, also when candidates of one class round to the same sum."""
+    binding, runner = gs
+    import torch
+    S, sizes, K, M, coarse = case
+    B, L = 3, 6
+    budget = np.array([M, M // 3, max(0, M - 65)], np.int32)
+    w, r_class = workloads.class_tables("classes", B, L, S, M, sizes, K=K, seed=S + len(sizes),
+                                        budget=budget, coarse=coarse)
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
+        out = runner.run_step(ctx, dw, backtrace="all", r_class=rc)
+        C, bp = ctx.gsearch_export_planes(want_bp=(mode == "bp"))
+        got = runner.to_numpy(out)
+        got["data_status"] = ctx.gsearch_data_status()
+        kernel = ctx.gsearch_forward_kernel()
+        C = C.cpu().numpy()
+        bp = bp.cpu().numpy() if bp is not None else None
+    assert kernel == ("k_dp_class" if S >= 9 else kernel)
+    assert_same(got, ref, w, f"classes {mode}")
+    for b in range(B):
+        E = int(w.budget[b])
+        one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True)
+        assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (case, b)
+        if bp is not None:
+            assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), (case, b)
+
+
+def test_rounding_tie_inside_a_class_keeps_the_lowest_index(gs, oracle_mod):
+    """Two strategies of one class, the SECOND has the smaller previous cost, and the class
+    transition value is large enough that both sums round to the same fp32 value: the
+    lowest-index rule then picks the first, which a class minimum alone would miss."""
+    _, runner = gs
+    S, L, M = 16, 2, 70
+    ulp = np.float32(2.0 ** -13)
+    T = np.full((1, L, S), 2000.0, np.float32)
+    T[0, 0, 0] = np.float32(1024.0) + ulp      # class 0, index 0: larger cost
+    T[0, 0, 1] = np.float32(1024.0)            # class 0, index 1: smaller cost
+    O = np.ones((1, L, S), np.int32)
+    r_class = np.repeat(np.arange(4, dtype=np.int32), 4)
+    Rc = np.full((4, 4), 4096.0, np.float32)
+    R = np.ascontiguousarray(Rc[r_class][:, r_class])[None]
+    w = Workload("tie", 1, L, S, M, 1, np.array([M], np.int32), np.zeros((1, L), np.int32),
+                 "tables", T=T, O=O, R=R)
+    assert np.float32(T[0, 0, 0] + np.float32(4096.0)) == np.float32(T[0, 0, 1] + np.float32(4096.0))
+    ref = oracle_mod.solve(T[0], O[0], R, w.r_index[0], M, want_planes=True)
+    assert (ref["bp"][1, 2:, :] == 0).all()                   # the oracle takes index 0
+    got = runner.solve_workload(w, r_class=r_class)
+    assert got["forward_kernel"] == "k_dp_class" and got["data_status"] == 0
+    assert np.array_equal(got["plan"][0], ref["plan"]) and got["plan"][0][0] == 0
+
+
+def test_bad_transition_classes_are_flagged(gs):
+    binding, runner = gs
+    w, r_class = workloads.class_tables("badclass", 2, 4, 24, 100, [4] * 6, seed=5)
+    ok = runner.solve_workload(w, r_class=r_class)
+    assert ok["data_status"] == 0 and np.isfinite(ok["best_cost"]).all()
+    cases = {}
+    c = r_class.copy(); c[5] = 3                      # not contiguous / not ascending by <= 1
+    cases["order"] = (w, c)
+    c = r_class.copy(); c[0] = 1
+    cases["start"] = (w, c)
+    c = r_class.copy(); c[3] = -2
+    cases["negative"] = (w, c)
+    w40, _ = workloads.class_tables("many", 2, 3, 40, 60, [1] * 40, seed=6)
+    cases["too_many"] = (w40, np.arange(40, dtype=np.int32))
+    import copy
+    w2 = copy.deepcopy(w); w2.R = w.R.copy(); w2.R[0, 1, 9] += np.float32(0.5)   # row differs inside class 0
+    cases["row"] = (w2, r_class)
+    w3 = copy.deepcopy(w); w3.R = w.R.copy(); w3.R[0, 9, 2] += np.float32(0.5)   # column differs
+    cases["column"] = (w3, r_class)
+    for name, (ww, cc) in cases.items():
+        got = runner.solve_workload(ww, r_class=cc)
+        assert got["data_status"] & binding.GSEARCH_DATA_BAD_RCLASS, name
+        assert np.isinf(got["best_cost"]).all() and (got["best_s"] == -1).all(), name
+        assert int(got["best_instance"][0]) == -1, name
+    # forced kernels ignore the classes but the promise is still checked
+    got = runner.solve_workload(w2, flags=MODES["bp_tile"], r_class=r_class)
+    assert got["data_status"] & binding.GSEARCH_DATA_BAD_RCLASS
+    got = runner.solve_workload(w, flags=MODES["bp_push"], r_class=r_class)
+    assert got["data_status"] == 0 and got["forward_kernel"] == "k_dp_push"
+
+
+def test_layout_classes_of_enumerated_strategies(gs, oracle_mod):
+    binding, _ = gs
+    for enum in (dict(N=32, tp_max=8, sp_max=4, tpsp_max=16), dict(N=64, sp_max=32), dict(N=8)):
+        desc, _ = binding.gsearch_enumerate(**enum)
+        r_class, count = binding.gsearch_layout_classes(desc)
+        d = oracle_mod.enumerate_strategies(**enum)
+        change = np.any(d[1:, :3] != d[:-1, :3], axis=1)
+        want = np.concatenate([[0], np.cumsum(change)]).astype(np.int32)
+        assert np.array_equal(r_class.cpu().numpy(), want)
+        assert int(count.cpu()[0]) == want[-1] + 1
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("i", [1, 3])
+def test_model_configs_without_classes_use_the_general_kernels(gs, oracle_mod, i):
+    """The model workloads hand their layout classes to the solve by default; withheld, the
+    general kernels must give the same bits."""
+    _, runner = gs
+    w = workloads.get_config(i) if i == 1 else workloads.config3()
+    if i == 3:
+        w.B, w.layer, w.budget, w.r_index = 2, w.layer[[0, 7]], w.budget[[0, 7]], w.r_index[[0, 7]]
+    desc = oracle_mod.enumerate_strategies(**w.enum)
+    T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
+    ref = oracle_batch(oracle_mod, w, T, O, R)
+    a = runner.solve_workload(w, classes=True)
+    b = runner.solve_workload(w, classes=False)
+    assert a["forward_kernel"] == "k_dp_class" and b["forward_kernel"] == "k_dp_tile"
+    assert_same(a, ref, w, "classes")
+    assert_same(b, ref, w, "general")
