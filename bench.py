@@ -1,6 +1,7 @@
 """Benchmark of the batched strategy-search DP on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--mode bp|nobp]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+                    [--mode bp|nobp|bp-general|nobp-general] [--also nobp,bp-general]
 
 A step is one pass of the whole hot path over one batch whose inputs are already resident
 in HBM: strategy enumeration, cost-table builder (model workloads), batched forward DP,
@@ -23,6 +24,7 @@ if ROOT not in sys.path:
 # 256 CUs x 4 SIMDs x 16 lanes per clock x 2.4 GHz.  The published 157.3 TFLOP/s is the
 # same machine counting a packed (x2) fused multiply-add (x2) on every lane.
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+HBM_PEAK_GBS = 8000.0
 def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     """Vector-ALU instructions per relaxation that the kernel's algorithm needs.
 
@@ -39,7 +41,7 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     return 4.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {(3, "bp"): 114.5e6, (3, "nobp"): 101.3e6}
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def cpu_baseline(w, cfg_index, target_relax=3.0e10):
@@ -69,9 +71,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--mode", choices=["bp", "nobp"], default="bp")
+    ap.add_argument("--mode", choices=["bp", "nobp", "bp-general", "nobp-general"], default="bp")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--also", default="", help="comma list of extra modes to time, e.g. nobp")
+    ap.add_argument("--also", default="nobp,bp-general",
+                    help="comma list of extra modes to time ('' for none)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -99,16 +102,27 @@ def main():
     relax = w.relaxations()
 
     def time_mode(mode):
-        flags = binding.GSEARCH_FLAG_NO_BACKPOINTERS if mode == "nobp" else 0
+        # "bp" / "nobp": with or without a backpointer stream; "-general": the layout classes
+        # of the strategies are withheld from the solve, so the general kernels run
+        classes = not mode.endswith("-general")
+        nobp = mode.startswith("nobp")
+        flags = binding.GSEARCH_FLAG_NO_BACKPOINTERS if nobp else 0
         with runner.make_context(w, flags=flags) as ctx:
             ctx.gsearch_set_profiling(True)
-            for _ in range(args.warmup):
-                runner.run_step(ctx, dw, backtrace="best")
+            # W untimed steps, and in any case half a second of them: on the test box the
+            # first launch phase that starts 0.1-0.2 s after a context's first solve has been
+            # seen to stall on the host for about 40 ms, once per context
+            tw = time.perf_counter()
+            done = 0
+            while done < args.warmup or time.perf_counter() - tw < 0.5:
+                runner.run_step(ctx, dw, backtrace="best", classes=classes)
+                torch.cuda.synchronize()
+                done += 1
             torch.cuda.synchronize()
             fwd = []
             t0 = time.perf_counter()
             for _ in range(args.steps):
-                out = runner.run_step(ctx, dw, backtrace="best")
+                out = runner.run_step(ctx, dw, backtrace="best", classes=classes)
                 fwd.append(ctx.gsearch_forward_ms())      # waits for this step's forward pass
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
@@ -125,33 +139,53 @@ def main():
             rows = w.budget.astype(np.int64)[:, None] + 1
             skipped = np.minimum(low[:, :-1] // 64 * 64, rows)
             executed = float((rows - skipped).sum()) / float((rows * (w.L - 1)).sum())
-            if kernel not in ("k_dp_push", "k_dp_tile"):
+            if kernel not in ("k_dp_push", "k_dp_tile", "k_dp_class"):
                 executed = 1.0
+            n_class = int(out["n_class"].cpu()[0]) if "n_class" in out else None
+            # algorithmic HBM bytes of one layer front: every computed source row is read
+            # once (4 B per state), every target row 0..E written once (4 B + 1 B backpointer)
+            front_bytes = float(((rows - skipped).sum() * 4.0 / (w.L - 1)
+                                 + rows.sum() * (4.0 if nobp else 5.0)) * w.S)
         ms_step = dt * 1e3 / args.steps
         fwd_ms = sum(fwd) / len(fwd)
         # The batch runs as `groups` chains of L-1 launches side by side (one stream each);
         # every chain spans the forward time, so a launch lasts fwd/(L-1) on average and
         # works on 1/groups of a layer front while the other chains' launches share the chip.
         launches = w.L - 1
-        opr = ops_per_relaxation(kernel, mode, w.S)
-        ops = opr * relax * executed / launches / groups        # executed, per launch
-        per_launch = ops / (fwd_ms * 1e-3 / launches) / 1e12
-        achieved = per_launch * groups                          # all concurrent launches
+        launch_s = fwd_ms * 1e-3 / launches
+        common = {"kernel": kernel, "concurrent_launches": groups,
+                  "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode))}
+        if kernel == "k_dp_class":
+            # With the transition classes the arithmetic shrinks to one minimum per class
+            # and one relaxation per pair of classes, and the launch is bound by the plane
+            # and backpointer traffic: roofline against HBM.
+            per_launch = front_bytes / groups / launch_s / 1e9
+            achieved = per_launch * groups
+            roof = dict(common, bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=achieved / HBM_PEAK_GBS, achieved_per_launch=per_launch,
+                        algorithmic_bytes_per_launch=front_bytes / groups, classes=n_class,
+                        executed_fraction_of_nominal_relaxations=executed
+                        * (n_class * n_class + w.S) / float(w.S * w.S))
+        else:
+            opr = ops_per_relaxation(kernel, "nobp" if nobp else "bp", w.S)
+            ops = opr * relax * executed / launches / groups        # executed, per launch
+            per_launch = ops / launch_s / 1e12
+            achieved = per_launch * groups                          # all concurrent launches
+            roof = dict(common, bound="alu", achieved=achieved, peak=ALU_PEAK_TLANEOPS,
+                        unit="Tlaneop/s", frac=achieved / ALU_PEAK_TLANEOPS,
+                        achieved_per_launch=per_launch, ops_per_relaxation=opr,
+                        executed_fraction_of_nominal_relaxations=executed)
         return {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
                 "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
                 "forward_grelax_per_s": relax / (fwd_ms * 1e-3) / 1e9,
                 "kernel_avg_us": fwd_ms * 1e3 / launches,
-                "roofline": {"bound": "alu", "achieved": achieved, "peak": ALU_PEAK_TLANEOPS,
-                             "unit": "Tlaneop/s", "frac": achieved / ALU_PEAK_TLANEOPS,
-                             "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode)),
-                             "kernel": kernel, "ops_per_relaxation": opr,
-                             "concurrent_launches": groups,
-                             "achieved_per_launch": per_launch,
-                             "executed_fraction_of_nominal_relaxations": executed},
-                "best_instance": best}
+                "roofline": roof, "best_instance": best}
 
     main_res = time_mode(args.mode)
-    extra = [time_mode(m) for m in args.also.split(",") if m and m != args.mode]
+    also = [m for m in args.also.split(",") if m and m != args.mode]
+    if w.kind != "model":       # table workloads state no classes: "-general" is the same run
+        also = [m for m in also if not m.endswith("-general")]
+    extra = [time_mode(m) for m in also]
 
     line = {
         "metric": "G DP relaxations/sec (min-plus updates) + batch search latency, 1 MI355X",

@@ -517,12 +517,13 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     int l, int pitch) {
   constexpr int NC = kMaxClasses;
   extern __shared__ float lds[];
-  float *tile = lds;                    // [SP][64]
-  float *cmin = tile + SP * kWave;      // [NC][64]
+  float *cmin = lds;                    // [NC][64]  class minima of the tile
   float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
-  int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1]
-  const int b = blockIdx.x % B;
-  const int tile_start = (int)(blockIdx.x / B) * kWave;
+  int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1], padded to NC + 32
+  float *tile = rc_lds + NC * NC + NC + 32;                // [SP][64], backpointer mode only
+  // grid = (instances, tiles): consecutive workgroups belong to different instances
+  const int b = blockIdx.x;
+  const int tile_start = (int)blockIdx.y * kWave;
   const int js = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int E = budget[b];
@@ -545,17 +546,23 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
 
   float cmv[NC];
   if (compute) {
+    // unconditional loads from clamped (always valid) addresses, padding selected
+    // afterwards: no lane-mask juggling or branches between the loads
     float stage[SP / NW];
+    const uint32_t rowc = (uint32_t)(valid ? row : E);
 #pragma unroll
     for (int u = 0; u < SP / NW; ++u) {
       const int i = u * NW + js;
-      stage[u] = (i < S && valid) ? srcb[(size_t)i * pitch + row] : GS_INF;
+      const float v = srcb[(uint32_t)(i < S ? i : S - 1) * (uint32_t)pitch + rowc];
+      stage[u] = (i < S && valid) ? v : GS_INF;
     }
     for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
     for (int x = threadIdx.x; x < NC * NC; x += NW * kWave) rc_lds[x] = rck[x];
     if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+    if (WITH_BP) {
 #pragma unroll
-    for (int u = 0; u < SP / NW; ++u) tile[(u * NW + js) * kWave + lane] = stage[u];
+      for (int u = 0; u < SP / NW; ++u) tile[(u * NW + js) * kWave + lane] = stage[u];
+    }
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < SP / NW; ++u) {
@@ -575,20 +582,29 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   }
 
   const bool rows_on = valid && row >= low; // source rows whose targets are computed
+  // run boundaries of this wave's first target class; those of the next one are requested
+  // an iteration ahead, like the O and T entries inside the loop over the class members
+  int jlo = 0, jhi = 0;
+  if (js < nc) { jlo = cstart[js]; jhi = cstart[js + 1]; }
   for (int cj = js; cj < nc; cj += NW) {
+    const int cn = cj + NW < NC ? cj + NW : NC - 1; // stays inside the run table
+    const int jlo_next = cstart[cn], jhi_next = cstart[cn + 1];
     float m = GS_INF;
     int arg = 0;
     if (compute) {
       const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
+      const float16_t r0 = *reinterpret_cast<const float16_t *>(rc);
+      const float16_t r1 = *reinterpret_cast<const float16_t *>(rc + 16);
       // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
       int g = 0;
 #pragma unroll
       for (int q = 0; q < NC / 8; ++q) {
         if (8 * q < nc) {
-          const float8_t r = *reinterpret_cast<const float8_t *>(rc + 8 * q);
-          float cm = __builtin_fminf(cmv[8 * q] + r[0], cmv[8 * q + 1] + r[1]);
+          const float16_t r = q < 2 ? r0 : r1;
+          const int h = (q & 1) * 8;
+          float cm = __builtin_fminf(cmv[8 * q] + r[h], cmv[8 * q + 1] + r[h + 1]);
 #pragma unroll
-          for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[k]);
+          for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
           chunk_update<true>(m, g, cm, q);
         }
       }
@@ -612,11 +628,18 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
         // wins); several members can round to the same sum
         const int lo = cs_lds[ca], hi = cs_lds[ca + 1];
         const float rr = rc_lds[cj * NC + ca];
-        for (int d = maxlen - 1; d >= 0; --d) {
-          // past the end of a short class the last member is simply looked at again
-          const int i = lo + d < hi ? lo + d : hi - 1;
-          const float v = tile[i * kWave + lane] + rr;
-          arg = (v == m) ? i : arg;
+        // four members per round so that their LDS reads are in flight together; past the
+        // end of a short class the last member is simply looked at again
+        for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
+          float tv[4];
+          int ti[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            ti[u] = lo + d0 + u < hi ? lo + d0 + u : hi - 1;
+            tv[u] = tile[ti[u] * kWave + lane];
+          }
+#pragma unroll
+          for (int u = 3; u >= 0; --u) arg = (tv[u] + rr == m) ? ti[u] : arg;
         }
       }
     }
@@ -624,14 +647,17 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     // with its own T added.  All offsets are 32-bit element offsets from the instance's
     // plane (the launcher admits the kernel only when S * pitch fits), so the per-strategy
     // bookkeeping stays on the scalar side and costs a handful of instructions.
-    const int jlo = cstart[cj], jhi = cstart[cj + 1];
     uint32_t joff = (uint32_t)jlo * (uint32_t)pitch;
+    int o = orow[jlo];
+    float t = trow[jlo];
     for (int j = jlo; j < jhi; ++j, joff += (uint32_t)pitch) {
-      const int o = orow[j];
+      const int jn = j + 1 < jhi ? j + 1 : j;
+      const int o_next = orow[jn];
+      const float t_next = trow[jn];
       if (compute) {
         if (rows_on && row <= E - o) {
           const uint32_t at = joff + (uint32_t)o + (uint32_t)row;
-          dstb[at] = m + trow[j];
+          dstb[at] = m + t;
           if (WITH_BP) bpb[at] = (uint8_t)arg;
         }
       }
@@ -642,7 +668,11 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
           if (WITH_BP) bpb[at] = 0;
         }
       }
+      o = o_next;
+      t = t_next;
     }
+    jlo = jlo_next;
+    jhi = jhi_next;
   }
 }
 
@@ -907,16 +937,18 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
 bool class_path_applies(const Shape &s) {
   const int tsp = tuned_sp_for(s.S);
   // the kernel addresses an instance's plane with 32-bit element offsets
-  return tsp >= 16 && tsp == s.SP && !s.bp16 && (size_t)s.S * s.pitch < ((size_t)1 << 31);
+  // and runs on a (instances, tiles) grid
+  return tsp >= 16 && tsp == s.SP && !s.bp16 && (size_t)s.S * s.pitch < ((size_t)1 << 31) &&
+         (s.M + kWave) / kWave <= 65535;
 }
 
 template <int SP, int NW>
 static void launch_class_nw(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st) {
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
-  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
-  const size_t lds = sizeof(float) * (SP * kWave + kMaxClasses * kWave + kMaxClasses * kMaxClasses) +
-                     sizeof(int) * (kMaxClasses + 1);
+  const dim3 grid((unsigned)s.B, (unsigned)tiles), block(NW * kWave);
+  const size_t lds = sizeof(float) * ((bp_l ? SP * kWave : 0) + kMaxClasses * kWave +
+                                      kMaxClasses * kMaxClasses + kMaxClasses + 32);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true>), grid, block, lds, st, src, dst, (uint8_t *)bp_l,
                        w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
@@ -930,8 +962,10 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
 template <int SP>
 static void launch_class(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                          void *bp_l, hipStream_t st) {
+  // eight waves per tile: measured, the kernel lives on latency hiding and the per-wave
+  // share of a tile is short (GSEARCH_JSPLIT overrides)
   int waves = tuning().jsplit;
-  if (waves < 1 || waves > 8) waves = 4;
+  if (waves < 1 || waves > 8) waves = 8;
   if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
