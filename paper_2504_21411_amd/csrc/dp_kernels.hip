@@ -520,7 +520,9 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   float *cmin = lds;                    // [NC][64]  class minima of the tile
   float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
   int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1], padded to NC + 32
-  float *tile = rc_lds + NC * NC + NC + 32;                // [SP][64], backpointer mode only
+  int *o_lds = cs_lds + NC + 32;                           // [SP]  this layer's O row
+  float *t_lds = reinterpret_cast<float *>(o_lds + SP);    // [SP]  this layer's T row
+  float *tile = t_lds + SP;                                // [SP][64], backpointer mode only
   // grid = (instances, tiles): consecutive workgroups belong to different instances
   const int b = blockIdx.x;
   const int tile_start = (int)blockIdx.y * kWave;
@@ -544,16 +546,25 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   const int nc = cmeta[0];
   const int maxlen = cmeta[1];
 
+  // The scalar unit is this kernel's scarce resource (one instruction per cycle for the
+  // whole compute unit, and every wave repeats the per-strategy bookkeeping), so the O and
+  // T rows go through LDS into vector registers and the comparisons that use them run on
+  // the vector side, which has slack.
+  for (int x = threadIdx.x; x < SP; x += NW * kWave) {
+    o_lds[x] = orow[x];
+    t_lds[x] = trow[x];
+  }
   float cmv[NC];
   if (compute) {
-    // unconditional loads from clamped (always valid) addresses, padding selected
-    // afterwards: no lane-mask juggling or branches between the loads
+    // Unconditional loads, padding selected afterwards: no lane-mask juggling or branches
+    // between the loads.  Strategy rows S..SP-1 do not exist; their addresses fall into the
+    // next instance or the slack behind the last plane (the workspace reserves it).
     float stage[SP / NW];
     const uint32_t rowc = (uint32_t)(valid ? row : E);
 #pragma unroll
     for (int u = 0; u < SP / NW; ++u) {
       const int i = u * NW + js;
-      const float v = srcb[(uint32_t)(i < S ? i : S - 1) * (uint32_t)pitch + rowc];
+      const float v = srcb[(uint32_t)i * (uint32_t)pitch + rowc];
       stage[u] = (i < S && valid) ? v : GS_INF;
     }
     for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
@@ -570,7 +581,11 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
       __hip_atomic_fetch_min(&cmin[c * kWave + lane], stage[u], __ATOMIC_RELAXED,
                              __HIP_MEMORY_SCOPE_WORKGROUP);
     }
-    __syncthreads();
+  } else {
+    __syncthreads(); // the O and T rows are needed for the +inf prefix in any case
+  }
+  __syncthreads();
+  if (compute) {
     // only the chunks of eight classes that exist are kept (the rest is never read)
 #pragma unroll
     for (int q = 0; q < NC / 8; ++q) {
@@ -648,28 +663,21 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     // plane (the launcher admits the kernel only when S * pitch fits), so the per-strategy
     // bookkeeping stays on the scalar side and costs a handful of instructions.
     uint32_t joff = (uint32_t)jlo * (uint32_t)pitch;
-    int o = orow[jlo];
-    float t = trow[jlo];
     for (int j = jlo; j < jhi; ++j, joff += (uint32_t)pitch) {
-      const int jn = j + 1 < jhi ? j + 1 : j;
-      const int o_next = orow[jn];
-      const float t_next = trow[jn];
+      const int o = o_lds[j]; // same address in every lane: an LDS broadcast
       if (compute) {
-        if (rows_on && row <= E - o) {
-          const uint32_t at = joff + (uint32_t)o + (uint32_t)row;
-          dstb[at] = m + t;
+        const int eo = row + o;
+        if (rows_on && eo <= E) {
+          const uint32_t at = joff + (uint32_t)eo;
+          dstb[at] = m + t_lds[j];
           if (WITH_BP) bpb[at] = (uint8_t)arg;
         }
       }
-      if (tile_start < o + low) { // uniform and rare: only the tiles around row `low`
-        if (valid && row < o + low) {
-          const uint32_t at = joff + (uint32_t)row;
-          dstb[at] = GS_INF;
-          if (WITH_BP) bpb[at] = 0;
-        }
+      if (valid && row < o + low) { // +inf prefix: only the tiles around row `low` have any
+        const uint32_t at = joff + (uint32_t)row;
+        dstb[at] = GS_INF;
+        if (WITH_BP) bpb[at] = 0;
       }
-      o = o_next;
-      t = t_next;
     }
     jlo = jlo_next;
     jhi = jhi_next;
@@ -948,7 +956,7 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)s.B, (unsigned)tiles), block(NW * kWave);
   const size_t lds = sizeof(float) * ((bp_l ? SP * kWave : 0) + kMaxClasses * kWave +
-                                      kMaxClasses * kMaxClasses + kMaxClasses + 32);
+                                      kMaxClasses * kMaxClasses + kMaxClasses + 32 + 2 * SP);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true>), grid, block, lds, st, src, dst, (uint8_t *)bp_l,
                        w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
@@ -962,10 +970,11 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
 template <int SP>
 static void launch_class(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                          void *bp_l, hipStream_t st) {
-  // eight waves per tile: measured, the kernel lives on latency hiding and the per-wave
-  // share of a tile is short (GSEARCH_JSPLIT overrides)
+  // waves per tile, measured: eight with backpointers (the kernel lives on latency hiding
+  // and a wave's share of a tile is short), four for the lighter min-only pass
+  // (GSEARCH_JSPLIT overrides)
   int waves = tuning().jsplit;
-  if (waves < 1 || waves > 8) waves = 8;
+  if (waves < 1 || waves > 8) waves = bp_l ? 8 : 4;
   if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);

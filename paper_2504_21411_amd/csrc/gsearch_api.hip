@@ -41,7 +41,10 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
     return at;
   };
   y.nplanes = keeps_all_planes(flags) ? s.L : (s.L < 2 ? s.L : 2);
-  y.planes = take(sizeof(float) * gs::plane_elems(s) * (size_t)y.nplanes);
+  // slack of one padded instance row block behind the last plane: the class kernel reads
+  // (and discards) the strategy rows S..SP-1 of an instance without clamping the address
+  y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)y.nplanes +
+                                   (size_t)s.SP * s.pitch));
   const bool want_bp = !(flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
   y.bp = take(want_bp ? gs::plane_elems(s) * (size_t)(s.L - 1) * (s.bp16 ? 2 : 1) : 0);
   y.Tq = take(sizeof(float) * (size_t)s.B * s.L * s.SP);
@@ -118,13 +121,15 @@ namespace {
 // 16 % on the large batches: a front there is a few rounds of long workgroups, and the
 // second chain fills the tail of each round and the gap between launches); more than two
 // add little, and fronts of a few microseconds lose to the fork and join.
-int group_count(const gs::Shape &s, int requested) {
+int group_count(const gs::Shape &s, int requested, bool class_kernel) {
   static const int env = [] {
     const char *e = getenv("GSEARCH_STREAMS");
     return e ? atoi(e) : 0;
   }();
   const double front = (double)s.B * (s.M + 1) * s.S * s.S;
-  int g = requested >= 1 ? requested : env >= 1 ? env : (front >= 5.0e8 ? 2 : 1);
+  // (the class kernel's workgroups are short and memory-bound; a second chain only takes
+  // bandwidth from the first)
+  int g = requested >= 1 ? requested : env >= 1 ? env : (front >= 5.0e8 && !class_kernel ? 2 : 1);
   if (g > gsearch_ctx::kMaxSide + 1) g = gsearch_ctx::kMaxSide + 1;
   return g < s.B ? g : s.B;
 }
@@ -296,7 +301,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   } else {
     gs::launch_init_layer0(s, w, w.planes, st);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
-    const int groups = s.L > 1 ? group_count(s, ctx->groups) : 1;
+    const int groups = s.L > 1 ? group_count(s, ctx->groups, use_classes) : 1;
     ctx->groups_used = groups;
     if (groups > 1) {
       if (!ensure_side_streams(ctx, groups - 1)) return GSEARCH_ERR_HIP;
