@@ -41,7 +41,7 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     return 4.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {(3, "bp"): 99.2e6, (3, "nobp"): 86.5e6, (3, "bp-general"): 54.0e6}
 
 
 def cpu_baseline(w, cfg_index, target_relax=3.0e10):
@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--mode", choices=["bp", "nobp", "bp-general", "nobp-general"], default="bp")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--min-warmup-seconds", type=float, default=0.5,
+                    help="keep warming up at least this long (0 for short profiling runs)")
     ap.add_argument("--also", default="nobp,bp-general",
                     help="comma list of extra modes to time ('' for none)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -114,7 +116,7 @@ def main():
             # seen to stall on the host for about 40 ms, once per context
             tw = time.perf_counter()
             done = 0
-            while done < args.warmup or time.perf_counter() - tw < 0.5:
+            while done < args.warmup or time.perf_counter() - tw < args.min_warmup_seconds:
                 runner.run_step(ctx, dw, backtrace="best", classes=classes)
                 torch.cuda.synchronize()
                 done += 1

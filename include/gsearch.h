@@ -182,14 +182,16 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
 
 /* Measurement aid.  With profiling enabled, every later solve records one HIP event on
  * its stream just before the first forward-DP launch (layer 1) and one just after the
- * last (layer L-1).  gsearch_forward_ms waits for the second event of the most recent
- * solve and returns the elapsed milliseconds between the two in *host_ms, i.e. the time
- * of the L-1 layer-front launches including the gaps between them.
+ * last (layer L-1; with instance groups: after the other groups' streams have joined).
+ * gsearch_forward_ms waits for the second event of the most recent solve and returns the
+ * elapsed milliseconds between the two in *host_ms, i.e. the time of the L-1 layer fronts
+ * of every group including the gaps between launches.
  * Errors: NOT_SOLVED (no profiled solve yet, or L == 1), HIP. */
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable);
 int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
 /* Name of the forward kernel the most recent solve launched for its layer fronts
- * ("k_dp_push", "k_dp_tile" or "k_dp_generic"; "" before any solve).  Static string. */
+ * ("k_dp_class", "k_dp_tile", "k_dp_push", "k_dp_generic" or "k_dp_small"; "" before any
+ * solve).  Static string. */
 const char *gsearch_forward_kernel(gsearch_ctx *ctx);
 
 /* Best cost for EVERY budget of the most recent solve (the last plane already holds
