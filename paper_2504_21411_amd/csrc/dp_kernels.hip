@@ -528,23 +528,27 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   const int tile_start = (int)blockIdx.y * kWave;
   const int js = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
+  // every scalar table entry is requested before the first of them is needed (one round
+  // trip to the scalar cache instead of three), so the early exit comes after the loads
+  const int bl = b * L + l;
   const int E = budget[b];
+  const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
+  const int mo = minO[bl];
+  const int kr = ridx[bl];
+  const int nc = cmeta[0];
+  const int maxlen = cmeta[1];
   if (tile_start > E) return; // whole workgroup
 
   const int row = tile_start + lane;
   const bool valid = row <= E;
-  const int bl = b * L + l;
-  const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
-  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave > low; // uniform
+  const bool compute = tile_start <= E - mo && tile_start + kWave > low; // uniform
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
   uint8_t *__restrict__ bpb = WITH_BP ? bp + plane_off : nullptr;
-  const float *__restrict__ rck = Rc + (size_t)ridx[bl] * NC * NC;
+  const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
   const float *__restrict__ trow = Tq + (size_t)bl * SP;
   const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
-  const int nc = cmeta[0];
-  const int maxlen = cmeta[1];
 
   // The scalar unit is this kernel's scarce resource (one instruction per cycle for the
   // whole compute unit, and every wave repeats the per-strategy bookkeeping), so the O and

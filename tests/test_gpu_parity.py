@@ -509,6 +509,31 @@ def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode):
             assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), (case, b)
 
 
+def test_class_kernel_with_instance_groups_and_single_layer(gs, oracle_mod):
+    """Classes combined with forced instance groups (the groups share the class tables), and
+    L == 1, where the promise is not even looked at."""
+    binding, runner = gs
+    import torch
+    w, r_class = workloads.class_tables("classgroups", 5, 7, 44, 500, [4] * 11, K=2, seed=31,
+                                        budget=np.array([500, 77, 300, 0, 499], np.int32),
+                                        coarse=True)
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    with runner.make_context(w) as ctx:
+        for groups in (2, 5, 1, 0):
+            ctx.gsearch_set_instance_groups(groups)
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+            assert ctx.gsearch_instance_groups() == (groups if groups else 1)
+            assert_same(got, ref, w, f"classes groups={groups}")
+    w1, rc1 = workloads.class_tables("classL1", 3, 1, 24, 60, [6] * 4, seed=32)
+    got = runner.solve_workload(w1, r_class=np.array([0, 5, 9] + [0] * 21, np.int32))  # nonsense
+    assert got["data_status"] == 0
+    assert_same(got, oracle_batch(oracle_mod, w1), w1, "L=1")
+
+
 def test_rounding_tie_inside_a_class_keeps_the_lowest_index(gs, oracle_mod):
     """Two strategies of one class, the SECOND has the smaller previous cost, and the class
     transition value is large enough that both sums round to the same fp32 value: the
