@@ -41,7 +41,7 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     return 4.0
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {(3, "bp"): 99.2e6, (3, "nobp"): 86.5e6, (3, "bp-general"): 54.0e6}
+MEASURED_TRAFFIC_BYTES = {(3, "bp"): 89.0e6, (3, "nobp"): 86.5e6, (3, "bp-general"): 54.0e6}
 
 
 def cpu_baseline(w, cfg_index, target_relax=3.0e10):
@@ -145,9 +145,14 @@ def main():
                 executed = 1.0
             n_class = int(out["n_class"].cpu()[0]) if "n_class" in out else None
             # algorithmic HBM bytes of one layer front: every computed source row is read
-            # once (4 B per state), every target row 0..E written once (4 B + 1 B backpointer)
-            front_bytes = float(((rows - skipped).sum() * 4.0 / (w.L - 1)
-                                 + rows.sum() * (4.0 if nobp else 5.0)) * w.S)
+            # once (4 B per state) and every target row 0..E written once (4 B per state);
+            # backpointers: 1 B per target state, or, from the class kernel, 1 B per computed
+            # source row and target CLASS
+            computed = float((rows - skipped).sum()) / (w.L - 1)
+            front_bytes = (computed * 4.0 + float(rows.sum()) * 4.0) * w.S
+            if not nobp:
+                front_bytes += (computed * n_class if kernel == "k_dp_class"
+                                else float(rows.sum()) * w.S)
         ms_step = dt * 1e3 / args.steps
         fwd_ms = sum(fwd) / len(fwd)
         # The batch runs as `groups` chains of L-1 launches side by side (one stream each);

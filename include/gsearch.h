@@ -230,7 +230,10 @@ int gsearch_export_planes(gsearch_ctx *ctx, float *C, int32_t *bp, void *stream)
  * recomputation flag.  Tree order: ascending (sp, tp, sdp, ckpt), ckpt fastest.
  * Caps: tp <= tp_max, sp <= sp_max, tp*sp <= tpsp_max; a cap <= 0 means "none". */
 
-/* Transition classes of an enumerated strategy set: r_class[s] (device [S]) counts the
+/* Transition classes of an enumerated strategy set (paper sections 1 and 2: a strategy
+ * combines the data / tensor / sequence degrees with sharded data parallelism and with
+ * recomputation as dimensions of their own; only the degrees fix how activations are laid
+ * out between layers).  r_class[s] (device [S]) counts the
  * changes of the layout (tp, sp, dp) along desc[0..s], so strategies that follow each other
  * with the same layout share a class; count_out (device [1], may be NULL) receives the
  * number of classes.  Feed r_class to gsearch_problem when R was built from the same

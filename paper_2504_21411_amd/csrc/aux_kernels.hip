@@ -281,8 +281,12 @@ __global__ void k_final_global(const float *__restrict__ ws_cost, int32_t *__res
 
 // Backtrace over stored backpointers: one thread per requested instance walks
 //   s <- best_s; e <- E_b; for l = L-1 .. 1: plan[l] = s; s' = bp[l][e][s]; e -= O[l][s]; s = s'
-template <typename BPT>
+// BY_CLASS: the class kernel stores one backpointer per (target class, SOURCE row):
+//   bp[l][e][s] = bpc[l][class s][e - O[l][s]].  A state on an optimal path is finite, so its
+// source row exists and lies above the rows that hold +inf only.
+template <typename BPT, bool BY_CLASS>
 __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__restrict__ Oq,
+                               const int32_t *__restrict__ cls,
                                const int32_t *__restrict__ budget,
                                const int32_t *__restrict__ ws_s,
                                const int32_t *__restrict__ instances, int n,
@@ -299,11 +303,14 @@ __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__rest
   }
   int e = budget[b];
   int used = 0;
-  const size_t layer_stride = (size_t)B * S * pitch;
+  const int cols = BY_CLASS ? kMaxClasses : S;
+  const size_t layer_stride = (size_t)B * cols * pitch;
   for (int l = L - 1; l >= 1; --l) {
     plan[(size_t)q * L + l] = s;
-    const int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * S + s) * pitch + e];
     const int o = Oq[((size_t)b * L + l) * SP + s];
+    const int col = BY_CLASS ? cls[s] : s;
+    const int at = BY_CLASS ? e - o : e;
+    const int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * cols + col) * pitch + at];
     used += o;
     e -= o;
     s = prev;
@@ -407,10 +414,12 @@ __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__
 }
 
 // Canonical [b][l][e][s] export of the kept planes and backpointers (debug).
-template <typename BPT>
+template <typename BPT, bool BY_CLASS>
 __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict__ bp,
-                         const int32_t *__restrict__ budget, float *__restrict__ C,
-                         int32_t *__restrict__ bpo, int B, int L, int S, int M, int pitch) {
+                         const int32_t *__restrict__ budget, const int32_t *__restrict__ Oq,
+                         const int32_t *__restrict__ cls, const int32_t *__restrict__ lowsum,
+                         float *__restrict__ C, int32_t *__restrict__ bpo, int B, int L, int S,
+                         int SP, int M, int pitch) {
   const long long total = (long long)B * L * (M + 1) * S;
   const size_t layer_stride = (size_t)B * S * pitch;
   for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
@@ -422,7 +431,22 @@ __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict
     const bool in = e <= budget[b];
     const size_t off = ((size_t)b * S + s) * pitch + e;
     if (C) C[x] = in ? planes[(size_t)l * layer_stride + off] : GS_INF;
-    if (bpo) bpo[x] = (in && l > 0 && bp) ? (int32_t)bp[(size_t)(l - 1) * layer_stride + off] : 0;
+    if (bpo) {
+      int32_t v = 0;
+      if (in && l > 0 && bp) {
+        if (BY_CLASS) {
+          // stored per (target class, source row); rows below the least memory of the
+          // earlier layers hold +inf only, their targets' backpointer is 0
+          const int src = e - Oq[((size_t)b * L + l) * SP + s];
+          if (src >= 0 && src >= lowsum[(size_t)b * L + l - 1])
+            v = (int32_t)bp[(size_t)(l - 1) * B * kMaxClasses * pitch +
+                            ((size_t)b * kMaxClasses + cls[s]) * pitch + src];
+        } else {
+          v = (int32_t)bp[(size_t)(l - 1) * layer_stride + off];
+        }
+      }
+      bpo[x] = v;
+    }
   }
 }
 
@@ -736,14 +760,18 @@ void launch_final(const Shape &s, const Workspace &w, const float *last_plane, f
 void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *instances, int n,
                          int32_t *plan, int32_t *mem_used, hipStream_t st) {
   const dim3 grid((n + 63) / 64), block(64);
-  if (s.bp16)
-    hipLaunchKernelGGL((k_backtrace_bp<uint16_t>), grid, block, 0, st, (const uint16_t *)w.bp,
-                       w.Oq, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S,
-                       s.SP, s.pitch);
+  if (w.bp_by_class)
+    hipLaunchKernelGGL((k_backtrace_bp<uint8_t, true>), grid, block, 0, st, (const uint8_t *)w.bp,
+                       w.Oq, w.cls, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L,
+                       s.S, s.SP, s.pitch);
+  else if (s.bp16)
+    hipLaunchKernelGGL((k_backtrace_bp<uint16_t, false>), grid, block, 0, st,
+                       (const uint16_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n, plan,
+                       mem_used, s.B, s.L, s.S, s.SP, s.pitch);
   else
-    hipLaunchKernelGGL((k_backtrace_bp<uint8_t>), grid, block, 0, st, (const uint8_t *)w.bp, w.Oq,
-                       w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S, s.SP,
-                       s.pitch);
+    hipLaunchKernelGGL((k_backtrace_bp<uint8_t, false>), grid, block, 0, st, (const uint8_t *)w.bp,
+                       w.Oq, w.cls, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L,
+                       s.S, s.SP, s.pitch);
 }
 
 void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *instances, int n,
@@ -772,12 +800,18 @@ void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_p
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st) {
   const long long total = (long long)s.B * s.L * (s.M + 1) * s.S;
   const dim3 grid(blocks_for(total, 256, 1 << 20)), block(256);
-  if (s.bp16)
-    hipLaunchKernelGGL((k_export<uint16_t>), grid, block, 0, st, w.planes,
-                       (const uint16_t *)w.bp, w.budget, C, bp, s.B, s.L, s.S, s.M, s.pitch);
+  if (w.bp_by_class)
+    hipLaunchKernelGGL((k_export<uint8_t, true>), grid, block, 0, st, w.planes,
+                       (const uint8_t *)w.bp, w.budget, w.Oq, w.cls, w.lowsum, C, bp, s.B, s.L, s.S,
+                       s.SP, s.M, s.pitch);
+  else if (s.bp16)
+    hipLaunchKernelGGL((k_export<uint16_t, false>), grid, block, 0, st, w.planes,
+                       (const uint16_t *)w.bp, w.budget, w.Oq, w.cls, w.lowsum, C, bp, s.B, s.L,
+                       s.S, s.SP, s.M, s.pitch);
   else
-    hipLaunchKernelGGL((k_export<uint8_t>), grid, block, 0, st, w.planes, (const uint8_t *)w.bp,
-                       w.budget, C, bp, s.B, s.L, s.S, s.M, s.pitch);
+    hipLaunchKernelGGL((k_export<uint8_t, false>), grid, block, 0, st, w.planes,
+                       (const uint8_t *)w.bp, w.budget, w.Oq, w.cls, w.lowsum, C, bp, s.B, s.L, s.S,
+                       s.SP, s.M, s.pitch);
 }
 
 void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,

@@ -545,7 +545,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
-  uint8_t *__restrict__ bpb = WITH_BP ? bp + plane_off : nullptr;
+  // backpointers: one per (target class, source row), [class][pitch] per instance
+  uint8_t *__restrict__ bpb = WITH_BP ? bp + (size_t)b * NC * pitch : nullptr;
   const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
   const float *__restrict__ trow = Tq + (size_t)bl * SP;
   const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
@@ -666,22 +667,18 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     // with its own T added.  All offsets are 32-bit element offsets from the instance's
     // plane (the launcher admits the kernel only when S * pitch fits), so the per-strategy
     // bookkeeping stays on the scalar side and costs a handful of instructions.
+    // the argmin is the same for every strategy of the class: stored once, under the source
+    // row (aligned 64-byte store); readers subtract the strategy's O to find it
+    if (WITH_BP && compute && rows_on) bpb[(uint32_t)cj * (uint32_t)pitch + (uint32_t)row] = (uint8_t)arg;
     uint32_t joff = (uint32_t)jlo * (uint32_t)pitch;
     for (int j = jlo; j < jhi; ++j, joff += (uint32_t)pitch) {
       const int o = o_lds[j]; // same address in every lane: an LDS broadcast
       if (compute) {
         const int eo = row + o;
-        if (rows_on && eo <= E) {
-          const uint32_t at = joff + (uint32_t)eo;
-          dstb[at] = m + t_lds[j];
-          if (WITH_BP) bpb[at] = (uint8_t)arg;
-        }
+        if (rows_on && eo <= E) dstb[joff + (uint32_t)eo] = m + t_lds[j];
       }
-      if (valid && row < o + low) { // +inf prefix: only the tiles around row `low` have any
-        const uint32_t at = joff + (uint32_t)row;
-        dstb[at] = GS_INF;
-        if (WITH_BP) bpb[at] = 0;
-      }
+      // +inf prefix: only the tiles around row `low` have any
+      if (valid && row < o + low) dstb[joff + (uint32_t)row] = GS_INF;
     }
     jlo = jlo_next;
     jhi = jhi_next;

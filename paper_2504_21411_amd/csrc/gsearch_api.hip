@@ -46,7 +46,9 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)y.nplanes +
                                    (size_t)s.SP * s.pitch));
   const bool want_bp = !(flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
-  y.bp = take(want_bp ? gs::plane_elems(s) * (size_t)(s.L - 1) * (s.bp16 ? 2 : 1) : 0);
+  // (the class kernel stores kMaxClasses columns per instance instead of S)
+  const size_t bp_cols = s.S > gs::kMaxClasses ? s.S : gs::kMaxClasses;
+  y.bp = take(want_bp ? (size_t)s.B * bp_cols * s.pitch * (size_t)(s.L - 1) * (s.bp16 ? 2 : 1) : 0);
   y.Tq = take(sizeof(float) * (size_t)s.B * s.L * s.SP);
   y.Oq = take(sizeof(int32_t) * (size_t)s.B * s.L * s.SP);
   y.Rt = take(sizeof(float) * ((size_t)s.K * s.SP * s.SP + s.SP));
@@ -252,6 +254,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   const Layout y = make_layout(s, c.flags);
   if (y.total > ctx->bytes) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
+  w.bp_by_class = 0;
   char *base = ctx->base;
   w.planes = reinterpret_cast<float *>(base + y.planes);
   const bool with_bp = !(c.flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
@@ -276,7 +279,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
 
   const size_t pe = gs::plane_elems(s);
   const bool keep = keeps_all_planes(c.flags);
-  const size_t bp_layer_bytes = pe * (s.bp16 ? 2 : 1);
+  size_t bp_layer_bytes = pe * (s.bp16 ? 2 : 1);
   gs::ForwardKernel which = gs::ForwardKernel::Auto;
   if (c.flags & GSEARCH_FLAG_FORCE_GENERIC) which = gs::ForwardKernel::Generic;
   else if (c.flags & GSEARCH_FLAG_FORCE_PUSH) which = gs::ForwardKernel::Push;
@@ -288,6 +291,13 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   if (p->r_class && s.L > 1) gs::launch_prepare_classes(s, p->r_class, w, st);
   const bool use_classes =
       p->r_class && s.L > 1 && which == gs::ForwardKernel::Auto && gs::class_path_applies(s);
+  w.bp_by_class = use_classes && with_bp;
+  size_t bp_inst_bytes = (size_t)s.S * s.pitch * (s.bp16 ? 2 : 1); // one instance, one layer
+  if (w.bp_by_class) {
+    bp_inst_bytes = (size_t)gs::kMaxClasses * s.pitch;
+    bp_layer_bytes = (size_t)s.B * bp_inst_bytes;
+  }
+  ctx->ws = w;
   int cur = 0;
   ctx->timed = false;
   const bool timing = ctx->profiling && s.L > 1;
@@ -321,7 +331,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
       for (int l = 1; l < s.L; ++l) {
         const int nxt = keep ? l : (c2 ^ 1);
         void *bp_l = with_bp ? static_cast<char *>(w.bp) + (size_t)(l - 1) * bp_layer_bytes +
-                                   (size_t)b0 * inst_elems * (s.bp16 ? 2 : 1)
+                                   (size_t)b0 * bp_inst_bytes
                              : nullptr;
         const float *src_l = w.planes + (size_t)c2 * pe + (size_t)b0 * inst_elems;
         float *dst_l = w.planes + (size_t)nxt * pe + (size_t)b0 * inst_elems;

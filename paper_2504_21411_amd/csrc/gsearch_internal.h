@@ -25,7 +25,11 @@ struct Shape {
 // Device pointers into the context's workspace.
 struct Workspace {
   float *planes;     // [nplanes][B][S][pitch]   C planes, budget index contiguous
-  void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null)
+  void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null);
+                     // after a class-kernel solve [L-1][B][kMaxClasses][pitch] uint8 indexed by
+                     // (target class, SOURCE row), see bp_by_class
+  int bp_by_class;   // 1: bp[l][e][sj] = bpc[l][class sj][e - O[l][sj]] when that row is >=
+                     // lowsum[l-1], else 0 (every strategy of a class shares the argmin)
   float *Tq;         // [B][L][SP]   sanitised copy of T
   int32_t *Oq;       // [B][L][SP]   sanitised copy of O, clamped to [0, M+1]
   float *Rt;         // [K][SP][SP]  transposed copy: Rt[k][sj][si] = R[k][si][sj]
