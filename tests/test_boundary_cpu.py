@@ -95,6 +95,34 @@ def test_create_reports_argument_errors_and_missing_device(lib):
                                     None) == b.GSEARCH_ERR_INVALID_ARG
 
 
+def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
+    from paper_2504_21411_amd import binding as b
+    assert lib.gsearch_set_instance_groups(None, 2) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_instance_groups(None) == 0
+    assert lib.gsearch_layout_classes(None, 4, None, None, None) == b.GSEARCH_ERR_INVALID_ARG
+    dummy = ctypes.c_void_p(64)       # never dereferenced: the size check comes first
+    assert lib.gsearch_layout_classes(dummy, 0, dummy, None, None) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_layout_classes(dummy, 1025, dummy, None, None) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_forward_kernel(None) == b""
+    # the problem struct carries the optional class promise as its last field
+    assert [f[0] for f in b.gsearch_problem._fields_][-1] == "r_class"
+    header = open(os.path.join(ROOT, "include", "gsearch.h")).read()
+    assert "const int32_t *r_class;" in header
+    assert b.GSEARCH_MAX_CLASSES == int(re.search(r"#define GSEARCH_MAX_CLASSES (\d+)", header).group(1))
+    assert b.GSEARCH_DATA_BAD_RCLASS == int(re.search(r"#define GSEARCH_DATA_BAD_RCLASS (0x[0-9a-f]+)",
+                                                     header).group(1), 16)
+
+
+def test_workspace_covers_class_tables_and_plane_slack(lib):
+    """More strategies never shrink the workspace; small S still reserves the 32 backpointer
+    columns of the class kernel and the slack block behind the planes."""
+    from paper_2504_21411_amd import binding as b
+    sizes = [b.gsearch_workspace_bytes(4, 10, S, 1000) for S in (9, 16, 24, 33, 44, 96)]
+    assert sizes == sorted(sizes)
+    pitch = 1024                                   # round_up(1001, 64)
+    assert sizes[0] >= 2 * 4 * 9 * pitch * 4 + 16 * pitch * 4 + 9 * 4 * 32 * pitch
+
+
 def test_product_package_never_touches_the_oracle():
     pkg = os.path.join(ROOT, "paper_2504_21411_amd")
     for dirpath, _, files in os.walk(pkg):
