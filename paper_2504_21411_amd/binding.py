@@ -93,6 +93,10 @@ def load_library() -> ctypes.CDLL:
         raise RuntimeError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2504_21411_amd.build` "
             "(there is no fallback path)")
+    # PyTorch ships its own HIP runtime and owns the device memory this library works on:
+    # import it first, so that libgsearch.so binds to the runtime PyTorch has loaded instead
+    # of bringing a second one into the process (whose calls would see no usable device).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32 = ctypes.c_void_p, ctypes.c_int32
     lib.gsearch_workspace_bytes.restype = ctypes.c_size_t

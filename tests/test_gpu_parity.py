@@ -534,6 +534,55 @@ def test_class_kernel_with_instance_groups_and_single_layer(gs, oracle_mod):
     assert_same(got, oracle_batch(oracle_mod, w1), w1, "L=1")
 
 
+def _random_partition(rng, S):
+    """Random contiguous partition of S strategies into at most 32 classes."""
+    nc = 1 + int(rng.randint(0, min(31, S - 1), 1)[0])
+    cuts = sorted(set(int(x) for x in rng.randint(1, max(1, S - 1), nc - 1))) if nc > 1 else []
+    edges = [0] + [c for c in cuts if 0 < c < S] + [S]
+    edges = sorted(set(edges))
+    return [b - a for a, b in zip(edges[:-1], edges[1:])]
+
+
+def _class_sweep_case(runner, oracle_mod, rng, case):
+    import torch
+    v = rng.randint(0, 10 ** 6, 10)
+    S = [9, 12, 16, 17, 24, 31, 32, 33, 44, 48, 49, 64, 65, 96, 100, 128][int(v[0]) % 16]
+    B, L, M, K = 1 + int(v[1]) % 5, 2 + int(v[2]) % 5, 1 + int(v[3]) % 600, 1 + int(v[4]) % 3
+    sizes = _random_partition(rng, S)
+    budget = rng.randint(0, M, B).astype(np.int32)
+    w, r_class = workloads.class_tables(f"csweep{case}", B, L, S, M, sizes, K=K, seed=9000 + case,
+                                        budget=budget, coarse=(case % 2 == 0))
+    if case % 3 == 0:
+        w.O[int(v[5]) % B, int(v[6]) % L, int(v[7]) % S] = 0
+    if case % 5 == 0:
+        w.O[:, int(v[5]) % L, int(v[6]) % S] = M + 7
+    if case % 4 == 0:                              # a forbidden class-to-class transition
+        ci, cj = int(v[8]) % len(sizes), int(v[9]) % len(sizes)
+        w.R[int(v[5]) % K][np.ix_(r_class == ci, r_class == cj)] = np.inf
+    ref = oracle_batch(oracle_mod, w)
+    flags = 0x4 if case % 3 == 1 else 0
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    with runner.make_context(w, flags=flags) as ctx:
+        if case % 6 == 5:
+            ctx.gsearch_set_instance_groups(1 + case % 3)
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+        got["data_status"] = ctx.gsearch_data_status()
+        assert ctx.gsearch_forward_kernel() == "k_dp_class", (case, S)
+    assert_same(got, ref, w, f"class sweep {case} S={S} sizes={sizes} flags={flags}")
+
+
+def test_class_kernel_random_sweep(gs, oracle_mod):
+    """Forty seeded random class-structured workloads: strategy counts around every
+    register-tile size, random partitions of 1..32 classes, several matrices, ragged budgets,
+    zero-memory and never-fitting strategies, forbidden class transitions, coarse values that
+    make sums collide, both modes, forced instance groups."""
+    _, runner = gs
+    rng = workloads.SplitMix64(777)
+    for case in range(40):
+        _class_sweep_case(runner, oracle_mod, rng, case)
+
+
 def test_rounding_tie_inside_a_class_keeps_the_lowest_index(gs, oracle_mod):
     """Two strategies of one class, the SECOND has the smaller previous cost, and the class
     transition value is large enough that both sums round to the same fp32 value: the
