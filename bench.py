@@ -153,6 +153,8 @@ def main():
             if not nobp:
                 front_bytes += (computed * n_class if kernel == "k_dp_class"
                                 else float(rows.sum()) * w.S)
+            if kernel == "k_dp_small":
+                front_bytes = 0.0 if nobp else float(rows.sum()) * w.S   # planes stay in LDS
         ms_step = dt * 1e3 / args.steps
         fwd_ms = sum(fwd) / len(fwd)
         # The batch runs as `groups` chains of L-1 launches side by side (one stream each);
@@ -178,10 +180,22 @@ def main():
             ops = opr * relax * executed / launches / groups        # executed, per launch
             per_launch = ops / launch_s / 1e12
             achieved = per_launch * groups                          # all concurrent launches
-            roof = dict(common, bound="alu", achieved=achieved, peak=ALU_PEAK_TLANEOPS,
-                        unit="Tlaneop/s", frac=achieved / ALU_PEAK_TLANEOPS,
-                        achieved_per_launch=per_launch, ops_per_relaxation=opr,
-                        executed_fraction_of_nominal_relaxations=executed)
+            alu_frac = achieved / ALU_PEAK_TLANEOPS
+            hbm_gbs = front_bytes / launch_s / 1e9              # same launches, bytes moved
+            hbm_frac = hbm_gbs / HBM_PEAK_GBS
+            if hbm_frac > alu_frac:
+                # few strategies per state (min-only pass of the outer-search batch): the
+                # plane traffic, not the arithmetic, is the tighter roof
+                roof = dict(common, bound="hbm", achieved=hbm_gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                            frac=hbm_frac, achieved_per_launch=hbm_gbs / groups,
+                            algorithmic_bytes_per_launch=front_bytes / groups,
+                            alu_frac=alu_frac, ops_per_relaxation=opr,
+                            executed_fraction_of_nominal_relaxations=executed)
+            else:
+                roof = dict(common, bound="alu", achieved=achieved, peak=ALU_PEAK_TLANEOPS,
+                            unit="Tlaneop/s", frac=alu_frac, achieved_per_launch=per_launch,
+                            ops_per_relaxation=opr, hbm_frac=hbm_frac,
+                            executed_fraction_of_nominal_relaxations=executed)
         return {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
                 "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
                 "forward_grelax_per_s": relax / (fwd_ms * 1e-3) / 1e9,
