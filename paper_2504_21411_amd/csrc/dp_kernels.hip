@@ -416,11 +416,16 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   if (compute) {
     // every wave fetches SP/NW strategy rows of the tile: all loads first, then the LDS
     // writes, so that the loads are in flight together
+    // (unconditional loads from a clamped row, padding selected afterwards: no lane-mask
+    // juggling between the loads; the strategy rows S..SP-1 do not exist, their addresses
+    // fall into the next instance or the slack behind the last plane)
     float stage[SP / NW];
+    const uint32_t rowc = (uint32_t)(valid ? row : E);
 #pragma unroll
     for (int u = 0; u < SP / NW; ++u) {
       const int i = u * NW + js;
-      stage[u] = (i < S && valid) ? srcb[(size_t)i * pitch + row] : GS_INF;
+      const float v = (srcb + (size_t)i * pitch)[rowc];
+      stage[u] = (i < S && valid) ? v : GS_INF;
     }
 #pragma unroll
     for (int u = 0; u < SP / NW; ++u) tile[(u * NW + js) * kWave + lane] = stage[u];
@@ -456,8 +461,11 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
     arg = (v0 == d.m) ? 8 * d.g : arg;
     const int eo = row + d.o;
     if (row >= low && eo <= E) {
-      dstb[(size_t)d.j * pitch + eo] = d.m + d.t;
-      bpb[(size_t)d.j * pitch + eo] = (uint8_t)arg;
+      // the column's base stays a scalar 64-bit address, the lanes add a 32-bit row offset
+      float *__restrict__ dj = dstb + (size_t)d.j * pitch;
+      uint8_t *__restrict__ bj = bpb + (size_t)d.j * pitch;
+      dj[(uint32_t)eo] = d.m + d.t;
+      bj[(uint32_t)eo] = (uint8_t)arg;
     }
   };
   for (int j = jbeg; j < jend; ++j) {
@@ -477,13 +485,15 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
         finish(d);
       } else {
         const int eo = row + o;
-        if (row >= low && eo <= E) dstb[(size_t)j * pitch + eo] = m + t;
+        float *__restrict__ dj = dstb + (size_t)j * pitch;
+        if (row >= low && eo <= E) dj[(uint32_t)eo] = m + t;
       }
     }
     if (tile_start < o + low) {
       if (valid && row < o + low) {
-        dstb[(size_t)j * pitch + row] = GS_INF;
-        if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
+        float *__restrict__ dj = dstb + (size_t)j * pitch;
+        dj[(uint32_t)row] = GS_INF;
+        if (WITH_BP) (bpb + (size_t)j * pitch)[(uint32_t)row] = 0;
       }
     }
   }
