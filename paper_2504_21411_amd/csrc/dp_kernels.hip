@@ -339,23 +339,28 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
           scan_chunks<SP, false>(m[u], arg[u], c[u], rc);
         }
       }
+      // the column's base stays a scalar 64-bit address, the lanes add a 32-bit row offset
+      float *__restrict__ dj = dstb + (size_t)j * pitch;
+      uint8_t *__restrict__ bj = WITH_BP ? bpb + (size_t)j * pitch : nullptr;
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
         const int row = row0 + u * kWave;
         const int eo = row + o;
         if (row >= low && eo <= E) {
-          dstb[(size_t)j * pitch + eo] = m[u] + t;
-          if (WITH_BP) bpb[(size_t)j * pitch + eo] = (uint8_t)arg[u];
+          dj[(uint32_t)eo] = m[u] + t;
+          if (WITH_BP) bj[(uint32_t)eo] = (uint8_t)arg[u];
         }
       }
     }
     if (tile_start < o + low) {
+      float *__restrict__ dj = dstb + (size_t)j * pitch;
+      uint8_t *__restrict__ bj = WITH_BP ? bpb + (size_t)j * pitch : nullptr;
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
         const int row = row0 + u * kWave;
         if (row <= E && row < o + low) {
-          dstb[(size_t)j * pitch + row] = GS_INF;
-          if (WITH_BP) bpb[(size_t)j * pitch + row] = 0;
+          dj[(uint32_t)row] = GS_INF;
+          if (WITH_BP) bj[(uint32_t)row] = 0;
         }
       }
     }
