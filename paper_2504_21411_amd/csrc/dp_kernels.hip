@@ -818,6 +818,11 @@ __global__ __launch_bounds__(1024) void k_dp_small(
 bool small_path_applies(const Shape &s) {
   if (s.M + 1 > 1024) return false;
   if ((size_t)2 * s.S * s.pitch * sizeof(float) > (size_t)96 * 1024) return false;
+  // Measured (24 layers, 1..8 instances): the one-launch kernel beats a launch per layer
+  // front only while a front is a few thousand relaxations per thread-row, e.g. S = 8 up to
+  // M = 300, S = 12 up to M = 130, S = 16 at M = 64; beyond that one workgroup per instance
+  // is too little parallelism (S = 24, M = 256: 0.27 ms against 0.13 ms).
+  if ((long long)s.S * s.S * (s.M + 1) > 20000) return false;
   const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
   return tiles <= 2048;
 }
@@ -1024,6 +1029,14 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // plain push kernel wins for small S (few chunks, relatively more fixed work per tile)
   // and for the min-only pass at S >= 96.  The context flags (or GSEARCH_KERNEL=1|2) force one.
   bool use_tile = bp_l ? tsp >= 48 : (tsp >= 48 && tsp <= 64);
+  // Small S: the push kernel wins on big batches (outer search: 2048 instances), but while
+  // the batch has few tiles a front is bound by the length of one wave's work, and the
+  // tile kernel's four waves per tile shorten it (measured crossover: about 16 K tiles with
+  // backpointers, 4 K without).
+  if (tsp != 0 && tsp <= 32) {
+    const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
+    use_tile = tile_inst <= (bp_l ? 16384 : 4096);
+  }
   if (tuning().kernel == 1 || which == ForwardKernel::Push) use_tile = false;
   if (tuning().kernel == 2 || which == ForwardKernel::Tile) use_tile = true;
   if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16 && use_tile) {
