@@ -1033,10 +1033,12 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // the batch has few tiles a front is bound by the length of one wave's work, and the
   // tile kernel's four waves per tile shorten it (measured crossover: about 16 K tiles with
   // backpointers, 4 K without).
-  if (tsp != 0 && tsp <= 32) {
-    const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
-    use_tile = tile_inst <= (bp_l ? 16384 : 4096);
-  }
+  const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
+  if (tsp != 0 && tsp <= 32) use_tile = tile_inst <= (bp_l ? 16384 : 4096);
+  // Large S on a handful of tiles: the push kernel slices the strategies over up to eight
+  // workgroups per tile and fills more of the chip (S = 96, 64 tiles: 0.22 against 0.31 ms
+  // for 11 fronts).
+  if (tsp >= 64 && tile_inst <= 256) use_tile = false;
   if (tuning().kernel == 1 || which == ForwardKernel::Push) use_tile = false;
   if (tuning().kernel == 2 || which == ForwardKernel::Tile) use_tile = true;
   if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16 && use_tile) {

@@ -415,7 +415,7 @@ def test_profiled_table_builder_matches_oracle_and_solves(gs, oracle_mod):
 
 def test_profiling_entry_points(gs):
     binding, runner = gs
-    w = random_tables("timing", 4, 6, 96, 2000, seed=91)       # too large for the one-launch path
+    w = random_tables("timing", 4, 6, 96, 6000, seed=91)       # 376 tiles: the tile kernel's range
     dw = runner.DeviceWorkload(w)
     with runner.make_context(w) as ctx:
         assert ctx.gsearch_forward_kernel() == ""
