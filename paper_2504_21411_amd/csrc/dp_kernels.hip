@@ -991,11 +991,14 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
 template <int SP>
 static void launch_class(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                          void *bp_l, hipStream_t st) {
-  // waves per tile, measured: eight with backpointers (the kernel lives on latency hiding
-  // and a wave's share of a tile is short), four for the lighter min-only pass
-  // (GSEARCH_JSPLIT overrides)
+  // Waves per tile, measured over S = 16..128 and 64..70 K tiles: eight while the batch is
+  // a few hundred tiles (pure latency) and with backpointers from 32 padded strategies up
+  // (the kernel lives on latency hiding and a wave's share of a tile is short); four for
+  // the lighter min-only pass and for few strategies, where eight waves mostly repeat the
+  // per-wave set-up.  GSEARCH_JSPLIT overrides.
+  const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
   int waves = tuning().jsplit;
-  if (waves < 1 || waves > 8) waves = bp_l ? 8 : 4;
+  if (waves < 1 || waves > 8) waves = tile_inst <= 512 ? 8 : (bp_l && SP >= 32 ? 8 : 4);
   if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
