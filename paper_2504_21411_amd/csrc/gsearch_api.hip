@@ -118,11 +118,12 @@ struct gsearch_ctx {
 
 namespace {
 
-// Number of instance groups for a batch (GSEARCH_STREAMS overrides).  Measured on MI355X:
-// two groups pay as soon as a layer front is worth about half a billion relaxations (8 to
-// 16 % on the large batches: a front there is a few rounds of long workgroups, and the
-// second chain fills the tail of each round and the gap between launches); more than two
-// add little, and fronts of a few microseconds lose to the fork and join.
+// Number of instance groups for a batch (GSEARCH_STREAMS overrides).  Measured on MI355X
+// over S = 24..128 and fronts of 6e7..2.4e9 relaxations: two groups pay as soon as a layer
+// front is worth about 3e8 relaxations (8 to 35 % on the large batches:
+// a front there is a few rounds of long workgroups, and the second chain fills the tail of
+// each round and the gap between launches) and cost 10 to 40 % below 1.5e8 (fronts of a
+// few microseconds lose to the fork and join); more than two add little.
 int group_count(const gs::Shape &s, int requested, bool class_kernel) {
   static const int env = [] {
     const char *e = getenv("GSEARCH_STREAMS");
@@ -131,7 +132,7 @@ int group_count(const gs::Shape &s, int requested, bool class_kernel) {
   const double front = (double)s.B * (s.M + 1) * s.S * s.S;
   // (the class kernel's workgroups are short and memory-bound; a second chain only takes
   // bandwidth from the first)
-  int g = requested >= 1 ? requested : env >= 1 ? env : (front >= 5.0e8 && !class_kernel ? 2 : 1);
+  int g = requested >= 1 ? requested : env >= 1 ? env : (front >= 3.0e8 && !class_kernel ? 2 : 1);
   if (g > gsearch_ctx::kMaxSide + 1) g = gsearch_ctx::kMaxSide + 1;
   return g < s.B ? g : s.B;
 }
