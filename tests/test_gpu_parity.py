@@ -317,12 +317,17 @@ def test_config3_large_dense_full_size(gs, oracle_mod):
     T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
     ref = oracle_batch(oracle_mod, w, T, O, R)
     dw = runner.DeviceWorkload(w)
-    for flags in (0, 0x4):
+    # the three launch configurations bench.py times (class kernel with and without
+    # backpointers, general kernel on two instance groups) and the general min-only pass
+    for flags, classes, kernel in ((0, True, "k_dp_class"), (0x4, True, "k_dp_class"),
+                                   (0, False, "k_dp_tile"), (0x4, False, "k_dp_push")):
         with runner.make_context(w, flags=flags) as ctx:
-            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=classes))
             got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == kernel
+            assert ctx.gsearch_instance_groups() == (1 if classes else 2)
         assert np.array_equal(bits(got["T"]), bits(T)) and np.array_equal(got["O"], O)
-        assert_same(got, ref, w, f"flags={flags}")
+        assert_same(got, ref, w, f"flags={flags} classes={classes}")
     assert np.isfinite(ref["best_cost"]).all()
 
 
