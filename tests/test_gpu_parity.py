@@ -672,3 +672,33 @@ def test_model_configs_without_classes_use_the_general_kernels(gs, oracle_mod, i
     assert a["forward_kernel"] == "k_dp_class" and b["forward_kernel"] == "k_dp_tile"
     assert_same(a, ref, w, "classes")
     assert_same(b, ref, w, "general")
+
+
+def test_a_whole_step_can_be_captured_in_a_hip_graph_and_replayed(gs, oracle_mod):
+    """A solve issues only kernel launches and event fork/joins (the status word is cleared
+    by a kernel, not a memset), so a whole step - two instance groups on parallel streams
+    included - can be captured and replayed.  Every replay, with eager solves of another
+    workload on the same context in between, must give the oracle's bits."""
+    binding, runner = gs
+    import torch
+    w = random_tables("graph", 6, 9, 44, 900, K=2, seed=321,
+                      budget=np.array([900, 450, 899, 64, 700, 333], np.int32))
+    other = random_tables("graph_other", 6, 9, 44, 900, K=2, seed=322)
+    ref, ref_other = oracle_batch(oracle_mod, w), oracle_batch(oracle_mod, other)
+    dw, dwo = runner.DeviceWorkload(w), runner.DeviceWorkload(other)
+    st = torch.cuda.Stream()
+    with runner.make_context(w) as ctx, torch.cuda.stream(st):
+        ctx.gsearch_set_instance_groups(2)
+        runner.run_step(ctx, dw, backtrace="all")                 # warm-up outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            captured = runner.run_step(ctx, dw, backtrace="all")
+        for _ in range(3):
+            eager = runner.to_numpy(runner.run_step(ctx, dwo, backtrace="all"))
+            eager["data_status"] = ctx.gsearch_data_status()
+            assert_same(eager, ref_other, other, "eager between replays")
+            graph.replay()
+            got = runner.to_numpy(captured)
+            got["data_status"] = ctx.gsearch_data_status()
+            assert_same(got, ref, w, "graph replay")
