@@ -30,6 +30,14 @@ class DeviceWorkload:
             self.layer = t(w.layer, torch.float64)
             self.rmodel = t(w.rmodel, torch.float64)
         self.desc = None
+        # Set-up, once per workload: how many layout classes the strategy set has.  A solve
+        # can exploit at most GSEARCH_MAX_CLASSES of them and would flag a longer list, so
+        # run_step hands the classes over only when they fit.
+        self.n_class = None
+        if w.kind == "model":
+            desc, _ = binding.gsearch_enumerate(device=self.device, **w.enum)
+            _, count = binding.gsearch_layout_classes(desc)
+            self.n_class = int(count.cpu()[0])
 
 
 def make_context(w: Workload, flags=0, device=0) -> binding.GSearch:
@@ -49,7 +57,7 @@ def run_step(ctx: binding.GSearch, dw: DeviceWorkload, backtrace="best", stream=
         desc, count = binding.gsearch_enumerate(device=dw.device, stream=stream, **w.enum)
         T, O, R = binding.gsearch_build_tables(desc, dw.layer, w.hw, dw.rmodel, w.M, stream=stream)
         out.update(desc=desc, count=count, T=T, O=O, R=R)
-        if classes and r_class is None:
+        if classes and r_class is None and dw.n_class <= binding.GSEARCH_MAX_CLASSES:
             r_class, n_class = binding.gsearch_layout_classes(desc, stream=stream)
             out.update(r_class=r_class, n_class=n_class)
     else:

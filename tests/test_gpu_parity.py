@@ -702,3 +702,27 @@ def test_a_whole_step_can_be_captured_in_a_hip_graph_and_replayed(gs, oracle_mod
             got = runner.to_numpy(captured)
             got["data_status"] = ctx.gsearch_data_status()
             assert_same(got, ref, w, "graph replay")
+
+
+def test_strategy_set_with_more_layouts_than_the_class_limit(gs, oracle_mod):
+    """128 devices without caps: 128 strategies in 36 layout classes, more than a solve can
+    exploit.  The runner then withholds the classes and the general kernels run; handing the
+    classes over regardless is flagged, not silently wrong."""
+    binding, runner = gs
+    import torch
+    w = workloads._model_workload("n128", 2, 5, 700, dict(N=128), [8192.0], [4096.0], 262144.0,
+                                  80.0e9, seed=77, S=128)
+    desc = oracle_mod.enumerate_strategies(**w.enum)
+    assert len(desc) == 128
+    T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
+    ref = oracle_batch(oracle_mod, w, T, O, R)
+    dw = runner.DeviceWorkload(w)
+    assert dw.n_class == 36 > binding.GSEARCH_MAX_CLASSES
+    with runner.make_context(w) as ctx:
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+        got["data_status"] = ctx.gsearch_data_status()
+        assert ctx.gsearch_forward_kernel() != "k_dp_class" and "r_class" not in got
+        assert_same(got, ref, w, "36 classes, general kernels")
+        r_class, _ = binding.gsearch_layout_classes(torch.from_numpy(desc).to(dw.device))
+        runner.run_step(ctx, dw, backtrace=None, r_class=r_class)
+        assert ctx.gsearch_data_status() & binding.GSEARCH_DATA_BAD_RCLASS
