@@ -323,14 +323,20 @@ __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__rest
 // Backtrace without stored backpointers: one wave per requested instance re-derives every
 // argmin from the kept planes, argmin_si ( C[l-1][e-O][si] + R[si][s] ), lowest si on ties
 // (all +inf gives 0) - the same value the forward pass would have stored.
+// BY_CLASS: the kept planes are the class kernel's compact ones, and
+// C[l-1][r][si] = Q[l-1][class si][r - O[l-1][si]] + T[l-1][si] (+inf when r < O[l-1][si]),
+// the very additions the forward pass made.
+template <bool BY_CLASS>
 __global__ void k_backtrace_planes(const float *__restrict__ planes,
-                                   const float *__restrict__ Rt, const int32_t *__restrict__ Oq,
+                                   const float *__restrict__ Rt, const float *__restrict__ Tq,
+                                   const int32_t *__restrict__ Oq,
+                                   const int32_t *__restrict__ cls,
                                    const int32_t *__restrict__ ridx,
                                    const int32_t *__restrict__ budget,
                                    const int32_t *__restrict__ ws_s,
                                    const int32_t *__restrict__ instances, int n,
                                    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used,
-                                   int B, int L, int S, int SP, int pitch) {
+                                   int B, int L, int S, int SP, int Sc, int pitch) {
   const int q = blockIdx.x;
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
@@ -343,17 +349,27 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
   int e = budget[b];
   int used = 0;
   const size_t layer_stride = (size_t)B * S * pitch;
+  const size_t inst = (size_t)b * (BY_CLASS ? Sc : S) * pitch;
   for (int l = L - 1; l >= 1; --l) {
     if (lane == 0) plan[(size_t)q * L + l] = s;
     const int o = Oq[((size_t)b * L + l) * SP + s];
     used += o;
     e -= o;
-    const float *prevp = planes + (size_t)(l - 1) * layer_stride + (size_t)b * S * pitch;
+    const float *prevp = planes + (size_t)(l - 1) * layer_stride + inst;
     const float *rc = Rt + ((size_t)ridx[(size_t)b * L + l] * SP + s) * SP;
+    const size_t prow = ((size_t)b * L + l - 1) * SP; // the previous layer's O and T rows
     float m = GS_INF;
     int arg = 0x7fffffff;
     for (int i = lane; i < S; i += kWave) {
-      const float v = prevp[(size_t)i * pitch + e] + rc[i];
+      float c;
+      if (BY_CLASS) {
+        const int d = e - Oq[prow + i];
+        c = GS_INF;
+        if (d >= 0) c = prevp[(size_t)cls[i] * pitch + d] + Tq[prow + i];
+      } else {
+        c = prevp[(size_t)i * pitch + e];
+      }
+      const float v = c + rc[i];
       if (v < m || arg == 0x7fffffff) { m = v; arg = i; }
     }
     wave_argmin(m, arg);
@@ -413,13 +429,16 @@ __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__
   curve[(size_t)b * (M + 1) + e] = m;
 }
 
-// Canonical [b][l][e][s] export of the kept planes and backpointers (debug).
+// Canonical [b][l][e][s] export of the kept planes and backpointers (debug).  BY_CLASS: the
+// planes are compact (one row per class) and the backpointers are stored per (target
+// class, source row); both are expanded here.
 template <typename BPT, bool BY_CLASS>
 __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict__ bp,
-                         const int32_t *__restrict__ budget, const int32_t *__restrict__ Oq,
-                         const int32_t *__restrict__ cls, const int32_t *__restrict__ lowsum,
-                         float *__restrict__ C, int32_t *__restrict__ bpo, int B, int L, int S,
-                         int SP, int M, int pitch) {
+                         const int32_t *__restrict__ budget, const float *__restrict__ Tq,
+                         const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+                         const int32_t *__restrict__ lowsum, float *__restrict__ C,
+                         int32_t *__restrict__ bpo, int B, int L, int S, int SP, int Sc, int M,
+                         int pitch) {
   const long long total = (long long)B * L * (M + 1) * S;
   const size_t layer_stride = (size_t)B * S * pitch;
   for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
@@ -430,14 +449,26 @@ __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict
     const int b = (int)(x / ((long long)S * (M + 1) * L));
     const bool in = e <= budget[b];
     const size_t off = ((size_t)b * S + s) * pitch + e;
-    if (C) C[x] = in ? planes[(size_t)l * layer_stride + off] : GS_INF;
+    const size_t tab = ((size_t)b * L + l) * SP + s;
+    const int src = e - Oq[tab]; // source row of this state
+    if (C) {
+      float v = GS_INF;
+      if (in) {
+        if (BY_CLASS) {
+          if (src >= 0)
+            v = planes[(size_t)l * layer_stride + ((size_t)b * Sc + cls[s]) * pitch + src] + Tq[tab];
+        } else {
+          v = planes[(size_t)l * layer_stride + off];
+        }
+      }
+      C[x] = v;
+    }
     if (bpo) {
       int32_t v = 0;
       if (in && l > 0 && bp) {
         if (BY_CLASS) {
-          // stored per (target class, source row); rows below the least memory of the
-          // earlier layers hold +inf only, their targets' backpointer is 0
-          const int src = e - Oq[((size_t)b * L + l) * SP + s];
+          // rows below the least memory of the earlier layers hold +inf only, their
+          // targets' backpointer is 0
           if (src >= 0 && src >= lowsum[(size_t)b * L + l - 1])
             v = (int32_t)bp[(size_t)(l - 1) * B * kMaxClasses * pitch +
                             ((size_t)b * kMaxClasses + cls[s]) * pitch + src];
@@ -760,7 +791,7 @@ void launch_final(const Shape &s, const Workspace &w, const float *last_plane, f
 void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *instances, int n,
                          int32_t *plan, int32_t *mem_used, hipStream_t st) {
   const dim3 grid((n + 63) / 64), block(64);
-  if (w.bp_by_class)
+  if (w.by_class)
     hipLaunchKernelGGL((k_backtrace_bp<uint8_t, true>), grid, block, 0, st, (const uint8_t *)w.bp,
                        w.Oq, w.cls, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L,
                        s.S, s.SP, s.pitch);
@@ -776,9 +807,14 @@ void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *inst
 
 void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *instances, int n,
                              int32_t *plan, int32_t *mem_used, hipStream_t st) {
-  hipLaunchKernelGGL(k_backtrace_planes, dim3(n), dim3(kWave), 0, st, w.planes, w.Rt, w.Oq,
-                     w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L, s.S,
-                     s.SP, s.pitch);
+  if (w.by_class)
+    hipLaunchKernelGGL((k_backtrace_planes<true>), dim3(n), dim3(kWave), 0, st, w.planes, w.Rt,
+                       w.Tq, w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used,
+                       s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
+  else
+    hipLaunchKernelGGL((k_backtrace_planes<false>), dim3(n), dim3(kWave), 0, st, w.planes, w.Rt,
+                       w.Tq, w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used,
+                       s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
 }
 
 void launch_pipeline_reduce(const Shape &s, const Workspace &w, int G, const int32_t *offsets,
@@ -800,18 +836,18 @@ void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_p
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st) {
   const long long total = (long long)s.B * s.L * (s.M + 1) * s.S;
   const dim3 grid(blocks_for(total, 256, 1 << 20)), block(256);
-  if (w.bp_by_class)
+  if (w.by_class)
     hipLaunchKernelGGL((k_export<uint8_t, true>), grid, block, 0, st, w.planes,
-                       (const uint8_t *)w.bp, w.budget, w.Oq, w.cls, w.lowsum, C, bp, s.B, s.L, s.S,
-                       s.SP, s.M, s.pitch);
+                       (const uint8_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
+                       s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
   else if (s.bp16)
     hipLaunchKernelGGL((k_export<uint16_t, false>), grid, block, 0, st, w.planes,
-                       (const uint16_t *)w.bp, w.budget, w.Oq, w.cls, w.lowsum, C, bp, s.B, s.L,
-                       s.S, s.SP, s.M, s.pitch);
+                       (const uint16_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp,
+                       s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
   else
     hipLaunchKernelGGL((k_export<uint8_t, false>), grid, block, 0, st, w.planes,
-                       (const uint8_t *)w.bp, w.budget, w.Oq, w.cls, w.lowsum, C, bp, s.B, s.L, s.S,
-                       s.SP, s.M, s.pitch);
+                       (const uint8_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
+                       s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
 }
 
 void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,

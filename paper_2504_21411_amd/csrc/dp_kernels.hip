@@ -517,132 +517,124 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
 // strategy is found by rebuilding the sums of this one class from the LDS tile (several of
 // its members may round to the same sum, so the member with the smallest C need not be it).
 //
-// One workgroup per 64-row tile, NW waves.  Tile HBM -> LDS once; the class minima are
-// formed by LDS float-minimum atomics while the rows arrive (cmin[class][lane]), then every
-// wave keeps all of them in registers and takes every NW-th target class.
+// The planes are COMPACT.  The plane of a layer need not be kept per strategy: for l >= 1 let
+//     Q[l][c][r] = min_si ( C[l-1][r][si] + R(l, si, c) )          (one row per CLASS c)
+// and Q[0][c][r] = 0.  Then C[l][e][s] = Q[l][class s][e - O[l][s]] + T[l][s] for
+// e >= O[l][s] (+inf below), which is exactly how the recurrence forms C, in the same
+// fp32 operations and order.  A layer front reads the nc rows of Q[l-1] (each source
+// strategy si at its own shift O[l-1][si], with its T[l-1][si] added on the fly) and writes
+// the nc rows of Q[l] and one backpointer per (target class, source row) with aligned
+// stores: 2 nc floats per budget row instead of 2 S cross HBM.  The shifted reads of one
+// instance overlap heavily and are served by the L2 of the XCD its workgroups run on.
+//
+// One workgroup per 64-row tile, NW waves, each rebuilding a contiguous run of source
+// strategies.  The class minima are formed by LDS float-minimum atomics (cmin[class][lane]),
+// then every wave keeps all of them in registers and takes every NW-th target class.
+//
+// Rows above E - min_s O[l][s] have no target within the budget and are neither computed
+// nor read by anyone; tiles wholly below the least memory of layers 0..l-1 hold +inf.
 // ---------------------------------------------------------------------------------------
 template <int SP, int NW, bool WITH_BP>
 __global__ __launch_bounds__(NW *kWave) void k_dp_class(
-    const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
+    const float *__restrict__ qsrc, float *__restrict__ qdst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
     const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int S,
+    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
     int l, int pitch) {
   constexpr int NC = kMaxClasses;
+  constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
   extern __shared__ float lds[];
   float *cmin = lds;                    // [NC][64]  class minima of the tile
   float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
   int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1], padded to NC + 32
-  int *o_lds = cs_lds + NC + 32;                           // [SP]  this layer's O row
-  float *t_lds = reinterpret_cast<float *>(o_lds + SP);    // [SP]  this layer's T row
-  float *tile = t_lds + SP;                                // [SP][64], backpointer mode only
-  // grid = (instances, tiles): consecutive workgroups belong to different instances
+  float *tile = reinterpret_cast<float *>(cs_lds + NC + 32); // [SP][64], backpointer mode only
   const int b = blockIdx.x;
   const int tile_start = (int)blockIdx.y * kWave;
   const int js = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  // every scalar table entry is requested before the first of them is needed (one round
-  // trip to the scalar cache instead of three), so the early exit comes after the loads
   const int bl = b * L + l;
   const int E = budget[b];
-  const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
+  const int low = lowsum[bl - 1]; // C[l-1] is +inf below this row
   const int mo = minO[bl];
   const int kr = ridx[bl];
   const int nc = cmeta[0];
   const int maxlen = cmeta[1];
-  if (tile_start > E) return; // whole workgroup
+  if (tile_start > E - mo) return; // no target row within the budget (whole workgroup)
 
   const int row = tile_start + lane;
-  const bool valid = row <= E;
-  const bool compute = tile_start <= E - mo && tile_start + kWave > low; // uniform
-  const size_t plane_off = (size_t)b * S * pitch;
-  const float *__restrict__ srcb = src + plane_off;
-  float *__restrict__ dstb = dst + plane_off;
-  // backpointers: one per (target class, source row), [class][pitch] per instance
+  const size_t inst = (size_t)b * Sc * pitch;
+  const float *__restrict__ qs = qsrc + inst;
+  float *__restrict__ qd = qdst + inst;
   uint8_t *__restrict__ bpb = WITH_BP ? bp + (size_t)b * NC * pitch : nullptr;
-  const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
-  const float *__restrict__ trow = Tq + (size_t)bl * SP;
-  const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
-
-  // The scalar unit is this kernel's scarce resource (one instruction per cycle for the
-  // whole compute unit, and every wave repeats the per-strategy bookkeeping), so the O and
-  // T rows go through LDS into vector registers and the comparisons that use them run on
-  // the vector side, which has slack.
-  for (int x = threadIdx.x; x < SP; x += NW * kWave) {
-    o_lds[x] = orow[x];
-    t_lds[x] = trow[x];
+  if (tile_start + kWave <= low) {
+    for (int cj = js; cj < nc; cj += NW) qd[(uint32_t)cj * (uint32_t)pitch + (uint32_t)row] = GS_INF;
+    return;
   }
-  float cmv[NC];
-  if (compute) {
-    // Unconditional loads, padding selected afterwards: no lane-mask juggling or branches
-    // between the loads.  Strategy rows S..SP-1 do not exist; their addresses fall into the
-    // next instance or the slack behind the last plane (the workspace reserves it).
-    float stage[SP / NW];
-    const uint32_t rowc = (uint32_t)(valid ? row : E);
+  const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
+  const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
+  const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
+
+  // C[l-1][row][si] for this wave's source strategies, rebuilt from the compact plane.
+  // Rows beyond the budget count as +inf; padding strategies have O = M + 1 and never fit.
+  const int rowm = row <= E ? row : -1;
+  float stage[PER];
 #pragma unroll
-    for (int u = 0; u < SP / NW; ++u) {
-      const int i = u * NW + js;
-      const float v = srcb[(uint32_t)i * (uint32_t)pitch + rowc];
-      stage[u] = (i < S && valid) ? v : GS_INF;
-    }
-    for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
-    for (int x = threadIdx.x; x < NC * NC; x += NW * kWave) rc_lds[x] = rck[x];
-    if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
-    if (WITH_BP) {
+  for (int u = 0; u < PER; ++u) {
+    const int i = js * PER + u;
+    const int o = oprev[i];
+    const int d = rowm - o;
+    const uint32_t at = (uint32_t)cls[i] * (uint32_t)pitch + (uint32_t)(d > 0 ? d : 0);
+    const float v = qs[at] + tprev[i];
+    stage[u] = d >= 0 ? v : GS_INF;
+  }
+  for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
+  for (int x = threadIdx.x; x < NC * NC; x += NW * kWave) rc_lds[x] = rck[x];
+  if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+  if (WITH_BP) {
 #pragma unroll
-      for (int u = 0; u < SP / NW; ++u) tile[(u * NW + js) * kWave + lane] = stage[u];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < SP / NW; ++u) {
-      const int c = cls[u * NW + js]; // wave-uniform
-      __hip_atomic_fetch_min(&cmin[c * kWave + lane], stage[u], __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_WORKGROUP);
-    }
-  } else {
-    __syncthreads(); // the O and T rows are needed for the +inf prefix in any case
+    for (int u = 0; u < PER; ++u) tile[(js * PER + u) * kWave + lane] = stage[u];
   }
   __syncthreads();
-  if (compute) {
-    // only the chunks of eight classes that exist are kept (the rest is never read)
+#pragma unroll
+  for (int u = 0; u < PER; ++u) {
+    const int c = cls[js * PER + u]; // wave-uniform
+    __hip_atomic_fetch_min(&cmin[c * kWave + lane], stage[u], __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  __syncthreads();
+  float cmv[NC];
+  // only the chunks of eight classes that exist are kept (the rest is never read)
+#pragma unroll
+  for (int q = 0; q < NC / 8; ++q) {
+    if (8 * q < nc) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) cmv[8 * q + k] = cmin[(8 * q + k) * kWave + lane];
+    }
+  }
+
+  for (int cj = js; cj < nc; cj += NW) {
+    const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
+    const float16_t r0 = *reinterpret_cast<const float16_t *>(rc);
+    const float16_t r1 = *reinterpret_cast<const float16_t *>(rc + 16);
+    // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
+    float m = GS_INF;
+    int g = 0;
 #pragma unroll
     for (int q = 0; q < NC / 8; ++q) {
       if (8 * q < nc) {
+        const float16_t r = q < 2 ? r0 : r1;
+        const int h = (q & 1) * 8;
+        float cm = __builtin_fminf(cmv[8 * q] + r[h], cmv[8 * q + 1] + r[h + 1]);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) cmv[8 * q + k] = cmin[(8 * q + k) * kWave + lane];
+        for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
+        chunk_update<true>(m, g, cm, q);
       }
     }
-  }
-
-  const bool rows_on = valid && row >= low; // source rows whose targets are computed
-  // run boundaries of this wave's first target class; those of the next one are requested
-  // an iteration ahead, like the O and T entries inside the loop over the class members
-  int jlo = 0, jhi = 0;
-  if (js < nc) { jlo = cstart[js]; jhi = cstart[js + 1]; }
-  for (int cj = js; cj < nc; cj += NW) {
-    const int cn = cj + NW < NC ? cj + NW : NC - 1; // stays inside the run table
-    const int jlo_next = cstart[cn], jhi_next = cstart[cn + 1];
-    float m = GS_INF;
-    int arg = 0;
-    if (compute) {
-      const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
-      const float16_t r0 = *reinterpret_cast<const float16_t *>(rc);
-      const float16_t r1 = *reinterpret_cast<const float16_t *>(rc + 16);
-      // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
-      int g = 0;
-#pragma unroll
-      for (int q = 0; q < NC / 8; ++q) {
-        if (8 * q < nc) {
-          const float16_t r = q < 2 ? r0 : r1;
-          const int h = (q & 1) * 8;
-          float cm = __builtin_fminf(cmv[8 * q] + r[h], cmv[8 * q + 1] + r[h + 1]);
-#pragma unroll
-          for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
-          chunk_update<true>(m, g, cm, q);
-        }
-      }
+    const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
+    qd[at] = m;
+    if (WITH_BP) {
       // level 1b: first class of chunk g attaining it (operands re-read from LDS: g varies
       // from lane to lane)
       int ca = 8 * g;
@@ -658,46 +650,55 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
           ca = (v == m) ? 8 * g + k : ca;
         }
       }
-      if (WITH_BP) {
-        // level 2: lowest member of class ca whose sum equals m (descending scan, last hit
-        // wins); several members can round to the same sum
-        const int lo = cs_lds[ca], hi = cs_lds[ca + 1];
-        const float rr = rc_lds[cj * NC + ca];
-        // four members per round so that their LDS reads are in flight together; past the
-        // end of a short class the last member is simply looked at again
-        for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
-          float tv[4];
-          int ti[4];
+      // level 2: lowest member of class ca whose sum equals m (descending scan, last hit
+      // wins); several members can round to the same sum
+      int arg = 0;
+      const int lo = cs_lds[ca], hi = cs_lds[ca + 1];
+      const float rr = rc_lds[cj * NC + ca];
+      // four members per round so that their LDS reads are in flight together; past the
+      // end of a short class the last member is simply looked at again
+      for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
+        float tv[4];
+        int ti[4];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            ti[u] = lo + d0 + u < hi ? lo + d0 + u : hi - 1;
-            tv[u] = tile[ti[u] * kWave + lane];
-          }
-#pragma unroll
-          for (int u = 3; u >= 0; --u) arg = (tv[u] + rr == m) ? ti[u] : arg;
+        for (int u = 0; u < 4; ++u) {
+          ti[u] = lo + d0 + u < hi ? lo + d0 + u : hi - 1;
+          tv[u] = tile[ti[u] * kWave + lane];
         }
+#pragma unroll
+        for (int u = 3; u >= 0; --u) arg = (tv[u] + rr == m) ? ti[u] : arg;
       }
+      bpb[at] = (uint8_t)arg;
     }
-    // Every strategy of the target class gets the same (m, arg), shifted by its own O and
-    // with its own T added.  All offsets are 32-bit element offsets from the instance's
-    // plane (the launcher admits the kernel only when S * pitch fits), so the per-strategy
-    // bookkeeping stays on the scalar side and costs a handful of instructions.
-    // the argmin is the same for every strategy of the class: stored once, under the source
-    // row (aligned 64-byte store); readers subtract the strategy's O to find it
-    if (WITH_BP && compute && rows_on) bpb[(uint32_t)cj * (uint32_t)pitch + (uint32_t)row] = (uint8_t)arg;
-    uint32_t joff = (uint32_t)jlo * (uint32_t)pitch;
-    for (int j = jlo; j < jhi; ++j, joff += (uint32_t)pitch) {
-      const int o = o_lds[j]; // same address in every lane: an LDS broadcast
-      if (compute) {
-        const int eo = row + o;
-        if (rows_on && eo <= E) dstb[joff + (uint32_t)eo] = m + t_lds[j];
-      }
-      // +inf prefix: only the tiles around row `low` have any
-      if (valid && row < o + low) dstb[joff + (uint32_t)row] = GS_INF;
-    }
-    jlo = jlo_next;
-    jhi = jhi_next;
   }
+}
+
+// C[l][e][s] = Q[l][class s][e - O[l][s]] + T[l][s] for O[l][s] <= e <= E, +inf otherwise:
+// the full plane of one layer from its compact form (for the final reductions, which read
+// a full plane).  grid = (instances, blocks of 256 rows).
+__global__ __launch_bounds__(256) void k_expand_class(
+    const float *__restrict__ q, float *__restrict__ plane, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ budget, int L, int S, int SP, int Sc, int l, int pitch) {
+  const int b = blockIdx.x;
+  const int e = (int)blockIdx.y * 256 + threadIdx.x;
+  if (e >= pitch) return;
+  const int E = budget[b];
+  const float *__restrict__ qb = q + (size_t)b * Sc * pitch;
+  float *__restrict__ pb = plane + (size_t)b * S * pitch;
+  const size_t bl = (size_t)b * L + l;
+  for (int s = 0; s < S; ++s) {
+    const int o = Oq[bl * SP + s];
+    const int d = e - o;
+    float v = GS_INF;
+    if (d >= 0 && e <= E) v = qb[(size_t)cls[s] * pitch + d] + Tq[bl * SP + s];
+    pb[(size_t)s * pitch + e] = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_zero_plane(float *__restrict__ q, size_t n) {
+  for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < n; x += (size_t)gridDim.x * 256)
+    q[x] = 0.0f;
 }
 
 // Shape-agnostic "pull" form: a lane owns one TARGET row e and, for each sj, scans the
@@ -977,15 +978,15 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)s.B, (unsigned)tiles), block(NW * kWave);
   const size_t lds = sizeof(float) * ((bp_l ? SP * kWave : 0) + kMaxClasses * kWave +
-                                      kMaxClasses * kMaxClasses + kMaxClasses + 32 + 2 * SP);
+                                      kMaxClasses * kMaxClasses + kMaxClasses + 32);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true>), grid, block, lds, st, src, dst, (uint8_t *)bp_l,
                        w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
-                       w.lowsum, s.B, s.L, s.S, l, s.pitch);
+                       w.lowsum, s.B, s.L, class_rows(s), l, s.pitch);
   else
     hipLaunchKernelGGL((k_dp_class<SP, NW, false>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.minO, w.lowsum, s.B, s.L, s.S, l, s.pitch);
+                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch);
 }
 
 template <int SP>
@@ -1018,6 +1019,19 @@ const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const flo
     default: break; // class_path_applies() admits no other pitch
   }
   return "k_dp_class";
+}
+
+void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {
+  const size_t n = (size_t)s.B * class_rows(s) * s.pitch;
+  const unsigned blocks = (unsigned)((n + 256 * 8 - 1) / (256 * 8));
+  hipLaunchKernelGGL(k_zero_plane, dim3(blocks < 1 ? 1 : blocks), dim3(256), 0, st, q0, n);
+}
+
+void launch_class_expand(const Shape &s, const Workspace &w, int l, const float *q, float *plane,
+                         hipStream_t st) {
+  const dim3 grid((unsigned)s.B, (unsigned)((s.pitch + 255) / 256));
+  hipLaunchKernelGGL(k_expand_class, grid, dim3(256), 0, st, q, plane, w.Tq, w.Oq, w.cls, w.budget,
+                     s.L, s.S, s.SP, class_rows(s), l, s.pitch);
 }
 
 const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,

@@ -41,9 +41,12 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
     return at;
   };
   y.nplanes = keeps_all_planes(flags) ? s.L : (s.L < 2 ? s.L : 2);
-  // slack of one padded instance row block behind the last plane: the class kernel reads
-  // (and discards) the strategy rows S..SP-1 of an instance without clamping the address
-  y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)y.nplanes +
+  // One slot more than the layers kept: the class kernel keeps compact planes (one row per
+  // class) at the head of the layer slots and expands the last layer into the extra slot
+  // for the final reductions.  Behind the last slot, slack of one padded instance row block:
+  // the tile kernel reads (and discards) the strategy rows S..SP-1 of an instance without
+  // clamping the address.
+  y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)(y.nplanes + 1) +
                                    (size_t)s.SP * s.pitch));
   const bool want_bp = !(flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
   // (the class kernel stores kMaxClasses columns per instance instead of S)
@@ -255,7 +258,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   const Layout y = make_layout(s, c.flags);
   if (y.total > ctx->bytes) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
-  w.bp_by_class = 0;
+  w.by_class = 0;
   char *base = ctx->base;
   w.planes = reinterpret_cast<float *>(base + y.planes);
   const bool with_bp = !(c.flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
@@ -292,9 +295,11 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   if (p->r_class && s.L > 1) gs::launch_prepare_classes(s, p->r_class, w, st);
   const bool use_classes =
       p->r_class && s.L > 1 && which == gs::ForwardKernel::Auto && gs::class_path_applies(s);
-  w.bp_by_class = use_classes && with_bp;
+  // The class kernel works on compact planes (one row per class, at the head of each plane
+  // slot) and stores one backpointer per (target class, source row).
+  w.by_class = use_classes;
   size_t bp_inst_bytes = (size_t)s.S * s.pitch * (s.bp16 ? 2 : 1); // one instance, one layer
-  if (w.bp_by_class) {
+  if (use_classes) {
     bp_inst_bytes = (size_t)gs::kMaxClasses * s.pitch;
     bp_layer_bytes = (size_t)s.B * bp_inst_bytes;
   }
@@ -310,7 +315,8 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
     ctx->forward_kernel = "k_dp_small";
     ctx->groups_used = 1;
   } else {
-    gs::launch_init_layer0(s, w, w.planes, st);
+    if (use_classes) gs::launch_class_zero(s, w.planes, st); // Q[0] = 0
+    else gs::launch_init_layer0(s, w, w.planes, st);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
     const int groups = s.L > 1 ? group_count(s, ctx->groups, use_classes) : 1;
     ctx->groups_used = groups;
@@ -318,7 +324,8 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
       if (!ensure_side_streams(ctx, groups - 1)) return GSEARCH_ERR_HIP;
       if (hipEventRecord(ctx->ev_fork, st) != hipSuccess) return GSEARCH_ERR_HIP;
     }
-    const size_t inst_elems = (size_t)s.S * s.pitch; // one instance's share of a plane
+    // one instance's share of a plane slot
+    const size_t inst_elems = (size_t)(use_classes ? gs::class_rows(s) : s.S) * s.pitch;
     int last = 0;
     for (int g = groups - 1; g >= 0; --g) { // the caller's stream (group 0) is fed last
       const int b0 = (int)((long long)s.B * g / groups);
@@ -353,6 +360,11 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   if (timing) {
     if (hipEventRecord(ctx->ev_end, st) != hipSuccess) return GSEARCH_ERR_HIP;
     ctx->timed = true;
+  }
+  if (use_classes) { // the final reductions read a full plane: expand layer L-1
+    gs::launch_class_expand(s, w, s.L - 1, w.planes + (size_t)cur * pe,
+                            w.planes + (size_t)y.nplanes * pe, st);
+    cur = y.nplanes;
   }
   ctx->last_plane = cur;
   gs::launch_final(s, w, w.planes + (size_t)cur * pe, r->best_cost, r->best_s, r->final_row,

@@ -24,12 +24,16 @@ struct Shape {
 
 // Device pointers into the context's workspace.
 struct Workspace {
-  float *planes;     // [nplanes][B][S][pitch]   C planes, budget index contiguous
+  float *planes;     // [nplanes + 1][B][S][pitch]  C planes, budget index contiguous; after a
+                     // class-kernel solve slot l holds the compact plane [B][class_rows][pitch]
+                     // of layer l at its head and the extra slot the full plane of layer L-1
   void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null);
                      // after a class-kernel solve [L-1][B][kMaxClasses][pitch] uint8 indexed by
-                     // (target class, SOURCE row), see bp_by_class
-  int bp_by_class;   // 1: bp[l][e][sj] = bpc[l][class sj][e - O[l][sj]] when that row is >=
-                     // lowsum[l-1], else 0 (every strategy of a class shares the argmin)
+                     // (target class, SOURCE row), see by_class
+  int by_class;      // 1: the class kernel ran.  Planes are compact, C[l][e][s] =
+                     // Q[l][class s][e - O[l][s]] + T[l][s] with Q[0] = 0, and bp[l][e][sj] =
+                     // bpc[l][class sj][e - O[l][sj]] when that row is >= lowsum[l-1], else 0
+                     // (every strategy of a class shares the argmin)
   float *Tq;         // [B][L][SP]   sanitised copy of T
   int32_t *Oq;       // [B][L][SP]   sanitised copy of O, clamped to [0, M+1]
   float *Rt;         // [K][SP][SP]  transposed copy: Rt[k][sj][si] = R[k][si][sj]
@@ -50,6 +54,8 @@ struct Workspace {
 };
 
 inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; }
+// Compact planes of the class kernel: one row per transition class instead of per strategy.
+inline int class_rows(const Shape &s) { return s.S < kMaxClasses ? s.S : kMaxClasses; }
 
 // ---- launchers (all asynchronous on `st`) -------------------------------------------
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
@@ -61,9 +67,15 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
 void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
                             hipStream_t st);
 bool class_path_applies(const Shape &s);
-// One layer front with the class kernel (same contract as launch_dp_layer).
+// One layer front with the class kernel: src and dst are compact planes
+// [B][class_rows][pitch] holding Q[l-1] and Q[l], where
+// C[l][e][s] = Q[l][class s][e - O[l][s]] + T[l][s] and Q[0] = 0 (launch_class_zero).
 const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st);
+void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
+// Full plane of layer l from its compact form.
+void launch_class_expand(const Shape &s, const Workspace &w, int l, const float *q, float *plane,
+                         hipStream_t st);
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
                            hipStream_t st);
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);
