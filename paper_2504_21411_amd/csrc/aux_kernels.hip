@@ -192,16 +192,26 @@ __global__ __launch_bounds__(1024) void k_layout_classes(const int32_t *__restri
 
 // lowsum[b][l] = min(M+1, sum_{l' <= l} min_s O[l'][s]): a plan of layers 0..l needs at
 // least that many bins, so C[l][e][.] is +inf for every e below it.  The forward kernels
-// use it to fill those rows without computing them.  One thread per instance.
-__global__ void k_prefix_min_memory(const int32_t *__restrict__ minO,
-                                    int32_t *__restrict__ lowsum, int B, int L, int M) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  int acc = 0;
-  for (int l = 0; l < L; ++l) {
-    acc += minO[(size_t)b * L + l];
-    if (acc > M + 1) acc = M + 1;
-    lowsum[(size_t)b * L + l] = acc;
+// use it to fill those rows without computing them.  One wave per instance: 64 layers per
+// round, inclusive scan across the lanes, carry from round to round (every term is at most
+// M + 1 <= 2^24 + 1 and the running sum is clamped each round, so int32 cannot overflow).
+__global__ __launch_bounds__(kWave) void k_prefix_min_memory(const int32_t *__restrict__ minO,
+                                                             int32_t *__restrict__ lowsum, int B,
+                                                             int L, int M) {
+  const int b = blockIdx.x;
+  const int lane = threadIdx.x;
+  int carry = 0;
+  for (int l0 = 0; l0 < L; l0 += kWave) {
+    const int l = l0 + lane;
+    int v = l < L ? minO[(size_t)b * L + l] : 0;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int up = __shfl_up(v, d, kWave);
+      if (lane >= d) v = (v + up > M + 1) ? M + 1 : v + up;
+    }
+    v = (v + carry > M + 1) ? M + 1 : v + carry;
+    if (l < L) lowsum[(size_t)b * L + l] = v;
+    carry = __shfl(v, kWave - 1, kWave);
   }
 }
 
@@ -230,20 +240,33 @@ static __device__ __forceinline__ void wave_argmin(float &v, int &idx) {
 }
 
 // One wave per instance: min_s C[L-1][E_b][s] with the lowest s on ties.
+// BY_CLASS: `last` is the class kernel's compact plane of layer L-1 and
+// C[L-1][E][s] = Q[class s][E - O[L-1][s]] + T[L-1][s] (+inf when the strategy does not fit).
+template <bool BY_CLASS>
 __global__ void k_final_instance(const float *__restrict__ last,
                                  const int32_t *__restrict__ budget,
-                                 const int32_t *__restrict__ status, float *__restrict__ ws_cost,
-                                 int32_t *__restrict__ ws_s, float *__restrict__ best_cost,
-                                 int32_t *__restrict__ best_s, float *__restrict__ final_row, int B,
-                                 int S, int pitch) {
+                                 const int32_t *__restrict__ status, const float *__restrict__ Tq,
+                                 const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+                                 float *__restrict__ ws_cost, int32_t *__restrict__ ws_s,
+                                 float *__restrict__ best_cost, int32_t *__restrict__ best_s,
+                                 float *__restrict__ final_row, int B, int L, int S, int SP, int Sc,
+                                 int pitch) {
   const int b = blockIdx.x;
   const int lane = threadIdx.x;
   const int E = budget[b];
   const bool poisoned = *status != 0;
+  const size_t tab = ((size_t)b * L + L - 1) * SP;
   float m = GS_INF;
   int arg = 0x7fffffff;
   for (int s = lane; s < S; s += kWave) {
-    float v = last[((size_t)b * S + s) * pitch + E];
+    float v;
+    if (BY_CLASS) {
+      const int d = E - Oq[tab + s];
+      v = GS_INF;
+      if (d >= 0) v = last[((size_t)b * Sc + cls[s]) * pitch + d] + Tq[tab + s];
+    } else {
+      v = last[((size_t)b * S + s) * pitch + E];
+    }
     if (poisoned) v = GS_INF;
     if (final_row) final_row[(size_t)b * S + s] = v;
     if (v < m || arg == 0x7fffffff) { m = v; arg = s; }
@@ -413,17 +436,29 @@ __global__ void k_pipeline_groups(const float *__restrict__ stage_cost, int B, i
   cost[g] = out;
 }
 
-// curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf above.
+// curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf above.  BY_CLASS: from the compact
+// plane, C[L-1][e][s] = Q[class s][e - O[L-1][s]] + T[L-1][s].
+template <bool BY_CLASS>
 __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__restrict__ budget,
-                               const int32_t *__restrict__ status, float *__restrict__ curve,
-                               int B, int S, int M, int pitch) {
+                               const int32_t *__restrict__ status, const float *__restrict__ Tq,
+                               const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+                               float *__restrict__ curve, int B, int L, int S, int SP, int Sc,
+                               int M, int pitch) {
   const int b = blockIdx.x % B;
   const int e = (blockIdx.x / B) * blockDim.x + threadIdx.x;
   if (e > M) return;
+  const size_t tab = ((size_t)b * L + L - 1) * SP;
   float m = GS_INF;
   if (e <= budget[b] && *status == 0)
     for (int s = 0; s < S; ++s) {
-      const float v = last[((size_t)b * S + s) * pitch + e];
+      float v;
+      if (BY_CLASS) {
+        const int d = e - Oq[tab + s];
+        v = GS_INF;
+        if (d >= 0) v = last[((size_t)b * Sc + cls[s]) * pitch + d] + Tq[tab + s];
+      } else {
+        v = last[((size_t)b * S + s) * pitch + e];
+      }
       m = v < m ? v : m;
     }
   curve[(size_t)b * (M + 1) + e] = m;
@@ -753,8 +788,8 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
   hipLaunchKernelGGL(k_prepare, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, T, O, R,
                      r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B,
                      s.L, s.S, s.M, s.K, s.SP);
-  hipLaunchKernelGGL(k_prefix_min_memory, dim3((s.B + 63) / 64), dim3(64), 0, st, w.minO,
-                     w.lowsum, s.B, s.L, s.M);
+  hipLaunchKernelGGL(k_prefix_min_memory, dim3(s.B), dim3(kWave), 0, st, w.minO, w.lowsum, s.B,
+                     s.L, s.M);
 }
 
 void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
@@ -780,9 +815,14 @@ void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipSt
 
 void launch_final(const Shape &s, const Workspace &w, const float *last_plane, float *best_cost,
                   int32_t *best_s, float *final_row, int32_t *best_instance, hipStream_t st) {
-  hipLaunchKernelGGL(k_final_instance, dim3(s.B), dim3(kWave), 0, st, last_plane, w.budget,
-                     w.status, w.best_cost, w.best_s, best_cost, best_s, final_row, s.B, s.S,
-                     s.pitch);
+  if (w.by_class)
+    hipLaunchKernelGGL((k_final_instance<true>), dim3(s.B), dim3(kWave), 0, st, last_plane,
+                       w.budget, w.status, w.Tq, w.Oq, w.cls, w.best_cost, w.best_s, best_cost,
+                       best_s, final_row, s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
+  else
+    hipLaunchKernelGGL((k_final_instance<false>), dim3(s.B), dim3(kWave), 0, st, last_plane,
+                       w.budget, w.status, w.Tq, w.Oq, w.cls, w.best_cost, w.best_s, best_cost,
+                       best_s, final_row, s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
   if (best_instance)
     hipLaunchKernelGGL(k_final_global, dim3(1), dim3(256), 0, st, w.best_cost, best_instance,
                        s.B);
@@ -829,8 +869,14 @@ void launch_pipeline_reduce(const Shape &s, const Workspace &w, int G, const int
 void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_plane,
                          float *curve, hipStream_t st) {
   const int per = (s.M + 1 + 255) / 256;
-  hipLaunchKernelGGL(k_budget_curve, dim3((unsigned)((size_t)per * s.B)), dim3(256), 0, st,
-                     last_plane, w.budget, w.status, curve, s.B, s.S, s.M, s.pitch);
+  const dim3 grid((unsigned)((size_t)per * s.B)), block(256);
+  if (w.by_class)
+    hipLaunchKernelGGL((k_budget_curve<true>), grid, block, 0, st, last_plane, w.budget, w.status,
+                       w.Tq, w.Oq, w.cls, curve, s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
+  else
+    hipLaunchKernelGGL((k_budget_curve<false>), grid, block, 0, st, last_plane, w.budget,
+                       w.status, w.Tq, w.Oq, w.cls, curve, s.B, s.L, s.S, s.SP, class_rows(s), s.M,
+                       s.pitch);
 }
 
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st) {

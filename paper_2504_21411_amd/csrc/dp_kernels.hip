@@ -549,7 +549,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   float *cmin = lds;                    // [NC][64]  class minima of the tile
   float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
   int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1], padded to NC + 32
-  float *tile = reinterpret_cast<float *>(cs_lds + NC + 32); // [SP][64], backpointer mode only
+  float *tile = reinterpret_cast<float *>(cs_lds + NC + 32); // [SP + 3][64], backpointer mode only
   const int b = blockIdx.x;
   const int tile_start = (int)blockIdx.y * kWave;
   const int js = wave_uniform(threadIdx.x >> 6);
@@ -579,14 +579,18 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   // C[l-1][row][si] for this wave's source strategies, rebuilt from the compact plane.
   // Rows beyond the budget count as +inf; padding strategies have O = M + 1 and never fit.
   const int rowm = row <= E ? row : -1;
+  const char *__restrict__ qsb = reinterpret_cast<const char *>(qs);
+  const uint32_t pitch4 = (uint32_t)pitch * 4u;
   float stage[PER];
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
     const int i = js * PER + u;
     const int o = oprev[i];
     const int d = rowm - o;
-    const uint32_t at = (uint32_t)cls[i] * (uint32_t)pitch + (uint32_t)(d > 0 ? d : 0);
-    const float v = qs[at] + tprev[i];
+    // byte offset inside the instance's compact plane (at most 32 rows of at most 2^24 + 64
+    // floats: fits 32 bits), so the load takes a scalar base and one vector offset
+    const uint32_t at = (uint32_t)cls[i] * pitch4 + ((uint32_t)(d > 0 ? d : 0) << 2);
+    const float v = *reinterpret_cast<const float *>(qsb + at) + tprev[i];
     stage[u] = d >= 0 ? v : GS_INF;
   }
   for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
@@ -633,7 +637,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
       }
     }
     const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
-    qd[at] = m;
+    *reinterpret_cast<float *>(reinterpret_cast<char *>(qd) + (at << 2)) = m;
     if (WITH_BP) {
       // level 1b: first class of chunk g attaining it (operands re-read from LDS: g varies
       // from lane to lane)
@@ -644,55 +648,35 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
         const float4 ra = *reinterpret_cast<const float4 *>(rg);
         const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
         const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+        int kk = 0;
 #pragma unroll
         for (int k = 7; k >= 0; --k) { // descending: the lowest matching class wins
           const float v = cg[k * kWave] + rr[k];
-          ca = (v == m) ? 8 * g + k : ca;
+          kk = (v == m) ? k : kk;
         }
+        ca += kk;
       }
       // level 2: lowest member of class ca whose sum equals m (descending scan, last hit
       // wins); several members can round to the same sum
       int arg = 0;
-      const int lo = cs_lds[ca], hi = cs_lds[ca + 1];
+      const int lo = cs_lds[ca];
       const float rr = rc_lds[cj * NC + ca];
-      // four members per round so that their LDS reads are in flight together; past the
-      // end of a short class the last member is simply looked at again
+      // Four members per round so that their LDS reads are in flight together, highest
+      // first.  Past the end of a short class the scan looks at members of the following
+      // classes (or at the rows of slack behind the tile); whatever those match is
+      // overwritten, because class ca attains m and its members come later in the scan.
+      const float *tl = tile + lo * kWave + lane;
+      int rel = 0;
       for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
         float tv[4];
-        int ti[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          ti[u] = lo + d0 + u < hi ? lo + d0 + u : hi - 1;
-          tv[u] = tile[ti[u] * kWave + lane];
-        }
+        for (int u = 0; u < 4; ++u) tv[u] = tl[(d0 + u) * kWave];
 #pragma unroll
-        for (int u = 3; u >= 0; --u) arg = (tv[u] + rr == m) ? ti[u] : arg;
+        for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? d0 + u : rel;
       }
+      arg = lo + rel;
       bpb[at] = (uint8_t)arg;
     }
-  }
-}
-
-// C[l][e][s] = Q[l][class s][e - O[l][s]] + T[l][s] for O[l][s] <= e <= E, +inf otherwise:
-// the full plane of one layer from its compact form (for the final reductions, which read
-// a full plane).  grid = (instances, blocks of 256 rows).
-__global__ __launch_bounds__(256) void k_expand_class(
-    const float *__restrict__ q, float *__restrict__ plane, const float *__restrict__ Tq,
-    const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
-    const int32_t *__restrict__ budget, int L, int S, int SP, int Sc, int l, int pitch) {
-  const int b = blockIdx.x;
-  const int e = (int)blockIdx.y * 256 + threadIdx.x;
-  if (e >= pitch) return;
-  const int E = budget[b];
-  const float *__restrict__ qb = q + (size_t)b * Sc * pitch;
-  float *__restrict__ pb = plane + (size_t)b * S * pitch;
-  const size_t bl = (size_t)b * L + l;
-  for (int s = 0; s < S; ++s) {
-    const int o = Oq[bl * SP + s];
-    const int d = e - o;
-    float v = GS_INF;
-    if (d >= 0 && e <= E) v = qb[(size_t)cls[s] * pitch + d] + Tq[bl * SP + s];
-    pb[(size_t)s * pitch + e] = v;
   }
 }
 
@@ -977,7 +961,7 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
                             float *dst, void *bp_l, hipStream_t st) {
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)s.B, (unsigned)tiles), block(NW * kWave);
-  const size_t lds = sizeof(float) * ((bp_l ? SP * kWave : 0) + kMaxClasses * kWave +
+  const size_t lds = sizeof(float) * ((bp_l ? (SP + 3) * kWave : 0) + kMaxClasses * kWave +
                                       kMaxClasses * kMaxClasses + kMaxClasses + 32);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true>), grid, block, lds, st, src, dst, (uint8_t *)bp_l,
@@ -992,14 +976,18 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
 template <int SP>
 static void launch_class(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                          void *bp_l, hipStream_t st) {
-  // Waves per tile, measured over S = 16..128 and 64..70 K tiles: eight while the batch is
-  // a few hundred tiles (pure latency) and with backpointers from 32 padded strategies up
-  // (the kernel lives on latency hiding and a wave's share of a tile is short); four for
-  // the lighter min-only pass and for few strategies, where eight waves mostly repeat the
-  // per-wave set-up.  GSEARCH_JSPLIT overrides.
+  // Waves per tile, measured over S = 16..128 and 64..33 K tiles: eight while the batch is
+  // a few hundred tiles (pure latency); otherwise eight from 64 padded strategies up with
+  // backpointers and at 128 without (a wave's share of the tile is long enough to pay for
+  // the per-wave set-up), four below, and two for the min-only pass over tens of thousands
+  // of tiles with few strategies.  GSEARCH_JSPLIT overrides.
   const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
   int waves = tuning().jsplit;
-  if (waves < 1 || waves > 8) waves = tile_inst <= 512 ? 8 : (bp_l && SP >= 32 ? 8 : 4);
+  if (waves < 1 || waves > 8) {
+    if (tile_inst <= 512) waves = 8;
+    else if (bp_l) waves = SP >= 64 ? 8 : 4;
+    else waves = SP >= 128 ? 8 : (SP <= 32 && tile_inst >= 16384 ? 2 : 4);
+  }
   if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
   else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
@@ -1025,13 +1013,6 @@ void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {
   const size_t n = (size_t)s.B * class_rows(s) * s.pitch;
   const unsigned blocks = (unsigned)((n + 256 * 8 - 1) / (256 * 8));
   hipLaunchKernelGGL(k_zero_plane, dim3(blocks < 1 ? 1 : blocks), dim3(256), 0, st, q0, n);
-}
-
-void launch_class_expand(const Shape &s, const Workspace &w, int l, const float *q, float *plane,
-                         hipStream_t st) {
-  const dim3 grid((unsigned)s.B, (unsigned)((s.pitch + 255) / 256));
-  hipLaunchKernelGGL(k_expand_class, grid, dim3(256), 0, st, q, plane, w.Tq, w.Oq, w.cls, w.budget,
-                     s.L, s.S, s.SP, class_rows(s), l, s.pitch);
 }
 
 const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,

@@ -41,12 +41,10 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
     return at;
   };
   y.nplanes = keeps_all_planes(flags) ? s.L : (s.L < 2 ? s.L : 2);
-  // One slot more than the layers kept: the class kernel keeps compact planes (one row per
-  // class) at the head of the layer slots and expands the last layer into the extra slot
-  // for the final reductions.  Behind the last slot, slack of one padded instance row block:
-  // the tile kernel reads (and discards) the strategy rows S..SP-1 of an instance without
-  // clamping the address.
-  y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)(y.nplanes + 1) +
+  // The class kernel keeps compact planes (one row per class) at the head of the slots.
+  // Behind the last slot, slack of one padded instance row block: the tile kernel reads
+  // (and discards) the strategy rows S..SP-1 of an instance without clamping the address.
+  y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)y.nplanes +
                                    (size_t)s.SP * s.pitch));
   const bool want_bp = !(flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
   // (the class kernel stores kMaxClasses columns per instance instead of S)
@@ -360,11 +358,6 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   if (timing) {
     if (hipEventRecord(ctx->ev_end, st) != hipSuccess) return GSEARCH_ERR_HIP;
     ctx->timed = true;
-  }
-  if (use_classes) { // the final reductions read a full plane: expand layer L-1
-    gs::launch_class_expand(s, w, s.L - 1, w.planes + (size_t)cur * pe,
-                            w.planes + (size_t)y.nplanes * pe, st);
-    cur = y.nplanes;
   }
   ctx->last_plane = cur;
   gs::launch_final(s, w, w.planes + (size_t)cur * pe, r->best_cost, r->best_s, r->final_row,

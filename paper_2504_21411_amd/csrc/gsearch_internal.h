@@ -24,9 +24,9 @@ struct Shape {
 
 // Device pointers into the context's workspace.
 struct Workspace {
-  float *planes;     // [nplanes + 1][B][S][pitch]  C planes, budget index contiguous; after a
-                     // class-kernel solve slot l holds the compact plane [B][class_rows][pitch]
-                     // of layer l at its head and the extra slot the full plane of layer L-1
+  float *planes;     // [nplanes][B][S][pitch]  C planes, budget index contiguous; after a
+                     // class-kernel solve every slot holds the compact plane
+                     // [B][class_rows][pitch] of its layer at its head instead
   void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null);
                      // after a class-kernel solve [L-1][B][kMaxClasses][pitch] uint8 indexed by
                      // (target class, SOURCE row), see by_class
@@ -73,9 +73,6 @@ bool class_path_applies(const Shape &s);
 const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st);
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
-// Full plane of layer l from its compact form.
-void launch_class_expand(const Shape &s, const Workspace &w, int l, const float *q, float *plane,
-                         hipStream_t st);
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
                            hipStream_t st);
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);
