@@ -39,9 +39,22 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     if kernel == "k_dp_tile":
         return 15.0 / 8.0 + 24.0 / S
     return 4.0
+
+
+def class_ops_per_row(S: int, nc: int, maxlen: int, nobp: bool) -> float:
+    """Vector-ALU (and LDS-minimum) operations per lane that the class kernel's algorithm
+    needs for one source row: rebuilding C from the compact plane (one add per strategy),
+    the class minima (one minimum per strategy), nc x nc relaxations priced as in the
+    general kernels (1.5 min-only, 15/8 with the two-level argmin), and per target class the
+    second look at one chunk of eight classes (24) and at the members of one class (3 each).
+    """
+    ops = 2.0 * S
+    if nobp:
+        return ops + 1.5 * nc * nc
+    return ops + 15.0 / 8.0 * nc * nc + nc * (24.0 + 3.0 * maxlen)
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {(3, "bp"): 89.0e6, (3, "nobp"): 86.5e6, (3, "bp-general"): 54.0e6}
+MEASURED_TRAFFIC_BYTES = {(3, "bp"): 27.6e6, (3, "nobp"): 25.1e6, (3, "bp-general"): 54.0e6}
 
 
 def cpu_baseline(w, cfg_index, target_relax=3.0e10):
@@ -144,15 +157,24 @@ def main():
             if kernel not in ("k_dp_push", "k_dp_tile", "k_dp_class"):
                 executed = 1.0
             n_class = int(out["n_class"].cpu()[0]) if "n_class" in out else None
-            # algorithmic HBM bytes of one layer front: every computed source row is read
-            # once (4 B per state) and every target row 0..E written once (4 B per state);
-            # backpointers: 1 B per target state, or, from the class kernel, 1 B per computed
-            # source row and target CLASS
             computed = float((rows - skipped).sum()) / (w.L - 1)
-            front_bytes = (computed * 4.0 + float(rows.sum()) * 4.0) * w.S
-            if not nobp:
-                front_bytes += (computed * n_class if kernel == "k_dp_class"
-                                else float(rows.sum()) * w.S)
+            if kernel == "k_dp_class":
+                # Compact planes: a front reads and writes one float per computed source
+                # row and CLASS (plus one backpointer byte); rows above E - min_s O[l][s]
+                # have no target within the budget and are not touched.
+                rc = out["r_class"].cpu().numpy()
+                max_len = int(np.bincount(rc).max())
+                upper = np.maximum(rows - np.minimum(O.min(axis=2), w.M + 1)[:, 1:], 0)
+                class_rows = float(np.maximum(upper - np.minimum(skipped, upper), 0).sum()) \
+                    / (w.L - 1)
+                front_bytes = class_rows * n_class * (8.0 if nobp else 9.0)
+            else:
+                # algorithmic HBM bytes of one layer front: every computed source row is
+                # read once (4 B per state) and every target row 0..E written once (4 B per
+                # state); backpointers: 1 B per target state
+                front_bytes = (computed * 4.0 + float(rows.sum()) * 4.0) * w.S
+                if not nobp:
+                    front_bytes += float(rows.sum()) * w.S
             if kernel == "k_dp_small":
                 front_bytes = 0.0 if nobp else float(rows.sum()) * w.S   # planes stay in LDS
         ms_step = dt * 1e3 / args.steps
@@ -166,15 +188,26 @@ def main():
                   "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode))}
         if kernel == "k_dp_class":
             # With the transition classes the arithmetic shrinks to one minimum per class
-            # and one relaxation per pair of classes, and the launch is bound by the plane
-            # and backpointer traffic: roofline against HBM.
-            per_launch = front_bytes / groups / launch_s / 1e9
-            achieved = per_launch * groups
-            roof = dict(common, bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=achieved / HBM_PEAK_GBS, achieved_per_launch=per_launch,
-                        algorithmic_bytes_per_launch=front_bytes / groups, classes=n_class,
-                        executed_fraction_of_nominal_relaxations=executed
-                        * (n_class * n_class + w.S) / float(w.S * w.S))
+            # and one relaxation per pair of classes, and with the compact planes the
+            # traffic to 2 floats per row and class: report the tighter of the two roofs.
+            opr_row = class_ops_per_row(w.S, n_class, max_len, nobp)
+            ops = opr_row * class_rows / groups
+            per_launch = ops / launch_s / 1e12
+            alu_frac = per_launch * groups / ALU_PEAK_TLANEOPS
+            hbm_gbs = front_bytes / launch_s / 1e9
+            hbm_frac = hbm_gbs / HBM_PEAK_GBS
+            extra = dict(classes=n_class, longest_class=max_len, ops_per_row=opr_row,
+                         algorithmic_bytes_per_launch=front_bytes / groups,
+                         executed_fraction_of_nominal_relaxations=executed
+                         * (n_class * n_class + w.S) / float(w.S * w.S))
+            if hbm_frac > alu_frac:
+                roof = dict(common, bound="hbm", achieved=hbm_gbs, peak=HBM_PEAK_GBS,
+                            unit="GB/s", frac=hbm_frac, achieved_per_launch=hbm_gbs / groups,
+                            alu_frac=alu_frac, **extra)
+            else:
+                roof = dict(common, bound="alu", achieved=per_launch * groups,
+                            peak=ALU_PEAK_TLANEOPS, unit="Tlaneop/s", frac=alu_frac,
+                            achieved_per_launch=per_launch, hbm_frac=hbm_frac, **extra)
         else:
             opr = ops_per_relaxation(kernel, "nobp" if nobp else "bp", w.S)
             ops = opr * relax * executed / launches / groups        # executed, per launch

@@ -578,27 +578,35 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
 
   // C[l-1][row][si] for this wave's source strategies, rebuilt from the compact plane.
   // Rows beyond the budget count as +inf; padding strategies have O = M + 1 and never fit.
-  const int rowm = row <= E ? row : -1;
+  // Byte offsets inside the instance's compact plane (the launcher admits the kernel only
+  // when they fit 31 bits), so a load takes a scalar base and one vector offset: row of
+  // class c, shifted down by O, clamped to the start of the row.
+  const int row4 = (row <= E ? row : -1) * 4;
   const char *__restrict__ qsb = reinterpret_cast<const char *>(qs);
-  const uint32_t pitch4 = (uint32_t)pitch * 4u;
+  const int pitch4 = pitch * 4;
   float stage[PER];
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
     const int i = js * PER + u;
-    const int o = oprev[i];
-    const int d = rowm - o;
-    // byte offset inside the instance's compact plane (at most 32 rows of at most 2^24 + 64
-    // floats: fits 32 bits), so the load takes a scalar base and one vector offset
-    const uint32_t at = (uint32_t)cls[i] * pitch4 + ((uint32_t)(d > 0 ? d : 0) << 2);
-    const float v = *reinterpret_cast<const float *>(qsb + at) + tprev[i];
-    stage[u] = d >= 0 ? v : GS_INF;
+    const int cb = cls[i] * pitch4;          // wave-uniform
+    const int t = row4 + (cb - oprev[i] * 4);
+    const float v = *reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb)) + tprev[i];
+    stage[u] = t >= cb ? v : GS_INF;
   }
-  for (int x = threadIdx.x; x < NC * kWave; x += NW * kWave) cmin[x] = GS_INF;
-  for (int x = threadIdx.x; x < NC * NC; x += NW * kWave) rc_lds[x] = rck[x];
-  if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+  {
+    const float4 inf4 = {GS_INF, GS_INF, GS_INF, GS_INF};
+    for (int x = threadIdx.x; x < NC * kWave / 4; x += NW * kWave)
+      reinterpret_cast<float4 *>(cmin)[x] = inf4;
+  }
   if (WITH_BP) {
+    // (the per-lane gathers of the argmin levels read the class table and the run table
+    // from LDS; the min-only pass takes both as scalar operands only)
+    for (int x = threadIdx.x; x < NC * NC / 4; x += NW * kWave)
+      reinterpret_cast<float4 *>(rc_lds)[x] = reinterpret_cast<const float4 *>(rck)[x];
+    if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+    float *tw = tile + (js * PER) * kWave + lane;
 #pragma unroll
-    for (int u = 0; u < PER; ++u) tile[(js * PER + u) * kWave + lane] = stage[u];
+    for (int u = 0; u < PER; ++u) tw[u * kWave] = stage[u];
   }
   __syncthreads();
 #pragma unroll
@@ -608,15 +616,10 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
                            __HIP_MEMORY_SCOPE_WORKGROUP);
   }
   __syncthreads();
+  // every wave keeps all class minima in registers (classes that do not exist hold +inf)
   float cmv[NC];
-  // only the chunks of eight classes that exist are kept (the rest is never read)
 #pragma unroll
-  for (int q = 0; q < NC / 8; ++q) {
-    if (8 * q < nc) {
-#pragma unroll
-      for (int k = 0; k < 8; ++k) cmv[8 * q + k] = cmin[(8 * q + k) * kWave + lane];
-    }
-  }
+  for (int k = 0; k < NC; ++k) cmv[k] = cmin[k * kWave + lane];
 
   for (int cj = js; cj < nc; cj += NW) {
     const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
@@ -632,7 +635,11 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
         const int h = (q & 1) * 8;
         float cm = __builtin_fminf(cmv[8 * q] + r[h], cmv[8 * q + 1] + r[h + 1]);
 #pragma unroll
-        for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
+        for (int k = 2; k < 4; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
+        if (8 * q + 4 < nc) { // the upper half of the last chunk may be padding (+inf)
+#pragma unroll
+          for (int k = 4; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
+        }
         chunk_update<true>(m, g, cm, q);
       }
     }
@@ -953,7 +960,7 @@ bool class_path_applies(const Shape &s) {
   // the kernel addresses an instance's plane with 32-bit element offsets
   // and runs on a (instances, tiles) grid
   return tsp >= 16 && tsp == s.SP && !s.bp16 && (size_t)s.S * s.pitch < ((size_t)1 << 31) &&
-         (s.M + kWave) / kWave <= 65535;
+         (size_t)class_rows(s) * s.pitch * 4 < ((size_t)1 << 31) && (s.M + kWave) / kWave <= 65535;
 }
 
 template <int SP, int NW>
