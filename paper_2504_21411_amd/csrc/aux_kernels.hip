@@ -405,6 +405,126 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
   }
 }
 
+// The same walk with one memory round trip per layer instead of four or five: the wave
+// keeps the O row of the current layer and the O and T rows of the layer below in registers
+// (PL strategies per lane, S <= 64 PL), fetches the rows two layers down and the next
+// r_index while the plane values it depends on are in flight, and picks O[l][s] out of the
+// registers with a lane read.  What still depends on the argmin just found - the plane
+// values at row e and the transition column of s - is requested together.
+template <bool BY_CLASS, int PL>
+__global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
+    const float *__restrict__ planes, const float *__restrict__ Rt, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ ws_s, const int32_t *__restrict__ instances, int n,
+    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP, int Sc,
+    int M, int pitch) {
+  const int q = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int b = instances ? instances[q] : q;
+  int s = (b >= 0 && b < B) ? ws_s[b] : -1;
+  if (s < 0) {
+    for (int l = lane; l < L; l += kWave) plan[(size_t)q * L + l] = -1;
+    if (mem_used && lane == 0) mem_used[q] = -1;
+    return;
+  }
+  int e = budget[b];
+  int used = 0;
+  const size_t layer_stride = (size_t)B * S * pitch;
+  const size_t inst = (size_t)b * (BY_CLASS ? Sc : S) * pitch;
+  const size_t tab = (size_t)b * L * SP;
+  // Every load below is unconditional (index clamped, value selected afterwards), so that
+  // the loads of a step are in flight together and are awaited once.
+  int ic[PL];      // lane + 64 u, or 0 for the lanes past the last strategy
+  int cl[PL];      // class of that strategy
+  int o_cur[PL];   // O[l][.]
+  int o_low[PL];   // O[l-1][.]  (padding strategies: M + 1, they never fit)
+  float t_low[PL]; // T[l-1][.]
+  const int lb = L > 1 ? L - 2 : 0;
+#pragma unroll
+  for (int u = 0; u < PL; ++u) {
+    const int i = lane + kWave * u;
+    ic[u] = i < S ? i : 0;
+    cl[u] = BY_CLASS ? cls[ic[u]] : 0;
+    const int oc = Oq[tab + (size_t)(L - 1) * SP + ic[u]];
+    const int ol = Oq[tab + (size_t)lb * SP + ic[u]];
+    o_cur[u] = i < S ? oc : M + 1;
+    o_low[u] = i < S ? ol : M + 1;
+    t_low[u] = Tq[tab + (size_t)lb * SP + ic[u]];
+  }
+  int k = L > 1 ? ridx[(size_t)b * L + L - 1] : 0;
+  for (int l = L - 1; l >= 1; --l) {
+    if (lane == 0) plan[(size_t)q * L + l] = s;
+    int o = 0;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      const int v = __shfl(o_cur[u], s & 63, kWave);
+      o = (s >> 6) == u ? v : o;
+    }
+    used += o;
+    e -= o;
+    // rows two layers down and the next matrix index: independent of (s, e)
+    int o_nxt[PL];
+    float t_nxt[PL];
+    const int l2 = l >= 2 ? l - 2 : 0;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      o_nxt[u] = Oq[tab + (size_t)l2 * SP + ic[u]];
+      t_nxt[u] = Tq[tab + (size_t)l2 * SP + ic[u]];
+    }
+    const int k_nxt = ridx[(size_t)b * L + (l >= 2 ? l - 1 : 1)];
+    // what depends on (s, e): the plane values and the transition column of s
+    const float *prevp = planes + (size_t)(l - 1) * layer_stride + inst;
+    const float *rcol = Rt + ((size_t)k * SP + s) * SP;
+    float craw[PL], rraw[PL];
+    int dd[PL];
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      if (BY_CLASS) {
+        dd[u] = e - o_low[u];
+        craw[u] = prevp[(size_t)cl[u] * pitch + (dd[u] > 0 ? dd[u] : 0)];
+      } else {
+        dd[u] = 0;
+        craw[u] = prevp[(size_t)ic[u] * pitch + (e > 0 ? e : 0)];
+      }
+      rraw[u] = rcol[ic[u]];
+    }
+    // (keeps the compiler from sinking a load into the branch that selects its value,
+    // where it would be awaited on its own)
+#pragma unroll
+    for (int u = 0; u < PL; ++u) asm volatile("" : "+v"(craw[u]), "+v"(rraw[u]));
+    float m = GS_INF;
+    int arg = lane;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      const int i = lane + kWave * u;
+      float c = BY_CLASS ? craw[u] + t_low[u] : craw[u];
+      c = (i < S && dd[u] >= 0) ? c : GS_INF;
+      const float v = c + rraw[u];
+      if (u == 0 || v < m) { m = v; arg = i; }
+    }
+    wave_argmin(m, arg);
+    s = arg;
+    k = k_nxt;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      const int i = lane + kWave * u;
+      o_cur[u] = o_low[u];
+      o_low[u] = i < S ? o_nxt[u] : M + 1;
+      t_low[u] = t_nxt[u];
+    }
+  }
+  if (lane == 0) plan[(size_t)q * L] = s;
+  // O[0][s] sits in o_cur (the loop left the row of layer 0 there)
+  int o = 0;
+#pragma unroll
+  for (int u = 0; u < PL; ++u) {
+    const int v = __shfl(o_cur[u], s & 63, kWave);
+    o = (s >> 6) == u ? v : o;
+  }
+  if (lane == 0 && mem_used) mem_used[q] = used + o;
+}
+
 // Pipeline-aware outer reduction: one thread per candidate (pipeline degree, stage split,
 // micro-batch count).  cost = (t_0 + ... + t_{pp-1}) + (m - 1) * max t, in fp32: the sum
 // left to right over the members as listed, the product rounded, then one add; +inf as
@@ -845,16 +965,28 @@ void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *inst
                        s.S, s.SP, s.pitch);
 }
 
+template <bool BY_CLASS>
+static void launch_backtrace_planes_of(const Shape &s, const Workspace &w, const int32_t *instances,
+                                       int n, int32_t *plan, int32_t *mem_used, hipStream_t st) {
+  const dim3 grid(n), block(kWave);
+#define GS_ROWS(PL)                                                                              \
+  hipLaunchKernelGGL((k_backtrace_planes_rows<BY_CLASS, PL>), grid, block, 0, st, w.planes, w.Rt, \
+                     w.Tq, w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, \
+                     s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch)
+  if (s.S <= 64) GS_ROWS(1);
+  else if (s.S <= 128) GS_ROWS(2);
+  else if (s.S <= 256) GS_ROWS(4);
+  else
+    hipLaunchKernelGGL((k_backtrace_planes<BY_CLASS>), grid, block, 0, st, w.planes, w.Rt, w.Tq,
+                       w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, s.B,
+                       s.L, s.S, s.SP, class_rows(s), s.pitch);
+#undef GS_ROWS
+}
+
 void launch_backtrace_planes(const Shape &s, const Workspace &w, const int32_t *instances, int n,
                              int32_t *plan, int32_t *mem_used, hipStream_t st) {
-  if (w.by_class)
-    hipLaunchKernelGGL((k_backtrace_planes<true>), dim3(n), dim3(kWave), 0, st, w.planes, w.Rt,
-                       w.Tq, w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used,
-                       s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
-  else
-    hipLaunchKernelGGL((k_backtrace_planes<false>), dim3(n), dim3(kWave), 0, st, w.planes, w.Rt,
-                       w.Tq, w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used,
-                       s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
+  if (w.by_class) launch_backtrace_planes_of<true>(s, w, instances, n, plan, mem_used, st);
+  else launch_backtrace_planes_of<false>(s, w, instances, n, plan, mem_used, st);
 }
 
 void launch_pipeline_reduce(const Shape &s, const Workspace &w, int G, const int32_t *offsets,
