@@ -343,6 +343,73 @@ __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__rest
   if (mem_used) mem_used[q] = used;
 }
 
+// The same walk by one WAVE per requested instance (S <= 64 PL, uint8 backpointers): the O
+// row of the current layer sits in registers, O[l][s] and the class of s are lane reads, and
+// the O row of the layer below is fetched while the backpointer load is in flight - one
+// memory round trip per layer instead of two.
+template <bool BY_CLASS, int PL>
+__global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
+    const uint8_t *__restrict__ bp, const int32_t *__restrict__ Oq,
+    const int32_t *__restrict__ cls, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ ws_s, const int32_t *__restrict__ instances, int n,
+    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP,
+    int pitch) {
+  const int q = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int b = instances ? instances[q] : q;
+  int s = (b >= 0 && b < B) ? ws_s[b] : -1;
+  if (s < 0) {
+    for (int l = lane; l < L; l += kWave) plan[(size_t)q * L + l] = -1;
+    if (mem_used && lane == 0) mem_used[q] = -1;
+    return;
+  }
+  int e = budget[b];
+  int used = 0;
+  const int cols = BY_CLASS ? kMaxClasses : S;
+  const size_t layer_stride = (size_t)B * cols * pitch;
+  const size_t tab = (size_t)b * L * SP;
+  int ic[PL], cl[PL], o_cur[PL];
+#pragma unroll
+  for (int u = 0; u < PL; ++u) {
+    const int i = lane + kWave * u;
+    ic[u] = i < S ? i : 0;
+    cl[u] = BY_CLASS ? cls[ic[u]] : 0;
+    o_cur[u] = Oq[tab + (size_t)(L - 1) * SP + ic[u]];
+  }
+  for (int l = L - 1; l >= 1; --l) {
+    if (lane == 0) plan[(size_t)q * L + l] = s;
+    int o = 0, col = s;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      const int vo = __shfl(o_cur[u], s & 63, kWave);
+      const int vc = __shfl(cl[u], s & 63, kWave);
+      o = (s >> 6) == u ? vo : o;
+      if (BY_CLASS) col = (s >> 6) == u ? vc : col;
+    }
+    int o_nxt[PL];
+#pragma unroll
+    for (int u = 0; u < PL; ++u) o_nxt[u] = Oq[tab + (size_t)(l - 1) * SP + ic[u]];
+    const int at = BY_CLASS ? e - o : e;
+    int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * cols + col) * pitch + at];
+    asm volatile("" : "+v"(prev));
+    used += o;
+    e -= o;
+    s = prev;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) o_cur[u] = o_nxt[u];
+  }
+  int o = 0;
+#pragma unroll
+  for (int u = 0; u < PL; ++u) {
+    const int vo = __shfl(o_cur[u], s & 63, kWave);
+    o = (s >> 6) == u ? vo : o;
+  }
+  if (lane == 0) {
+    plan[(size_t)q * L] = s;
+    if (mem_used) mem_used[q] = used + o;
+  }
+}
+
 // Backtrace without stored backpointers: one wave per requested instance re-derives every
 // argmin from the kept planes, argmin_si ( C[l-1][e-O][si] + R[si][s] ), lowest si on ties
 // (all +inf gives 0) - the same value the forward pass would have stored.
@@ -948,21 +1015,30 @@ void launch_final(const Shape &s, const Workspace &w, const float *last_plane, f
                        s.B);
 }
 
+template <bool BY_CLASS>
+static void launch_backtrace_bp_rows(const Shape &s, const Workspace &w, const int32_t *instances,
+                                     int n, int32_t *plan, int32_t *mem_used, hipStream_t st) {
+  const dim3 grid(n), block(kWave);
+#define GS_ROWS(PL)                                                                          \
+  hipLaunchKernelGGL((k_backtrace_bp_rows<BY_CLASS, PL>), grid, block, 0, st,               \
+                     (const uint8_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n,  \
+                     plan, mem_used, s.B, s.L, s.S, s.SP, s.pitch)
+  if (s.S <= 64) GS_ROWS(1);
+  else if (s.S <= 128) GS_ROWS(2);
+  else GS_ROWS(4);
+#undef GS_ROWS
+}
+
 void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *instances, int n,
                          int32_t *plan, int32_t *mem_used, hipStream_t st) {
-  const dim3 grid((n + 63) / 64), block(64);
-  if (w.by_class)
-    hipLaunchKernelGGL((k_backtrace_bp<uint8_t, true>), grid, block, 0, st, (const uint8_t *)w.bp,
-                       w.Oq, w.cls, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L,
-                       s.S, s.SP, s.pitch);
-  else if (s.bp16)
-    hipLaunchKernelGGL((k_backtrace_bp<uint16_t, false>), grid, block, 0, st,
-                       (const uint16_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n, plan,
-                       mem_used, s.B, s.L, s.S, s.SP, s.pitch);
-  else
-    hipLaunchKernelGGL((k_backtrace_bp<uint8_t, false>), grid, block, 0, st, (const uint8_t *)w.bp,
-                       w.Oq, w.cls, w.budget, w.best_s, instances, n, plan, mem_used, s.B, s.L,
-                       s.S, s.SP, s.pitch);
+  if (!s.bp16) { // S <= 256: one wave per instance, table rows in registers
+    if (w.by_class) launch_backtrace_bp_rows<true>(s, w, instances, n, plan, mem_used, st);
+    else launch_backtrace_bp_rows<false>(s, w, instances, n, plan, mem_used, st);
+    return;
+  }
+  hipLaunchKernelGGL((k_backtrace_bp<uint16_t, false>), dim3((n + 63) / 64), dim3(64), 0, st,
+                     (const uint16_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n, plan,
+                     mem_used, s.B, s.L, s.S, s.SP, s.pitch);
 }
 
 template <bool BY_CLASS>
