@@ -555,12 +555,30 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   const int js = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int bl = b * L + l;
-  const int E = budget[b];
-  const int low = lowsum[bl - 1]; // C[l-1] is +inf below this row
-  const int mo = minO[bl];
-  const int kr = ridx[bl];
-  const int nc = cmeta[0];
-  const int maxlen = cmeta[1];
+  // Every scalar table entry this wave will need is requested before the first of them is
+  // looked at (one round trip to the scalar cache instead of one per dependent step): the
+  // per-instance scalars, and the O, T and class entries of the wave's source strategies.
+  int E = budget[b];
+  int low = lowsum[bl - 1]; // C[l-1] is +inf below this row
+  int mo = minO[bl];
+  int kr = ridx[bl];
+  int nc = cmeta[0];
+  int maxlen = cmeta[1];
+  int o_s[PER], c_s[PER];
+  float t_s[PER];
+  {
+    const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
+    const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      o_s[u] = oprev[js * PER + u];
+      c_s[u] = cls[js * PER + u];
+      t_s[u] = tprev[js * PER + u];
+    }
+  }
+  asm volatile("" : "+s"(E), "+s"(low), "+s"(mo), "+s"(kr), "+s"(nc), "+s"(maxlen));
+#pragma unroll
+  for (int u = 0; u < PER; ++u) asm volatile("" : "+s"(o_s[u]), "+s"(c_s[u]), "+s"(t_s[u]));
   if (tile_start > E - mo) return; // no target row within the budget (whole workgroup)
 
   const int row = tile_start + lane;
@@ -573,8 +591,6 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     return;
   }
   const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
-  const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
-  const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
 
   // C[l-1][row][si] for this wave's source strategies, rebuilt from the compact plane.
   // Rows beyond the budget count as +inf; padding strategies have O = M + 1 and never fit.
@@ -587,10 +603,9 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   float stage[PER];
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
-    const int i = js * PER + u;
-    const int cb = cls[i] * pitch4;          // wave-uniform
-    const int t = row4 + (cb - oprev[i] * 4);
-    const float v = *reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb)) + tprev[i];
+    const int cb = c_s[u] * pitch4;          // wave-uniform
+    const int t = row4 + (cb - o_s[u] * 4);
+    const float v = *reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb)) + t_s[u];
     stage[u] = t >= cb ? v : GS_INF;
   }
   {
@@ -611,7 +626,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   __syncthreads();
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
-    const int c = cls[js * PER + u]; // wave-uniform
+    const int c = c_s[u]; // wave-uniform
     __hip_atomic_fetch_min(&cmin[c * kWave + lane], stage[u], __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_WORKGROUP);
   }
