@@ -726,3 +726,35 @@ def test_strategy_set_with_more_layouts_than_the_class_limit(gs, oracle_mod):
         r_class, _ = binding.gsearch_layout_classes(torch.from_numpy(desc).to(dw.device))
         runner.run_step(ctx, dw, backtrace=None, r_class=r_class)
         assert ctx.gsearch_data_status() & binding.GSEARCH_DATA_BAD_RCLASS
+
+
+@pytest.mark.parametrize("mode", ["bp", "nobp"])
+def test_one_context_solves_different_workloads_in_turn(gs, oracle_mod, mode):
+    """A context is a workspace, not a cache: problems of different shapes, budgets and class
+    structure solved one after the other in the same context (whose planes then hold whatever
+    the previous solve left, including rows the next solve never writes) each match the
+    oracle, whole planes included."""
+    binding, runner = gs
+    import torch
+    big, rc_big = workloads.class_tables("reuse_big", 4, 7, 96, 900, [4] * 24, K=2, seed=501,
+                                         budget=np.array([900, 850, 400, 899], np.int32),
+                                         coarse=True)
+    small, rc_small = workloads.class_tables("reuse_small", 3, 5, 44, 300, [4] * 11, K=1, seed=502,
+                                             budget=np.array([120, 300, 7], np.int32))
+    plain = random_tables("reuse_plain", 2, 6, 24, 500, K=2, seed=503)
+    cases = [(big, rc_big), (small, rc_small), (plain, None), (small, rc_small), (big, rc_big)]
+    refs = {id(w): oracle_batch(oracle_mod, w) for w, _ in cases}
+    flags = MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES
+    with binding.GSearch(4, 7, 96, 900, 2, flags=flags) as ctx:
+        for n, (w, rc) in enumerate(cases):
+            dw = runner.DeviceWorkload(w)
+            r_class = None if rc is None else torch.from_numpy(rc).to(dw.device)
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=r_class))
+            got["data_status"] = ctx.gsearch_data_status()
+            C, _ = ctx.gsearch_export_planes(want_bp=False)
+            C = C.cpu().numpy()
+            assert_same(got, refs[id(w)], w, f"solve {n} ({w.name}, {mode})")
+            for b in range(w.B):
+                E = int(w.budget[b])
+                one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True)
+                assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (n, w.name, b)
