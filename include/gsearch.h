@@ -80,10 +80,12 @@ typedef enum {
 #define GSEARCH_DATA_BAD_O 0x4
 #define GSEARCH_DATA_BAD_BUDGET 0x8
 #define GSEARCH_DATA_BAD_RINDEX 0x10
-#define GSEARCH_DATA_BAD_RCLASS 0x20 /* r_class is not a valid partition, has more than
-                                        GSEARCH_MAX_CLASSES classes, or R differs inside one */
+#define GSEARCH_DATA_BAD_RCLASS 0x20 /* r_class is not a valid partition, has more classes
+                                        than announced (r_class_bound) or than
+                                        GSEARCH_MAX_CLASSES, or R differs inside one */
 
-#define GSEARCH_MAX_CLASSES 32 /* transition classes a solve can exploit (see r_class) */
+#define GSEARCH_MAX_CLASSES 64 /* transition classes a solve can exploit (see r_class) */
+#define GSEARCH_DEFAULT_CLASSES 32 /* ... unless r_class_bound announces more */
 
 #define GSEARCH_MAX_S 1024 /* strategies per layer (bp is uint8 up to 256, uint16 above) */
 
@@ -114,7 +116,7 @@ typedef struct {
                              less work for bit-identical results: strategies are grouped
                              into contiguous classes (r_class[0] = 0, each entry equal to
                              its predecessor or one more, at most GSEARCH_MAX_CLASSES
-                             classes), and R depends on the strategies only through their
+                             classes, see r_class_bound), and R depends on the strategies only through their
                              classes, i.e. rows si, si' of one class are equal in every
                              matrix of the pool and so are columns sj, sj' of one class.
                              That is the case when the transition cost is a resharding
@@ -124,6 +126,13 @@ typedef struct {
                              The promise is checked on the device: a violation sets
                              GSEARCH_DATA_BAD_RCLASS and the solve reports every instance
                              as infeasible.  NULL: no assumption.                        */
+  int32_t r_class_bound;  /* HOST value: upper bound on the number of classes in r_class
+                             (gsearch_layout_classes reports the count).  0 or anything up
+                             to GSEARCH_DEFAULT_CLASSES: at most 32 classes, the narrow
+                             and faster form of the class kernel; up to GSEARCH_MAX_CLASSES:
+                             the wide form.  More classes than announced (or than 64) are
+                             flagged like any other broken promise.  Ignored without
+                             r_class.                                                    */
 } gsearch_problem;
 
 /* Caller-allocated DEVICE outputs of a solve; any pointer may be NULL to skip it. */

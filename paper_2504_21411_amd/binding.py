@@ -34,7 +34,8 @@ GSEARCH_DATA_BAD_O = 0x4
 GSEARCH_DATA_BAD_BUDGET = 0x8
 GSEARCH_DATA_BAD_RINDEX = 0x10
 GSEARCH_DATA_BAD_RCLASS = 0x20
-GSEARCH_MAX_CLASSES = 32
+GSEARCH_MAX_CLASSES = 64
+GSEARCH_DEFAULT_CLASSES = 32
 
 EXPORTS = [
     "gsearch_workspace_bytes", "gsearch_create", "gsearch_destroy", "gsearch_solve_batch",
@@ -56,7 +57,8 @@ class gsearch_problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("L", ctypes.c_int32), ("S", ctypes.c_int32),
                 ("M", ctypes.c_int32), ("K", ctypes.c_int32), ("T", ctypes.c_void_p),
                 ("O", ctypes.c_void_p), ("R", ctypes.c_void_p), ("r_index", ctypes.c_void_p),
-                ("budget", ctypes.c_void_p), ("r_class", ctypes.c_void_p)]
+                ("budget", ctypes.c_void_p), ("r_class", ctypes.c_void_p),
+                ("r_class_bound", ctypes.c_int32)]
 
 
 class gsearch_result(ctypes.Structure):
@@ -281,10 +283,11 @@ class GSearch:
             pass
 
     def gsearch_solve_batch(self, T, O, R, r_index, budget, M, want_final_row=True, stream=None,
-                            out=None, r_class=None):
+                            out=None, r_class=None, r_class_bound=0):
         """T fp32 [B][L][S], O int32 [B][L][S], R fp32 [K][S][S], r_index int32 [B][L],
-        budget int32 [B], optional r_class int32 [S], all on the GPU.  Returns a dict of
-        device tensors (asynchronous)."""
+        budget int32 [B], optional r_class int32 [S], all on the GPU; r_class_bound: host
+        upper bound on the number of classes (needed above 32).  Returns a dict of device
+        tensors (asynchronous)."""
         import torch
         B, L, S = T.shape
         K = R.shape[0]
@@ -303,7 +306,7 @@ class GSearch:
                                _ptr(O, torch.int32, "O"), _ptr(R, torch.float32, "R"),
                                _ptr(r_index, torch.int32, "r_index"),
                                _ptr(budget, torch.int32, "budget"),
-                               _ptr(r_class, torch.int32, "r_class"))
+                               _ptr(r_class, torch.int32, "r_class"), int(r_class_bound))
         res = gsearch_result(_ptr(out["best_cost"]), _ptr(out["best_s"]),
                              _ptr(out.get("final_row")), _ptr(out["best_instance"]))
         _check(self._lib.gsearch_solve_batch(self._ctx, ctypes.byref(prob), ctypes.byref(res),

@@ -91,7 +91,7 @@ __global__ void k_clear_status(int32_t *status) { *status = 0; }
 // ----------------------------------------------------------------------------------------
 // Transition classes.  The caller's r_class[S] promises that R depends on the strategies
 // only through contiguous classes.  Block 0 checks the partition itself (starts at 0, steps
-// of 0 or 1, at most kMaxClasses classes) and writes its run table; every block checks a
+// of 0 or 1, at most NC classes) and writes its run table; every block checks a
 // share of the table entries against their left and upper neighbours of the same class,
 // which together imply that R is constant on every (class, class) block.  A bad partition
 // is replaced by the single class {0..S-1} so that whatever reads the run table stays in
@@ -100,7 +100,7 @@ __global__ void k_clear_status(int32_t *status) { *status = 0; }
 __global__ __launch_bounds__(256) void k_prepare_classes(
     const int32_t *__restrict__ r_class, const float *__restrict__ Rt,
     int32_t *__restrict__ cmeta, int32_t *__restrict__ cstart, int32_t *__restrict__ cls,
-    int32_t *__restrict__ status, int S, int SP, int K) {
+    int32_t *__restrict__ status, int S, int SP, int K, int NC) {
   __shared__ int s_bad, s_maxlen;
   int bad = 0;
   if (blockIdx.x == 0) {
@@ -111,13 +111,13 @@ __global__ __launch_bounds__(256) void k_prepare_classes(
       const int c = r_class[i];
       const int prev = i ? r_class[i - 1] : 0;
       if (i == 0 ? c != 0 : (c != prev && c != prev + 1)) pbad = 1;
-      if (c < 0 || c >= kMaxClasses) pbad = 1;
+      if (c < 0 || c >= NC) pbad = 1;
     }
     if (pbad) atomicOr(&s_bad, 1);
     __syncthreads();
     const bool ok = s_bad == 0;
     const int nc = ok ? r_class[S - 1] + 1 : 1;
-    for (int c = threadIdx.x; c <= kMaxClasses; c += blockDim.x) cstart[c] = c == 0 ? 0 : S;
+    for (int c = threadIdx.x; c <= NC; c += blockDim.x) cstart[c] = c == 0 ? 0 : S;
     __syncthreads();
     for (int i = threadIdx.x; i < SP; i += blockDim.x) {
       const int c = (ok && i < S) ? r_class[i] : 0;
@@ -153,14 +153,14 @@ __global__ __launch_bounds__(256) void k_prepare_classes(
 __global__ __launch_bounds__(256) void k_build_Rc(const float *__restrict__ Rt,
                                                   const int32_t *__restrict__ cmeta,
                                                   const int32_t *__restrict__ cstart,
-                                                  float *__restrict__ Rc, int SP, int K) {
+                                                  float *__restrict__ Rc, int SP, int K, int NC) {
   const int nc = cmeta[0];
-  const long long total = (long long)K * kMaxClasses * kMaxClasses;
+  const long long total = (long long)K * NC * NC;
   for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
        x += (long long)gridDim.x * blockDim.x) {
-    const int ci = (int)(x % kMaxClasses);
-    const int cj = (int)((x / kMaxClasses) % kMaxClasses);
-    const long long k = x / (kMaxClasses * kMaxClasses);
+    const int ci = (int)(x % NC);
+    const int cj = (int)((x / NC) % NC);
+    const long long k = x / (NC * NC);
     float r = GS_INF;
     if (ci < nc && cj < nc) r = Rt[k * SP * SP + (size_t)cstart[cj] * SP + cstart[ci]];
     Rc[x] = r;
@@ -304,12 +304,9 @@ __global__ void k_final_global(const float *__restrict__ ws_cost, int32_t *__res
 
 // Backtrace over stored backpointers: one thread per requested instance walks
 //   s <- best_s; e <- E_b; for l = L-1 .. 1: plan[l] = s; s' = bp[l][e][s]; e -= O[l][s]; s = s'
-// BY_CLASS: the class kernel stores one backpointer per (target class, SOURCE row):
-//   bp[l][e][s] = bpc[l][class s][e - O[l][s]].  A state on an optimal path is finite, so its
-// source row exists and lies above the rows that hold +inf only.
-template <typename BPT, bool BY_CLASS>
+// (the form for more than 256 strategies, uint16 backpointers).
+template <typename BPT>
 __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__restrict__ Oq,
-                               const int32_t *__restrict__ cls,
                                const int32_t *__restrict__ budget,
                                const int32_t *__restrict__ ws_s,
                                const int32_t *__restrict__ instances, int n,
@@ -326,14 +323,11 @@ __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__rest
   }
   int e = budget[b];
   int used = 0;
-  const int cols = BY_CLASS ? kMaxClasses : S;
-  const size_t layer_stride = (size_t)B * cols * pitch;
+  const size_t layer_stride = (size_t)B * S * pitch;
   for (int l = L - 1; l >= 1; --l) {
     plan[(size_t)q * L + l] = s;
     const int o = Oq[((size_t)b * L + l) * SP + s];
-    const int col = BY_CLASS ? cls[s] : s;
-    const int at = BY_CLASS ? e - o : e;
-    const int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * cols + col) * pitch + at];
+    const int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * S + s) * pitch + e];
     used += o;
     e -= o;
     s = prev;
@@ -347,13 +341,16 @@ __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__rest
 // row of the current layer sits in registers, O[l][s] and the class of s are lane reads, and
 // the O row of the layer below is fetched while the backpointer load is in flight - one
 // memory round trip per layer instead of two.
+// BY_CLASS: the class kernel stores one backpointer per (target class, SOURCE row), NC
+// columns per instance: bp[l][e][s] = bpc[l][class s][e - O[l][s]].  A state on an optimal
+// path is finite, so its source row exists and lies above the rows that hold +inf only.
 template <bool BY_CLASS, int PL>
 __global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
     const uint8_t *__restrict__ bp, const int32_t *__restrict__ Oq,
     const int32_t *__restrict__ cls, const int32_t *__restrict__ budget,
     const int32_t *__restrict__ ws_s, const int32_t *__restrict__ instances, int n,
     int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP,
-    int pitch) {
+    int NC, int pitch) {
   const int q = blockIdx.x;
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
@@ -365,7 +362,7 @@ __global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
   }
   int e = budget[b];
   int used = 0;
-  const int cols = BY_CLASS ? kMaxClasses : S;
+  const int cols = BY_CLASS ? NC : S;
   const size_t layer_stride = (size_t)B * cols * pitch;
   const size_t tab = (size_t)b * L * SP;
   int ic[PL], cl[PL], o_cur[PL];
@@ -659,8 +656,8 @@ __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict
                          const int32_t *__restrict__ budget, const float *__restrict__ Tq,
                          const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
                          const int32_t *__restrict__ lowsum, float *__restrict__ C,
-                         int32_t *__restrict__ bpo, int B, int L, int S, int SP, int Sc, int M,
-                         int pitch) {
+                         int32_t *__restrict__ bpo, int B, int L, int S, int SP, int Sc, int NC,
+                         int M, int pitch) {
   const long long total = (long long)B * L * (M + 1) * S;
   const size_t layer_stride = (size_t)B * S * pitch;
   for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
@@ -692,8 +689,8 @@ __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict
           // rows below the least memory of the earlier layers hold +inf only, their
           // targets' backpointer is 0
           if (src >= 0 && src >= lowsum[(size_t)b * L + l - 1])
-            v = (int32_t)bp[(size_t)(l - 1) * B * kMaxClasses * pitch +
-                            ((size_t)b * kMaxClasses + cls[s]) * pitch + src];
+            v = (int32_t)bp[(size_t)(l - 1) * B * NC * pitch +
+                            ((size_t)b * NC + cls[s]) * pitch + src];
         } else {
           v = (int32_t)bp[(size_t)(l - 1) * layer_stride + off];
         }
@@ -983,10 +980,10 @@ void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Worksp
                             hipStream_t st) {
   const long long total = (long long)s.K * s.S * s.S;
   hipLaunchKernelGGL(k_prepare_classes, dim3(blocks_for(total, 256, 4096)), dim3(256), 0, st,
-                     r_class, w.Rt, w.cmeta, w.cstart, w.cls, w.status, s.S, s.SP, s.K);
-  const long long nrc = (long long)s.K * kMaxClasses * kMaxClasses;
+                     r_class, w.Rt, w.cmeta, w.cstart, w.cls, w.status, s.S, s.SP, s.K, s.NC);
+  const long long nrc = (long long)s.K * s.NC * s.NC;
   hipLaunchKernelGGL(k_build_Rc, dim3(blocks_for(nrc, 256, 4096)), dim3(256), 0, st, w.Rt,
-                     w.cmeta, w.cstart, w.Rc, s.SP, s.K);
+                     w.cmeta, w.cstart, w.Rc, s.SP, s.K, s.NC);
 }
 
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
@@ -1022,7 +1019,7 @@ static void launch_backtrace_bp_rows(const Shape &s, const Workspace &w, const i
 #define GS_ROWS(PL)                                                                          \
   hipLaunchKernelGGL((k_backtrace_bp_rows<BY_CLASS, PL>), grid, block, 0, st,               \
                      (const uint8_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n,  \
-                     plan, mem_used, s.B, s.L, s.S, s.SP, s.pitch)
+                     plan, mem_used, s.B, s.L, s.S, s.SP, s.NC, s.pitch)
   if (s.S <= 64) GS_ROWS(1);
   else if (s.S <= 128) GS_ROWS(2);
   else GS_ROWS(4);
@@ -1036,9 +1033,9 @@ void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *inst
     else launch_backtrace_bp_rows<false>(s, w, instances, n, plan, mem_used, st);
     return;
   }
-  hipLaunchKernelGGL((k_backtrace_bp<uint16_t, false>), dim3((n + 63) / 64), dim3(64), 0, st,
-                     (const uint16_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n, plan,
-                     mem_used, s.B, s.L, s.S, s.SP, s.pitch);
+  hipLaunchKernelGGL((k_backtrace_bp<uint16_t>), dim3((n + 63) / 64), dim3(64), 0, st,
+                     (const uint16_t *)w.bp, w.Oq, w.budget, w.best_s, instances, n, plan, mem_used,
+                     s.B, s.L, s.S, s.SP, s.pitch);
 }
 
 template <bool BY_CLASS>
@@ -1093,15 +1090,15 @@ void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hi
   if (w.by_class)
     hipLaunchKernelGGL((k_export<uint8_t, true>), grid, block, 0, st, w.planes,
                        (const uint8_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
-                       s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
+                       s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
   else if (s.bp16)
     hipLaunchKernelGGL((k_export<uint16_t, false>), grid, block, 0, st, w.planes,
                        (const uint16_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp,
-                       s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
+                       s.B, s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
   else
     hipLaunchKernelGGL((k_export<uint8_t, false>), grid, block, 0, st, w.planes,
                        (const uint8_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
-                       s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
+                       s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
 }
 
 void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,

@@ -534,7 +534,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
 // Rows above E - min_s O[l][s] have no target within the budget and are neither computed
 // nor read by anyone; tiles wholly below the least memory of layers 0..l-1 hold +inf.
 // ---------------------------------------------------------------------------------------
-template <int SP, int NW, bool WITH_BP>
+template <int SP, int NW, bool WITH_BP, int NC>
 __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     const float *__restrict__ qsrc, float *__restrict__ qdst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
     const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
     int l, int pitch) {
-  constexpr int NC = kMaxClasses;
+  // NC: class capacity (32 or 64): registers for the class minima, rows of the class table
   constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
   extern __shared__ float lds[];
   float *cmin = lds;                    // [NC][64]  class minima of the tile
@@ -638,15 +638,16 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
 
   for (int cj = js; cj < nc; cj += NW) {
     const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
-    const float16_t r0 = *reinterpret_cast<const float16_t *>(rc);
-    const float16_t r1 = *reinterpret_cast<const float16_t *>(rc + 16);
+    float16_t rv[NC / 16];
+#pragma unroll
+    for (int x = 0; x < NC / 16; ++x) rv[x] = *reinterpret_cast<const float16_t *>(rc + 16 * x);
     // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
     float m = GS_INF;
     int g = 0;
 #pragma unroll
     for (int q = 0; q < NC / 8; ++q) {
       if (8 * q < nc) {
-        const float16_t r = q < 2 ? r0 : r1;
+        const float16_t r = rv[q >> 1];
         const int h = (q & 1) * 8;
         float cm = __builtin_fminf(cmv[8 * q] + r[h], cmv[8 * q + 1] + r[h + 1]);
 #pragma unroll
@@ -978,21 +979,36 @@ bool class_path_applies(const Shape &s) {
          (size_t)class_rows(s) * s.pitch * 4 < ((size_t)1 << 31) && (s.M + kWave) / kWave <= 65535;
 }
 
-template <int SP, int NW>
-static void launch_class_nw(const Shape &s, const Workspace &w, int l, const float *src,
+template <int SP, int NW, int NC>
+static void launch_class_nc(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st) {
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)s.B, (unsigned)tiles), block(NW * kWave);
-  const size_t lds = sizeof(float) * ((bp_l ? (SP + 3) * kWave : 0) + kMaxClasses * kWave +
-                                      kMaxClasses * kMaxClasses + kMaxClasses + 32);
+  const size_t lds = sizeof(float) * ((bp_l ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
+  if (lds > 64 * 1024) { // only the wide form at 128 strategies with backpointers: opt in once
+    static const hipError_t optin =
+        hipFuncSetAttribute((const void *)k_dp_class<SP, NW, true, NC>,
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)optin;
+  }
   if (bp_l)
-    hipLaunchKernelGGL((k_dp_class<SP, NW, true>), grid, block, lds, st, src, dst, (uint8_t *)bp_l,
-                       w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
-                       w.lowsum, s.B, s.L, class_rows(s), l, s.pitch);
+    hipLaunchKernelGGL((k_dp_class<SP, NW, true, NC>), grid, block, lds, st, src, dst,
+                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch);
   else
-    hipLaunchKernelGGL((k_dp_class<SP, NW, false>), grid, block, lds, st, src, dst,
+    hipLaunchKernelGGL((k_dp_class<SP, NW, false, NC>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
                        w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch);
+}
+
+template <int SP, int NW>
+static void launch_class_nw(const Shape &s, const Workspace &w, int l, const float *src,
+                            float *dst, void *bp_l, hipStream_t st) {
+  // more than 32 classes need more than 32 strategies: the wide variant exists from 48 up
+  if constexpr (SP >= 48) {
+    if (s.NC > 32) return launch_class_nc<SP, NW, 64>(s, w, l, src, dst, bp_l, st);
+  }
+  launch_class_nc<SP, NW, 32>(s, w, l, src, dst, bp_l, st);
 }
 
 template <int SP>

@@ -25,6 +25,7 @@ gs::Shape make_shape(int B, int L, int S, int M, int K) {
   s.pitch = (int)align_up((size_t)M + 1, 64);
   s.bp16 = S > 256;
   s.Bc = B;
+  s.NC = 32;
   return s;
 }
 
@@ -47,8 +48,8 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.planes = take(sizeof(float) * (gs::plane_elems(s) * (size_t)y.nplanes +
                                    (size_t)s.SP * s.pitch));
   const bool want_bp = !(flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
-  // (the class kernel stores kMaxClasses columns per instance instead of S)
-  const size_t bp_cols = s.S > gs::kMaxClasses ? s.S : gs::kMaxClasses;
+  // (the class kernel stores one column per class, 32 or 64 per instance, instead of S)
+  const size_t bp_cols = s.S > gs::kMaxClasses ? s.S : (s.S > 32 ? gs::kMaxClasses : 32);
   y.bp = take(want_bp ? (size_t)s.B * bp_cols * s.pitch * (size_t)(s.L - 1) * (s.bp16 ? 2 : 1) : 0);
   y.Tq = take(sizeof(float) * (size_t)s.B * s.L * s.SP);
   y.Oq = take(sizeof(int32_t) * (size_t)s.B * s.L * s.SP);
@@ -252,7 +253,9 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   if (!scope.ok) return GSEARCH_ERR_HIP;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  const gs::Shape s = make_shape(p->B, p->L, p->S, p->M, p->K);
+  gs::Shape s = make_shape(p->B, p->L, p->S, p->M, p->K);
+  // class capacity of this solve: the wide form only when the caller announces it
+  if (p->r_class && p->r_class_bound > 32 && p->S > 32) s.NC = gs::kMaxClasses;
   const Layout y = make_layout(s, c.flags);
   if (y.total > ctx->bytes) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
@@ -298,7 +301,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   w.by_class = use_classes;
   size_t bp_inst_bytes = (size_t)s.S * s.pitch * (s.bp16 ? 2 : 1); // one instance, one layer
   if (use_classes) {
-    bp_inst_bytes = (size_t)gs::kMaxClasses * s.pitch;
+    bp_inst_bytes = (size_t)s.NC * s.pitch;
     bp_layer_bytes = (size_t)s.B * bp_inst_bytes;
   }
   ctx->ws = w;

@@ -10,7 +10,8 @@ namespace gs {
 
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kRowsPerBlock = 256; // budget rows handled by one workgroup (4 waves)
-constexpr int kMaxClasses = 32;    // transition classes the class kernel keeps in registers
+constexpr int kMaxClasses = 64;    // most transition classes a solve can exploit (capacity of the
+                                   // class kernel's wide variant; the narrow one holds 32)
 
 // Shape of the batch being solved plus the padded pitches of the workspace copies.
 struct Shape {
@@ -20,6 +21,9 @@ struct Shape {
   int bp16;  // backpointers are uint16 (S > 256) instead of uint8
   int Bc;    // instances in flight at the same time (>= B when this shape is one group of
              // a batch whose groups run on parallel streams); launch heuristics only
+  int NC;    // class capacity of this solve (32, or 64 when the caller announces more than 32
+             // classes): row stride of Rc, columns of the per-class backpointers, cap of the
+             // compact planes' rows
 };
 
 // Device pointers into the context's workspace.
@@ -28,7 +32,7 @@ struct Workspace {
                      // class-kernel solve every slot holds the compact plane
                      // [B][class_rows][pitch] of its layer at its head instead
   void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null);
-                     // after a class-kernel solve [L-1][B][kMaxClasses][pitch] uint8 indexed by
+                     // after a class-kernel solve [L-1][B][NC][pitch] uint8 indexed by
                      // (target class, SOURCE row), see by_class
   int by_class;      // 1: the class kernel ran.  Planes are compact, C[l][e][s] =
                      // Q[l][class s][e - O[l][s]] + T[l][s] with Q[0] = 0, and bp[l][e][sj] =
@@ -47,15 +51,15 @@ struct Workspace {
   int32_t *status;   // [1]          data-status bits
   // Transition classes (only meaningful when the caller gave r_class):
   int32_t *cmeta;    // [2]          number of classes, longest class
-  int32_t *cstart;   // [kMaxClasses+1]  first strategy of class c; S for c >= number of classes
+  int32_t *cstart;   // [NC+1]  first strategy of class c; S for c >= number of classes
   int32_t *cls;      // [SP]         class of strategy s (0 for the padding)
-  float *Rc;         // [K][kMaxClasses][kMaxClasses]  Rc[k][cj][ci] = R between the classes'
+  float *Rc;         // [K][NC][NC]  Rc[k][cj][ci] = R between the classes'
                      //              first strategies, +inf for padding classes
 };
 
 inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; }
 // Compact planes of the class kernel: one row per transition class instead of per strategy.
-inline int class_rows(const Shape &s) { return s.S < kMaxClasses ? s.S : kMaxClasses; }
+inline int class_rows(const Shape &s) { return s.S < s.NC ? s.S : s.NC; }
 
 // ---- launchers (all asynchronous on `st`) -------------------------------------------
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,

@@ -32,7 +32,8 @@ class DeviceWorkload:
         self.desc = None
         # Set-up, once per workload: how many layout classes the strategy set has.  A solve
         # can exploit at most GSEARCH_MAX_CLASSES of them and would flag a longer list, so
-        # run_step hands the classes over only when they fit.
+        # run_step hands the classes over only when they fit, and announces their number
+        # (above 32 the solve needs the wide form of the class kernel).
         self.n_class = None
         if w.kind == "model":
             desc, _ = binding.gsearch_enumerate(device=self.device, **w.enum)
@@ -45,7 +46,7 @@ def make_context(w: Workload, flags=0, device=0) -> binding.GSearch:
 
 
 def run_step(ctx: binding.GSearch, dw: DeviceWorkload, backtrace="best", stream=None,
-             classes=True, r_class=None):
+             classes=True, r_class=None, r_class_bound=0):
     """One pass of the hot path.  Returns device tensors; nothing is synchronised here.
 
     Model workloads build R from the strategy layouts, so the layout classes of the
@@ -59,11 +60,13 @@ def run_step(ctx: binding.GSearch, dw: DeviceWorkload, backtrace="best", stream=
         out.update(desc=desc, count=count, T=T, O=O, R=R)
         if classes and r_class is None and dw.n_class <= binding.GSEARCH_MAX_CLASSES:
             r_class, n_class = binding.gsearch_layout_classes(desc, stream=stream)
+            r_class_bound = dw.n_class
             out.update(r_class=r_class, n_class=n_class)
     else:
         T, O, R = dw.T, dw.O, dw.R
     res = ctx.gsearch_solve_batch(T, O, R, dw.r_index, dw.budget, w.M, stream=stream,
-                                  r_class=r_class if classes else None)
+                                  r_class=r_class if classes else None,
+                                  r_class_bound=r_class_bound)
     out.update(res)
     if backtrace == "best":
         out.update(ctx.gsearch_backtrace(res["best_instance"], 1, stream=stream))
@@ -78,15 +81,20 @@ def to_numpy(out: dict) -> dict:
     return {k: (v.cpu().numpy() if v is not None else None) for k, v in out.items()}
 
 
-def solve_workload(w: Workload, flags=0, backtrace="all", classes=True, r_class=None) -> dict:
+def solve_workload(w: Workload, flags=0, backtrace="all", classes=True, r_class=None,
+                   r_class_bound=None) -> dict:
     """Convenience: upload, run one step, download everything as numpy.  r_class: optional
-    numpy int32 [S] for table workloads."""
+    numpy int32 [S] for table workloads (its class count is announced unless r_class_bound
+    says otherwise)."""
     import torch
     dw = DeviceWorkload(w)
     if r_class is not None:
+        if r_class_bound is None:
+            r_class_bound = int(np.max(r_class)) + 1
         r_class = torch.from_numpy(np.ascontiguousarray(r_class, np.int32)).to(dw.device)
     with make_context(w, flags=flags) as ctx:
-        out = to_numpy(run_step(ctx, dw, backtrace=backtrace, classes=classes, r_class=r_class))
+        out = to_numpy(run_step(ctx, dw, backtrace=backtrace, classes=classes, r_class=r_class,
+                                r_class_bound=r_class_bound or 0))
         out["data_status"] = ctx.gsearch_data_status()
         out["forward_kernel"] = ctx.gsearch_forward_kernel()
     return out

@@ -104,10 +104,12 @@ def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.gsearch_layout_classes(dummy, 0, dummy, None, None) == b.GSEARCH_ERR_INVALID_ARG
     assert lib.gsearch_layout_classes(dummy, 1025, dummy, None, None) == b.GSEARCH_ERR_INVALID_ARG
     assert lib.gsearch_forward_kernel(None) == b""
-    # the problem struct carries the optional class promise as its last field
-    assert [f[0] for f in b.gsearch_problem._fields_][-1] == "r_class"
+    # the problem struct carries the optional class promise as its last two fields
+    assert [f[0] for f in b.gsearch_problem._fields_][-2:] == ["r_class", "r_class_bound"]
     header = open(os.path.join(ROOT, "include", "gsearch.h")).read()
-    assert "const int32_t *r_class;" in header
+    assert "const int32_t *r_class;" in header and "int32_t r_class_bound;" in header
+    assert b.GSEARCH_DEFAULT_CLASSES == int(re.search(r"#define GSEARCH_DEFAULT_CLASSES (\d+)",
+                                                      header).group(1))
     assert b.GSEARCH_MAX_CLASSES == int(re.search(r"#define GSEARCH_MAX_CLASSES (\d+)", header).group(1))
     assert b.GSEARCH_DATA_BAD_RCLASS == int(re.search(r"#define GSEARCH_DATA_BAD_RCLASS (0x[0-9a-f]+)",
                                                      header).group(1), 16)

@@ -477,6 +477,10 @@ CLASS_CASES = [
     (64, [2] * 32, 1, 129, False), (96, [4, 4, 4, 4, 4, 4, 2] * 3 + [4, 4, 4, 2, 4], 1, 260, True),
     (100, [25, 25, 25, 25], 2, 100, True), (128, [4] * 32, 1, 70, False),
     (13, [6, 7], 1, 140, True),
+    # more than 32 classes: the wide form of the class kernel (announced through r_class_bound)
+    (44, [1] * 44, 1, 150, True), (64, [1] * 64, 2, 129, False), (96, [2] * 48, 1, 200, True),
+    (128, [2] * 64, 1, 100, True), (100, [1] * 30 + [7] * 10, 1, 130, True),
+    (128, [5, 1, 3] * 11 + [29], 3, 90, False),
 ]
 
 
@@ -497,7 +501,7 @@ def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode):
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
     with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
-        out = runner.run_step(ctx, dw, backtrace="all", r_class=rc)
+        out = runner.run_step(ctx, dw, backtrace="all", r_class=rc, r_class_bound=len(sizes))
         C, bp = ctx.gsearch_export_planes(want_bp=(mode == "bp"))
         got = runner.to_numpy(out)
         got["data_status"] = ctx.gsearch_data_status()
@@ -540,8 +544,8 @@ def test_class_kernel_with_instance_groups_and_single_layer(gs, oracle_mod):
 
 
 def _random_partition(rng, S):
-    """Random contiguous partition of S strategies into at most 32 classes."""
-    nc = 1 + int(rng.randint(0, min(31, S - 1), 1)[0])
+    """Random contiguous partition of S strategies into at most 64 classes."""
+    nc = 1 + int(rng.randint(0, min(63, S - 1), 1)[0])
     cuts = sorted(set(int(x) for x in rng.randint(1, max(1, S - 1), nc - 1))) if nc > 1 else []
     edges = [0] + [c for c in cuts if 0 < c < S] + [S]
     edges = sorted(set(edges))
@@ -571,20 +575,21 @@ def _class_sweep_case(runner, oracle_mod, rng, case):
     with runner.make_context(w, flags=flags) as ctx:
         if case % 6 == 5:
             ctx.gsearch_set_instance_groups(1 + case % 3)
-        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc,
+                                              r_class_bound=len(sizes)))
         got["data_status"] = ctx.gsearch_data_status()
         assert ctx.gsearch_forward_kernel() == "k_dp_class", (case, S)
     assert_same(got, ref, w, f"class sweep {case} S={S} sizes={sizes} flags={flags}")
 
 
 def test_class_kernel_random_sweep(gs, oracle_mod):
-    """Forty seeded random class-structured workloads: strategy counts around every
-    register-tile size, random partitions of 1..32 classes, several matrices, ragged budgets,
+    """Sixty seeded random class-structured workloads: strategy counts around every
+    register-tile size, random partitions of 1..64 classes, several matrices, ragged budgets,
     zero-memory and never-fitting strategies, forbidden class transitions, coarse values that
     make sums collide, both modes, forced instance groups."""
     _, runner = gs
     rng = workloads.SplitMix64(777)
-    for case in range(40):
+    for case in range(60):
         _class_sweep_case(runner, oracle_mod, rng, case)
 
 
@@ -625,14 +630,19 @@ def test_bad_transition_classes_are_flagged(gs):
     c = r_class.copy(); c[3] = -2
     cases["negative"] = (w, c)
     w40, _ = workloads.class_tables("many", 2, 3, 40, 60, [1] * 40, seed=6)
-    cases["too_many"] = (w40, np.arange(40, dtype=np.int32))
+    cases["more_than_announced"] = (w40, np.arange(40, dtype=np.int32), 32)
+    w80, _ = workloads.class_tables("toomany", 2, 3, 80, 60, [1] * 80, seed=7)
+    cases["too_many"] = (w80, np.arange(80, dtype=np.int32), 80)
     import copy
     w2 = copy.deepcopy(w); w2.R = w.R.copy(); w2.R[0, 1, 9] += np.float32(0.5)   # row differs inside class 0
     cases["row"] = (w2, r_class)
     w3 = copy.deepcopy(w); w3.R = w.R.copy(); w3.R[0, 9, 2] += np.float32(0.5)   # column differs
     cases["column"] = (w3, r_class)
-    for name, (ww, cc) in cases.items():
-        got = runner.solve_workload(ww, r_class=cc)
+    ok40 = runner.solve_workload(w40, r_class=np.arange(40, dtype=np.int32))   # announced: fine
+    assert ok40["data_status"] == 0 and ok40["forward_kernel"] == "k_dp_class"
+    for name, case in cases.items():
+        ww, cc = case[0], case[1]
+        got = runner.solve_workload(ww, r_class=cc, r_class_bound=case[2] if len(case) > 2 else None)
         assert got["data_status"] & binding.GSEARCH_DATA_BAD_RCLASS, name
         assert np.isinf(got["best_cost"]).all() and (got["best_s"] == -1).all(), name
         assert int(got["best_instance"][0]) == -1, name
@@ -704,10 +714,12 @@ def test_a_whole_step_can_be_captured_in_a_hip_graph_and_replayed(gs, oracle_mod
             assert_same(got, ref, w, "graph replay")
 
 
-def test_strategy_set_with_more_layouts_than_the_class_limit(gs, oracle_mod):
-    """128 devices without caps: 128 strategies in 36 layout classes, more than a solve can
-    exploit.  The runner then withholds the classes and the general kernels run; handing the
-    classes over regardless is flagged, not silently wrong."""
+def test_strategy_sets_with_more_than_32_layouts(gs, oracle_mod):
+    """128 devices without caps: 128 strategies in 36 layout classes, which the runner
+    announces, so the wide form of the class kernel runs; the same classes handed over
+    without the announcement are flagged, not silently wrong.  1024 devices: 242 strategies in
+    66 classes, more than a solve can exploit: the runner withholds them and the general
+    kernels run."""
     binding, runner = gs
     import torch
     w = workloads._model_workload("n128", 2, 5, 700, dict(N=128), [8192.0], [4096.0], 262144.0,
@@ -717,15 +729,31 @@ def test_strategy_set_with_more_layouts_than_the_class_limit(gs, oracle_mod):
     T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
     ref = oracle_batch(oracle_mod, w, T, O, R)
     dw = runner.DeviceWorkload(w)
-    assert dw.n_class == 36 > binding.GSEARCH_MAX_CLASSES
+    assert dw.n_class == 36
+    for flags in (0, binding.GSEARCH_FLAG_NO_BACKPOINTERS):
+        with runner.make_context(w, flags=flags) as ctx:
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+            assert_same(got, ref, w, f"36 classes, wide class kernel, flags={flags}")
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=False))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() != "k_dp_class"
+            assert_same(got, ref, w, f"36 classes withheld, flags={flags}")
+            r_class, _ = binding.gsearch_layout_classes(torch.from_numpy(desc).to(dw.device))
+            runner.run_step(ctx, dw, backtrace=None, r_class=r_class)       # bound not announced
+            assert ctx.gsearch_data_status() & binding.GSEARCH_DATA_BAD_RCLASS
+    w = workloads._model_workload("n1024", 1, 3, 300, dict(N=1024), [8192.0], [4096.0], 262144.0,
+                                  80.0e9, seed=78, S=242)
+    desc = oracle_mod.enumerate_strategies(**w.enum)
+    T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
+    dw = runner.DeviceWorkload(w)
+    assert len(desc) == 242 and dw.n_class == 66 > binding.GSEARCH_MAX_CLASSES
     with runner.make_context(w) as ctx:
         got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
         got["data_status"] = ctx.gsearch_data_status()
         assert ctx.gsearch_forward_kernel() != "k_dp_class" and "r_class" not in got
-        assert_same(got, ref, w, "36 classes, general kernels")
-        r_class, _ = binding.gsearch_layout_classes(torch.from_numpy(desc).to(dw.device))
-        runner.run_step(ctx, dw, backtrace=None, r_class=r_class)
-        assert ctx.gsearch_data_status() & binding.GSEARCH_DATA_BAD_RCLASS
+        assert_same(got, oracle_batch(oracle_mod, w, T, O, R), w, "66 classes, general kernels")
 
 
 @pytest.mark.parametrize("mode", ["bp", "nobp"])
