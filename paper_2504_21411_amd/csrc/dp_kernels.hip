@@ -864,6 +864,15 @@ int tuned_sp_for(int S) {
   return 0;
 }
 
+// The class kernel keeps only its own share of the strategies per wave, so it also exists
+// for 192 and 256 padded strategies (129..256 strategies: the paper's strategy space on 256
+// and 512 devices), where the general path is left with the pull-form fallback.
+int class_sp_for(int S) {
+  const int t = tuned_sp_for(S);
+  if (t) return t;
+  return S <= 192 ? 192 : (S <= 256 ? 256 : 0);
+}
+
 // Launch shape of the register-tiled kernel.  Work is cut into (64-row tile) x (slice of
 // target strategies) pieces, one per wave; slicing the strategies costs a repeated load
 // of the tile's source values but multiplies the number of waves, which is what hides
@@ -972,7 +981,7 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
 }
 
 bool class_path_applies(const Shape &s) {
-  const int tsp = tuned_sp_for(s.S);
+  const int tsp = class_sp_for(s.S);
   // the kernel addresses an instance's plane with 32-bit element offsets
   // and runs on a (instances, tiles) grid
   return tsp >= 16 && tsp == s.SP && !s.bp16 && (size_t)s.S * s.pitch < ((size_t)1 << 31) &&
@@ -1026,10 +1035,14 @@ static void launch_class(const Shape &s, const Workspace &w, int l, const float 
     else if (bp_l) waves = SP >= 64 ? 8 : 4;
     else waves = SP >= 128 ? 8 : (SP <= 32 && tile_inst >= 16384 ? 2 : 4);
   }
-  if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
-  else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
-  else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
-  else launch_class_nw<SP, 1>(s, w, l, src, dst, bp_l, st);
+  if constexpr (SP > 128) { // a wave's share of the strategies has to stay in registers
+    launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
+  } else {
+    if (waves >= 8) launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
+    else if (waves >= 4) launch_class_nw<SP, 4>(s, w, l, src, dst, bp_l, st);
+    else if (waves >= 2) launch_class_nw<SP, 2>(s, w, l, src, dst, bp_l, st);
+    else launch_class_nw<SP, 1>(s, w, l, src, dst, bp_l, st);
+  }
 }
 
 const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
@@ -1042,6 +1055,8 @@ const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const flo
     case 64: launch_class<64>(s, w, l, src, dst, bp_l, st); break;
     case 96: launch_class<96>(s, w, l, src, dst, bp_l, st); break;
     case 128: launch_class<128>(s, w, l, src, dst, bp_l, st); break;
+    case 192: launch_class<192>(s, w, l, src, dst, bp_l, st); break;
+    case 256: launch_class<256>(s, w, l, src, dst, bp_l, st); break;
     default: break; // class_path_applies() admits no other pitch
   }
   return "k_dp_class";

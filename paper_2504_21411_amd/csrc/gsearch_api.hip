@@ -20,7 +20,7 @@ struct Layout {
 gs::Shape make_shape(int B, int L, int S, int M, int K) {
   gs::Shape s;
   s.B = B; s.L = L; s.S = S; s.M = M; s.K = K;
-  const int tsp = gs::tuned_sp_for(S);
+  const int tsp = gs::class_sp_for(S);
   s.SP = tsp ? tsp : (int)align_up((size_t)S, 8);
   s.pitch = (int)align_up((size_t)M + 1, 64);
   s.bp16 = S > 256;

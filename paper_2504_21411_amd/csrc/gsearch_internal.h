@@ -116,5 +116,6 @@ void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,
 
 // Register-tiled forward kernels exist for these padded strategy counts.
 int tuned_sp_for(int S); // smallest supported SP >= S, or 0 if S is too large
+int class_sp_for(int S); // the same for the class kernel, which also has 192 and 256
 
 } // namespace gs

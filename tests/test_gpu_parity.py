@@ -481,6 +481,9 @@ CLASS_CASES = [
     (44, [1] * 44, 1, 150, True), (64, [1] * 64, 2, 129, False), (96, [2] * 48, 1, 200, True),
     (128, [2] * 64, 1, 100, True), (100, [1] * 30 + [7] * 10, 1, 130, True),
     (128, [5, 1, 3] * 11 + [29], 3, 90, False),
+    # 129..256 strategies: only the class kernel has a register-tiled form there
+    (162, [4] * 36 + [2] * 9, 1, 120, True), (192, [6] * 32, 2, 100, False),
+    (200, [4] * 50, 1, 90, True), (256, [4] * 64, 1, 70, True), (130, [2] * 63 + [4], 1, 80, False),
 ]
 
 
@@ -555,7 +558,8 @@ def _random_partition(rng, S):
 def _class_sweep_case(runner, oracle_mod, rng, case):
     import torch
     v = rng.randint(0, 10 ** 6, 10)
-    S = [9, 12, 16, 17, 24, 31, 32, 33, 44, 48, 49, 64, 65, 96, 100, 128][int(v[0]) % 16]
+    S = [9, 12, 16, 17, 24, 31, 32, 33, 44, 48, 49, 64, 65, 96, 100, 128, 129, 162, 192,
+         256][int(v[0]) % 20]
     B, L, M, K = 1 + int(v[1]) % 5, 2 + int(v[2]) % 5, 1 + int(v[3]) % 600, 1 + int(v[4]) % 3
     sizes = _random_partition(rng, S)
     budget = rng.randint(0, M, B).astype(np.int32)
@@ -717,7 +721,9 @@ def test_a_whole_step_can_be_captured_in_a_hip_graph_and_replayed(gs, oracle_mod
 def test_strategy_sets_with_more_than_32_layouts(gs, oracle_mod):
     """128 devices without caps: 128 strategies in 36 layout classes, which the runner
     announces, so the wide form of the class kernel runs; the same classes handed over
-    without the announcement are flagged, not silently wrong.  1024 devices: 242 strategies in
+    without the announcement are flagged, not silently wrong.  256 devices: 162 strategies in
+    45 classes, beyond the general kernels' register-tiled sizes but not the class kernel's.
+    1024 devices: 242 strategies in
     66 classes, more than a solve can exploit: the runner withholds them and the general
     kernels run."""
     binding, runner = gs
@@ -743,6 +749,17 @@ def test_strategy_sets_with_more_than_32_layouts(gs, oracle_mod):
             r_class, _ = binding.gsearch_layout_classes(torch.from_numpy(desc).to(dw.device))
             runner.run_step(ctx, dw, backtrace=None, r_class=r_class)       # bound not announced
             assert ctx.gsearch_data_status() & binding.GSEARCH_DATA_BAD_RCLASS
+    w = workloads._model_workload("n256", 2, 4, 400, dict(N=256), [8192.0], [4096.0], 262144.0,
+                                  80.0e9, seed=79, S=162)
+    desc = oracle_mod.enumerate_strategies(**w.enum)
+    T, O, R = oracle_mod.build_tables(desc, w.layer, w.hw, w.rmodel, w.M)
+    dw = runner.DeviceWorkload(w)
+    assert len(desc) == 162 and dw.n_class == 45
+    with runner.make_context(w) as ctx:
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+        got["data_status"] = ctx.gsearch_data_status()
+        assert ctx.gsearch_forward_kernel() == "k_dp_class"
+        assert_same(got, oracle_batch(oracle_mod, w, T, O, R), w, "256 devices, 45 classes")
     w = workloads._model_workload("n1024", 1, 3, 300, dict(N=1024), [8192.0], [4096.0], 262144.0,
                                   80.0e9, seed=78, S=242)
     desc = oracle_mod.enumerate_strategies(**w.enum)
