@@ -247,6 +247,7 @@ __global__ void k_final_instance(const float *__restrict__ last,
                                  const int32_t *__restrict__ budget,
                                  const int32_t *__restrict__ status, const float *__restrict__ Tq,
                                  const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+                                 const int32_t *__restrict__ lowsum,
                                  float *__restrict__ ws_cost, int32_t *__restrict__ ws_s,
                                  float *__restrict__ best_cost, int32_t *__restrict__ best_s,
                                  float *__restrict__ final_row, int B, int L, int S, int SP, int Sc,
@@ -256,6 +257,8 @@ __global__ void k_final_instance(const float *__restrict__ last,
   const int E = budget[b];
   const bool poisoned = *status != 0;
   const size_t tab = ((size_t)b * L + L - 1) * SP;
+  // rows of the compact plane below the least memory of the earlier layers are +inf and not stored
+  const int ql = (BY_CLASS && L > 1) ? lowsum[(size_t)b * L + L - 2] : 0;
   float m = GS_INF;
   int arg = 0x7fffffff;
   for (int s = lane; s < S; s += kWave) {
@@ -263,7 +266,7 @@ __global__ void k_final_instance(const float *__restrict__ last,
     if (BY_CLASS) {
       const int d = E - Oq[tab + s];
       v = GS_INF;
-      if (d >= 0) v = last[((size_t)b * Sc + cls[s]) * pitch + d] + Tq[tab + s];
+      if (d >= ql) v = last[((size_t)b * Sc + cls[s]) * pitch + d] + Tq[tab + s];
     } else {
       v = last[((size_t)b * S + s) * pitch + E];
     }
@@ -418,6 +421,7 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
                                    const float *__restrict__ Rt, const float *__restrict__ Tq,
                                    const int32_t *__restrict__ Oq,
                                    const int32_t *__restrict__ cls,
+                                   const int32_t *__restrict__ lowsum,
                                    const int32_t *__restrict__ ridx,
                                    const int32_t *__restrict__ budget,
                                    const int32_t *__restrict__ ws_s,
@@ -445,6 +449,9 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
     const float *prevp = planes + (size_t)(l - 1) * layer_stride + inst;
     const float *rc = Rt + ((size_t)ridx[(size_t)b * L + l] * SP + s) * SP;
     const size_t prow = ((size_t)b * L + l - 1) * SP; // the previous layer's O and T rows
+    // rows of the compact plane of layer l-1 below the least memory of layers 0..l-2 are
+    // +inf and not stored
+    const int ql = (BY_CLASS && l >= 2) ? lowsum[(size_t)b * L + l - 2] : 0;
     float m = GS_INF;
     int arg = 0x7fffffff;
     for (int i = lane; i < S; i += kWave) {
@@ -452,7 +459,7 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
       if (BY_CLASS) {
         const int d = e - Oq[prow + i];
         c = GS_INF;
-        if (d >= 0) c = prevp[(size_t)cls[i] * pitch + d] + Tq[prow + i];
+        if (d >= ql) c = prevp[(size_t)cls[i] * pitch + d] + Tq[prow + i];
       } else {
         c = prevp[(size_t)i * pitch + e];
       }
@@ -479,10 +486,10 @@ template <bool BY_CLASS, int PL>
 __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     const float *__restrict__ planes, const float *__restrict__ Rt, const float *__restrict__ Tq,
     const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
-    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ ws_s, const int32_t *__restrict__ instances, int n,
-    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP, int Sc,
-    int M, int pitch) {
+    const int32_t *__restrict__ lowsum, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ ws_s,
+    const int32_t *__restrict__ instances, int n, int32_t *__restrict__ plan,
+    int32_t *__restrict__ mem_used, int B, int L, int S, int SP, int Sc, int M, int pitch) {
   const int q = blockIdx.x;
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
@@ -517,6 +524,9 @@ __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     t_low[u] = Tq[tab + (size_t)lb * SP + ic[u]];
   }
   int k = L > 1 ? ridx[(size_t)b * L + L - 1] : 0;
+  // rows of the compact plane of layer l-1 below the least memory of layers 0..l-2 are +inf
+  // and not stored: ql for the current step, fetched a step ahead like the other rows
+  int ql = (BY_CLASS && L > 2) ? lowsum[(size_t)b * L + L - 3] : 0;
   for (int l = L - 1; l >= 1; --l) {
     if (lane == 0) plan[(size_t)q * L + l] = s;
     int o = 0;
@@ -531,6 +541,8 @@ __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     int o_nxt[PL];
     float t_nxt[PL];
     const int l2 = l >= 2 ? l - 2 : 0;
+    int ql_nxt = BY_CLASS ? lowsum[(size_t)b * L + (l >= 3 ? l - 3 : 0)] : 0;
+    ql_nxt = l >= 3 ? ql_nxt : 0;
 #pragma unroll
     for (int u = 0; u < PL; ++u) {
       o_nxt[u] = Oq[tab + (size_t)l2 * SP + ic[u]];
@@ -563,13 +575,14 @@ __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     for (int u = 0; u < PL; ++u) {
       const int i = lane + kWave * u;
       float c = BY_CLASS ? craw[u] + t_low[u] : craw[u];
-      c = (i < S && dd[u] >= 0) ? c : GS_INF;
+      c = (i < S && dd[u] >= ql) ? c : GS_INF;
       const float v = c + rraw[u];
       if (u == 0 || v < m) { m = v; arg = i; }
     }
     wave_argmin(m, arg);
     s = arg;
     k = k_nxt;
+    ql = ql_nxt;
 #pragma unroll
     for (int u = 0; u < PL; ++u) {
       const int i = lane + kWave * u;
@@ -626,12 +639,13 @@ template <bool BY_CLASS>
 __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__restrict__ budget,
                                const int32_t *__restrict__ status, const float *__restrict__ Tq,
                                const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
-                               float *__restrict__ curve, int B, int L, int S, int SP, int Sc,
-                               int M, int pitch) {
+                               const int32_t *__restrict__ lowsum, float *__restrict__ curve,
+                               int B, int L, int S, int SP, int Sc, int M, int pitch) {
   const int b = blockIdx.x % B;
   const int e = (blockIdx.x / B) * blockDim.x + threadIdx.x;
   if (e > M) return;
   const size_t tab = ((size_t)b * L + L - 1) * SP;
+  const int ql = (BY_CLASS && L > 1) ? lowsum[(size_t)b * L + L - 2] : 0; // as in k_final_instance
   float m = GS_INF;
   if (e <= budget[b] && *status == 0)
     for (int s = 0; s < S; ++s) {
@@ -639,7 +653,7 @@ __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__
       if (BY_CLASS) {
         const int d = e - Oq[tab + s];
         v = GS_INF;
-        if (d >= 0) v = last[((size_t)b * Sc + cls[s]) * pitch + d] + Tq[tab + s];
+        if (d >= ql) v = last[((size_t)b * Sc + cls[s]) * pitch + d] + Tq[tab + s];
       } else {
         v = last[((size_t)b * S + s) * pitch + e];
       }
@@ -674,7 +688,9 @@ __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict
       float v = GS_INF;
       if (in) {
         if (BY_CLASS) {
-          if (src >= 0)
+          // (rows of a compact plane below the least memory of the earlier layers: +inf, not stored)
+          const int ql = l > 0 ? lowsum[(size_t)b * L + l - 1] : 0;
+          if (src >= ql)
             v = planes[(size_t)l * layer_stride + ((size_t)b * Sc + cls[s]) * pitch + src] + Tq[tab];
         } else {
           v = planes[(size_t)l * layer_stride + off];
@@ -1001,11 +1017,11 @@ void launch_final(const Shape &s, const Workspace &w, const float *last_plane, f
                   int32_t *best_s, float *final_row, int32_t *best_instance, hipStream_t st) {
   if (w.by_class)
     hipLaunchKernelGGL((k_final_instance<true>), dim3(s.B), dim3(kWave), 0, st, last_plane,
-                       w.budget, w.status, w.Tq, w.Oq, w.cls, w.best_cost, w.best_s, best_cost,
+                       w.budget, w.status, w.Tq, w.Oq, w.cls, w.lowsum, w.best_cost, w.best_s, best_cost,
                        best_s, final_row, s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
   else
     hipLaunchKernelGGL((k_final_instance<false>), dim3(s.B), dim3(kWave), 0, st, last_plane,
-                       w.budget, w.status, w.Tq, w.Oq, w.cls, w.best_cost, w.best_s, best_cost,
+                       w.budget, w.status, w.Tq, w.Oq, w.cls, w.lowsum, w.best_cost, w.best_s, best_cost,
                        best_s, final_row, s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
   if (best_instance)
     hipLaunchKernelGGL(k_final_global, dim3(1), dim3(256), 0, st, w.best_cost, best_instance,
@@ -1044,15 +1060,15 @@ static void launch_backtrace_planes_of(const Shape &s, const Workspace &w, const
   const dim3 grid(n), block(kWave);
 #define GS_ROWS(PL)                                                                              \
   hipLaunchKernelGGL((k_backtrace_planes_rows<BY_CLASS, PL>), grid, block, 0, st, w.planes, w.Rt, \
-                     w.Tq, w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, \
-                     s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch)
+                     w.Tq, w.Oq, w.cls, w.lowsum, w.ridx, w.budget, w.best_s, instances, n, plan, \
+                     mem_used, s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch)
   if (s.S <= 64) GS_ROWS(1);
   else if (s.S <= 128) GS_ROWS(2);
   else if (s.S <= 256) GS_ROWS(4);
   else
     hipLaunchKernelGGL((k_backtrace_planes<BY_CLASS>), grid, block, 0, st, w.planes, w.Rt, w.Tq,
-                       w.Oq, w.cls, w.ridx, w.budget, w.best_s, instances, n, plan, mem_used, s.B,
-                       s.L, s.S, s.SP, class_rows(s), s.pitch);
+                       w.Oq, w.cls, w.lowsum, w.ridx, w.budget, w.best_s, instances, n, plan,
+                       mem_used, s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
 #undef GS_ROWS
 }
 
@@ -1077,11 +1093,12 @@ void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_p
   const dim3 grid((unsigned)((size_t)per * s.B)), block(256);
   if (w.by_class)
     hipLaunchKernelGGL((k_budget_curve<true>), grid, block, 0, st, last_plane, w.budget, w.status,
-                       w.Tq, w.Oq, w.cls, curve, s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch);
+                       w.Tq, w.Oq, w.cls, w.lowsum, curve, s.B, s.L, s.S, s.SP, class_rows(s), s.M,
+                       s.pitch);
   else
     hipLaunchKernelGGL((k_budget_curve<false>), grid, block, 0, st, last_plane, w.budget,
-                       w.status, w.Tq, w.Oq, w.cls, curve, s.B, s.L, s.S, s.SP, class_rows(s), s.M,
-                       s.pitch);
+                       w.status, w.Tq, w.Oq, w.cls, w.lowsum, curve, s.B, s.L, s.S, s.SP,
+                       class_rows(s), s.M, s.pitch);
 }
 
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st) {

@@ -532,7 +532,9 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
 // then every wave keeps all of them in registers and takes every NW-th target class.
 //
 // Rows above E - min_s O[l][s] have no target within the budget and are neither computed
-// nor read by anyone; tiles wholly below the least memory of layers 0..l-1 hold +inf.
+// nor read by anyone.  Rows of Q[l] below the least memory of layers 0..l-1 are +inf by
+// definition; the tiles wholly below it are not stored, and every reader of a compact plane
+// (the next layer front, the final reductions, the backtrace, the export) applies that bound.
 // ---------------------------------------------------------------------------------------
 template <int SP, int NW, bool WITH_BP, int NC>
 __global__ __launch_bounds__(NW *kWave) void k_dp_class(
@@ -559,7 +561,11 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   // looked at (one round trip to the scalar cache instead of one per dependent step): the
   // per-instance scalars, and the O, T and class entries of the wave's source strategies.
   int E = budget[b];
-  int low = lowsum[bl - 1]; // C[l-1] is +inf below this row
+  int low = lowsum[bl - 1]; // C[l-1], and with it Q[l], is +inf below this row
+  // Q[l-1] is +inf below the least memory of layers 0..l-2 (Q[0] = 0 has no such rows).
+  // Those rows are not stored anywhere: every reader of a compact plane applies this bound.
+  int lowq = lowsum[bl - (l >= 2 ? 2 : 1)];
+  lowq = l >= 2 ? lowq : 0;
   int mo = minO[bl];
   int kr = ridx[bl];
   int nc = cmeta[0];
@@ -576,9 +582,13 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
       t_s[u] = tprev[js * PER + u];
     }
   }
-  asm volatile("" : "+s"(E), "+s"(low), "+s"(mo), "+s"(kr), "+s"(nc), "+s"(maxlen));
+  asm volatile("" : "+s"(E), "+s"(low), "+s"(lowq), "+s"(mo), "+s"(kr), "+s"(nc), "+s"(maxlen));
+  // (a longer run would not fit the scalar registers next to the class table row: there the
+  // compiler places the loads where the values are used)
+  if constexpr (PER <= 16) {
 #pragma unroll
-  for (int u = 0; u < PER; ++u) asm volatile("" : "+s"(o_s[u]), "+s"(c_s[u]), "+s"(t_s[u]));
+    for (int u = 0; u < PER; ++u) asm volatile("" : "+s"(o_s[u]), "+s"(c_s[u]), "+s"(t_s[u]));
+  }
   if (tile_start > E - mo) return; // no target row within the budget (whole workgroup)
 
   const int row = tile_start + lane;
@@ -586,10 +596,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   const float *__restrict__ qs = qsrc + inst;
   float *__restrict__ qd = qdst + inst;
   uint8_t *__restrict__ bpb = WITH_BP ? bp + (size_t)b * NC * pitch : nullptr;
-  if (tile_start + kWave <= low) {
-    for (int cj = js; cj < nc; cj += NW) qd[(uint32_t)cj * (uint32_t)pitch + (uint32_t)row] = GS_INF;
-    return;
-  }
+  if (tile_start + kWave <= low) return; // +inf throughout, implied by the bound, not stored
   const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
 
   // C[l-1][row][si] for this wave's source strategies, rebuilt from the compact plane.
@@ -600,13 +607,14 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   const int row4 = (row <= E ? row : -1) * 4;
   const char *__restrict__ qsb = reinterpret_cast<const char *>(qs);
   const int pitch4 = pitch * 4;
+  const int lowq4 = lowq * 4;
   float stage[PER];
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
     const int cb = c_s[u] * pitch4;          // wave-uniform
     const int t = row4 + (cb - o_s[u] * 4);
     const float v = *reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb)) + t_s[u];
-    stage[u] = t >= cb ? v : GS_INF;
+    stage[u] = t >= cb + lowq4 ? v : GS_INF; // source row >= lowq (and >= 0), row within budget
   }
   {
     const float4 inf4 = {GS_INF, GS_INF, GS_INF, GS_INF};
@@ -1026,14 +1034,14 @@ static void launch_class(const Shape &s, const Workspace &w, int l, const float 
   // Waves per tile, measured over S = 16..128 and 64..33 K tiles: eight while the batch is
   // a few hundred tiles (pure latency); otherwise eight from 64 padded strategies up with
   // backpointers and at 128 without (a wave's share of the tile is long enough to pay for
-  // the per-wave set-up), four below, and two for the min-only pass over tens of thousands
-  // of tiles with few strategies.  GSEARCH_JSPLIT overrides.
+  // the per-wave set-up), four below; the min-only pass takes eight at 96 while the batch
+  // is a few thousand tiles and two up to 32 strategies.  GSEARCH_JSPLIT overrides.
   const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
   int waves = tuning().jsplit;
   if (waves < 1 || waves > 8) {
     if (tile_inst <= 512) waves = 8;
     else if (bp_l) waves = SP >= 64 ? 8 : 4;
-    else waves = SP >= 128 ? 8 : (SP <= 32 && tile_inst >= 16384 ? 2 : 4);
+    else waves = SP >= 128 ? 8 : (SP >= 96 ? (tile_inst <= 4096 ? 8 : 4) : (SP <= 32 ? 2 : 4));
   }
   if constexpr (SP > 128) { // a wave's share of the strategies has to stay in registers
     launch_class_nw<SP, 8>(s, w, l, src, dst, bp_l, st);
