@@ -62,7 +62,10 @@ typedef enum {
 
 /* gsearch_config.flags */
 #define GSEARCH_FLAG_KEEP_PLANES 0x1u    /* keep every C plane (needed by export / curve of
-                                            any layer); default keeps two ping-pong planes */
+                                            any layer); default keeps two ping-pong planes.
+                                            (With r_class the planes are kept in a compact
+                                            form, one row per class, from which C is rebuilt
+                                            wherever it is read.)                          */
 #define GSEARCH_FLAG_FORCE_GENERIC 0x2u  /* always use the shape-agnostic forward kernel    */
 #define GSEARCH_FLAG_NO_BACKPOINTERS 0x4u /* min-only forward pass: no bp stream is written,
                                             every C plane is kept instead and the backtrace

@@ -132,8 +132,8 @@ int group_count(const gs::Shape &s, int requested, bool class_kernel) {
     return e ? atoi(e) : 0;
   }();
   const double front = (double)s.B * (s.M + 1) * s.S * s.S;
-  // (the class kernel's workgroups are short and memory-bound; a second chain only takes
-  // bandwidth from the first)
+  // (the class kernel's launches are one round of short workgroups; a second chain was
+  // measured to add its own launch overhead without filling anything)
   int g = requested >= 1 ? requested : env >= 1 ? env : (front >= 3.0e8 && !class_kernel ? 2 : 1);
   if (g > gsearch_ctx::kMaxSide + 1) g = gsearch_ctx::kMaxSide + 1;
   return g < s.B ? g : s.B;
