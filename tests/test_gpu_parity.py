@@ -644,6 +644,15 @@ def test_bad_transition_classes_are_flagged(gs):
     cases["column"] = (w3, r_class)
     ok40 = runner.solve_workload(w40, r_class=np.arange(40, dtype=np.int32))   # announced: fine
     assert ok40["data_status"] == 0 and ok40["forward_kernel"] == "k_dp_class"
+    # the bound is an upper bound: larger than the count (even absurdly) is fine, and a
+    # negative one means "not announced"
+    for bound in (64, 10 ** 6, -5):
+        got = runner.solve_workload(w, r_class=r_class, r_class_bound=bound)
+        assert got["data_status"] == 0 and got["forward_kernel"] == "k_dp_class", bound
+        assert np.array_equal(bits(got["best_cost"]), bits(ok["best_cost"])), bound
+        assert np.array_equal(got["plan"], ok["plan"]), bound
+    got = runner.solve_workload(w40, r_class=np.arange(40, dtype=np.int32), r_class_bound=10 ** 6)
+    assert got["data_status"] == 0 and np.array_equal(got["plan"], ok40["plan"])
     for name, case in cases.items():
         ww, cc = case[0], case[1]
         got = runner.solve_workload(ww, r_class=cc, r_class_bound=case[2] if len(case) > 2 else None)
