@@ -812,3 +812,36 @@ def test_one_context_solves_different_workloads_in_turn(gs, oracle_mod, mode):
                 E = int(w.budget[b])
                 one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True)
                 assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (n, w.name, b)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("case", [(256, [4] * 64, 16384), (162, [4] * 36 + [2] * 9, 20000),
+                                  (96, [2] * 48, 33000)],
+                         ids=lambda c: "S%dnc%dM%d" % (c[0], len(c[1]), c[2]))
+def test_wide_class_kernel_at_large_budgets(gs, oracle_mod, case):
+    """The wide form and the 192/256-strategy forms of the class kernel with tens of thousands
+    of budget rows (row pitches and per-class strides of the size the benchmark uses, several
+    hundred tiles, a ragged last tile), both modes, against the oracle."""
+    binding, runner = gs
+    import torch
+    S, sizes, M = case
+    B, L = 2, 3
+    budget = np.array([M, M - 4097], np.int32)
+    w, r_class = workloads.class_tables("widebig", B, L, S, M, sizes, K=1, seed=S + M,
+                                        budget=budget, coarse=True)
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    for mode in ("bp", "nobp"):
+        with runner.make_context(w, flags=MODES[mode]) as ctx:
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc,
+                                                  r_class_bound=len(sizes)))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+            curve = ctx.gsearch_budget_curve().cpu().numpy()
+        assert_same(got, ref, w, f"{case[0]} strategies, {len(sizes)} classes, M={M}, {mode}")
+        for b in range(B):
+            E = int(w.budget[b])
+            one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_curve=True)
+            assert np.array_equal(bits(curve[b, :E + 1]), bits(one["curve"])), (case, mode, b)
+            assert np.isinf(curve[b, E + 1:]).all()
