@@ -532,14 +532,24 @@ def test_class_kernel_with_instance_groups_and_single_layer(gs, oracle_mod):
     ref = oracle_batch(oracle_mod, w)
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
-    with runner.make_context(w) as ctx:
-        for groups in (2, 5, 1, 0):
-            ctx.gsearch_set_instance_groups(groups)
-            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
-            got["data_status"] = ctx.gsearch_data_status()
-            assert ctx.gsearch_forward_kernel() == "k_dp_class"
-            assert ctx.gsearch_instance_groups() == (groups if groups else 1)
-            assert_same(got, ref, w, f"classes groups={groups}")
+    for flags in (0, binding.GSEARCH_FLAG_NO_BACKPOINTERS, binding.GSEARCH_FLAG_KEEP_PLANES):
+        with runner.make_context(w, flags=flags) as ctx:
+            for groups in (2, 5, 1, 0):
+                ctx.gsearch_set_instance_groups(groups)
+                got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+                got["data_status"] = ctx.gsearch_data_status()
+                assert ctx.gsearch_forward_kernel() == "k_dp_class"
+                assert ctx.gsearch_instance_groups() == (groups if groups else 1)
+                assert_same(got, ref, w, f"classes groups={groups} flags={flags}")
+                if flags & binding.GSEARCH_FLAG_KEEP_PLANES:
+                    C, bp = ctx.gsearch_export_planes(want_bp=True)
+                    C, bp = C.cpu().numpy(), bp.cpu().numpy()
+                    for b in range(w.B):
+                        E = int(w.budget[b])
+                        one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E,
+                                               want_planes=True)
+                        assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (groups, b)
+                        assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32))
     w1, rc1 = workloads.class_tables("classL1", 3, 1, 24, 60, [6] * 4, seed=32)
     got = runner.solve_workload(w1, r_class=np.array([0, 5, 9] + [0] * 21, np.int32))  # nonsense
     assert got["data_status"] == 0
