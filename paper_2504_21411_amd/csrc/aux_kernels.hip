@@ -229,14 +229,38 @@ __global__ void k_init_layer0(float *__restrict__ plane, const float *__restrict
   }
 }
 
-// Lexicographic (value, index) minimum across the 64 lanes of a wave.
+// Lexicographic (value, index) minimum across the 64 lanes of a wave, left in every lane.
+// Inside a row of 16 lanes the partners come from DPP moves (two quad permutations, then
+// rotations by 4 and 8: the minimum is idempotent, so a rotation serves as well as an
+// exchange); the four row results are read out as scalars and combined.  About a quarter
+// of the latency of six rounds of cross-lane permutes through the LDS crossbar, which
+// matters to the backtrace from planes, where one such reduction sits in every layer's
+// dependent chain.
+static __device__ __forceinline__ void lexmin(float &v, int &idx, float ov, int oi) {
+  const bool take = (ov < v) | ((ov == v) & (oi < idx)); // no short circuit: no branches
+  v = take ? ov : v;
+  idx = take ? oi : idx;
+}
+template <int CTRL>
+static __device__ __forceinline__ void lexmin_dpp(float &v, int &idx) {
+  const int vb = __float_as_int(v);
+  const float ov = __int_as_float(__builtin_amdgcn_update_dpp(vb, vb, CTRL, 0xF, 0xF, false));
+  const int oi = __builtin_amdgcn_update_dpp(idx, idx, CTRL, 0xF, 0xF, false);
+  lexmin(v, idx, ov, oi);
+}
 static __device__ __forceinline__ void wave_argmin(float &v, int &idx) {
+  lexmin_dpp<0xB1>(v, idx);  // quad_perm [1,0,3,2]
+  lexmin_dpp<0x4E>(v, idx);  // quad_perm [2,3,0,1]
+  lexmin_dpp<0x124>(v, idx); // row_ror 4
+  lexmin_dpp<0x128>(v, idx); // row_ror 8
+  float rv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  int ri = __builtin_amdgcn_readlane(idx, 0);
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    const float ov = __shfl_xor(v, d, 64);
-    const int oi = __shfl_xor(idx, d, 64);
-    if (ov < v || (ov == v && oi < idx)) { v = ov; idx = oi; }
-  }
+  for (int row = 1; row < 4; ++row)
+    lexmin(rv, ri, __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16 * row)),
+           __builtin_amdgcn_readlane(idx, 16 * row));
+  v = rv;
+  idx = ri;
 }
 
 // One wave per instance: min_s C[L-1][E_b][s] with the lowest s on ties.
