@@ -855,3 +855,21 @@ def test_wide_class_kernel_at_large_budgets(gs, oracle_mod, case):
             one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_curve=True)
             assert np.array_equal(bits(curve[b, :E + 1]), bits(one["curve"])), (case, mode, b)
             assert np.isinf(curve[b, E + 1:]).all()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("mode", ["bp", "nobp", "bp_tile", "nobp_push", "generic"])
+def test_several_hundred_thousand_budget_rows(gs, oracle_mod, mode):
+    """Long planes: 300 001 budget rows (4688 tiles, row pitch above 2^18, plane offsets in
+    the tens of millions of elements), ragged budgets and strategies that use thousands of
+    bins, every general kernel; and the largest strategy count (1024) on a short plane."""
+    _, runner = gs
+    M = 300000
+    w = random_tables("longplane", 2, 3, 12, M, K=2, seed=91, o_hi=9000,
+                      budget=np.array([M, M - 70001], np.int32))
+    assert_same(runner.solve_workload(w, MODES[mode]), oracle_batch(oracle_mod, w), w,
+                f"M={M} {mode}")
+    if mode in ("bp", "nobp"):
+        w = random_tables("maxS", 1, 3, 1024, 40, seed=92, o_hi=8)
+        assert_same(runner.solve_workload(w, MODES[mode]), oracle_batch(oracle_mod, w), w,
+                    f"S=1024 {mode}")
