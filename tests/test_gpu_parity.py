@@ -873,3 +873,27 @@ def test_several_hundred_thousand_budget_rows(gs, oracle_mod, mode):
         w = random_tables("maxS", 1, 3, 1024, 40, seed=92, o_hi=8)
         assert_same(runner.solve_workload(w, MODES[mode]), oracle_batch(oracle_mod, w), w,
                     f"S=1024 {mode}")
+
+
+@pytest.mark.parametrize("B", [9, 37, 257])
+def test_class_kernel_batch_sizes_that_are_not_a_multiple_of_eight(gs, oracle_mod, B):
+    """For such batches the class kernel numbers its workgroups in eight contiguous runs of
+    the instance-major tile list (one per XCD): every (instance, tile) must still be computed
+    exactly once, whatever the division of the list comes to."""
+    binding, runner = gs
+    import torch
+    rng = workloads.SplitMix64(4000 + B)
+    M = 333
+    budget = rng.randint(0, M, B).astype(np.int32)
+    budget[0] = M
+    w, r_class = workloads.class_tables("oddbatch", B, 4, 44, M, [4] * 11, K=2, seed=600 + B,
+                                        budget=budget, coarse=True)
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    for mode in ("bp", "nobp"):
+        with runner.make_context(w, flags=MODES[mode]) as ctx:
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+        assert_same(got, ref, w, f"B={B} {mode}")
