@@ -159,6 +159,16 @@ def test_uint16_backpointers_above_256_strategies(gs, oracle_mod):
     assert_same(got, ref, w, "uint16")
     assert ref["plan"].max() > 255
     assert_same(runner.solve_workload(w, 0x4), ref, w, "uint16 nobp")
+    # classes stated for a strategy count beyond the class kernel's sizes: the promise is
+    # checked, the general kernels run
+    wc, r_class = workloads.class_tables("wideclass", 2, 3, 300, 90, [6] * 50, seed=33,
+                                         budget=np.array([90, 41], np.int32))
+    got = runner.solve_workload(wc, 0, r_class=r_class)
+    assert got["forward_kernel"] != "k_dp_class" and got["data_status"] == 0
+    assert_same(got, oracle_batch(oracle_mod, wc), wc, "300 strategies with classes")
+    wc.R[0, 0, 7] += np.float32(1.0)
+    got = runner.solve_workload(wc, 0, r_class=r_class)
+    assert got["data_status"] & 0x20
 
 
 def test_backtrace_instance_lists_and_capacity_errors(gs, oracle_mod):
