@@ -36,7 +36,7 @@ def ops_per_relaxation(kernel: str, mode: str, S: int) -> float:
     """
     if mode == "nobp":
         return 1.5
-    if kernel == "k_dp_tile":
+    if kernel in ("k_dp_tile", "k_dp_wide"):
         return 15.0 / 8.0 + 24.0 / S
     return 4.0
 
@@ -154,7 +154,7 @@ def main():
             rows = w.budget.astype(np.int64)[:, None] + 1
             skipped = np.minimum(low[:, :-1] // 64 * 64, rows)
             executed = float((rows - skipped).sum()) / float((rows * (w.L - 1)).sum())
-            if kernel not in ("k_dp_push", "k_dp_tile", "k_dp_class"):
+            if kernel not in ("k_dp_push", "k_dp_tile", "k_dp_wide", "k_dp_class"):
                 executed = 1.0
             n_class = int(out["n_class"].cpu()[0]) if "n_class" in out else None
             computed = float((rows - skipped).sum()) / (w.L - 1)

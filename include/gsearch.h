@@ -202,7 +202,7 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable);
 int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
 /* Name of the forward kernel the most recent solve launched for its layer fronts
- * ("k_dp_class", "k_dp_tile", "k_dp_push", "k_dp_generic" or "k_dp_small"; "" before any
+ * ("k_dp_class", "k_dp_tile", "k_dp_wide", "k_dp_push", "k_dp_generic" or "k_dp_small"; "" before any
  * solve).  Static string. */
 const char *gsearch_forward_kernel(gsearch_ctx *ctx);
 

@@ -505,7 +505,138 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
 }
 
 // ---------------------------------------------------------------------------------------
-// Class kernel: the transition table depends on the strategies only through nc <= 32
+// The same tile kernel for strategy counts beyond the register-tiled sizes (129 .. 608):
+// the tile stays in LDS and level 1 streams it from there, two target strategies per pass
+// so that every LDS read serves two relaxations (2 B of LDS traffic per relaxation; the
+// scalar transition values of the next chunk are requested while the current one is being
+// added up).  Same two-level argmin, same stores, uint8 or uint16 backpointers.  About half
+// the rate of the register-tiled kernel, against a seventieth for the pull-form fallback.
+// ---------------------------------------------------------------------------------------
+template <typename BPT, int NW, bool WITH_BP>
+__global__ __launch_bounds__(NW *kWave) void k_dp_wide(
+    const float *__restrict__ src, float *__restrict__ dst, BPT *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ lowsum, int B, int L, int S, int SP, int l, int pitch) {
+  extern __shared__ float tile[]; // [SP][64]
+  const int b = blockIdx.x % B;
+  const int tile_start = (int)(blockIdx.x / B) * kWave;
+  const int js = wave_uniform(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int E = budget[b];
+  if (tile_start > E) return; // whole workgroup
+
+  const int row = tile_start + lane;
+  const bool valid = row <= E;
+  const int bl = b * L + l;
+  const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
+  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave > low; // uniform
+  const size_t plane_off = (size_t)b * S * pitch;
+  const float *__restrict__ srcb = src + plane_off;
+  float *__restrict__ dstb = dst + plane_off;
+  BPT *__restrict__ bpb = WITH_BP ? bp + plane_off : nullptr;
+  const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
+  const float *__restrict__ trow = Tq + (size_t)bl * SP;
+  const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
+  const int nq = SP / 8; // chunks of eight candidates (SP is a multiple of 8)
+
+  if (compute) {
+    // tile HBM -> LDS, four rows per wave in flight; padding strategies and rows beyond the
+    // budget are +inf
+    const uint32_t rowc = (uint32_t)(valid ? row : E);
+    for (int i0 = js * 4; i0 < SP; i0 += NW * 4) {
+      float v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int i = i0 + u;
+        const int ic = i < S ? i : S - 1;
+        v[u] = (srcb + (size_t)ic * pitch)[rowc];
+        v[u] = (i < S && valid) ? v[u] : GS_INF;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (i0 + u < SP) tile[(i0 + u) * kWave + lane] = v[u];
+    }
+    __syncthreads();
+  }
+
+  const int jper = (S + NW - 1) / NW;
+  const int jbeg = js * jper;
+  const int jend = jbeg + jper < S ? jbeg + jper : S;
+  // level 2 and the stores of one column (see k_dp_tile)
+  auto finish = [&](int j, int o, float t, float m, int g) {
+    if constexpr (WITH_BP) {
+      const float *tg = tile + (8 * g) * kWave + lane;        // per-lane slice of the tile
+      const float *__restrict__ rg = rk + (size_t)j * SP + 8 * g; // and of the column
+      const float4 ra = *reinterpret_cast<const float4 *>(rg);
+      const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
+      const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+      int kk = 0;
+#pragma unroll
+      for (int k = 7; k >= 0; --k) { // descending: the lowest matching candidate wins
+        const float v = tg[k * kWave] + rr[k];
+        kk = (v == m) ? k : kk;
+      }
+      const int eo = row + o;
+      if (row >= low && eo <= E) {
+        (dstb + (size_t)j * pitch)[(uint32_t)eo] = m + t;
+        (bpb + (size_t)j * pitch)[(uint32_t)eo] = (BPT)(8 * g + kk);
+      }
+    } else {
+      const int eo = row + o;
+      if (row >= low && eo <= E) (dstb + (size_t)j * pitch)[(uint32_t)eo] = m + t;
+    }
+  };
+  for (int j = jbeg; j < jend; j += 2) {
+    const bool two = j + 1 < jend;
+    const int j1 = two ? j + 1 : j;
+    const int o0 = orow[j], o1 = orow[j1];
+    const float t0 = trow[j], t1 = trow[j1];
+    if (compute) {
+      const float *__restrict__ rc0 = rk + (size_t)j * SP;
+      const float *__restrict__ rc1 = rk + (size_t)j1 * SP;
+      float m0 = GS_INF, m1 = GS_INF;
+      int g0 = 0, g1 = 0;
+      float8_t r0 = *reinterpret_cast<const float8_t *>(rc0);
+      float8_t r1 = *reinterpret_cast<const float8_t *>(rc1);
+      for (int q = 0; q < nq; ++q) {
+        const int qn = q + 1 < nq ? q + 1 : q;
+        const float8_t n0 = *reinterpret_cast<const float8_t *>(rc0 + 8 * qn);
+        const float8_t n1 = *reinterpret_cast<const float8_t *>(rc1 + 8 * qn);
+        const float *tq = tile + (8 * q) * kWave + lane;
+        float c[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
+        float cm0 = __builtin_fminf(c[0] + r0[0], c[1] + r0[1]);
+        float cm1 = __builtin_fminf(c[0] + r1[0], c[1] + r1[1]);
+#pragma unroll
+        for (int k = 2; k < 8; ++k) {
+          cm0 = __builtin_fminf(cm0, c[k] + r0[k]);
+          cm1 = __builtin_fminf(cm1, c[k] + r1[k]);
+        }
+        chunk_update<WITH_BP>(m0, g0, cm0, q);
+        chunk_update<WITH_BP>(m1, g1, cm1, q);
+        r0 = n0;
+        r1 = n1;
+      }
+      finish(j, o0, t0, m0, g0);
+      if (two) finish(j1, o1, t1, m1, g1);
+    }
+    // +inf prefix of the target rows that no computed source row reaches
+    if (tile_start < o0 + low && valid && row < o0 + low) {
+      (dstb + (size_t)j * pitch)[(uint32_t)row] = GS_INF;
+      if (WITH_BP) (bpb + (size_t)j * pitch)[(uint32_t)row] = 0;
+    }
+    if (two && tile_start < o1 + low && valid && row < o1 + low) {
+      (dstb + (size_t)j1 * pitch)[(uint32_t)row] = GS_INF;
+      if (WITH_BP) (bpb + (size_t)j1 * pitch)[(uint32_t)row] = 0;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Class kernel: the transition table depends on the strategies only through nc <= 64
 // contiguous classes (checked on the device beforehand), R[si][sj] = Rc[class si][class sj].
 // Then, for a source row,
 //     min_si (C[si] + R[si][sj]) = min_ci ( (min_{si in ci} C[si]) + Rc[ci][cj] )
@@ -911,7 +1042,7 @@ struct PushTuning {
   PushTuning() {
     if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
     if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
-    if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile
+    if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile, 3 = wide
     if (const char *e = getenv("GSEARCH_ROW_GROUPS")) row_groups = atoi(e);
   }
 };
@@ -1110,6 +1241,33 @@ void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {
   hipLaunchKernelGGL(k_zero_plane, dim3(blocks < 1 ? 1 : blocks), dim3(256), 0, st, q0, n);
 }
 
+template <typename BPT, bool WITH_BP>
+static void launch_wide_as(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                           void *bp_l, hipStream_t st) {
+  constexpr int NW = 8;
+  const long long tiles = (s.M + 1 + kWave - 1) / kWave;
+  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
+  const size_t lds = (size_t)s.SP * kWave * sizeof(float);
+  if (lds > 64 * 1024) { // opt in to the large LDS allocation (the largest asked for so far)
+    static size_t granted = 0;
+    if (lds > granted) {
+      (void)hipFuncSetAttribute((const void *)k_dp_wide<BPT, NW, WITH_BP>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      granted = lds;
+    }
+  }
+  hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP>), grid, block, lds, st, src, dst, (BPT *)bp_l,
+                     w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, s.SP, l,
+                     s.pitch);
+}
+
+static void launch_wide(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
+                        void *bp_l, hipStream_t st) {
+  if (!bp_l) launch_wide_as<uint8_t, false>(s, w, l, src, dst, bp_l, st);
+  else if (s.bp16) launch_wide_as<uint16_t, true>(s, w, l, src, dst, bp_l, st);
+  else launch_wide_as<uint8_t, true>(s, w, l, src, dst, bp_l, st);
+}
+
 const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, ForwardKernel which, hipStream_t st) {
   const bool force_generic = which == ForwardKernel::Generic;
@@ -1132,6 +1290,11 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // workgroups per tile and fills more of the chip (S = 96, 64 tiles: 0.22 against 0.31 ms
   // for 11 fronts).
   if (tsp >= 64 && tile_inst <= 256) use_tile = false;
+  if (tuning().kernel == 3 && !force_generic && which == ForwardKernel::Auto && s.SP % 8 == 0 &&
+      (size_t)s.SP * kWave * sizeof(float) <= 152 * 1024) { // GSEARCH_KERNEL=3: measure it anywhere
+    launch_wide(s, w, l, src, dst, bp_l, st);
+    return "k_dp_wide";
+  }
   if (tuning().kernel == 1 || which == ForwardKernel::Push) use_tile = false;
   if (tuning().kernel == 2 || which == ForwardKernel::Tile) use_tile = true;
   if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16 && use_tile) {
@@ -1162,6 +1325,11 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
       case 128: launch_push<128>(s, w, l, src, dst, bp_l, st); return "k_dp_push";
       default: break;
     }
+  }
+  // Beyond the register-tiled sizes: the LDS-streamed tile kernel while the tile fits
+  if (!force_generic && tsp == 0 && s.SP % 8 == 0 && (size_t)s.SP * kWave * sizeof(float) <= 152 * 1024) {
+    launch_wide(s, w, l, src, dst, bp_l, st);
+    return "k_dp_wide";
   }
   if (!bp_l) {
     hipLaunchKernelGGL((k_dp_generic<uint8_t, false>), grid, dim3(kRowsPerBlock), 0, st, src,

@@ -58,6 +58,9 @@ SHAPES = [
     (2, 3, 64, 320, 1), (2, 3, 65, 200, 2), (2, 3, 96, 260, 1), (1, 3, 100, 130, 1),
     (2, 3, 128, 129, 2), (5, 1, 9, 40, 1), (1, 2, 2, 1, 1),
     (2, 4, 41, 200, 1), (2, 3, 45, 130, 2),   # either side of the half-chunk variant (41..44)
+    # beyond the register-tiled sizes: the LDS-streamed tile kernel (uint8 and uint16 bp)
+    (2, 3, 129, 130, 2), (3, 4, 200, 150, 1), (2, 3, 256, 70, 1), (2, 3, 300, 90, 2),
+    (1, 3, 601, 40, 1),
 ]
 
 
