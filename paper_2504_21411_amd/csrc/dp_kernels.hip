@@ -539,13 +539,14 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
   const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
   const float *__restrict__ trow = Tq + (size_t)bl * SP;
   const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
-  const int nq = SP / 8; // chunks of eight candidates (SP is a multiple of 8)
+  const int nq = (S + 7) / 8; // chunks of eight candidates that hold a strategy (8 nq <= SP)
+  const int rows_used = 8 * nq;
 
   if (compute) {
     // tile HBM -> LDS, four rows per wave in flight; padding strategies and rows beyond the
     // budget are +inf
     const uint32_t rowc = (uint32_t)(valid ? row : E);
-    for (int i0 = js * 4; i0 < SP; i0 += NW * 4) {
+    for (int i0 = js * 4; i0 < rows_used; i0 += NW * 4) {
       float v[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -556,7 +557,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (i0 + u < SP) tile[(i0 + u) * kWave + lane] = v[u];
+        if (i0 + u < rows_used) tile[(i0 + u) * kWave + lane] = v[u];
     }
     __syncthreads();
   }
