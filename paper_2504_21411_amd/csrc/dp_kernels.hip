@@ -506,13 +506,13 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
 
 // ---------------------------------------------------------------------------------------
 // The same tile kernel for strategy counts beyond the register-tiled sizes (129 .. 608):
-// the tile stays in LDS and level 1 streams it from there, two target strategies per pass
-// so that every LDS read serves two relaxations (2 B of LDS traffic per relaxation; the
+// the tile stays in LDS and level 1 streams it from there, JB target strategies per pass
+// so that every LDS read serves JB relaxations (4 / JB bytes of LDS traffic per relaxation; the
 // scalar transition values of the next chunk are requested while the current one is being
 // added up).  Same two-level argmin, same stores, uint8 or uint16 backpointers.  About half
 // the rate of the register-tiled kernel, against a seventieth for the pull-form fallback.
 // ---------------------------------------------------------------------------------------
-template <typename BPT, int NW, bool WITH_BP>
+template <typename BPT, int NW, bool WITH_BP, int JB>
 __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
     const float *__restrict__ src, float *__restrict__ dst, BPT *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
@@ -589,49 +589,56 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
       if (row >= low && eo <= E) (dstb + (size_t)j * pitch)[(uint32_t)eo] = m + t;
     }
   };
-  for (int j = jbeg; j < jend; j += 2) {
-    const bool two = j + 1 < jend;
-    const int j1 = two ? j + 1 : j;
-    const int o0 = orow[j], o1 = orow[j1];
-    const float t0 = trow[j], t1 = trow[j1];
+  for (int j = jbeg; j < jend; j += JB) {
+    int jj[JB], oo[JB];
+    float tt[JB];
+#pragma unroll
+    for (int x = 0; x < JB; ++x) {
+      jj[x] = j + x < jend ? j + x : j; // the last pass may repeat column j (results dropped)
+      oo[x] = orow[jj[x]];
+      tt[x] = trow[jj[x]];
+    }
     if (compute) {
-      const float *__restrict__ rc0 = rk + (size_t)j * SP;
-      const float *__restrict__ rc1 = rk + (size_t)j1 * SP;
-      float m0 = GS_INF, m1 = GS_INF;
-      int g0 = 0, g1 = 0;
-      float8_t r0 = *reinterpret_cast<const float8_t *>(rc0);
-      float8_t r1 = *reinterpret_cast<const float8_t *>(rc1);
+      const float *__restrict__ rc[JB];
+      float m[JB];
+      int g[JB];
+      float8_t r[JB];
+#pragma unroll
+      for (int x = 0; x < JB; ++x) {
+        rc[x] = rk + (size_t)jj[x] * SP;
+        m[x] = GS_INF;
+        g[x] = 0;
+        r[x] = *reinterpret_cast<const float8_t *>(rc[x]);
+      }
       for (int q = 0; q < nq; ++q) {
         const int qn = q + 1 < nq ? q + 1 : q;
-        const float8_t n0 = *reinterpret_cast<const float8_t *>(rc0 + 8 * qn);
-        const float8_t n1 = *reinterpret_cast<const float8_t *>(rc1 + 8 * qn);
+        float8_t n[JB];
+#pragma unroll
+        for (int x = 0; x < JB; ++x) n[x] = *reinterpret_cast<const float8_t *>(rc[x] + 8 * qn);
         const float *tq = tile + (8 * q) * kWave + lane;
         float c[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
-        float cm0 = __builtin_fminf(c[0] + r0[0], c[1] + r0[1]);
-        float cm1 = __builtin_fminf(c[0] + r1[0], c[1] + r1[1]);
 #pragma unroll
-        for (int k = 2; k < 8; ++k) {
-          cm0 = __builtin_fminf(cm0, c[k] + r0[k]);
-          cm1 = __builtin_fminf(cm1, c[k] + r1[k]);
+        for (int x = 0; x < JB; ++x) {
+          float cm = __builtin_fminf(c[0] + r[x][0], c[1] + r[x][1]);
+#pragma unroll
+          for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[k] + r[x][k]);
+          chunk_update<WITH_BP>(m[x], g[x], cm, q);
+          r[x] = n[x];
         }
-        chunk_update<WITH_BP>(m0, g0, cm0, q);
-        chunk_update<WITH_BP>(m1, g1, cm1, q);
-        r0 = n0;
-        r1 = n1;
       }
-      finish(j, o0, t0, m0, g0);
-      if (two) finish(j1, o1, t1, m1, g1);
+#pragma unroll
+      for (int x = 0; x < JB; ++x)
+        if (x == 0 || j + x < jend) finish(jj[x], oo[x], tt[x], m[x], g[x]);
     }
     // +inf prefix of the target rows that no computed source row reaches
-    if (tile_start < o0 + low && valid && row < o0 + low) {
-      (dstb + (size_t)j * pitch)[(uint32_t)row] = GS_INF;
-      if (WITH_BP) (bpb + (size_t)j * pitch)[(uint32_t)row] = 0;
-    }
-    if (two && tile_start < o1 + low && valid && row < o1 + low) {
-      (dstb + (size_t)j1 * pitch)[(uint32_t)row] = GS_INF;
-      if (WITH_BP) (bpb + (size_t)j1 * pitch)[(uint32_t)row] = 0;
+#pragma unroll
+    for (int x = 0; x < JB; ++x) {
+      if ((x == 0 || j + x < jend) && tile_start < oo[x] + low && valid && row < oo[x] + low) {
+        (dstb + (size_t)jj[x] * pitch)[(uint32_t)row] = GS_INF;
+        if (WITH_BP) (bpb + (size_t)jj[x] * pitch)[(uint32_t)row] = 0;
+      }
     }
   }
 }
@@ -1245,19 +1252,20 @@ void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {
 template <typename BPT, bool WITH_BP>
 static void launch_wide_as(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                            void *bp_l, hipStream_t st) {
-  constexpr int NW = 8;
+  // target strategies per pass: four for the min-only scan, two with the argmin (measured)
+  constexpr int NW = 8, JB = WITH_BP ? 2 : 4;
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
   const size_t lds = (size_t)s.SP * kWave * sizeof(float);
   if (lds > 64 * 1024) { // opt in to the large LDS allocation (the largest asked for so far)
     static size_t granted = 0;
     if (lds > granted) {
-      (void)hipFuncSetAttribute((const void *)k_dp_wide<BPT, NW, WITH_BP>,
+      (void)hipFuncSetAttribute((const void *)k_dp_wide<BPT, NW, WITH_BP, JB>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       granted = lds;
     }
   }
-  hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP>), grid, block, lds, st, src, dst, (BPT *)bp_l,
+  hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP, JB>), grid, block, lds, st, src, dst, (BPT *)bp_l,
                      w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, s.SP, l,
                      s.pitch);
 }
@@ -1291,10 +1299,21 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // workgroups per tile and fills more of the chip (S = 96, 64 tiles: 0.22 against 0.31 ms
   // for 11 fronts).
   if (tsp >= 64 && tile_inst <= 256) use_tile = false;
-  if (tuning().kernel == 3 && !force_generic && which == ForwardKernel::Auto && s.SP % 8 == 0 &&
-      (size_t)s.SP * kWave * sizeof(float) <= 152 * 1024) { // GSEARCH_KERNEL=3: measure it anywhere
-    launch_wide(s, w, l, src, dst, bp_l, st);
-    return "k_dp_wide";
+  // The LDS-streamed kernel (made for more than 128 strategies) also wins below that where
+  // the register-tiled ones run out of registers or of parallel work (measured, 7 fronts,
+  // ms: S = 128, 8 x 16385 rows: 0.79 against 0.85 with backpointers, 0.62 against 0.71
+  // without; S = 96 min-only 0.38 against 0.40 up to a few thousand tiles, but 1.46 against
+  // 1.27 on 8 K tiles; S = 64..96 on a handful of tiles 0.08 / 0.13 against 0.09 / 0.15).
+  // GSEARCH_KERNEL=3 forces it wherever its tile fits.
+  if (which == ForwardKernel::Auto && tsp == s.SP && s.SP % 8 == 0 && tuning().kernel != 1 &&
+      tuning().kernel != 2) {
+    const bool wide = tuning().kernel == 3 || tsp == 128 ||
+                      (tsp == 96 && (tile_inst <= 512 || (!bp_l && tile_inst <= 4096))) ||
+                      (tsp == 64 && tile_inst <= 256);
+    if (wide) {
+      launch_wide(s, w, l, src, dst, bp_l, st);
+      return "k_dp_wide";
+    }
   }
   if (tuning().kernel == 1 || which == ForwardKernel::Push) use_tile = false;
   if (tuning().kernel == 2 || which == ForwardKernel::Tile) use_tile = true;

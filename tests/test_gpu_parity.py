@@ -333,7 +333,7 @@ def test_config3_large_dense_full_size(gs, oracle_mod):
     # the three launch configurations bench.py times (class kernel with and without
     # backpointers, general kernel on two instance groups) and the general min-only pass
     for flags, classes, kernel in ((0, True, "k_dp_class"), (0x4, True, "k_dp_class"),
-                                   (0, False, "k_dp_tile"), (0x4, False, "k_dp_push")):
+                                   (0, False, "k_dp_tile"), (0x4, False, "k_dp_wide")):
         with runner.make_context(w, flags=flags) as ctx:
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=classes))
             got["data_status"] = ctx.gsearch_data_status()
@@ -433,7 +433,7 @@ def test_profiled_table_builder_matches_oracle_and_solves(gs, oracle_mod):
 
 def test_profiling_entry_points(gs):
     binding, runner = gs
-    w = random_tables("timing", 4, 6, 96, 6000, seed=91)       # 376 tiles: the tile kernel's range
+    w = random_tables("timing", 4, 6, 96, 6000, seed=91)       # 376 tiles: the LDS-streamed kernel's range
     dw = runner.DeviceWorkload(w)
     with runner.make_context(w) as ctx:
         assert ctx.gsearch_forward_kernel() == ""
@@ -444,7 +444,7 @@ def test_profiling_entry_points(gs):
         ctx.gsearch_set_profiling(True)
         runner.run_step(ctx, dw, backtrace=None)
         assert 0.0 < ctx.gsearch_forward_ms() < 1000.0
-        assert ctx.gsearch_forward_kernel() == "k_dp_tile"
+        assert ctx.gsearch_forward_kernel() == "k_dp_wide"
     small = random_tables("timing_small", 1, 5, 12, 100, seed=92)
     with runner.make_context(small) as ctx:
         runner.run_step(ctx, runner.DeviceWorkload(small), backtrace=None)
@@ -715,7 +715,7 @@ def test_model_configs_without_classes_use_the_general_kernels(gs, oracle_mod, i
     ref = oracle_batch(oracle_mod, w, T, O, R)
     a = runner.solve_workload(w, classes=True)
     b = runner.solve_workload(w, classes=False)
-    assert a["forward_kernel"] == "k_dp_class" and b["forward_kernel"] == "k_dp_tile"
+    assert a["forward_kernel"] == "k_dp_class" and b["forward_kernel"] in ("k_dp_tile", "k_dp_wide")
     assert_same(a, ref, w, "classes")
     assert_same(b, ref, w, "general")
 
