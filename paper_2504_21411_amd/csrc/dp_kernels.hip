@@ -1302,13 +1302,14 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // The LDS-streamed kernel (made for more than 128 strategies) also wins below that where
   // the register-tiled ones run out of registers or of parallel work (measured, 7 fronts,
   // ms: S = 128, 8 x 16385 rows: 0.79 against 0.85 with backpointers, 0.62 against 0.71
-  // without; S = 96 min-only 0.38 against 0.40 up to a few thousand tiles, but 1.46 against
-  // 1.27 on 8 K tiles; S = 64..96 on a handful of tiles 0.08 / 0.13 against 0.09 / 0.15).
+  // without; S = 96 up to a few thousand tiles: configs[3] 6.9 against 7.3 ms with
+  // backpointers, 5.5 against 5.8 without, but 8 K tiles 2.04 against 1.87 and 1.46 against
+  // 1.27; S = 64 on a handful of tiles 0.08 against 0.09).
   // GSEARCH_KERNEL=3 forces it wherever its tile fits.
   if (which == ForwardKernel::Auto && tsp == s.SP && s.SP % 8 == 0 && tuning().kernel != 1 &&
       tuning().kernel != 2) {
     const bool wide = tuning().kernel == 3 || tsp == 128 ||
-                      (tsp == 96 && (tile_inst <= 512 || (!bp_l && tile_inst <= 4096))) ||
+                      (tsp == 96 && tile_inst <= 4096) ||
                       (tsp == 64 && tile_inst <= 256);
     if (wide) {
       launch_wide(s, w, l, src, dst, bp_l, st);

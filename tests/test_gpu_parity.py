@@ -333,7 +333,7 @@ def test_config3_large_dense_full_size(gs, oracle_mod):
     # the three launch configurations bench.py times (class kernel with and without
     # backpointers, general kernel on two instance groups) and the general min-only pass
     for flags, classes, kernel in ((0, True, "k_dp_class"), (0x4, True, "k_dp_class"),
-                                   (0, False, "k_dp_tile"), (0x4, False, "k_dp_wide")):
+                                   (0, False, "k_dp_wide"), (0x4, False, "k_dp_wide")):
         with runner.make_context(w, flags=flags) as ctx:
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=classes))
             got["data_status"] = ctx.gsearch_data_status()
