@@ -539,8 +539,9 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
   const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
   const float *__restrict__ trow = Tq + (size_t)bl * SP;
   const int32_t *__restrict__ orow = Oq + (size_t)bl * SP;
-  const int nq = (S + 7) / 8; // chunks of eight candidates that hold a strategy (8 nq <= SP)
-  const int rows_used = 8 * nq;
+  // pairs of chunks of eight candidates that hold a strategy (SP is a multiple of 16 here)
+  const int np = (S + 15) / 16;
+  const int rows_used = 16 * np;
 
   if (compute) {
     // tile HBM -> LDS, four rows per wave in flight; padding strategies and rows beyond the
@@ -602,30 +603,63 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
       const float *__restrict__ rc[JB];
       float m[JB];
       int g[JB];
-      float8_t r[JB];
 #pragma unroll
       for (int x = 0; x < JB; ++x) {
         rc[x] = rk + (size_t)jj[x] * SP;
         m[x] = GS_INF;
         g[x] = 0;
-        r[x] = *reinterpret_cast<const float8_t *>(rc[x]);
       }
-      for (int q = 0; q < nq; ++q) {
-        const int qn = q + 1 < nq ? q + 1 : q;
-        float8_t n[JB];
+      if constexpr (JB <= 2) {
+        // sixteen transition values per scalar request (two chunks), the next request in
+        // flight meanwhile: 2 x JB x 16 scalar registers
+        float16_t r[JB];
 #pragma unroll
-        for (int x = 0; x < JB; ++x) n[x] = *reinterpret_cast<const float8_t *>(rc[x] + 8 * qn);
-        const float *tq = tile + (8 * q) * kWave + lane;
-        float c[8];
+        for (int x = 0; x < JB; ++x) r[x] = *reinterpret_cast<const float16_t *>(rc[x]);
+        for (int p = 0; p < np; ++p) {
+          const int pn = p + 1 < np ? p + 1 : p;
+          float16_t n[JB];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
+          for (int x = 0; x < JB; ++x) n[x] = *reinterpret_cast<const float16_t *>(rc[x] + 16 * pn);
 #pragma unroll
-        for (int x = 0; x < JB; ++x) {
-          float cm = __builtin_fminf(c[0] + r[x][0], c[1] + r[x][1]);
+          for (int h = 0; h < 2; ++h) {
+            const float *tq = tile + (16 * p + 8 * h) * kWave + lane;
+            float c[8];
 #pragma unroll
-          for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[k] + r[x][k]);
-          chunk_update<WITH_BP>(m[x], g[x], cm, q);
-          r[x] = n[x];
+            for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
+#pragma unroll
+            for (int x = 0; x < JB; ++x) {
+              float cm = __builtin_fminf(c[0] + r[x][8 * h], c[1] + r[x][8 * h + 1]);
+#pragma unroll
+              for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[k] + r[x][8 * h + k]);
+              chunk_update<WITH_BP>(m[x], g[x], cm, 2 * p + h);
+            }
+          }
+#pragma unroll
+          for (int x = 0; x < JB; ++x) r[x] = n[x];
+        }
+      } else {
+        // more columns per pass: eight values per request, or the scalar registers run out
+        float8_t r[JB];
+#pragma unroll
+        for (int x = 0; x < JB; ++x) r[x] = *reinterpret_cast<const float8_t *>(rc[x]);
+        const int nq = 2 * np;
+        for (int q = 0; q < nq; ++q) {
+          const int qn = q + 1 < nq ? q + 1 : q;
+          float8_t n[JB];
+#pragma unroll
+          for (int x = 0; x < JB; ++x) n[x] = *reinterpret_cast<const float8_t *>(rc[x] + 8 * qn);
+          const float *tq = tile + (8 * q) * kWave + lane;
+          float c[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
+#pragma unroll
+          for (int x = 0; x < JB; ++x) {
+            float cm = __builtin_fminf(c[0] + r[x][0], c[1] + r[x][1]);
+#pragma unroll
+            for (int k = 2; k < 8; ++k) cm = __builtin_fminf(cm, c[k] + r[x][k]);
+            chunk_update<WITH_BP>(m[x], g[x], cm, q);
+            r[x] = n[x];
+          }
         }
       }
 #pragma unroll
@@ -1306,7 +1340,7 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // backpointers, 5.5 against 5.8 without, but 8 K tiles 2.04 against 1.87 and 1.46 against
   // 1.27; S = 64 on a handful of tiles 0.08 against 0.09).
   // GSEARCH_KERNEL=3 forces it wherever its tile fits.
-  if (which == ForwardKernel::Auto && tsp == s.SP && s.SP % 8 == 0 && tuning().kernel != 1 &&
+  if (which == ForwardKernel::Auto && tsp == s.SP && s.SP % 16 == 0 && tuning().kernel != 1 &&
       tuning().kernel != 2) {
     const bool wide = tuning().kernel == 3 || tsp == 128 ||
                       (tsp == 96 && tile_inst <= 4096) ||
@@ -1348,7 +1382,7 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
     }
   }
   // Beyond the register-tiled sizes: the LDS-streamed tile kernel while the tile fits
-  if (!force_generic && tsp == 0 && s.SP % 8 == 0 && (size_t)s.SP * kWave * sizeof(float) <= 152 * 1024) {
+  if (!force_generic && tsp == 0 && s.SP % 16 == 0 && (size_t)s.SP * kWave * sizeof(float) <= 152 * 1024) {
     launch_wide(s, w, l, src, dst, bp_l, st);
     return "k_dp_wide";
   }

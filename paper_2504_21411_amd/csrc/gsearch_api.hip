@@ -21,7 +21,7 @@ gs::Shape make_shape(int B, int L, int S, int M, int K) {
   gs::Shape s;
   s.B = B; s.L = L; s.S = S; s.M = M; s.K = K;
   const int tsp = gs::class_sp_for(S);
-  s.SP = tsp ? tsp : (int)align_up((size_t)S, 8);
+  s.SP = tsp ? tsp : (int)align_up((size_t)S, 16); // (16: k_dp_wide takes two chunks per request)
   s.pitch = (int)align_up((size_t)M + 1, 64);
   s.bp16 = S > 256;
   s.Bc = B;
