@@ -1180,6 +1180,18 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
   launch_push_ru<SP, 1>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
 }
 
+// More than 64 KB of dynamic LDS per workgroup has to be asked for, per kernel and per
+// device: `granted` remembers the largest size already asked for on each device.
+constexpr int kMaxDevices = 64;
+static void lds_opt_in(const void *kernel, size_t lds, size_t (&granted)[kMaxDevices]) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+  if (lds > granted[dev]) {
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    granted[dev] = lds;
+  }
+}
+
 bool class_path_applies(const Shape &s) {
   const int tsp = class_sp_for(s.S);
   // the kernel addresses an instance's plane with 32-bit offsets and numbers its
@@ -1207,11 +1219,9 @@ static void launch_class_nc(const Shape &s, const Workspace &w, int l, const flo
   const dim3 grid = by_instance ? dim3((unsigned)s.B, (unsigned)tiles) : dim3((unsigned)(8 * per_xcd));
   const dim3 block(NW * kWave);
   const size_t lds = sizeof(float) * ((bp_l ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
-  if (lds > 64 * 1024) { // only the wide form at 128 strategies with backpointers: opt in once
-    static const hipError_t optin =
-        hipFuncSetAttribute((const void *)k_dp_class<SP, NW, true, NC>,
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)optin;
+  if (lds > 64 * 1024) { // the forms with backpointers from 128 (wide) or 192 strategies up
+    static size_t granted[kMaxDevices] = {};
+    lds_opt_in((const void *)k_dp_class<SP, NW, true, NC>, lds, granted);
   }
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true, NC>), grid, block, lds, st, src, dst,
@@ -1291,13 +1301,9 @@ static void launch_wide_as(const Shape &s, const Workspace &w, int l, const floa
   const long long tiles = (s.M + 1 + kWave - 1) / kWave;
   const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
   const size_t lds = (size_t)s.SP * kWave * sizeof(float);
-  if (lds > 64 * 1024) { // opt in to the large LDS allocation (the largest asked for so far)
-    static size_t granted = 0;
-    if (lds > granted) {
-      (void)hipFuncSetAttribute((const void *)k_dp_wide<BPT, NW, WITH_BP, JB>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      granted = lds;
-    }
+  if (lds > 64 * 1024) {
+    static size_t granted[kMaxDevices] = {};
+    lds_opt_in((const void *)k_dp_wide<BPT, NW, WITH_BP, JB>, lds, granted);
   }
   hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP, JB>), grid, block, lds, st, src, dst, (BPT *)bp_l,
                      w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, s.SP, l,
