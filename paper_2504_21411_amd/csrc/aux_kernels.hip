@@ -392,42 +392,80 @@ __global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
   const int cols = BY_CLASS ? NC : S;
   const size_t layer_stride = (size_t)B * cols * pitch;
   const size_t tab = (size_t)b * L * SP;
-  int ic[PL], cl[PL], o_cur[PL];
+  // Two layers per memory round trip: while the backpointer of layer l is in flight, every
+  // lane requests the backpointer of layer l-1 that would be needed if ITS strategy were the
+  // answer (the row e - O[l][s] is already known, only the strategy is not); the answer then
+  // picks its successor out of the lanes.
+  int ic[PL], cl[PL], o_cur[PL], o_low[PL];
+  const int lb = L > 1 ? L - 2 : 0;
 #pragma unroll
   for (int u = 0; u < PL; ++u) {
     const int i = lane + kWave * u;
     ic[u] = i < S ? i : 0;
     cl[u] = BY_CLASS ? cls[ic[u]] : 0;
     o_cur[u] = Oq[tab + (size_t)(L - 1) * SP + ic[u]];
+    o_low[u] = Oq[tab + (size_t)lb * SP + ic[u]];
   }
-  for (int l = L - 1; l >= 1; --l) {
-    if (lane == 0) plan[(size_t)q * L + l] = s;
-    int o = 0, col = s;
+  auto pick = [&](const int (&row)[PL], int idx) {
+    int r = 0;
 #pragma unroll
     for (int u = 0; u < PL; ++u) {
-      const int vo = __shfl(o_cur[u], s & 63, kWave);
-      const int vc = __shfl(cl[u], s & 63, kWave);
-      o = (s >> 6) == u ? vo : o;
-      if (BY_CLASS) col = (s >> 6) == u ? vc : col;
+      const int v = __shfl(row[u], idx & 63, kWave);
+      r = (idx >> 6) == u ? v : r;
     }
-    int o_nxt[PL];
-#pragma unroll
-    for (int u = 0; u < PL; ++u) o_nxt[u] = Oq[tab + (size_t)(l - 1) * SP + ic[u]];
+    return r;
+  };
+  int l = L - 1;
+  for (; l >= 2; l -= 2) {
+    const int o = pick(o_cur, s);
+    const int col = BY_CLASS ? pick(cl, s) : s;
     const int at = BY_CLASS ? e - o : e;
-    int prev = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * cols + col) * pitch + at];
-    asm volatile("" : "+v"(prev));
+    const int e1 = e - o; // budget row of layer l-1
+    int p1 = (int)bp[(size_t)(l - 1) * layer_stride + ((size_t)b * cols + col) * pitch + at];
+    int spec[PL];
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      const int cc = BY_CLASS ? cl[u] : ic[u];
+      int a2 = BY_CLASS ? e1 - o_low[u] : e1;
+      a2 = a2 > 0 ? a2 : 0; // a strategy that does not fit is never the answer
+      spec[u] = (int)bp[(size_t)(l - 2) * layer_stride + ((size_t)b * cols + cc) * pitch + a2];
+    }
+    int n0[PL], n1[PL]; // O rows of layers l-2 and l-3 for the next round
+    const int l3 = l >= 3 ? l - 3 : 0;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) {
+      n0[u] = Oq[tab + (size_t)(l - 2) * SP + ic[u]];
+      n1[u] = Oq[tab + (size_t)l3 * SP + ic[u]];
+    }
+    asm volatile("" : "+v"(p1));
+#pragma unroll
+    for (int u = 0; u < PL; ++u) asm volatile("" : "+v"(spec[u]));
+    const int s1 = p1;
+    const int o1 = pick(o_low, s1);
+    const int s2 = pick(spec, s1);
+    if (lane == 0) {
+      plan[(size_t)q * L + l] = s;
+      plan[(size_t)q * L + l - 1] = s1;
+    }
+    used += o + o1;
+    e = e1 - o1;
+    s = s2;
+#pragma unroll
+    for (int u = 0; u < PL; ++u) { o_cur[u] = n0[u]; o_low[u] = n1[u]; }
+  }
+  if (l == 1) { // an odd layer left over: the plain step
+    const int o = pick(o_cur, s);
+    const int col = BY_CLASS ? pick(cl, s) : s;
+    const int at = BY_CLASS ? e - o : e;
+    const int prev = (int)bp[((size_t)b * cols + col) * pitch + at];
+    if (lane == 0) plan[(size_t)q * L + 1] = s;
     used += o;
     e -= o;
     s = prev;
 #pragma unroll
-    for (int u = 0; u < PL; ++u) o_cur[u] = o_nxt[u];
+    for (int u = 0; u < PL; ++u) o_cur[u] = o_low[u];
   }
-  int o = 0;
-#pragma unroll
-  for (int u = 0; u < PL; ++u) {
-    const int vo = __shfl(o_cur[u], s & 63, kWave);
-    o = (s >> 6) == u ? vo : o;
-  }
+  const int o = pick(o_cur, s); // O[0][s]: the loops leave the row of layer 0 in o_cur
   if (lane == 0) {
     plan[(size_t)q * L] = s;
     if (mem_used) mem_used[q] = used + o;
