@@ -64,7 +64,9 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.cmeta = take(sizeof(int32_t) * 2);
   y.cstart = take(sizeof(int32_t) * (gs::kMaxClasses + 1));
   y.cls = take(sizeof(int32_t) * (size_t)s.SP);
-  y.Rc = take(sizeof(float) * (size_t)s.K * gs::kMaxClasses * gs::kMaxClasses);
+  // (more than 32 classes need more than 32 strategies)
+  const size_t ncap = s.S > 32 ? gs::kMaxClasses : 32;
+  y.Rc = take(sizeof(float) * (size_t)s.K * ncap * ncap);
   y.total = off;
   return y;
 }
