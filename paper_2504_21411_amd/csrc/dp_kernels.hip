@@ -505,33 +505,37 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
 }
 
 // ---------------------------------------------------------------------------------------
-// The same tile kernel for strategy counts beyond the register-tiled sizes (129 .. 608):
+// The same tile kernel for strategy counts beyond the register-tiled sizes (129 .. 1024):
 // the tile stays in LDS and level 1 streams it from there, JB target strategies per pass
 // so that every LDS read serves JB relaxations (4 / JB bytes of LDS traffic per relaxation; the
 // scalar transition values of the next chunk are requested while the current one is being
 // added up).  Same two-level argmin, same stores, uint8 or uint16 backpointers.  About half
 // the rate of the register-tiled kernel, against a seventieth for the pull-form fallback.
+// Tiles of 64 budget rows up to 608 strategies (152 KB of LDS), of 32 rows beyond.
 // ---------------------------------------------------------------------------------------
-template <typename BPT, int NW, bool WITH_BP, int JB>
+template <typename BPT, int NW, bool WITH_BP, int JB, int ROWS>
 __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
     const float *__restrict__ src, float *__restrict__ dst, BPT *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
     const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
     const int32_t *__restrict__ lowsum, int B, int L, int S, int SP, int l, int pitch) {
-  extern __shared__ float tile[]; // [SP][64]
+  // ROWS: budget rows per tile, 64, or 32 when S x 64 floats would not fit LDS (then the
+  // upper half of every wave repeats the lower half's rows and stores nothing)
+  extern __shared__ float tile[]; // [SP][ROWS]
   const int b = blockIdx.x % B;
-  const int tile_start = (int)(blockIdx.x / B) * kWave;
+  const int tile_start = (int)(blockIdx.x / B) * ROWS;
   const int js = wave_uniform(threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
+  const int lane = threadIdx.x & (ROWS - 1);
+  const bool act = ROWS == kWave || (threadIdx.x & 63) < ROWS; // this lane stores
   const int E = budget[b];
   if (tile_start > E) return; // whole workgroup
 
   const int row = tile_start + lane;
-  const bool valid = row <= E;
+  const bool valid = row <= E && act;
   const int bl = b * L + l;
   const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
-  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave > low; // uniform
+  const bool compute = tile_start <= E - minO[bl] && tile_start + ROWS > low; // uniform
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
@@ -546,7 +550,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
   if (compute) {
     // tile HBM -> LDS, four rows per wave in flight; padding strategies and rows beyond the
     // budget are +inf
-    const uint32_t rowc = (uint32_t)(valid ? row : E);
+    const uint32_t rowc = (uint32_t)(row <= E ? row : E);
     for (int i0 = js * 4; i0 < rows_used; i0 += NW * 4) {
       float v[4];
 #pragma unroll
@@ -554,11 +558,11 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
         const int i = i0 + u;
         const int ic = i < S ? i : S - 1;
         v[u] = (srcb + (size_t)ic * pitch)[rowc];
-        v[u] = (i < S && valid) ? v[u] : GS_INF;
+        v[u] = (i < S && row <= E) ? v[u] : GS_INF;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        if (i0 + u < rows_used) tile[(i0 + u) * kWave + lane] = v[u];
+        if (i0 + u < rows_used) tile[(i0 + u) * ROWS + lane] = v[u];
     }
     __syncthreads();
   }
@@ -569,7 +573,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
   // level 2 and the stores of one column (see k_dp_tile)
   auto finish = [&](int j, int o, float t, float m, int g) {
     if constexpr (WITH_BP) {
-      const float *tg = tile + (8 * g) * kWave + lane;        // per-lane slice of the tile
+      const float *tg = tile + (8 * g) * ROWS + lane;        // per-lane slice of the tile
       const float *__restrict__ rg = rk + (size_t)j * SP + 8 * g; // and of the column
       const float4 ra = *reinterpret_cast<const float4 *>(rg);
       const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
@@ -577,17 +581,17 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
       int kk = 0;
 #pragma unroll
       for (int k = 7; k >= 0; --k) { // descending: the lowest matching candidate wins
-        const float v = tg[k * kWave] + rr[k];
+        const float v = tg[k * ROWS] + rr[k];
         kk = (v == m) ? k : kk;
       }
       const int eo = row + o;
-      if (row >= low && eo <= E) {
+      if (act && row >= low && eo <= E) {
         (dstb + (size_t)j * pitch)[(uint32_t)eo] = m + t;
         (bpb + (size_t)j * pitch)[(uint32_t)eo] = (BPT)(8 * g + kk);
       }
     } else {
       const int eo = row + o;
-      if (row >= low && eo <= E) (dstb + (size_t)j * pitch)[(uint32_t)eo] = m + t;
+      if (act && row >= low && eo <= E) (dstb + (size_t)j * pitch)[(uint32_t)eo] = m + t;
     }
   };
   for (int j = jbeg; j < jend; j += JB) {
@@ -622,10 +626,10 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
           for (int x = 0; x < JB; ++x) n[x] = *reinterpret_cast<const float16_t *>(rc[x] + 16 * pn);
 #pragma unroll
           for (int h = 0; h < 2; ++h) {
-            const float *tq = tile + (16 * p + 8 * h) * kWave + lane;
+            const float *tq = tile + (16 * p + 8 * h) * ROWS + lane;
             float c[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
+            for (int k = 0; k < 8; ++k) c[k] = tq[k * ROWS];
 #pragma unroll
             for (int x = 0; x < JB; ++x) {
               float cm = __builtin_fminf(c[0] + r[x][8 * h], c[1] + r[x][8 * h + 1]);
@@ -648,10 +652,10 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
           float8_t n[JB];
 #pragma unroll
           for (int x = 0; x < JB; ++x) n[x] = *reinterpret_cast<const float8_t *>(rc[x] + 8 * qn);
-          const float *tq = tile + (8 * q) * kWave + lane;
+          const float *tq = tile + (8 * q) * ROWS + lane;
           float c[8];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) c[k] = tq[k * kWave];
+          for (int k = 0; k < 8; ++k) c[k] = tq[k * ROWS];
 #pragma unroll
           for (int x = 0; x < JB; ++x) {
             float cm = __builtin_fminf(c[0] + r[x][0], c[1] + r[x][1]);
@@ -1293,21 +1297,33 @@ void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {
   hipLaunchKernelGGL(k_zero_plane, dim3(blocks < 1 ? 1 : blocks), dim3(256), 0, st, q0, n);
 }
 
+template <typename BPT, bool WITH_BP, int ROWS>
+static void launch_wide_rows(const Shape &s, const Workspace &w, int l, const float *src,
+                             float *dst, void *bp_l, hipStream_t st) {
+  // target strategies per pass: four for the min-only scan, two with the argmin (measured)
+  constexpr int NW = 8, JB = WITH_BP ? 2 : 4;
+  const long long tiles = (s.M + 1 + ROWS - 1) / ROWS;
+  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
+  const size_t lds = (size_t)s.SP * ROWS * sizeof(float);
+  if (lds > 64 * 1024) {
+    static size_t granted[kMaxDevices] = {};
+    lds_opt_in((const void *)k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>, lds, granted);
+  }
+  hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>), grid, block, lds, st, src, dst,
+                     (BPT *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
+                     s.S, s.SP, l, s.pitch);
+}
+
+// 64-row tiles while S x 64 floats fit LDS (152 KB are asked for at most), else 32-row tiles
+static bool wide_fits(const Shape &s, int rows) {
+  return s.SP % 16 == 0 && (size_t)s.SP * rows * sizeof(float) <= 152 * 1024;
+}
+
 template <typename BPT, bool WITH_BP>
 static void launch_wide_as(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
                            void *bp_l, hipStream_t st) {
-  // target strategies per pass: four for the min-only scan, two with the argmin (measured)
-  constexpr int NW = 8, JB = WITH_BP ? 2 : 4;
-  const long long tiles = (s.M + 1 + kWave - 1) / kWave;
-  const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
-  const size_t lds = (size_t)s.SP * kWave * sizeof(float);
-  if (lds > 64 * 1024) {
-    static size_t granted[kMaxDevices] = {};
-    lds_opt_in((const void *)k_dp_wide<BPT, NW, WITH_BP, JB>, lds, granted);
-  }
-  hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP, JB>), grid, block, lds, st, src, dst, (BPT *)bp_l,
-                     w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, s.SP, l,
-                     s.pitch);
+  if (wide_fits(s, kWave)) launch_wide_rows<BPT, WITH_BP, 64>(s, w, l, src, dst, bp_l, st);
+  else launch_wide_rows<BPT, WITH_BP, 32>(s, w, l, src, dst, bp_l, st);
 }
 
 static void launch_wide(const Shape &s, const Workspace &w, int l, const float *src, float *dst,
@@ -1387,8 +1403,8 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
       default: break;
     }
   }
-  // Beyond the register-tiled sizes: the LDS-streamed tile kernel while the tile fits
-  if (!force_generic && tsp == 0 && s.SP % 16 == 0 && (size_t)s.SP * kWave * sizeof(float) <= 152 * 1024) {
+  // Beyond the register-tiled sizes: the LDS-streamed tile kernel (every S the library accepts)
+  if (!force_generic && tsp == 0 && wide_fits(s, 32)) {
     launch_wide(s, w, l, src, dst, bp_l, st);
     return "k_dp_wide";
   }

@@ -61,6 +61,8 @@ SHAPES = [
     # beyond the register-tiled sizes: the LDS-streamed tile kernel (uint8 and uint16 bp)
     (2, 3, 129, 130, 2), (3, 4, 200, 150, 1), (2, 3, 256, 70, 1), (2, 3, 300, 90, 2),
     (1, 3, 601, 40, 1),
+    # beyond 608 strategies the same kernel runs on 32-row tiles (tile tail at M = 75 and 100)
+    (2, 3, 609, 75, 1), (1, 3, 777, 100, 2),
 ]
 
 
