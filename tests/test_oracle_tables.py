@@ -72,6 +72,13 @@ def test_table_builder_exact_on_power_of_two_inputs(oracle_mod):
     rmodel = np.array([[h, n]], np.float64)
     T, O, R = oracle_mod.build_tables(desc, layer, hw, rmodel, M)
     Tx, Ox = _exact_tables(desc, h, q, n, F, BW, binb, keep, M)
+    # a bin size that divides none of the memories: the count of bins must round UP (a true
+    # quotient with denominator 3 is at least 1/3 away from an integer, far beyond the
+    # rounding of one fp64 division)
+    odd_bin = 3 << 22
+    _, O3, _ = oracle_mod.build_tables(desc, layer, np.array([F, BW, odd_bin, 0.25]), rmodel, M)
+    _, Ox3 = _exact_tables(desc, h, q, n, F, BW, odd_bin, keep, M)
+    assert O3[0, 0].tolist() == Ox3 and Ox3 != Ox
     for s, d in enumerate(desc.tolist()):
         want = np.float32(float(Tx[s]))
         if d[4] == 0:
@@ -163,6 +170,18 @@ def test_profiled_table_builder_exact_on_power_of_two_inputs(oracle_mod):
         assert abs(float(T[0, 0, s]) - float(want)) <= 4 * float(np.spacing(np.float32(float(want))))
         mem = Fraction(sf * param, tp * (dp if sdp else 1)) + Fraction(act, 1) * t / tp * (keep if ckpt else 1)
         assert O[0, 0, s] == min(max(1, int(-((-mem) // binb))), M + 1)
+    # a bin size that divides few of the memories: the count of bins rounds up
+    odd_bin = 3 << 22
+    _, O3 = oracle_mod.build_tables_profiled(
+        desc, [[0]], [[float(fwd), param, act]], [float(x) for x in bw],
+        [tokens, float(overlap), odd_bin, float(keep), sf], M)
+    ragged = 0
+    for s, (tp, sp, dp, sdp, ckpt) in enumerate(desc.tolist()):
+        mem = (Fraction(sf * param, tp * (dp if sdp else 1))
+               + Fraction(act, 1) * Fraction(tokens, dp * sp) / tp * (keep if ckpt else 1))
+        ragged += mem % odd_bin != 0
+        assert O3[0, 0, s] == min(max(1, int(-((-mem) // odd_bin))), M + 1)
+    assert ragged >= 10
     # more overlap can only hide data-parallel communication
     T2, _ = oracle_mod.build_tables_profiled(
         desc, [[0]], [[float(fwd), param, act]], [float(x) for x in bw],
