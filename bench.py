@@ -90,6 +90,9 @@ def main():
                     help="keep warming up at least this long (0 for short profiling runs)")
     ap.add_argument("--also", default="nobp,bp-general",
                     help="comma list of extra modes to time ('' for none)")
+    ap.add_argument("--also-configs", default="2",
+                    help="comma list of further configs to time once, with backpointers, and "
+                         "report beside the main line ('' for none)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -114,9 +117,9 @@ def main():
 
     w = workloads.get_config(args.config)
     dw = runner.DeviceWorkload(w)
-    relax = w.relaxations()
 
-    def time_mode(mode):
+    def time_mode(mode, w=w, dw=dw, cfg_index=args.config):
+        relax = w.relaxations()
         # "bp" / "nobp": with or without a backpointer stream; "-general": the layout classes
         # of the strategies are withheld from the solve, so the general kernels run
         classes = not mode.endswith("-general")
@@ -185,7 +188,7 @@ def main():
         launches = w.L - 1
         launch_s = fwd_ms * 1e-3 / launches
         common = {"kernel": kernel, "concurrent_launches": groups,
-                  "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, mode))}
+                  "traffic": MEASURED_TRAFFIC_BYTES.get((cfg_index, mode))}
         if kernel == "k_dp_class":
             # With the transition classes the arithmetic shrinks to one minimum per class
             # and one relaxation per pair of classes, and with the compact planes the
@@ -240,6 +243,14 @@ def main():
     if w.kind != "model":       # table workloads state no classes: "-general" is the same run
         also = [m for m in also if not m.endswith("-general")]
     extra = [time_mode(m) for m in also]
+    relax = w.relaxations()
+    others = []
+    for c in [int(x) for x in args.also_configs.split(",") if x and int(x) != args.config]:
+        wc = workloads.get_config(c)
+        res = time_mode("bp", wc, runner.DeviceWorkload(wc), c)
+        res["workload"] = f"configs[{c}] {wc.name}: B={wc.B} L={wc.L} S={wc.S} M={wc.M}"
+        res["relaxations_per_step"] = wc.relaxations()
+        others.append(res)
 
     line = {
         "metric": "G DP relaxations/sec (min-plus updates) + batch search latency, 1 MI355X",
@@ -258,6 +269,8 @@ def main():
     }
     if extra:
         line["other_modes"] = extra
+    if others:
+        line["other_configs"] = others
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, args.config)
     print(json.dumps(line))

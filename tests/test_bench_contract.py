@@ -46,3 +46,7 @@ def test_bench_prints_one_json_line_with_the_contract_keys(config):
     # value = nominal relaxations of the step / wall time of the step
     assert abs(d["value"] - d["config"]["relaxations_per_step"] / d["ms_per_step"] / 1e6) \
         <= 1e-6 * d["value"]
+    # the heterogeneous batch is timed beside the main workload
+    (o,) = d["other_configs"]
+    assert o["workload"].startswith("configs[2]") and o["ms_per_step"] > 0
+    assert 0 < o["roofline"]["frac"] <= 1.0
