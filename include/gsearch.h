@@ -76,6 +76,13 @@ typedef enum {
                                             kernel (flat four-instruction argmin)          */
 #define GSEARCH_FLAG_FORCE_TILE 0x10u     /* testing/tuning: always the LDS-staged kernel
                                             with the two-level argmin                      */
+#define GSEARCH_FLAG_NO_BIN_UNIT 0x20u    /* testing: do not rescale an instance whose memories
+                                            share a divisor.  By default an instance is solved
+                                            in its own bin unit g = gcd of the O[l][s] that fit
+                                            its budget at all (rows e .. e + g - 1 of a plane
+                                            are equal, so only one is computed): same costs
+                                            and plans bit for bit, mem_used, budget curve and
+                                            export still in the caller's bins               */
 
 /* bits of the data-status word */
 #define GSEARCH_DATA_BAD_T 0x1

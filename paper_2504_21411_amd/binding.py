@@ -27,6 +27,7 @@ GSEARCH_FLAG_FORCE_GENERIC = 0x2
 GSEARCH_FLAG_NO_BACKPOINTERS = 0x4
 GSEARCH_FLAG_FORCE_PUSH = 0x8
 GSEARCH_FLAG_FORCE_TILE = 0x10
+GSEARCH_FLAG_NO_BIN_UNIT = 0x20
 
 GSEARCH_DATA_BAD_T = 0x1
 GSEARCH_DATA_BAD_R = 0x2

@@ -89,6 +89,89 @@ __global__ __launch_bounds__(256) void k_prepare(
 __global__ void k_clear_status(int32_t *status) { *status = 0; }
 
 // ----------------------------------------------------------------------------------------
+// Bin unit of an instance.  Let g be the greatest common divisor of the memories O[l][s]
+// that can fit at all (O <= E; the others never fit whatever the unit).  Every reachable
+// memory sum is a multiple of g, so C[l][e][s] depends on e only through floor(e / g), and
+// the instance can be solved with O / g under the budget floor(E / g): the same plans are
+// feasible, their costs are the same sums, every argmin sees the same candidates, and the
+// planes have g times fewer rows.  This kernel (one workgroup per instance) finds g,
+// rewrites the sanitised O table, its per-layer minima and the budget in that unit and
+// keeps g and the budget in the caller's bins for the readers that report in the caller's
+// bins (memory of a plan, budget curve, export).  g = 1 when nothing fits, when everything
+// that fits needs no memory, or when the compression is switched off.
+// Each wave stops scanning as soon as its running divisor is 1, the usual case.
+// ----------------------------------------------------------------------------------------
+static __device__ __forceinline__ int gcd_i32(int a, int b) { // a, b >= 0; gcd(0, x) = x
+  while (b != 0) {
+    const int t = a % b;
+    a = b;
+    b = t;
+  }
+  return a;
+}
+
+static __device__ __forceinline__ int wave_gcd(int g) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) g = gcd_i32(g, __shfl_xor(g, d, kWave));
+  return g;
+}
+
+__global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
+                                                  int32_t *__restrict__ budget,
+                                                  int32_t *__restrict__ budget0,
+                                                  int32_t *__restrict__ unit,
+                                                  int32_t *__restrict__ minO, int L, int SP,
+                                                  int M, int enable) {
+  __shared__ int red[4];
+  const int b = blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int lane = threadIdx.x & 63;
+  const int E0 = budget[b];
+  const int n = L * SP;
+  int32_t *__restrict__ o = Oq + (size_t)b * n;
+  int g = 0; // divisor of what this wave has seen so far (0: nothing yet)
+  if (enable) {
+    for (int x0 = wave * kWave; x0 < n; x0 += 4 * kWave) {
+      const int x = x0 + lane;
+      const int v = x < n ? o[x] : 0;
+      g = wave_gcd(gcd_i32(g, v <= E0 ? v : 0));
+      if (g == 1) break; // wave-uniform
+    }
+  } else {
+    g = 1;
+  }
+  if (lane == 0) red[wave] = g;
+  __syncthreads(); // also: every thread has read the budget before thread 0 rewrites it
+  g = gcd_i32(gcd_i32(red[0], red[1]), gcd_i32(red[2], red[3]));
+  g = g < 1 ? 1 : g;
+  if (g > 1) {
+    for (int x = threadIdx.x; x < n; x += 256) {
+      const int v = o[x];
+      if (v <= E0) o[x] = v / g;
+    }
+    __syncthreads();
+    for (int l = wave; l < L; l += 4) {
+      int mo = M + 1;
+      for (int s = lane; s < SP; s += kWave) {
+        const int v = o[l * SP + s];
+        mo = v < mo ? v : mo;
+      }
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) {
+        const int other = __shfl_xor(mo, d, kWave);
+        mo = other < mo ? other : mo;
+      }
+      if (lane == 0) minO[(size_t)b * L + l] = mo;
+    }
+  }
+  if (threadIdx.x == 0) {
+    budget0[b] = E0;
+    budget[b] = E0 / g;
+    unit[b] = g;
+  }
+}
+
+// ----------------------------------------------------------------------------------------
 // Transition classes.  The caller's r_class[S] promises that R depends on the strategies
 // only through contiguous classes.  Block 0 checks the partition itself (starts at 0, steps
 // of 0 or 1, at most NC classes) and writes its run table; every block checks a
@@ -335,6 +418,7 @@ __global__ void k_final_global(const float *__restrict__ ws_cost, int32_t *__res
 template <typename BPT>
 __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__restrict__ Oq,
                                const int32_t *__restrict__ budget,
+                               const int32_t *__restrict__ unit,
                                const int32_t *__restrict__ ws_s,
                                const int32_t *__restrict__ instances, int n,
                                int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B,
@@ -361,7 +445,7 @@ __global__ void k_backtrace_bp(const BPT *__restrict__ bp, const int32_t *__rest
   }
   plan[(size_t)q * L] = s;
   used += Oq[(size_t)b * L * SP + s];
-  if (mem_used) mem_used[q] = used;
+  if (mem_used) mem_used[q] = used * unit[b]; // back to the caller's bins
 }
 
 // The same walk by one WAVE per requested instance (S <= 64 PL, uint8 backpointers): the O
@@ -375,9 +459,9 @@ template <bool BY_CLASS, int PL>
 __global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
     const uint8_t *__restrict__ bp, const int32_t *__restrict__ Oq,
     const int32_t *__restrict__ cls, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ ws_s, const int32_t *__restrict__ instances, int n,
-    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP,
-    int NC, int pitch) {
+    const int32_t *__restrict__ unit, const int32_t *__restrict__ ws_s,
+    const int32_t *__restrict__ instances, int n, int32_t *__restrict__ plan,
+    int32_t *__restrict__ mem_used, int B, int L, int S, int SP, int NC, int pitch) {
   const int q = blockIdx.x;
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
@@ -468,7 +552,7 @@ __global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
   const int o = pick(o_cur, s); // O[0][s]: the loops leave the row of layer 0 in o_cur
   if (lane == 0) {
     plan[(size_t)q * L] = s;
-    if (mem_used) mem_used[q] = used + o;
+    if (mem_used) mem_used[q] = (used + o) * unit[b]; // back to the caller's bins
   }
 }
 
@@ -486,6 +570,7 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
                                    const int32_t *__restrict__ lowsum,
                                    const int32_t *__restrict__ ridx,
                                    const int32_t *__restrict__ budget,
+                                   const int32_t *__restrict__ unit,
                                    const int32_t *__restrict__ ws_s,
                                    const int32_t *__restrict__ instances, int n,
                                    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used,
@@ -534,7 +619,7 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
   if (lane == 0) {
     plan[(size_t)q * L] = s;
     used += Oq[(size_t)b * L * SP + s];
-    if (mem_used) mem_used[q] = used;
+    if (mem_used) mem_used[q] = used * unit[b]; // back to the caller's bins
   }
 }
 
@@ -549,9 +634,10 @@ __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     const float *__restrict__ planes, const float *__restrict__ Rt, const float *__restrict__ Tq,
     const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
     const int32_t *__restrict__ lowsum, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ ws_s,
-    const int32_t *__restrict__ instances, int n, int32_t *__restrict__ plan,
-    int32_t *__restrict__ mem_used, int B, int L, int S, int SP, int Sc, int M, int pitch) {
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ unit,
+    const int32_t *__restrict__ ws_s, const int32_t *__restrict__ instances, int n,
+    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP,
+    int Sc, int M, int pitch) {
   const int q = blockIdx.x;
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
@@ -661,7 +747,7 @@ __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     const int v = __shfl(o_cur[u], s & 63, kWave);
     o = (s >> 6) == u ? v : o;
   }
-  if (lane == 0 && mem_used) mem_used[q] = used + o;
+  if (lane == 0 && mem_used) mem_used[q] = (used + o) * unit[b]; // back to the caller's bins
 }
 
 // Pipeline-aware outer reduction: one thread per candidate (pipeline degree, stage split,
@@ -696,20 +782,24 @@ __global__ void k_pipeline_groups(const float *__restrict__ stage_cost, int B, i
 }
 
 // curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf above.  BY_CLASS: from the compact
-// plane, C[L-1][e][s] = Q[class s][e - O[L-1][s]] + T[L-1][s].
+// plane, C[L-1][e][s] = Q[class s][e - O[L-1][s]] + T[L-1][s].  The plane is indexed in the
+// instance's own bin unit g (row e / g holds the caller's rows e .. e + g - 1); budget0 is the
+// budget in the caller's bins.
 template <bool BY_CLASS>
-__global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__restrict__ budget,
+__global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__restrict__ budget0,
+                               const int32_t *__restrict__ unit,
                                const int32_t *__restrict__ status, const float *__restrict__ Tq,
                                const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
                                const int32_t *__restrict__ lowsum, float *__restrict__ curve,
                                int B, int L, int S, int SP, int Sc, int M, int pitch) {
   const int b = blockIdx.x % B;
-  const int e = (blockIdx.x / B) * blockDim.x + threadIdx.x;
-  if (e > M) return;
+  const int e0 = (blockIdx.x / B) * blockDim.x + threadIdx.x; // row in the caller's bins
+  if (e0 > M) return;
+  const int e = e0 / unit[b];
   const size_t tab = ((size_t)b * L + L - 1) * SP;
   const int ql = (BY_CLASS && L > 1) ? lowsum[(size_t)b * L + L - 2] : 0; // as in k_final_instance
   float m = GS_INF;
-  if (e <= budget[b] && *status == 0)
+  if (e0 <= budget0[b] && *status == 0)
     for (int s = 0; s < S; ++s) {
       float v;
       if (BY_CLASS) {
@@ -721,7 +811,7 @@ __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__
       }
       m = v < m ? v : m;
     }
-  curve[(size_t)b * (M + 1) + e] = m;
+  curve[(size_t)b * (M + 1) + e0] = m;
 }
 
 // Canonical [b][l][e][s] export of the kept planes and backpointers (debug).  BY_CLASS: the
@@ -729,7 +819,8 @@ __global__ void k_budget_curve(const float *__restrict__ last, const int32_t *__
 // class, source row); both are expanded here.
 template <typename BPT, bool BY_CLASS>
 __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict__ bp,
-                         const int32_t *__restrict__ budget, const float *__restrict__ Tq,
+                         const int32_t *__restrict__ budget0,
+                         const int32_t *__restrict__ unit, const float *__restrict__ Tq,
                          const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
                          const int32_t *__restrict__ lowsum, float *__restrict__ C,
                          int32_t *__restrict__ bpo, int B, int L, int S, int SP, int Sc, int NC,
@@ -739,10 +830,11 @@ __global__ void k_export(const float *__restrict__ planes, const BPT *__restrict
   for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
        x += (long long)gridDim.x * blockDim.x) {
     const int s = (int)(x % S);
-    const int e = (int)((x / S) % (M + 1));
+    const int e0 = (int)((x / S) % (M + 1)); // row in the caller's bins
     const int l = (int)((x / ((long long)S * (M + 1))) % L);
     const int b = (int)(x / ((long long)S * (M + 1) * L));
-    const bool in = e <= budget[b];
+    const bool in = e0 <= budget0[b];
+    const int e = e0 / unit[b]; // the planes are indexed in the instance's own bin unit
     const size_t off = ((size_t)b * S + s) * pitch + e;
     const size_t tab = ((size_t)b * L + l) * SP + s;
     const int src = e - Oq[tab]; // source row of this state
@@ -1043,13 +1135,15 @@ static unsigned blocks_for(long long items, int threads, long long cap = 65535) 
 
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
                     const int32_t *r_index, const int32_t *budget, const Workspace &w,
-                    hipStream_t st) {
+                    bool compress_bins, hipStream_t st) {
   hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, w.status);
   const long long nr = (long long)s.K * s.SP * s.SP + s.SP;
   const long long waves = (long long)s.B * s.L + (nr + kWave - 1) / kWave + (s.B + kWave - 1) / kWave;
   hipLaunchKernelGGL(k_prepare, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, T, O, R,
                      r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B,
                      s.L, s.S, s.M, s.K, s.SP);
+  hipLaunchKernelGGL(k_bin_unit, dim3(s.B), dim3(256), 0, st, w.Oq, w.budget, w.budget0, w.unit,
+                     w.minO, s.L, s.SP, s.M, compress_bins ? 1 : 0);
   hipLaunchKernelGGL(k_prefix_min_memory, dim3(s.B), dim3(kWave), 0, st, w.minO, w.lowsum, s.B,
                      s.L, s.M);
 }
@@ -1096,7 +1190,7 @@ static void launch_backtrace_bp_rows(const Shape &s, const Workspace &w, const i
   const dim3 grid(n), block(kWave);
 #define GS_ROWS(PL)                                                                          \
   hipLaunchKernelGGL((k_backtrace_bp_rows<BY_CLASS, PL>), grid, block, 0, st,               \
-                     (const uint8_t *)w.bp, w.Oq, w.cls, w.budget, w.best_s, instances, n,  \
+                     (const uint8_t *)w.bp, w.Oq, w.cls, w.budget, w.unit, w.best_s, instances, n, \
                      plan, mem_used, s.B, s.L, s.S, s.SP, s.NC, s.pitch)
   if (s.S <= 64) GS_ROWS(1);
   else if (s.S <= 128) GS_ROWS(2);
@@ -1112,7 +1206,7 @@ void launch_backtrace_bp(const Shape &s, const Workspace &w, const int32_t *inst
     return;
   }
   hipLaunchKernelGGL((k_backtrace_bp<uint16_t>), dim3((n + 63) / 64), dim3(64), 0, st,
-                     (const uint16_t *)w.bp, w.Oq, w.budget, w.best_s, instances, n, plan, mem_used,
+                     (const uint16_t *)w.bp, w.Oq, w.budget, w.unit, w.best_s, instances, n, plan, mem_used,
                      s.B, s.L, s.S, s.SP, s.pitch);
 }
 
@@ -1122,14 +1216,14 @@ static void launch_backtrace_planes_of(const Shape &s, const Workspace &w, const
   const dim3 grid(n), block(kWave);
 #define GS_ROWS(PL)                                                                              \
   hipLaunchKernelGGL((k_backtrace_planes_rows<BY_CLASS, PL>), grid, block, 0, st, w.planes, w.Rt, \
-                     w.Tq, w.Oq, w.cls, w.lowsum, w.ridx, w.budget, w.best_s, instances, n, plan, \
+                     w.Tq, w.Oq, w.cls, w.lowsum, w.ridx, w.budget, w.unit, w.best_s, instances, n, plan, \
                      mem_used, s.B, s.L, s.S, s.SP, class_rows(s), s.M, s.pitch)
   if (s.S <= 64) GS_ROWS(1);
   else if (s.S <= 128) GS_ROWS(2);
   else if (s.S <= 256) GS_ROWS(4);
   else
     hipLaunchKernelGGL((k_backtrace_planes<BY_CLASS>), grid, block, 0, st, w.planes, w.Rt, w.Tq,
-                       w.Oq, w.cls, w.lowsum, w.ridx, w.budget, w.best_s, instances, n, plan,
+                       w.Oq, w.cls, w.lowsum, w.ridx, w.budget, w.unit, w.best_s, instances, n, plan,
                        mem_used, s.B, s.L, s.S, s.SP, class_rows(s), s.pitch);
 #undef GS_ROWS
 }
@@ -1154,11 +1248,11 @@ void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_p
   const int per = (s.M + 1 + 255) / 256;
   const dim3 grid((unsigned)((size_t)per * s.B)), block(256);
   if (w.by_class)
-    hipLaunchKernelGGL((k_budget_curve<true>), grid, block, 0, st, last_plane, w.budget, w.status,
+    hipLaunchKernelGGL((k_budget_curve<true>), grid, block, 0, st, last_plane, w.budget0, w.unit, w.status,
                        w.Tq, w.Oq, w.cls, w.lowsum, curve, s.B, s.L, s.S, s.SP, class_rows(s), s.M,
                        s.pitch);
   else
-    hipLaunchKernelGGL((k_budget_curve<false>), grid, block, 0, st, last_plane, w.budget,
+    hipLaunchKernelGGL((k_budget_curve<false>), grid, block, 0, st, last_plane, w.budget0, w.unit,
                        w.status, w.Tq, w.Oq, w.cls, w.lowsum, curve, s.B, s.L, s.S, s.SP,
                        class_rows(s), s.M, s.pitch);
 }
@@ -1168,15 +1262,15 @@ void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hi
   const dim3 grid(blocks_for(total, 256, 1 << 20)), block(256);
   if (w.by_class)
     hipLaunchKernelGGL((k_export<uint8_t, true>), grid, block, 0, st, w.planes,
-                       (const uint8_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
+                       (const uint8_t *)w.bp, w.budget0, w.unit, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
                        s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
   else if (s.bp16)
     hipLaunchKernelGGL((k_export<uint16_t, false>), grid, block, 0, st, w.planes,
-                       (const uint16_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp,
+                       (const uint16_t *)w.bp, w.budget0, w.unit, w.Tq, w.Oq, w.cls, w.lowsum, C, bp,
                        s.B, s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
   else
     hipLaunchKernelGGL((k_export<uint8_t, false>), grid, block, 0, st, w.planes,
-                       (const uint8_t *)w.bp, w.budget, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
+                       (const uint8_t *)w.bp, w.budget0, w.unit, w.Tq, w.Oq, w.cls, w.lowsum, C, bp, s.B,
                        s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
 }
 

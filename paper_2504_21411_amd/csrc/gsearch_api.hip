@@ -12,8 +12,8 @@ namespace {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-  size_t planes, bp, Tq, Oq, Rt, ridx, budget, minO, lowsum, best_s, best_cost, status, cmeta,
-      cstart, cls, Rc, total;
+  size_t planes, bp, Tq, Oq, Rt, ridx, budget, budget0, unit, minO, lowsum, best_s, best_cost,
+      status, cmeta, cstart, cls, Rc, total;
   int nplanes;
 };
 
@@ -56,6 +56,8 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.Rt = take(sizeof(float) * ((size_t)s.K * s.SP * s.SP + s.SP));
   y.ridx = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.budget = take(sizeof(int32_t) * (size_t)s.B);
+  y.budget0 = take(sizeof(int32_t) * (size_t)s.B);
+  y.unit = take(sizeof(int32_t) * (size_t)s.B);
   y.minO = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.lowsum = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.best_s = take(sizeof(int32_t) * (size_t)s.B);
@@ -77,7 +79,7 @@ bool config_ok(const gsearch_config *c) {
          c->max_L <= (1 << 16) && c->max_M <= (1 << 24) && c->max_K <= (1 << 16) &&
          (c->flags & ~(GSEARCH_FLAG_KEEP_PLANES | GSEARCH_FLAG_FORCE_GENERIC |
                        GSEARCH_FLAG_NO_BACKPOINTERS | GSEARCH_FLAG_FORCE_PUSH |
-                       GSEARCH_FLAG_FORCE_TILE)) == 0;
+                       GSEARCH_FLAG_FORCE_TILE | GSEARCH_FLAG_NO_BIN_UNIT)) == 0;
 }
 
 // Makes the context's device current for the duration of a call.
@@ -167,6 +169,8 @@ gs::Workspace group_view(const gs::Shape &s, const gs::Workspace &w, int b0) {
   g.Oq = w.Oq + (size_t)b0 * s.L * s.SP;
   g.ridx = w.ridx + (size_t)b0 * s.L;
   g.budget = w.budget + b0;
+  g.budget0 = w.budget0 + b0;
+  g.unit = w.unit + b0;
   g.minO = w.minO + (size_t)b0 * s.L;
   g.lowsum = w.lowsum + (size_t)b0 * s.L;
   return g;
@@ -271,6 +275,8 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   w.Rt = reinterpret_cast<float *>(base + y.Rt);
   w.ridx = reinterpret_cast<int32_t *>(base + y.ridx);
   w.budget = reinterpret_cast<int32_t *>(base + y.budget);
+  w.budget0 = reinterpret_cast<int32_t *>(base + y.budget0);
+  w.unit = reinterpret_cast<int32_t *>(base + y.unit);
   w.minO = reinterpret_cast<int32_t *>(base + y.minO);
   w.lowsum = reinterpret_cast<int32_t *>(base + y.lowsum);
   w.best_s = reinterpret_cast<int32_t *>(base + y.best_s);
@@ -292,7 +298,8 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   else if (c.flags & GSEARCH_FLAG_FORCE_PUSH) which = gs::ForwardKernel::Push;
   else if (c.flags & GSEARCH_FLAG_FORCE_TILE) which = gs::ForwardKernel::Tile;
 
-  gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w, st);
+  gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w,
+                     !(c.flags & GSEARCH_FLAG_NO_BIN_UNIT), st);
   // Transition classes: checked whenever the caller states them, exploited by the class
   // kernel when no particular kernel is forced and the shape has a register-tiled size.
   if (p->r_class && s.L > 1) gs::launch_prepare_classes(s, p->r_class, w, st);

@@ -39,10 +39,13 @@ struct Workspace {
                      // bpc[l][class sj][e - O[l][sj]] when that row is >= lowsum[l-1], else 0
                      // (every strategy of a class shares the argmin)
   float *Tq;         // [B][L][SP]   sanitised copy of T
-  int32_t *Oq;       // [B][L][SP]   sanitised copy of O, clamped to [0, M+1]
+  int32_t *Oq;       // [B][L][SP]   sanitised copy of O, clamped to [0, M+1], divided by unit
   float *Rt;         // [K][SP][SP]  transposed copy: Rt[k][sj][si] = R[k][si][sj]
   int32_t *ridx;     // [B][L]       clamped r_index (entry l=0 is 0)
-  int32_t *budget;   // [B]          clamped budgets
+  int32_t *budget;   // [B]          clamped budgets, in the instance's own bin unit
+  int32_t *budget0;  // [B]          clamped budgets in the caller's bins
+  int32_t *unit;     // [B]          bin unit g of the instance (see k_bin_unit): Oq, minO,
+                     //              lowsum, budget and every plane row count multiples of g
   int32_t *minO;     // [B][L]       min_s Oq
   int32_t *lowsum;   // [B][L]       sum over layers 0..l of minO, clamped to M+1: budget rows
                      //              below it cannot hold any plan of layers 0..l (all +inf)
@@ -64,7 +67,7 @@ inline int class_rows(const Shape &s) { return s.S < s.NC ? s.S : s.NC; }
 // ---- launchers (all asynchronous on `st`) -------------------------------------------
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
                     const int32_t *r_index, const int32_t *budget, const Workspace &w,
-                    hipStream_t st);
+                    bool compress_bins, hipStream_t st);
 // Validates r_class and R against each other (status bit on violation) and fills
 // cmeta / cstart / cls / Rc; with an invalid partition it installs the one-class partition,
 // so that the class kernel stays memory-safe.  Must follow launch_prepare on the stream.

@@ -590,6 +590,9 @@ def _class_sweep_case(runner, oracle_mod, rng, case):
     budget = rng.randint(0, M, B).astype(np.int32)
     w, r_class = workloads.class_tables(f"csweep{case}", B, L, S, M, sizes, K=K, seed=9000 + case,
                                         budget=budget, coarse=(case % 2 == 0))
+    if case % 7 == 3:                              # memories with a common divisor
+        for b in range(B):
+            w.O[b] *= [1, 2, 3, 4, 6][(case + b) % 5]
     if case % 3 == 0:
         w.O[int(v[5]) % B, int(v[6]) % L, int(v[7]) % S] = 0
     if case % 5 == 0:
@@ -615,7 +618,7 @@ def test_class_kernel_random_sweep(gs, oracle_mod):
     """Sixty seeded random class-structured workloads: strategy counts around every
     register-tile size, random partitions of 1..64 classes, several matrices, ragged budgets,
     zero-memory and never-fitting strategies, forbidden class transitions, coarse values that
-    make sums collide, both modes, forced instance groups."""
+    make sums collide, memories with a common divisor, both modes, forced instance groups."""
     _, runner = gs
     rng = workloads.SplitMix64(777)
     for case in range(60):
@@ -912,3 +915,94 @@ def test_class_kernel_batch_sizes_that_are_not_a_multiple_of_eight(gs, oracle_mo
             got["data_status"] = ctx.gsearch_data_status()
             assert ctx.gsearch_forward_kernel() == "k_dp_class"
         assert_same(got, ref, w, f"B={B} {mode}")
+
+
+def _coarse_memories(w, units, seed):
+    """Multiply every instance's memories by its unit, then plant what must not disturb the
+    unit (a zero, entries beyond the budget that are no multiple of it) - and, for the last
+    instance, one entry that fits and is no multiple, which must bring its unit back to 1."""
+    rng = workloads.SplitMix64(seed)
+    v = rng.randint(0, 10 ** 6, 6 * w.B).reshape(w.B, 6)
+    for b in range(w.B):
+        w.O[b] *= int(units[b])
+        w.O[b, v[b, 0] % w.L, v[b, 1] % w.S] = 0
+        w.O[b, v[b, 2] % w.L, v[b, 3] % w.S] = int(w.budget[b]) + 1      # never fits
+        w.O[b, v[b, 4] % w.L, v[b, 5] % w.S] = w.M + 5                   # nor does this
+    b = w.B - 1
+    w.O[b, 0, 0] = 1 if w.budget[b] >= 1 else 0
+    return w
+
+
+@pytest.mark.parametrize("mode", ["bp", "nobp", "bp_push", "bp_tile", "nobp_push", "generic",
+                                  "class", "class_nobp"])
+def test_instances_are_solved_in_their_own_bin_unit(gs, oracle_mod, mode):
+    """Memories with a common divisor: the library divides it out per instance (fewer plane
+    rows), which must change nothing that is reported: costs, plans, memory in the caller's
+    bins, whole planes, backpointers and the budget curve, against the oracle on the
+    original tables.  Budgets that are no multiple of the unit, units that differ from
+    instance to instance, entries that never fit and are no multiple, zero memories."""
+    binding, runner = gs
+    import torch
+    units = np.array([4, 1, 3, 7, 2, 16, 5, 6], np.int32)
+    B, L, S, M = len(units), 6, 44, 700
+    budget = np.array([700, 650, 333, 699, 1, 640, 14, 500], np.int32)
+    rc = None
+    if mode.startswith("class"):
+        w, rc = workloads.class_tables("unit", B, L, S, M, [4] * 11, K=2, seed=61, budget=budget)
+        w.O = np.minimum(w.O, 20)
+        flags = binding.GSEARCH_FLAG_NO_BACKPOINTERS if mode == "class_nobp" else 0
+    else:
+        w = random_tables("unit", B, L, S, M, K=2, seed=61, budget=budget, o_hi=20)
+        flags = MODES[mode]
+    w = _coarse_memories(w, units, 62)
+    ref = oracle_batch(oracle_mod, w)
+    assert np.isfinite(ref["best_cost"]).sum() >= 5       # the budgets bind, but not all fail
+    for extra in (0, binding.GSEARCH_FLAG_NO_BIN_UNIT):
+        got = runner.solve_workload(w, flags | extra, r_class=rc)
+        assert_same(got, ref, w, f"{mode} flags {flags | extra:#x}")
+        if rc is not None:
+            assert got["forward_kernel"] == "k_dp_class"
+    # whole planes, backpointers and curve in the caller's bins
+    dw = runner.DeviceWorkload(w)
+    rct = None if rc is None else torch.from_numpy(rc).to(dw.device)
+    with runner.make_context(w, flags=flags | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
+        out = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rct,
+                                              r_class_bound=0 if rc is None else 11))
+        C, bp = ctx.gsearch_export_planes(want_bp="nobp" not in mode)
+        curve = ctx.gsearch_budget_curve().cpu().numpy()
+        C = C.cpu().numpy()
+        bp = bp.cpu().numpy() if bp is not None else None
+    for b in range(B):
+        E = int(w.budget[b])
+        one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True,
+                               want_curve=True)
+        assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (mode, b)
+        assert np.isinf(C[b, :, E + 1:, :]).all()
+        if bp is not None:
+            assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), (mode, b)
+        assert np.array_equal(bits(curve[b, :E + 1]), bits(one["curve"])), (mode, b)
+        assert np.isinf(curve[b, E + 1:]).all()
+        assert np.array_equal(out["plan"][b], one["plan"]) and out["mem_used"][b] == one["mem_used"]
+
+
+def test_a_common_divisor_of_the_memories_shortens_the_forward_pass(gs, oracle_mod):
+    """The point of the bin unit: with every memory a multiple of 8 the planes have an eighth
+    of the rows.  Checked through the results (identical to the oracle's on the original
+    tables) and, loosely, through the forward time against the same solve with the rescaling
+    switched off."""
+    binding, runner = gs
+    w = random_tables("unit8", 32, 12, 64, 16000, seed=63, o_hi=150)
+    w.O *= 8
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    ms = {}
+    for flags in (0, binding.GSEARCH_FLAG_NO_BIN_UNIT):
+        with runner.make_context(w, flags=flags) as ctx:
+            ctx.gsearch_set_profiling(True)
+            for _ in range(3):
+                out = runner.run_step(ctx, dw, backtrace="all")
+            ms[flags] = ctx.gsearch_forward_ms()
+            got = runner.to_numpy(out)
+            got["data_status"] = ctx.gsearch_data_status()
+        assert_same(got, ref, w, f"flags {flags:#x}")
+    assert ms[0] < 0.5 * ms[binding.GSEARCH_FLAG_NO_BIN_UNIT], ms     # measured: 0.19 of it
