@@ -131,10 +131,16 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
   int32_t *__restrict__ o = Oq + (size_t)b * n;
   int g = 0; // divisor of what this wave has seen so far (0: nothing yet)
   if (enable) {
-    for (int x0 = wave * kWave; x0 < n; x0 += 4 * kWave) {
-      const int x = x0 + lane;
-      const int v = x < n ? o[x] : 0;
-      g = wave_gcd(gcd_i32(g, v <= E0 ? v : 0));
+    for (int x0 = wave * 4 * kWave; x0 < n; x0 += 16 * kWave) { // four loads in flight per lane
+      int v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int x = x0 + u * kWave + lane;
+        v[u] = x < n ? o[x] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) g = gcd_i32(g, v[u] <= E0 ? v[u] : 0);
+      g = wave_gcd(g);
       if (g == 1) break; // wave-uniform
     }
   } else {
