@@ -100,6 +100,12 @@ __global__ void k_clear_status(int32_t *status) { *status = 0; }
 // bins (memory of a plan, budget curve, export).  g = 1 when nothing fits, when everything
 // that fits needs no memory, or when the compression is switched off.
 // Each wave stops scanning as soon as its running divisor is 1, the usual case.
+//
+// Last, in the same unit: lowsum[b][l] = min(M+1, sum_{l' <= l} min_s O[l'][s]).  A plan of
+// layers 0..l needs at least that many bins, so C[l][e][.] is +inf for every e below it, and
+// the forward kernels fill those rows without computing them.  Wave 0 scans 64 layers per
+// round, inclusive scan across the lanes, carry from round to round (every term is at most
+// M + 1 <= 2^24 + 1 and the running sum is clamped each round, so int32 cannot overflow).
 // ----------------------------------------------------------------------------------------
 static __device__ __forceinline__ int gcd_i32(int a, int b) { // a, b >= 0; gcd(0, x) = x
   while (b != 0) {
@@ -120,7 +126,8 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
                                                   int32_t *__restrict__ budget,
                                                   int32_t *__restrict__ budget0,
                                                   int32_t *__restrict__ unit,
-                                                  int32_t *__restrict__ minO, int L, int SP,
+                                                  int32_t *__restrict__ minO,
+                                                  int32_t *__restrict__ lowsum, int L, int SP,
                                                   int M, int enable) {
   __shared__ int red[4];
   const int b = blockIdx.x;
@@ -174,6 +181,21 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
     budget0[b] = E0;
     budget[b] = E0 / g;
     unit[b] = g;
+  }
+  __syncthreads(); // the minima rewritten above are visible to wave 0
+  if (wave != 0) return;
+  int carry = 0;
+  for (int l0 = 0; l0 < L; l0 += kWave) {
+    const int l = l0 + lane;
+    int v = l < L ? minO[(size_t)b * L + l] : 0;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int up = __shfl_up(v, d, kWave);
+      if (lane >= d) v = (v + up > M + 1) ? M + 1 : v + up;
+    }
+    v = (v + carry > M + 1) ? M + 1 : v + carry;
+    if (l < L) lowsum[(size_t)b * L + l] = v;
+    carry = __shfl(v, kWave - 1, kWave);
   }
 }
 
@@ -277,31 +299,6 @@ __global__ __launch_bounds__(1024) void k_layout_classes(const int32_t *__restri
   }
   if (s < S) r_class[s] = flag[s];
   if (s == S - 1 && count_out) *count_out = flag[s] + 1;
-}
-
-// lowsum[b][l] = min(M+1, sum_{l' <= l} min_s O[l'][s]): a plan of layers 0..l needs at
-// least that many bins, so C[l][e][.] is +inf for every e below it.  The forward kernels
-// use it to fill those rows without computing them.  One wave per instance: 64 layers per
-// round, inclusive scan across the lanes, carry from round to round (every term is at most
-// M + 1 <= 2^24 + 1 and the running sum is clamped each round, so int32 cannot overflow).
-__global__ __launch_bounds__(kWave) void k_prefix_min_memory(const int32_t *__restrict__ minO,
-                                                             int32_t *__restrict__ lowsum, int B,
-                                                             int L, int M) {
-  const int b = blockIdx.x;
-  const int lane = threadIdx.x;
-  int carry = 0;
-  for (int l0 = 0; l0 < L; l0 += kWave) {
-    const int l = l0 + lane;
-    int v = l < L ? minO[(size_t)b * L + l] : 0;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-      const int up = __shfl_up(v, d, kWave);
-      if (lane >= d) v = (v + up > M + 1) ? M + 1 : v + up;
-    }
-    v = (v + carry > M + 1) ? M + 1 : v + carry;
-    if (l < L) lowsum[(size_t)b * L + l] = v;
-    carry = __shfl(v, kWave - 1, kWave);
-  }
 }
 
 // Layer 0 has no predecessor: C[0][e][s] = T[0][s] if e >= O[0][s] else +inf.
@@ -1149,9 +1146,7 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
                      r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B,
                      s.L, s.S, s.M, s.K, s.SP);
   hipLaunchKernelGGL(k_bin_unit, dim3(s.B), dim3(256), 0, st, w.Oq, w.budget, w.budget0, w.unit,
-                     w.minO, s.L, s.SP, s.M, compress_bins ? 1 : 0);
-  hipLaunchKernelGGL(k_prefix_min_memory, dim3(s.B), dim3(kWave), 0, st, w.minO, w.lowsum, s.B,
-                     s.L, s.M);
+                     w.minO, w.lowsum, s.L, s.SP, s.M, compress_bins ? 1 : 0);
 }
 
 void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,

@@ -721,7 +721,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
     const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
-    int l, int pitch, int tiles, unsigned div_magic, int div_shift) {
+    int l, int pitch, int src_pitch, int tiles, unsigned div_magic, int div_shift) {
   // NC: class capacity (32 or 64): registers for the class minima, rows of the class table
   constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
   extern __shared__ float lds[];
@@ -789,7 +789,9 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
 
   const int row = tile_start + lane;
   const size_t inst = (size_t)b * Sc * pitch;
-  const float *__restrict__ qs = qsrc + inst;
+  // (src_pitch == 0: Q[0] = 0 is not stored, every class of every instance reads one shared
+  // row of zeros)
+  const float *__restrict__ qs = src_pitch ? qsrc + inst : qsrc;
   float *__restrict__ qd = qdst + inst;
   uint8_t *__restrict__ bpb = WITH_BP ? bp + (size_t)b * NC * pitch : nullptr;
   if (tile_start + kWave <= low) return; // +inf throughout, implied by the bound, not stored
@@ -802,12 +804,12 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   // class c, shifted down by O, clamped to the start of the row.
   const int row4 = (row <= E ? row : -1) * 4;
   const char *__restrict__ qsb = reinterpret_cast<const char *>(qs);
-  const int pitch4 = pitch * 4;
+  const int spitch4 = src_pitch * 4;
   const int lowq4 = lowq * 4;
   float stage[PER];
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
-    const int cb = c_s[u] * pitch4;          // wave-uniform
+    const int cb = c_s[u] * spitch4;         // wave-uniform
     const int t = row4 + (cb - o_s[u] * 4);
     const float v = *reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb)) + t_s[u];
     stage[u] = t >= cb + lowq4 ? v : GS_INF; // source row >= lowq (and >= 0), row within budget
@@ -1222,6 +1224,7 @@ static void launch_class_nc(const Shape &s, const Workspace &w, int l, const flo
   const int div_shift = p - 32 > 0 ? p - 32 : 0;
   const dim3 grid = by_instance ? dim3((unsigned)s.B, (unsigned)tiles) : dim3((unsigned)(8 * per_xcd));
   const dim3 block(NW * kWave);
+  const int src_pitch = src == w.zero_row ? 0 : s.pitch; // the shared row of zeros stands for Q[0]
   const size_t lds = sizeof(float) * ((bp_l ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
   if (lds > 64 * 1024) { // the forms with backpointers from 128 (wide) or 192 strategies up
     static size_t granted[kMaxDevices] = {};
@@ -1230,12 +1233,12 @@ static void launch_class_nc(const Shape &s, const Workspace &w, int l, const flo
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true, NC>), grid, block, lds, st, src, dst,
                        (uint8_t *)bp_l, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, (int)tiles,
+                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, src_pitch, (int)tiles,
                        div_magic, div_shift);
   else
     hipLaunchKernelGGL((k_dp_class<SP, NW, false, NC>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, (int)tiles,
+                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, src_pitch, (int)tiles,
                        div_magic, div_shift);
 }
 

@@ -73,6 +73,10 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   return y;
 }
 
+// Behind the per-solve layout: one plane row of zeros, cleared when the context is created and
+// never written afterwards (it stands for Q[0] = 0 in the class kernel's first front).
+size_t zero_row_bytes(int max_M) { return align_up(((size_t)max_M + 1 + 63) / 64 * 64 * sizeof(float), 256); }
+
 bool config_ok(const gsearch_config *c) {
   return c && c->max_B >= 1 && c->max_L >= 1 && c->max_S >= 1 && c->max_S <= GSEARCH_MAX_S &&
          c->max_M >= 1 && c->max_K >= 1 && c->device >= 0 && c->max_B <= (1 << 20) &&
@@ -198,7 +202,8 @@ size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
   if (!config_ok(cfg)) return 0;
   return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
                      cfg->flags)
-      .total;
+             .total +
+         zero_row_bytes(cfg->max_M);
 }
 
 int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
@@ -223,6 +228,15 @@ int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
     return GSEARCH_ERR_NO_MEMORY;
   }
   ctx->base = static_cast<char *>(p);
+  const size_t zb = zero_row_bytes(cfg->max_M);
+  // (waited for here: solves may run on streams that do not order themselves after it)
+  if (hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) != hipSuccess ||
+      hipStreamSynchronize(nullptr) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(p);
+    delete ctx;
+    return GSEARCH_ERR_HIP;
+  }
   *out = ctx;
   return GSEARCH_OK;
 }
@@ -263,10 +277,12 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   // class capacity of this solve: the wide form only when the caller announces it
   if (p->r_class && p->r_class_bound > 32 && p->S > 32) s.NC = gs::kMaxClasses;
   const Layout y = make_layout(s, c.flags);
-  if (y.total > ctx->bytes) return GSEARCH_ERR_CAPACITY;
+  const size_t zb = zero_row_bytes(c.max_M);
+  if (y.total > ctx->bytes - zb) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
   w.by_class = 0;
   char *base = ctx->base;
+  w.zero_row = reinterpret_cast<const float *>(base + (ctx->bytes - zb));
   w.planes = reinterpret_cast<float *>(base + y.planes);
   const bool with_bp = !(c.flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
   w.bp = with_bp ? static_cast<void *>(base + y.bp) : nullptr;
@@ -325,8 +341,10 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
     ctx->forward_kernel = "k_dp_small";
     ctx->groups_used = 1;
   } else {
-    if (use_classes) gs::launch_class_zero(s, w.planes, st); // Q[0] = 0
-    else gs::launch_init_layer0(s, w, w.planes, st);
+    // Q[0] = 0: stored only when the planes are kept (the readers of kept planes read it);
+    // otherwise the first front reads the context's row of zeros for every class
+    if (use_classes && keep) gs::launch_class_zero(s, w.planes, st);
+    else if (!use_classes) gs::launch_init_layer0(s, w, w.planes, st);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
     const int groups = s.L > 1 ? group_count(s, ctx->groups, use_classes) : 1;
     ctx->groups_used = groups;
@@ -352,6 +370,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
                                    (size_t)b0 * bp_inst_bytes
                              : nullptr;
         const float *src_l = w.planes + (size_t)c2 * pe + (size_t)b0 * inst_elems;
+        if (use_classes && !keep && l == 1) src_l = w.zero_row; // Q[0] = 0 is not stored
         float *dst_l = w.planes + (size_t)nxt * pe + (size_t)b0 * inst_elems;
         ctx->forward_kernel = use_classes
                                   ? gs::launch_dp_class(sg, wg, l, src_l, dst_l, bp_l, sst)

@@ -34,6 +34,8 @@ struct Workspace {
   void *bp;          // [L-1][B][S][pitch]       uint8 or uint16 backpointers (may be null);
                      // after a class-kernel solve [L-1][B][NC][pitch] uint8 indexed by
                      // (target class, SOURCE row), see by_class
+  const float *zero_row; // [pitch of max_M] zeros, written once when the context is created:
+                     // source of the class kernel's first front when Q[0] = 0 is not stored
   int by_class;      // 1: the class kernel ran.  Planes are compact, C[l][e][s] =
                      // Q[l][class s][e - O[l][s]] + T[l][s] with Q[0] = 0, and bp[l][e][sj] =
                      // bpc[l][class sj][e - O[l][sj]] when that row is >= lowsum[l-1], else 0
