@@ -942,12 +942,13 @@ __global__ __launch_bounds__(1024) void k_enumerate(int N, int k, int tp_max, in
 // fp64, one rounding per operation in the order written (the file is compiled without
 // floating-point contraction), one final rounding to the output type.
 // ----------------------------------------------------------------------------------------
-__global__ void k_build_TO(int B, int L, int S, int M, const int32_t *__restrict__ desc,
-                           const double *__restrict__ layer, double F, double BW, double bin,
-                           double keep, float *__restrict__ T, int32_t *__restrict__ O) {
+static __device__ void build_TO(long long first, long long stride, int B, int L, int S, int M,
+                                const int32_t *__restrict__ desc,
+                                const double *__restrict__ layer, double F, double BW,
+                                double bin, double keep, float *__restrict__ T,
+                                int32_t *__restrict__ O) {
   const long long total = (long long)B * L * S;
-  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
-       x += (long long)gridDim.x * blockDim.x) {
+  for (long long x = first; x < total; x += stride) {
     const int s = (int)(x % S);
     const long long row = x / S;
     const double *p = layer + row * 6;
@@ -1101,11 +1102,12 @@ __global__ void k_build_TO_profiled(int B, int L, int S, int M, int Y, int NB,
   }
 }
 
-__global__ void k_build_R(int S, int K, const int32_t *__restrict__ desc,
-                          const double *__restrict__ rmodel, double BW, float *__restrict__ R) {
+static __device__ void build_R(long long first, long long stride, int S, int K,
+                               const int32_t *__restrict__ desc,
+                               const double *__restrict__ rmodel, double BW,
+                               float *__restrict__ R) {
   const long long total = (long long)K * S * S;
-  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
-       x += (long long)gridDim.x * blockDim.x) {
+  for (long long x = first; x < total; x += stride) {
     const int j = (int)(x % S), i = (int)((x / S) % S), k = (int)(x / ((long long)S * S));
     const int32_t *a = desc + i * 5, *c = desc + j * 5;
     float r = 0.0f;
@@ -1134,6 +1136,22 @@ static unsigned blocks_for(long long items, int threads, long long cap = 65535) 
   if (b < 1) b = 1;
   if (b > cap) b = cap;
   return (unsigned)b;
+}
+
+// Both tables of the alpha-beta model in one launch: the first nb_to workgroups fill T and O,
+// the others R.
+__global__ __launch_bounds__(256) void k_build_tables(
+    int nb_to, int B, int L, int S, int M, int K, const int32_t *__restrict__ desc,
+    const double *__restrict__ layer, double F, double BW, double bin, double keep,
+    const double *__restrict__ rmodel, float *__restrict__ T, int32_t *__restrict__ O,
+    float *__restrict__ R) {
+  const int nb = (int)blockIdx.x;
+  if (nb < nb_to)
+    build_TO((long long)nb * 256 + threadIdx.x, (long long)nb_to * 256, B, L, S, M, desc, layer, F,
+             BW, bin, keep, T, O);
+  else
+    build_R((long long)(nb - nb_to) * 256 + threadIdx.x, (long long)((int)gridDim.x - nb_to) * 256,
+            S, K, desc, rmodel, BW, R);
 }
 
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
@@ -1296,10 +1314,11 @@ void launch_build_tables(int B, int L, int S, int M, int K, const int32_t *desc,
                          const double *layer, double flops_per_s, double bytes_per_s,
                          double bin_bytes, double ckpt_keep, const double *rmodel, float *T,
                          int32_t *O, float *R, hipStream_t st) {
-  hipLaunchKernelGGL(k_build_TO, dim3(blocks_for((long long)B * L * S, 256)), dim3(256), 0, st, B,
-                     L, S, M, desc, layer, flops_per_s, bytes_per_s, bin_bytes, ckpt_keep, T, O);
-  hipLaunchKernelGGL(k_build_R, dim3(blocks_for((long long)K * S * S, 256)), dim3(256), 0, st, S,
-                     K, desc, rmodel, bytes_per_s, R);
+  const unsigned nb_to = blocks_for((long long)B * L * S, 256);
+  const unsigned nb_r = blocks_for((long long)K * S * S, 256);
+  hipLaunchKernelGGL(k_build_tables, dim3(nb_to + nb_r), dim3(256), 0, st, (int)nb_to, B, L, S, M,
+                     K, desc, layer, flops_per_s, bytes_per_s, bin_bytes, ckpt_keep, rmodel, T, O,
+                     R);
 }
 
 } // namespace gs
