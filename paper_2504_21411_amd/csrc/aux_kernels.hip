@@ -147,7 +147,8 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) g = gcd_i32(g, v[u] <= E0 ? v[u] : 0);
-      g = wave_gcd(g);
+      // (a lane that has reached 1 settles it for the wave without the reduction)
+      g = __builtin_amdgcn_ballot_w64(g == 1) != 0 ? 1 : wave_gcd(g);
       if (g == 1) break; // wave-uniform
     }
   } else {
