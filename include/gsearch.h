@@ -158,7 +158,8 @@ typedef struct {
 size_t gsearch_workspace_bytes(const gsearch_config *cfg);
 
 /* Create a context on cfg->device and allocate its workspace.
- * Errors: INVALID_ARG (null, sizes < 1, max_S > GSEARCH_MAX_S), NO_DEVICE, NO_MEMORY. */
+ * Errors: INVALID_ARG (null, sizes < 1, max_S > GSEARCH_MAX_S, unknown flag bits), NO_DEVICE,
+ * NO_MEMORY, HIP. */
 int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out);
 
 /* Free the workspace and the context.  NULL is accepted.  The caller must have

@@ -37,6 +37,7 @@ GSEARCH_DATA_BAD_RINDEX = 0x10
 GSEARCH_DATA_BAD_RCLASS = 0x20
 GSEARCH_MAX_CLASSES = 64
 GSEARCH_DEFAULT_CLASSES = 32
+GSEARCH_MAX_S = 1024
 
 EXPORTS = [
     "gsearch_workspace_bytes", "gsearch_create", "gsearch_destroy", "gsearch_solve_batch",

@@ -115,6 +115,25 @@ def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
                                                      header).group(1), 16)
 
 
+def test_binding_constants_equal_the_header():
+    """Every flag, data-status bit, limit and status code of the binding is the header's."""
+    from paper_2504_21411_amd import binding as b
+    header = open(os.path.join(ROOT, "include", "gsearch.h")).read()
+    defines = {m.group(1): int(m.group(2), 0) for m in
+               re.finditer(r"#define (GSEARCH_[A-Z0-9_]+) (0x[0-9a-fA-F]+|\d+)u?\b", header)}
+    enums = {m.group(1): int(m.group(2)) for m in
+             re.finditer(r"(GSEARCH_(?:OK|ERR_[A-Z_]+)) = (-?\d+)", header)}
+    assert len(defines) >= 15 and len(enums) >= 7
+    for name, value in {**defines, **enums}.items():
+        assert getattr(b, name) == value, name
+    for name in dir(b):
+        if name.startswith("GSEARCH_") and isinstance(getattr(b, name), int):
+            assert name in defines or name in enums, f"{name} is not in the header"
+    # a context refuses flag bits it does not know (before touching any device)
+    assert b.gsearch_workspace_bytes(1, 2, 2, 2, flags=0x40) == 0
+    assert b.gsearch_workspace_bytes(1, 2, 2, 2, flags=b.GSEARCH_FLAG_NO_BIN_UNIT) > 0
+
+
 def test_workspace_covers_class_tables_and_plane_slack(lib):
     """More strategies never shrink the workspace; small S still reserves the 32 backpointer
     columns of the class kernel and the slack block behind the planes."""
