@@ -78,7 +78,9 @@ void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Worksp
 bool class_path_applies(const Shape &s);
 // One layer front with the class kernel: src and dst are compact planes
 // [B][class_rows][pitch] holding Q[l-1] and Q[l], where
-// C[l][e][s] = Q[l][class s][e - O[l][s]] + T[l][s] and Q[0] = 0 (launch_class_zero).
+// C[l][e][s] = Q[l][class s][e - O[l][s]] + T[l][s] and Q[0] = 0: a plane filled by
+// launch_class_zero when the planes are kept, else src = w.zero_row, one row of zeros that
+// every class of every instance reads.
 const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st);
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
