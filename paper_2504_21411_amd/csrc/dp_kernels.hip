@@ -964,14 +964,31 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_generic(
 // workspace so that the final reductions, the budget curve and the plane-based backtrace
 // read what they always read.
 // ---------------------------------------------------------------------------------------
-template <typename BPT>
+// STAGED: the transition pool and the instance's T, O and r_index rows are copied to LDS
+// first (they fit next to the planes for every shape this path is chosen for unless the pool
+// or the layer count is unusually large): the scan of a target then waits for LDS reads
+// instead of a chain of scalar loads per target, which was most of a layer's time.
+template <typename BPT, bool STAGED>
 __global__ __launch_bounds__(1024) void k_dp_small(
     float *__restrict__ planes, BPT *__restrict__ bp, const float *__restrict__ Tq,
     const int32_t *__restrict__ Oq, const float *__restrict__ Rt,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget, int B, int L, int S,
-    int SP, int pitch, int keep_all, int last_plane) {
-  extern __shared__ float lds[]; // two planes of S * pitch floats
+    int SP, int K, int pitch, int keep_all, int last_plane) {
+  extern __shared__ float lds[]; // two planes of S * pitch floats, then the staged tables
   const int b = blockIdx.x;
+  float *Rl = lds + (size_t)2 * S * pitch;               // [K][SP][SP]
+  float *Tl = Rl + (size_t)K * SP * SP;                  // [L][SP]
+  int *Ol = reinterpret_cast<int *>(Tl + (size_t)L * SP); // [L][SP]
+  int *kl = Ol + (size_t)L * SP;                         // [L]
+  if constexpr (STAGED) {
+    for (int x = threadIdx.x; x < K * SP * SP; x += blockDim.x) Rl[x] = Rt[x];
+    for (int x = threadIdx.x; x < L * SP; x += blockDim.x) {
+      Tl[x] = Tq[(size_t)b * L * SP + x];
+      Ol[x] = Oq[(size_t)b * L * SP + x];
+    }
+    for (int x = threadIdx.x; x < L; x += blockDim.x) kl[x] = ridx[(size_t)b * L + x];
+    __syncthreads();
+  }
   const int E = budget[b];
   const int rows64 = (E + 1 + kWave - 1) / kWave * kWave; // threads along e
   const int groups = (int)blockDim.x / rows64;             // >= 1 by the launch condition
@@ -985,23 +1002,25 @@ __global__ __launch_bounds__(1024) void k_dp_small(
 
   if (active)
     for (int s = jg; s < S; s += groups) {
-      const float v = (e >= Oq[(size_t)b * L * SP + s]) ? Tq[(size_t)b * L * SP + s] : GS_INF;
+      const int o0 = STAGED ? Ol[s] : Oq[(size_t)b * L * SP + s];
+      const float t0 = STAGED ? Tl[s] : Tq[(size_t)b * L * SP + s];
+      const float v = (e >= o0) ? t0 : GS_INF;
       cur[s * pitch + e] = v;
       if (keep_all || L == 1) planes[plane_off + (size_t)s * pitch + e] = v;
     }
   for (int l = 1; l < L; ++l) {
     __syncthreads();
     const int bl = b * L + l;
-    const float *__restrict__ rk = Rt + (size_t)ridx[bl] * SP * SP;
+    const float *rk = STAGED ? Rl + (size_t)kl[l] * SP * SP : Rt + (size_t)ridx[bl] * SP * SP;
     float *gplane = planes + (keep_all ? (size_t)l * plane_elems_all : (size_t)last_plane * plane_elems_all) + plane_off;
     const bool to_global = keep_all || l == L - 1;
     if (active)
       for (int j = jg; j < S; j += groups) {
-        const int o = Oq[(size_t)bl * SP + j];
+        const int o = STAGED ? Ol[l * SP + j] : Oq[(size_t)bl * SP + j];
         float out = GS_INF;
         int arg = 0;
         if (e >= o) {
-          const float *__restrict__ rc = rk + (size_t)j * SP;
+          const float *rc = rk + (size_t)j * SP;
           const float *src = cur + (e - o);
           float m = GS_INF;
           // eight candidates at a time: the LDS reads and the scalar load of the eight
@@ -1017,7 +1036,7 @@ __global__ __launch_bounds__(1024) void k_dp_small(
               if (t < m) { m = t; arg = i0 + k; }
             }
           }
-          out = m + Tq[(size_t)bl * SP + j];
+          out = m + (STAGED ? Tl[l * SP + j] : Tq[(size_t)bl * SP + j]);
         }
         nxt[j * pitch + e] = out;
         if (to_global) gplane[(size_t)j * pitch + e] = out;
@@ -1029,37 +1048,73 @@ __global__ __launch_bounds__(1024) void k_dp_small(
 
 // The latency path applies when an instance's budget rows fit one workgroup, its two planes
 // fit LDS, and the batch is too small to fill the GPU through the per-layer kernels anyway.
-bool small_path_applies(const Shape &s) {
+bool small_path_applies(const Shape &s, bool with_bp) {
   if (s.M + 1 > 1024) return false;
   if ((size_t)2 * s.S * s.pitch * sizeof(float) > (size_t)96 * 1024) return false;
-  // Measured (24 layers, 1..8 instances): the one-launch kernel beats a launch per layer
-  // front only while a front is a few thousand relaxations per thread-row, e.g. S = 8 up to
-  // M = 300, S = 12 up to M = 130, S = 16 at M = 64; beyond that one workgroup per instance
-  // is too little parallelism (S = 24, M = 256: 0.27 ms against 0.13 ms).
-  if ((long long)s.S * s.S * (s.M + 1) > 20000) return false;
+  // One workgroup per instance means one compute unit per instance, so the one-launch kernel
+  // wins only while a thread's share of a layer front is short.  A thread owns a budget row
+  // and every groups-th target strategy, i.e. per = ceil(S / groups) scans of S candidates.
+  // Measured (24 layers, 1..64 instances, one launch against 23 launches of the tile
+  // kernel): S = 8: 42 against 70 us at M = 256 (per = 3), 94 against 74 at M = 512 (per =
+  // 8); S = 12: 55 against 84 at M = 128, even at M = 256; S = 16: 71 against 94 at M = 128,
+  // 111 against 103 at M = 256; S = 24: 94 against 117 at M = 64, even at M = 128.
+  // The rule below, per * S <= 34 + 2 S, reproduces those crossovers; the min-only tile
+  // kernel is faster (S = 12, M = 256: 77 us; S = 24, M = 64: 92 us), so that mode takes
+  // 20 + 2 S.  GSEARCH_SMALL = 0 / 1 (tuning) switches the path off / on wherever it fits.
+  static const int forced = [] {
+    const char *e = getenv("GSEARCH_SMALL");
+    return e ? atoi(e) : -1;
+  }();
+  if (forced == 0) return false;
+  const int rows64 = (s.M + 1 + kWave - 1) / kWave * kWave;
+  const int groups = s.S < 1024 / rows64 ? s.S : 1024 / rows64;
+  const int per = (s.S + groups - 1) / groups;
+  if (forced != 1 && per * s.S > (with_bp ? 34 : 20) + 2 * s.S) return false;
   const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
   return tiles <= 2048;
 }
 
+// More than 64 KB of dynamic LDS per workgroup has to be asked for, per kernel and per
+// device: `granted` remembers the largest size already asked for on each device.
+constexpr int kMaxDevices = 64;
+static void lds_opt_in(const void *kernel, size_t lds, size_t (&granted)[kMaxDevices]) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+  if (lds > granted[dev]) {
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    granted[dev] = lds;
+  }
+}
+
+template <typename BPT, bool STAGED>
+static void launch_small_as(const Shape &s, const Workspace &w, bool keep_all, int last_plane,
+                            size_t lds, int threads, hipStream_t st) {
+  if (lds > 64 * 1024) {
+    static size_t granted[kMaxDevices] = {};
+    lds_opt_in((const void *)k_dp_small<BPT, STAGED>, lds, granted);
+  }
+  hipLaunchKernelGGL((k_dp_small<BPT, STAGED>), dim3(s.B), dim3(threads), lds, st, w.planes,
+                     (BPT *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, s.SP, s.K,
+                     s.pitch, keep_all ? 1 : 0, last_plane);
+}
+
 void launch_dp_small(const Shape &s, const Workspace &w, bool keep_all, int last_plane,
                      hipStream_t st) {
-  const size_t lds = (size_t)2 * s.S * s.pitch * sizeof(float);
+  const size_t plane_bytes = (size_t)2 * s.S * s.pitch * sizeof(float);
+  const size_t table_bytes =
+      sizeof(float) * ((size_t)s.K * s.SP * s.SP + (size_t)2 * s.L * s.SP + (size_t)s.L);
+  const bool staged = table_bytes <= (size_t)48 * 1024; // planes take up to 96 KB of the 160
+  const size_t lds = plane_bytes + (staged ? table_bytes : 0);
   const int rows64 = (s.M + 1 + kWave - 1) / kWave * kWave;
   int threads = (1024 / rows64) * rows64; // whole groups of target strategies
   const int useful = ((s.S < 1024 / rows64) ? s.S : 1024 / rows64) * rows64;
   if (useful < threads) threads = useful;
   if (s.bp16) {
-    (void)hipFuncSetAttribute((const void *)k_dp_small<uint16_t>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((k_dp_small<uint16_t>), dim3(s.B), dim3(threads), lds, st, w.planes,
-                       (uint16_t *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, s.SP,
-                       s.pitch, keep_all ? 1 : 0, last_plane);
+    if (staged) launch_small_as<uint16_t, true>(s, w, keep_all, last_plane, lds, threads, st);
+    else launch_small_as<uint16_t, false>(s, w, keep_all, last_plane, lds, threads, st);
   } else {
-    (void)hipFuncSetAttribute((const void *)k_dp_small<uint8_t>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((k_dp_small<uint8_t>), dim3(s.B), dim3(threads), lds, st, w.planes,
-                       (uint8_t *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, s.SP,
-                       s.pitch, keep_all ? 1 : 0, last_plane);
+    if (staged) launch_small_as<uint8_t, true>(s, w, keep_all, last_plane, lds, threads, st);
+    else launch_small_as<uint8_t, false>(s, w, keep_all, last_plane, lds, threads, st);
   }
 }
 
@@ -1184,18 +1239,6 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
     if (ru >= 2) return launch_push_ru<SP, 2>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
   }
   launch_push_ru<SP, 1>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
-}
-
-// More than 64 KB of dynamic LDS per workgroup has to be asked for, per kernel and per
-// device: `granted` remembers the largest size already asked for on each device.
-constexpr int kMaxDevices = 64;
-static void lds_opt_in(const void *kernel, size_t lds, size_t (&granted)[kMaxDevices]) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
-  if (lds > granted[dev]) {
-    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    granted[dev] = lds;
-  }
 }
 
 bool class_path_applies(const Shape &s) {

@@ -333,7 +333,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   int cur = 0;
   ctx->timed = false;
   const bool timing = ctx->profiling && s.L > 1;
-  if (which == gs::ForwardKernel::Auto && !use_classes && gs::small_path_applies(s)) {
+  if (which == gs::ForwardKernel::Auto && !use_classes && gs::small_path_applies(s, with_bp)) {
     // latency path: layer 0 and every layer front in one launch, planes in LDS
     cur = keep ? s.L - 1 : ((s.L - 1) & 1);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;

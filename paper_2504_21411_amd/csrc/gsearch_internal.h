@@ -94,7 +94,7 @@ enum class ForwardKernel { Auto, Generic, Push, Tile };
 const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, ForwardKernel which, hipStream_t st);
 // Single-launch forward pass for small instances (includes layer 0); see dp_kernels.hip.
-bool small_path_applies(const Shape &s);
+bool small_path_applies(const Shape &s, bool with_bp);
 void launch_dp_small(const Shape &s, const Workspace &w, bool keep_all, int last_plane,
                      hipStream_t st);
 void launch_final(const Shape &s, const Workspace &w, const float *last_plane,

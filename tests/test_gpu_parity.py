@@ -1006,3 +1006,45 @@ def test_a_common_divisor_of_the_memories_shortens_the_forward_pass(gs, oracle_m
             got["data_status"] = ctx.gsearch_data_status()
         assert_same(got, ref, w, f"flags {flags:#x}")
     assert ms[0] < 0.5 * ms[binding.GSEARCH_FLAG_NO_BIN_UNIT], ms     # measured: 0.19 of it
+
+
+@pytest.mark.parametrize("case", [
+    # B, L, S, M, K: where the one-launch kernel takes over, with its tables staged in LDS ...
+    (3, 9, 12, 100, 2), (2, 24, 12, 255, 1), (5, 6, 8, 256, 3), (2, 7, 24, 63, 2),
+    (4, 5, 16, 127, 1), (2, 12, 4, 1000, 1), (1, 30, 2, 1023, 2), (70, 4, 6, 90, 1),
+    # ... and with a transition pool too large to stage (220 matrices of 8 x 8 padded entries)
+    (2, 6, 7, 80, 220),
+], ids=lambda c: "B%dL%dS%dM%dK%d" % c)
+def test_one_launch_kernel_for_small_instances(gs, oracle_mod, case):
+    """The latency path: every layer front of an instance in one launch, planes in LDS.
+    Costs, plans, whole planes, backpointers and the budget curve against the oracle, with
+    and without backpointers, ragged budgets, a zero-memory and a never-fitting strategy."""
+    binding, runner = gs
+    B, L, S, M, K = case
+    rng = workloads.SplitMix64(sum(case))
+    budget = rng.randint(0, M, B).astype(np.int32)
+    budget[0] = M
+    w = random_tables("onelaunch", B, L, S, M, K=K, seed=sum(case) + 5, budget=budget,
+                      o_hi=max(1, (2 * M) // L))
+    w.O[0, L // 2, S // 2] = 0
+    w.O[B - 1, 0, S - 1] = M + 3
+    ref = oracle_batch(oracle_mod, w)
+    for mode in ("bp", "nobp"):
+        got = runner.solve_workload(w, MODES[mode])
+        assert got["forward_kernel"] == "k_dp_small", (case, mode)
+        assert_same(got, ref, w, mode)
+    dw = runner.DeviceWorkload(w)
+    with runner.make_context(w, flags=binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
+        out = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+        assert ctx.gsearch_forward_kernel() == "k_dp_small"
+        C, bp = ctx.gsearch_export_planes(want_bp=True)
+        curve = ctx.gsearch_budget_curve().cpu().numpy()
+        C, bp = C.cpu().numpy(), bp.cpu().numpy()
+    for b in range(B):
+        E = int(w.budget[b])
+        one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True,
+                               want_curve=True)
+        assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), (case, b)
+        assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), (case, b)
+        assert np.array_equal(bits(curve[b, :E + 1]), bits(one["curve"])), (case, b)
+        assert np.array_equal(out["plan"][b], one["plan"]), (case, b)
