@@ -956,39 +956,38 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_generic(
 //
 // One workgroup per instance runs layer 0 .. L-1 back to back; the two ping-pong planes
 // live in LDS ([s][e], pitch a multiple of 64), so a layer front costs one workgroup
-// barrier instead of a kernel launch.  Threads are laid out as (budget row e) x (group of
-// target strategies): all lanes of a wave share sj, so R, T and O stay wave-uniform scalar
-// operands, and the LDS reads prev[si][e - O] are conflict-free (consecutive lanes,
-// consecutive addresses).  Flat strict-"<" scan; backpointers go to HBM as in the other
-// kernels.  The last plane (or every plane when all are kept) is copied to the HBM
+// barrier instead of a kernel launch.  The transition pool and the instance's T, O and
+// r_index rows are copied to LDS first, so that no layer waits for a chain of scalar loads.
+// Threads are laid out as (budget row) x (group of target strategies).  A thread owns a
+// SOURCE row e' ("push" form): it reads C[l-1][e'][.] from LDS once per layer, scans it
+// against the staged column of every target sj of its group (all lanes of a wave share sj,
+// so those are broadcast LDS reads), and stores the result at row e' + O[l][sj] of the next
+// plane; the rows e < O[l][sj], which no source row reaches, are filled with +inf by the
+// thread that owns that row.  Every row 0..E of every target is written exactly once.
+// Flat strict-"<" scan, four candidates at a time up to S; backpointers go to HBM as in the
+// other kernels.  The last plane (or every plane when all are kept) is copied to the HBM
 // workspace so that the final reductions, the budget curve and the plane-based backtrace
 // read what they always read.
 // ---------------------------------------------------------------------------------------
-// STAGED: the transition pool and the instance's T, O and r_index rows are copied to LDS
-// first (they fit next to the planes for every shape this path is chosen for unless the pool
-// or the layer count is unusually large): the scan of a target then waits for LDS reads
-// instead of a chain of scalar loads per target, which was most of a layer's time.
-template <typename BPT, bool STAGED>
+template <int SP>
 __global__ __launch_bounds__(1024) void k_dp_small(
-    float *__restrict__ planes, BPT *__restrict__ bp, const float *__restrict__ Tq,
+    float *__restrict__ planes, uint8_t *__restrict__ bp, const float *__restrict__ Tq,
     const int32_t *__restrict__ Oq, const float *__restrict__ Rt,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget, int B, int L, int S,
-    int SP, int K, int pitch, int keep_all, int last_plane) {
+    int K, int pitch, int keep_all, int last_plane) {
   extern __shared__ float lds[]; // two planes of S * pitch floats, then the staged tables
   const int b = blockIdx.x;
   float *Rl = lds + (size_t)2 * S * pitch;               // [K][SP][SP]
   float *Tl = Rl + (size_t)K * SP * SP;                  // [L][SP]
   int *Ol = reinterpret_cast<int *>(Tl + (size_t)L * SP); // [L][SP]
   int *kl = Ol + (size_t)L * SP;                         // [L]
-  if constexpr (STAGED) {
-    for (int x = threadIdx.x; x < K * SP * SP; x += blockDim.x) Rl[x] = Rt[x];
-    for (int x = threadIdx.x; x < L * SP; x += blockDim.x) {
-      Tl[x] = Tq[(size_t)b * L * SP + x];
-      Ol[x] = Oq[(size_t)b * L * SP + x];
-    }
-    for (int x = threadIdx.x; x < L; x += blockDim.x) kl[x] = ridx[(size_t)b * L + x];
-    __syncthreads();
+  for (int x = threadIdx.x; x < K * SP * SP; x += blockDim.x) Rl[x] = Rt[x];
+  for (int x = threadIdx.x; x < L * SP; x += blockDim.x) {
+    Tl[x] = Tq[(size_t)b * L * SP + x];
+    Ol[x] = Oq[(size_t)b * L * SP + x];
   }
+  for (int x = threadIdx.x; x < L; x += blockDim.x) kl[x] = ridx[(size_t)b * L + x];
+  __syncthreads();
   const int E = budget[b];
   const int rows64 = (E + 1 + kWave - 1) / kWave * kWave; // threads along e
   const int groups = (int)blockDim.x / rows64;             // >= 1 by the launch condition
@@ -1001,77 +1000,93 @@ __global__ __launch_bounds__(1024) void k_dp_small(
   float *nxt = lds + (size_t)S * pitch;
 
   if (active)
-    for (int s = jg; s < S; s += groups) {
-      const int o0 = STAGED ? Ol[s] : Oq[(size_t)b * L * SP + s];
-      const float t0 = STAGED ? Tl[s] : Tq[(size_t)b * L * SP + s];
-      const float v = (e >= o0) ? t0 : GS_INF;
-      cur[s * pitch + e] = v;
-      if (keep_all || L == 1) planes[plane_off + (size_t)s * pitch + e] = v;
+    for (int s0 = jg; s0 < S; s0 += groups) {
+      const float v = (e >= Ol[s0]) ? Tl[s0] : GS_INF;
+      cur[s0 * pitch + e] = v;
+      if (keep_all || L == 1) planes[plane_off + (size_t)s0 * pitch + e] = v;
     }
   for (int l = 1; l < L; ++l) {
     __syncthreads();
-    const int bl = b * L + l;
-    const float *rk = STAGED ? Rl + (size_t)kl[l] * SP * SP : Rt + (size_t)ridx[bl] * SP * SP;
+    const float *rk = Rl + (size_t)kl[l] * SP * SP;
     float *gplane = planes + (keep_all ? (size_t)l * plane_elems_all : (size_t)last_plane * plane_elems_all) + plane_off;
+    uint8_t *gbp = bp ? bp + (size_t)(l - 1) * plane_elems_all + plane_off : nullptr;
     const bool to_global = keep_all || l == L - 1;
-    if (active)
+    if (active) {
+      float c[SP];
+#pragma unroll
+      for (int i = 0; i < SP; ++i) c[i] = i < S ? cur[i * pitch + e] : GS_INF;
       for (int j = jg; j < S; j += groups) {
-        const int o = STAGED ? Ol[l * SP + j] : Oq[(size_t)bl * SP + j];
-        float out = GS_INF;
+        const int o = Ol[l * SP + j];
+        const float t = Tl[l * SP + j];
+        const float *rc = rk + (size_t)j * SP;
+        float m = GS_INF;
         int arg = 0;
-        if (e >= o) {
-          const float *rc = rk + (size_t)j * SP;
-          const float *src = cur + (e - o);
-          float m = GS_INF;
-          // eight candidates at a time: the LDS reads and the scalar load of the eight
-          // transition values are issued together, then the strict-"<" scan runs
-          for (int i0 = 0; i0 < S; i0 += 8) {
-            float v[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = (i0 + k < S) ? src[(i0 + k) * pitch] : GS_INF;
-            const float8_t r = *reinterpret_cast<const float8_t *>(rc + i0);
+        for (int i0 = 0; i0 < SP; i0 += 4) {
+          if (i0 < S) { // uniform: whole chunks of padding are skipped
+            const float4 r = *reinterpret_cast<const float4 *>(rc + i0);
+            const float rr[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-              const float t = v[k] + r[k];
-              if (t < m) { m = t; arg = i0 + k; }
+            for (int k = 0; k < 4; ++k) {
+              const float v = c[i0 + k] + rr[k];
+              if (v < m) { m = v; arg = i0 + k; }
             }
           }
-          out = m + (STAGED ? Tl[l * SP + j] : Tq[(size_t)bl * SP + j]);
         }
-        nxt[j * pitch + e] = out;
-        if (to_global) gplane[(size_t)j * pitch + e] = out;
-        if (bp) bp[(size_t)(l - 1) * plane_elems_all + plane_off + (size_t)j * pitch + e] = (BPT)arg;
+        const int eo = e + o;
+        if (eo <= E) {
+          const float out = m + t;
+          nxt[j * pitch + eo] = out;
+          if (to_global) gplane[(size_t)j * pitch + eo] = out;
+          if (gbp) gbp[(size_t)j * pitch + eo] = (uint8_t)arg;
+        }
+        if (e < o) { // no source row reaches this target row
+          nxt[j * pitch + e] = GS_INF;
+          if (to_global) gplane[(size_t)j * pitch + e] = GS_INF;
+          if (gbp) gbp[(size_t)j * pitch + e] = 0;
+        }
       }
-    float *t = cur; cur = nxt; nxt = t;
+    }
+    float *tmp = cur; cur = nxt; nxt = tmp;
   }
+}
+
+// LDS bytes of the staged tables: transition pool, T and O rows, r_index row
+static size_t small_table_bytes(const Shape &s) {
+  return sizeof(float) * ((size_t)s.K * s.SP * s.SP + (size_t)2 * s.L * s.SP + (size_t)s.L);
 }
 
 // The latency path applies when an instance's budget rows fit one workgroup, its two planes
 // fit LDS, and the batch is too small to fill the GPU through the per-layer kernels anyway.
 bool small_path_applies(const Shape &s, bool with_bp) {
-  if (s.M + 1 > 1024) return false;
+  if (s.M + 1 > 1024 || s.SP > 32) return false;
   if ((size_t)2 * s.S * s.pitch * sizeof(float) > (size_t)96 * 1024) return false;
+  if (small_table_bytes(s) > (size_t)48 * 1024) return false;
+  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
+  if (tiles > 2048) return false;
   // One workgroup per instance means one compute unit per instance, so the one-launch kernel
   // wins only while a thread's share of a layer front is short.  A thread owns a budget row
-  // and every groups-th target strategy, i.e. per = ceil(S / groups) scans of S candidates.
-  // Measured (24 layers, 1..64 instances, one launch against 23 launches of the tile
-  // kernel): S = 8: 42 against 70 us at M = 256 (per = 3), 94 against 74 at M = 512 (per =
-  // 8); S = 12: 55 against 84 at M = 128, even at M = 256; S = 16: 71 against 94 at M = 128,
-  // 111 against 103 at M = 256; S = 24: 94 against 117 at M = 64, even at M = 128.
-  // The rule below, per * S <= 34 + 2 S, reproduces those crossovers; the min-only tile
-  // kernel is faster (S = 12, M = 256: 77 us; S = 24, M = 64: 92 us), so that mode takes
-  // 20 + 2 S.  GSEARCH_SMALL = 0 / 1 (tuning) switches the path off / on wherever it fits.
+  // and every groups-th target strategy: per = ceil(S / groups) scans of S candidates, and
+  // the workgroup's waves share one compute unit.  Measured per layer (24 layers, 1 and 64
+  // instances, S = 8..44, M = 64..1000), in microseconds:
+  //   one launch  0.9 + 0.0021 * per * S * max(waves, 14)
+  //   tile kernel 1.6 + 0.18 S per launch with backpointers, 1.5 + 0.13 S without
+  // e.g. S = 12, M = 256 (per = 4, 15 waves): 62 us against 88 (77 min-only) for 23 fronts;
+  // S = 8, M = 512: 66 against 74; S = 24, M = 128: 100 against 123 (100); S = 32, M = 64: 121
+  // against 157 (124); S = 16, M = 512: 185 against 105.  GSEARCH_SMALL = 0 / 1 (tuning)
+  // switches the path off / on wherever it fits.
   static const int forced = [] {
     const char *e = getenv("GSEARCH_SMALL");
     return e ? atoi(e) : -1;
   }();
-  if (forced == 0) return false;
+  if (forced == 0 || forced == 1) return forced == 1;
   const int rows64 = (s.M + 1 + kWave - 1) / kWave * kWave;
   const int groups = s.S < 1024 / rows64 ? s.S : 1024 / rows64;
   const int per = (s.S + groups - 1) / groups;
-  if (forced != 1 && per * s.S > (with_bp ? 34 : 20) + 2 * s.S) return false;
-  const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
-  return tiles <= 2048;
+  const int waves = groups * rows64 / kWave;
+  const double one_launch = 0.9 + 0.0021 * per * s.S * (waves > 14 ? waves : 14);
+  const double per_front = with_bp ? 1.6 + 0.18 * s.S : 1.5 + 0.13 * s.S;
+  return one_launch <= per_front;
 }
 
 // More than 64 KB of dynamic LDS per workgroup has to be asked for, per kernel and per
@@ -1086,36 +1101,31 @@ static void lds_opt_in(const void *kernel, size_t lds, size_t (&granted)[kMaxDev
   }
 }
 
-template <typename BPT, bool STAGED>
-static void launch_small_as(const Shape &s, const Workspace &w, bool keep_all, int last_plane,
-                            size_t lds, int threads, hipStream_t st) {
-  if (lds > 64 * 1024) {
-    static size_t granted[kMaxDevices] = {};
-    lds_opt_in((const void *)k_dp_small<BPT, STAGED>, lds, granted);
-  }
-  hipLaunchKernelGGL((k_dp_small<BPT, STAGED>), dim3(s.B), dim3(threads), lds, st, w.planes,
-                     (BPT *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, s.SP, s.K,
-                     s.pitch, keep_all ? 1 : 0, last_plane);
-}
-
 void launch_dp_small(const Shape &s, const Workspace &w, bool keep_all, int last_plane,
                      hipStream_t st) {
-  const size_t plane_bytes = (size_t)2 * s.S * s.pitch * sizeof(float);
-  const size_t table_bytes =
-      sizeof(float) * ((size_t)s.K * s.SP * s.SP + (size_t)2 * s.L * s.SP + (size_t)s.L);
-  const bool staged = table_bytes <= (size_t)48 * 1024; // planes take up to 96 KB of the 160
-  const size_t lds = plane_bytes + (staged ? table_bytes : 0);
+  const size_t lds = (size_t)2 * s.S * s.pitch * sizeof(float) + small_table_bytes(s);
   const int rows64 = (s.M + 1 + kWave - 1) / kWave * kWave;
   int threads = (1024 / rows64) * rows64; // whole groups of target strategies
   const int useful = ((s.S < 1024 / rows64) ? s.S : 1024 / rows64) * rows64;
   if (useful < threads) threads = useful;
-  if (s.bp16) {
-    if (staged) launch_small_as<uint16_t, true>(s, w, keep_all, last_plane, lds, threads, st);
-    else launch_small_as<uint16_t, false>(s, w, keep_all, last_plane, lds, threads, st);
-  } else {
-    if (staged) launch_small_as<uint8_t, true>(s, w, keep_all, last_plane, lds, threads, st);
-    else launch_small_as<uint8_t, false>(s, w, keep_all, last_plane, lds, threads, st);
+#define GS_SMALL(SPV)                                                                     \
+  do {                                                                                    \
+    if (lds > 64 * 1024) {                                                                \
+      static size_t granted[kMaxDevices] = {};                                            \
+      lds_opt_in((const void *)k_dp_small<SPV>, lds, granted);                            \
+    }                                                                                     \
+    hipLaunchKernelGGL((k_dp_small<SPV>), dim3(s.B), dim3(threads), lds, st, w.planes,    \
+                       (uint8_t *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, \
+                       s.K, s.pitch, keep_all ? 1 : 0, last_plane);                       \
+  } while (0)
+  switch (s.SP) { // small_path_applies() admits no other size
+    case 8: GS_SMALL(8); break;
+    case 16: GS_SMALL(16); break;
+    case 24: GS_SMALL(24); break;
+    case 32: GS_SMALL(32); break;
+    default: break;
   }
+#undef GS_SMALL
 }
 
 int tuned_sp_for(int S) {

@@ -1009,10 +1009,11 @@ def test_a_common_divisor_of_the_memories_shortens_the_forward_pass(gs, oracle_m
 
 
 @pytest.mark.parametrize("case", [
-    # B, L, S, M, K: where the one-launch kernel takes over, with its tables staged in LDS ...
+    # B, L, S, M, K: where the one-launch kernel takes over (its tables fit LDS) ...
     (3, 9, 12, 100, 2), (2, 24, 12, 255, 1), (5, 6, 8, 256, 3), (2, 7, 24, 63, 2),
     (4, 5, 16, 127, 1), (2, 12, 4, 1000, 1), (1, 30, 2, 1023, 2), (70, 4, 6, 90, 1),
-    # ... and with a transition pool too large to stage (220 matrices of 8 x 8 padded entries)
+    # ... and a transition pool too large to stage (220 matrices of 8 x 8 padded entries),
+    # which the per-layer kernels take instead
     (2, 6, 7, 80, 220),
 ], ids=lambda c: "B%dL%dS%dM%dK%d" % c)
 def test_one_launch_kernel_for_small_instances(gs, oracle_mod, case):
@@ -1031,12 +1032,12 @@ def test_one_launch_kernel_for_small_instances(gs, oracle_mod, case):
     ref = oracle_batch(oracle_mod, w)
     for mode in ("bp", "nobp"):
         got = runner.solve_workload(w, MODES[mode])
-        assert got["forward_kernel"] == "k_dp_small", (case, mode)
+        assert (got["forward_kernel"] == "k_dp_small") == (K < 220), (case, mode)
         assert_same(got, ref, w, mode)
     dw = runner.DeviceWorkload(w)
     with runner.make_context(w, flags=binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
         out = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
-        assert ctx.gsearch_forward_kernel() == "k_dp_small"
+        assert (ctx.gsearch_forward_kernel() == "k_dp_small") == (K < 220)
         C, bp = ctx.gsearch_export_planes(want_bp=True)
         curve = ctx.gsearch_budget_curve().cpu().numpy()
         C, bp = C.cpu().numpy(), bp.cpu().numpy()
