@@ -86,8 +86,6 @@ __global__ __launch_bounds__(256) void k_prepare(
   if (bad) atomicOr(status, bad);
 }
 
-__global__ void k_clear_status(int32_t *status) { *status = 0; }
-
 // ----------------------------------------------------------------------------------------
 // Bin unit of an instance.  Let g be the greatest common divisor of the memories O[l][s]
 // that can fit at all (O <= E; the others never fit whatever the unit).  Every reachable
@@ -127,7 +125,9 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
                                                   int32_t *__restrict__ budget0,
                                                   int32_t *__restrict__ unit,
                                                   int32_t *__restrict__ minO,
-                                                  int32_t *__restrict__ lowsum, int L, int SP,
+                                                  int32_t *__restrict__ lowsum,
+                                                  int32_t *__restrict__ status,
+                                                  int32_t *__restrict__ status_acc, int L, int SP,
                                                   int M, int enable) {
   __shared__ int red[4];
   const int b = blockIdx.x;
@@ -182,6 +182,10 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
     budget0[b] = E0;
     budget[b] = E0 / g;
     unit[b] = g;
+    if (b == 0) { // the data-status word of this solve: what k_prepare found; cleared for the next
+      *status = *status_acc;
+      *status_acc = 0;
+    }
   }
   __syncthreads(); // the minima rewritten above are visible to wave 0
   if (wave != 0) return;
@@ -354,17 +358,13 @@ static __device__ __forceinline__ void wave_argmin(float &v, int &idx) {
 // BY_CLASS: `last` is the class kernel's compact plane of layer L-1 and
 // C[L-1][E][s] = Q[class s][E - O[L-1][s]] + T[L-1][s] (+inf when the strategy does not fit).
 template <bool BY_CLASS>
-__global__ void k_final_instance(const float *__restrict__ last,
-                                 const int32_t *__restrict__ budget,
-                                 const int32_t *__restrict__ status, const float *__restrict__ Tq,
-                                 const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
-                                 const int32_t *__restrict__ lowsum,
-                                 float *__restrict__ ws_cost, int32_t *__restrict__ ws_s,
-                                 float *__restrict__ best_cost, int32_t *__restrict__ best_s,
-                                 float *__restrict__ final_row, int B, int L, int S, int SP, int Sc,
-                                 int pitch) {
-  const int b = blockIdx.x;
-  const int lane = threadIdx.x;
+static __device__ __forceinline__ float final_of_instance(
+    int b, int lane, const float *__restrict__ last, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ status, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ lowsum, float *__restrict__ ws_cost, int32_t *__restrict__ ws_s,
+    float *__restrict__ best_cost, int32_t *__restrict__ best_s, float *__restrict__ final_row,
+    int L, int S, int SP, int Sc, int pitch) {
   const int E = budget[b];
   const bool poisoned = *status != 0;
   const size_t tab = ((size_t)b * L + L - 1) * SP;
@@ -392,6 +392,55 @@ __global__ void k_final_instance(const float *__restrict__ last,
     ws_s[b] = s;
     if (best_cost) best_cost[b] = m;
     if (best_s) best_s[b] = s;
+  }
+  return m; // the same in every lane
+}
+
+template <bool BY_CLASS>
+__global__ void k_final_instance(const float *__restrict__ last,
+                                 const int32_t *__restrict__ budget,
+                                 const int32_t *__restrict__ status, const float *__restrict__ Tq,
+                                 const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+                                 const int32_t *__restrict__ lowsum,
+                                 float *__restrict__ ws_cost, int32_t *__restrict__ ws_s,
+                                 float *__restrict__ best_cost, int32_t *__restrict__ best_s,
+                                 float *__restrict__ final_row, int B, int L, int S, int SP, int Sc,
+                                 int pitch) {
+  (void)final_of_instance<BY_CLASS>((int)blockIdx.x, (int)threadIdx.x, last, budget, status, Tq,
+                                    Oq, cls, lowsum, ws_cost, ws_s, best_cost, best_s, final_row,
+                                    L, S, SP, Sc, pitch);
+  (void)B;
+}
+
+// Both final reductions in one launch for a batch of a few instances: one workgroup, a wave
+// per instance (in turns), then the minimum over instances, lowest instance on ties.
+template <bool BY_CLASS>
+__global__ __launch_bounds__(1024) void k_final_few(
+    const float *__restrict__ last, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ status, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ lowsum, float *__restrict__ ws_cost, int32_t *__restrict__ ws_s,
+    float *__restrict__ best_cost, int32_t *__restrict__ best_s, float *__restrict__ final_row,
+    int32_t *__restrict__ best_instance, int B, int L, int S, int SP, int Sc, int pitch) {
+  __shared__ float sv[1024 / kWave];
+  __shared__ int si[1024 / kWave];
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int lane = threadIdx.x & 63;
+  const int nw = (int)(blockDim.x >> 6);
+  float m = GS_INF;
+  int arg = 0x7fffffff;
+  for (int b = wave; b < B; b += nw) { // ascending: a strict "<" keeps the lowest instance
+    const float v = final_of_instance<BY_CLASS>(b, lane, last, budget, status, Tq, Oq, cls, lowsum,
+                                                ws_cost, ws_s, best_cost, best_s, final_row, L,
+                                                S, SP, Sc, pitch);
+    if (v < m) { m = v; arg = b; }
+  }
+  if (lane == 0) { sv[wave] = m; si[wave] = arg; }
+  __syncthreads();
+  if (threadIdx.x == 0 && best_instance) {
+    for (int w = 1; w < nw; ++w)
+      if (sv[w] < m || (sv[w] == m && si[w] < arg)) { m = sv[w]; arg = si[w]; }
+    *best_instance = (m < GS_INF) ? arg : -1;
   }
 }
 
@@ -1158,14 +1207,14 @@ __global__ __launch_bounds__(256) void k_build_tables(
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
                     const int32_t *r_index, const int32_t *budget, const Workspace &w,
                     bool compress_bins, hipStream_t st) {
-  hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(1), 0, st, w.status);
   const long long nr = (long long)s.K * s.SP * s.SP + s.SP;
   const long long waves = (long long)s.B * s.L + (nr + kWave - 1) / kWave + (s.B + kWave - 1) / kWave;
   hipLaunchKernelGGL(k_prepare, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, T, O, R,
-                     r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status, s.B,
+                     r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status_acc, s.B,
                      s.L, s.S, s.M, s.K, s.SP);
   hipLaunchKernelGGL(k_bin_unit, dim3(s.B), dim3(256), 0, st, w.Oq, w.budget, w.budget0, w.unit,
-                     w.minO, w.lowsum, s.L, s.SP, s.M, compress_bins ? 1 : 0);
+                     w.minO, w.lowsum, w.status, w.status_acc, s.L, s.SP, s.M,
+                     compress_bins ? 1 : 0);
 }
 
 void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
@@ -1191,6 +1240,20 @@ void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipSt
 
 void launch_final(const Shape &s, const Workspace &w, const float *last_plane, float *best_cost,
                   int32_t *best_s, float *final_row, int32_t *best_instance, hipStream_t st) {
+  if (s.B <= 64) { // one launch: a wave per instance in turns, at most four turns
+    const dim3 block(kWave * (s.B < 16 ? s.B : 16));
+    if (w.by_class)
+      hipLaunchKernelGGL((k_final_few<true>), dim3(1), block, 0, st, last_plane, w.budget,
+                         w.status, w.Tq, w.Oq, w.cls, w.lowsum, w.best_cost, w.best_s, best_cost,
+                         best_s, final_row, best_instance, s.B, s.L, s.S, s.SP, class_rows(s),
+                         s.pitch);
+    else
+      hipLaunchKernelGGL((k_final_few<false>), dim3(1), block, 0, st, last_plane, w.budget,
+                         w.status, w.Tq, w.Oq, w.cls, w.lowsum, w.best_cost, w.best_s, best_cost,
+                         best_s, final_row, best_instance, s.B, s.L, s.S, s.SP, class_rows(s),
+                         s.pitch);
+    return;
+  }
   if (w.by_class)
     hipLaunchKernelGGL((k_final_instance<true>), dim3(s.B), dim3(kWave), 0, st, last_plane,
                        w.budget, w.status, w.Tq, w.Oq, w.cls, w.lowsum, w.best_cost, w.best_s, best_cost,

@@ -75,7 +75,10 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
 
 // Behind the per-solve layout: one plane row of zeros, cleared when the context is created and
 // never written afterwards (it stands for Q[0] = 0 in the class kernel's first front).
-size_t zero_row_bytes(int max_M) { return align_up(((size_t)max_M + 1 + 63) / 64 * 64 * sizeof(float), 256); }
+// Its last 256 bytes hold the word in which k_prepare collects data-status bits (zero between solves).
+size_t zero_row_bytes(int max_M) {
+  return align_up(((size_t)max_M + 1 + 63) / 64 * 64 * sizeof(float), 256) + 256;
+}
 
 bool config_ok(const gsearch_config *c) {
   return c && c->max_B >= 1 && c->max_L >= 1 && c->max_S >= 1 && c->max_S <= GSEARCH_MAX_S &&
@@ -283,6 +286,7 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   w.by_class = 0;
   char *base = ctx->base;
   w.zero_row = reinterpret_cast<const float *>(base + (ctx->bytes - zb));
+  w.status_acc = reinterpret_cast<int32_t *>(base + (ctx->bytes - 256));
   w.planes = reinterpret_cast<float *>(base + y.planes);
   const bool with_bp = !(c.flags & GSEARCH_FLAG_NO_BACKPOINTERS) && s.L > 1;
   w.bp = with_bp ? static_cast<void *>(base + y.bp) : nullptr;

@@ -54,6 +54,8 @@ struct Workspace {
   int32_t *best_s;   // [B]          result of the final reduction (kept for backtrace)
   float *best_cost;  // [B]
   int32_t *status;   // [1]          data-status bits
+  int32_t *status_acc; // [1]        where k_prepare collects its bits; zero between solves
+                     //              (k_bin_unit moves them to `status` and clears it again)
   // Transition classes (only meaningful when the caller gave r_class):
   int32_t *cmeta;    // [2]          number of classes, longest class
   int32_t *cstart;   // [NC+1]  first strategy of class c; S for c >= number of classes
