@@ -42,6 +42,9 @@ def test_bench_prints_one_json_line_with_the_contract_keys(config):
     assert r["bound"] in ("hbm", "alu") and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"]
+    if config == 1:      # 64 instances: the oracle is also timed on several cores side by side
+        m = d["cpu_baseline_all_cores"]
+        assert m["kind"] == "oracle" and 2 <= m["cores"] <= 16 and m["value"] > 0 and m["sample"]
     assert d["value"] > 0 and d["ms_per_step"] > 0
     # value = nominal relaxations of the step / wall time of the step
     assert abs(d["value"] - d["config"]["relaxations_per_step"] / d["ms_per_step"] / 1e6) \
