@@ -54,7 +54,9 @@ def class_ops_per_row(S: int, nc: int, maxlen: int, nobp: bool) -> float:
     return ops + 15.0 / 8.0 * nc * nc + nc * (24.0 + 3.0 * maxlen)
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  Keyed by (config, mode); None = not measured.
-MEASURED_TRAFFIC_BYTES = {(3, "bp"): 23.6e6, (3, "nobp"): 21.1e6, (3, "bp-general"): 54.0e6}
+MEASURED_TRAFFIC_BYTES = {(3, "bp"): 23.6e6, (3, "nobp"): 21.1e6, (3, "bp-general"): 54.0e6,
+                          (4, "bp"): 353.3e6, (4, "nobp"): 307.4e6,
+                          (2, "bp"): 216.7e6, (2, "nobp"): 192.7e6}
 
 
 def cpu_baseline(w, cfg_index, target_relax=3.0e10):
