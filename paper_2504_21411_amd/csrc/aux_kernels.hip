@@ -412,8 +412,8 @@ __global__ void k_final_instance(const float *__restrict__ last,
   (void)B;
 }
 
-// Both final reductions in one launch for a batch of a few instances: one workgroup, a wave
-// per instance (in turns), then the minimum over instances, lowest instance on ties.
+// Both final reductions in one launch for a batch of at most 16 instances: one workgroup, a
+// wave per instance, then the minimum over instances, lowest instance on ties.
 template <bool BY_CLASS>
 __global__ __launch_bounds__(1024) void k_final_few(
     const float *__restrict__ last, const int32_t *__restrict__ budget,
@@ -1240,8 +1240,9 @@ void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipSt
 
 void launch_final(const Shape &s, const Workspace &w, const float *last_plane, float *best_cost,
                   int32_t *best_s, float *final_row, int32_t *best_instance, hipStream_t st) {
-  if (s.B <= 64) { // one launch: a wave per instance in turns, at most four turns
-    const dim3 block(kWave * (s.B < 16 ? s.B : 16));
+  if (s.B <= 16) { // one launch, a wave per instance (64 instances in four turns measured
+                   // 10.2 us against 8.6 us for the two launches)
+    const dim3 block(kWave * s.B);
     if (w.by_class)
       hipLaunchKernelGGL((k_final_few<true>), dim3(1), block, 0, st, last_plane, w.budget,
                          w.status, w.Tq, w.Oq, w.cls, w.lowsum, w.best_cost, w.best_s, best_cost,
