@@ -60,41 +60,44 @@ MEASURED_TRAFFIC_BYTES = {(3, "bp"): 23.6e6, (3, "nobp"): 21.1e6, (3, "bp-genera
 
 
 def cpu_baseline(w, cfg_index, target_relax=3.0e10):
-    """The oracle as it stands on a bounded sample of the same workload: on one core, and as
-    independent single-threaded solves on up to 16 cores.  Returns (one, many or None)."""
+    """The oracle as it stands on a bounded sample of the same workload: the first instances
+    one after the other on one core (about target_relax relaxations, at least one instance,
+    layers cut off if one instance alone is more than that), and as independent
+    single-threaded solves side by side on up to 16 cores.  Returns (one, many or None)."""
     import numpy as np
     import oracle
+    E0 = int(w.budget[0])
+    per_layer = (E0 + 1) * w.S * w.S
+    Ls = int(max(2, min(w.L, 1 + target_relax // per_layer)))
+    n1 = int(max(1, min(w.B, target_relax // max(1, (Ls - 1) * per_layer))))
+    P = int(min(16, os.cpu_count() or 1, w.B))
+    nP = int(min(w.B, P * n1))
+    n = max(n1, nP)
     if w.kind == "model":
         desc = oracle.enumerate_strategies(**w.enum)
-        T, O, R = oracle.build_tables(desc, w.layer[:1], w.hw, w.rmodel, w.M)
+        T, O, R = oracle.build_tables(desc, w.layer[:n], w.hw, w.rmodel, w.M)
     else:
-        T, O, R = w.T[:1], w.O[:1], w.R
-    E = int(w.budget[0])
-    per_layer = (E + 1) * w.S * w.S
-    Ls = int(max(2, min(w.L, 1 + target_relax // per_layer)))
-    t0 = time.perf_counter()
-    oracle.solve(T[0][:Ls], O[0][:Ls], R, w.r_index[0][:Ls], E)
-    dt = time.perf_counter() - t0
-    relax = (Ls - 1) * per_layer
-    one = {"value": relax / dt / 1e9, "unit": "Grelax/s", "cores": 1, "kind": "oracle",
-           "sample": f"instance 0 of cfg{cfg_index}, first {Ls} of {w.L} layers, "
-                     f"{relax / 1e9:.2f} G relaxations in {dt:.1f} s"}
-    # The same oracle on several host cores: P independent single-threaded solves side by
-    # side, one instance each (the C code itself never threads), same number of layers.
-    P = int(min(16, os.cpu_count() or 1, w.B))
+        T, O, R = w.T[:n], w.O[:n], w.R
+    relax_of = lambda k: float(sum((Ls - 1) * (int(e) + 1) * w.S * w.S for e in w.budget[:k]))
+
+    def timed(k, threads):
+        t0 = time.perf_counter()
+        oracle.solve_batch(T[:k, :Ls], O[:k, :Ls], R, w.r_index[:k, :Ls], w.budget[:k],
+                           threads=threads)
+        return time.perf_counter() - t0
+
+    dt = timed(n1, 1)
+    what = f"first {Ls} of {w.L} layers" if Ls < w.L else f"all {w.L} layers"
+    one = {"value": relax_of(n1) / dt / 1e9, "unit": "Grelax/s", "cores": 1, "kind": "oracle",
+           "sample": f"instances 0..{n1 - 1} of cfg{cfg_index} one after the other, {what}, "
+                     f"{relax_of(n1) / 1e9:.2f} G relaxations in {dt:.1f} s"}
     if P < 2:
         return one, None
-    if w.kind == "model":
-        T, O, R = oracle.build_tables(desc, w.layer[:P], w.hw, w.rmodel, w.M)
-    else:
-        T, O, R = w.T[:P], w.O[:P], w.R
-    t0 = time.perf_counter()
-    oracle.solve_batch(T[:, :Ls], O[:, :Ls], R, w.r_index[:P, :Ls], w.budget[:P], threads=P)
-    dt = time.perf_counter() - t0
-    relax = float(sum((Ls - 1) * (int(e) + 1) * w.S * w.S for e in w.budget[:P]))
-    many = {"value": relax / dt / 1e9, "unit": "Grelax/s", "cores": P, "kind": "oracle",
-            "sample": f"instances 0..{P - 1} of cfg{cfg_index} side by side, first {Ls} of {w.L} "
-                      f"layers each, {relax / 1e9:.2f} G relaxations in {dt:.1f} s"}
+    dt = timed(nP, P)
+    many = {"value": relax_of(nP) / dt / 1e9, "unit": "Grelax/s", "cores": P, "kind": "oracle",
+            "sample": f"instances 0..{nP - 1} of cfg{cfg_index}, {P} independent single-threaded "
+                      f"solves side by side, {what}, {relax_of(nP) / 1e9:.2f} G relaxations in "
+                      f"{dt:.1f} s"}
     return one, many
 
 
