@@ -1049,3 +1049,42 @@ def test_one_launch_kernel_for_small_instances(gs, oracle_mod, case):
         assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), (case, b)
         assert np.array_equal(bits(curve[b, :E + 1]), bits(one["curve"])), (case, b)
         assert np.array_equal(out["plan"][b], one["plan"]), (case, b)
+
+
+def test_general_kernels_random_sweep(gs, oracle_mod):
+    """Two hundred seeded random table workloads through the general kernels: strategy counts
+    on both sides of every tile size, 1..9 instances, 1..7 layers, up to 1500 bins, several
+    matrices, ragged budgets, integer tables (ties), zero-memory and never-fitting
+    strategies, a forbidden source strategy, memories with a common divisor, forced instance
+    groups; the default choice and one forced kernel or mode per case."""
+    _, runner = gs
+    rng = workloads.SplitMix64(4242)
+    variants = [0x8, 0x10, 0x2, 0xC, 0x14, 0x4, 0x6]
+    sizes = [1, 2, 7, 8, 9, 15, 16, 17, 23, 24, 25, 31, 33, 41, 44, 45, 47, 48, 49, 63, 64, 65,
+             95, 96, 97, 127, 128, 129, 200]
+    for case in range(200):
+        v = rng.randint(0, 10 ** 6, 9)
+        S = sizes[int(v[0]) % len(sizes)]
+        B, L, M, K = 1 + int(v[1]) % 9, 1 + int(v[2]) % 7, 1 + int(v[3]) % 1500, 1 + int(v[4]) % 4
+        budget = rng.randint(0, M, B).astype(np.int32)
+        w = random_tables(f"sweep{case}", B, L, S, M, K=K, seed=60000 + case, budget=budget,
+                          o_hi=max(1, M // max(1, L - 1)), integer=(case % 4 == 0))
+        if case % 3 == 0:
+            w.O[int(v[5]) % B, int(v[6]) % L, int(v[7]) % S] = 0
+        if case % 3 == 1:
+            for b in range(B):
+                w.O[b] *= [1, 2, 3, 4, 6][(case + b) % 5]
+        if case % 5 == 0:
+            w.O[:, int(v[5]) % L, int(v[6]) % S] = M + 7
+        if case % 7 == 0:
+            w.R[int(v[5]) % K, int(v[6]) % S, :] = np.inf
+        ref = oracle_batch(oracle_mod, w)
+        dw = runner.DeviceWorkload(w)
+        for flags in (0, variants[case % len(variants)]):
+            with runner.make_context(w, flags=flags) as ctx:
+                g = int(v[8]) % 4
+                if g:
+                    ctx.gsearch_set_instance_groups(g)
+                got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
+                got["data_status"] = ctx.gsearch_data_status()
+            assert_same(got, ref, w, f"sweep {case} S={S} flags={flags:#x} groups={g}")
