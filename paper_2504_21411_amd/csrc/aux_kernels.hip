@@ -16,8 +16,9 @@ namespace gs {
 //                           (incl. the padding row behind it, which the push kernel's
 //                           prefetch reads but never uses), then the budgets
 // ----------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_prepare(
-    const float *__restrict__ T, const int32_t *__restrict__ O, const float *__restrict__ R,
+static __device__ void prepare_part(
+    int block, const float *__restrict__ T, const int32_t *__restrict__ O,
+    const float *__restrict__ R,
     const int32_t *__restrict__ r_index, const int32_t *__restrict__ budget,
     float *__restrict__ Tq, int32_t *__restrict__ Oq, float *__restrict__ Rt,
     int32_t *__restrict__ ridx, int32_t *__restrict__ budq, int32_t *__restrict__ minO,
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(256) void k_prepare(
   const long long nr = (long long)K * SP * SP + SP;
   const long long nr_waves = (nr + kWave - 1) / kWave;
   const long long nb_waves = ((long long)B + kWave - 1) / kWave;
-  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const long long wave = ((long long)block * blockDim.x + threadIdx.x) >> 6;
   const int lane = threadIdx.x & 63;
   int bad = 0;
   if (wave < nrow) {
@@ -120,17 +121,14 @@ static __device__ __forceinline__ int wave_gcd(int g) {
   return g;
 }
 
-__global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
-                                                  int32_t *__restrict__ budget,
-                                                  int32_t *__restrict__ budget0,
-                                                  int32_t *__restrict__ unit,
-                                                  int32_t *__restrict__ minO,
-                                                  int32_t *__restrict__ lowsum,
-                                                  int32_t *__restrict__ status,
-                                                  int32_t *__restrict__ status_acc, int L, int SP,
-                                                  int M, int enable) {
+static __device__ void bin_unit_part(int b, int32_t *__restrict__ Oq,
+                                     int32_t *__restrict__ budget,
+                                     int32_t *__restrict__ budget0, int32_t *__restrict__ unit,
+                                     int32_t *__restrict__ minO, int32_t *__restrict__ lowsum,
+                                     int32_t *__restrict__ status,
+                                     int32_t *__restrict__ status_acc, int L, int SP, int M,
+                                     int enable) {
   __shared__ int red[4];
-  const int b = blockIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int lane = threadIdx.x & 63;
   const int E0 = budget[b];
@@ -213,13 +211,13 @@ __global__ __launch_bounds__(256) void k_bin_unit(int32_t *__restrict__ Oq,
 // is replaced by the single class {0..S-1} so that whatever reads the run table stays in
 // bounds; the status bit makes the solve report every instance as infeasible anyway.
 // ----------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_prepare_classes(
-    const int32_t *__restrict__ r_class, const float *__restrict__ Rt,
+static __device__ void prepare_classes_part(
+    int block, int nblocks, const int32_t *__restrict__ r_class, const float *__restrict__ R,
     int32_t *__restrict__ cmeta, int32_t *__restrict__ cstart, int32_t *__restrict__ cls,
     int32_t *__restrict__ status, int S, int SP, int K, int NC) {
   __shared__ int s_bad, s_maxlen;
   int bad = 0;
-  if (blockIdx.x == 0) {
+  if (block == 0) {
     if (threadIdx.x == 0) { s_bad = 0; s_maxlen = 0; }
     __syncthreads();
     int pbad = 0;
@@ -248,32 +246,34 @@ __global__ __launch_bounds__(256) void k_prepare_classes(
     if (threadIdx.x == 0) { cmeta[0] = nc; cmeta[1] = s_maxlen; }
     if (!ok) bad = 0x20;
   }
-  // R constant inside classes: compare with the left (si-1) and upper (sj-1) neighbour
+  // R constant inside classes: compare with the left (sj-1) and upper (si-1) neighbour, in
+  // the caller's table (the sanitised copy holds the same values, transposed)
   const long long total = (long long)K * S * S;
-  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
-       x += (long long)gridDim.x * blockDim.x) {
-    const int i = (int)(x % S);
-    const int j = (int)((x / S) % S);
+  for (long long x = (long long)block * blockDim.x + threadIdx.x; x < total;
+       x += (long long)nblocks * blockDim.x) {
+    const int j = (int)(x % S);
+    const int i = (int)((x / S) % S);
     const long long k = x / ((long long)S * S);
-    const float *m = Rt + k * SP * SP;
-    const uint32_t v = __float_as_uint(m[(size_t)j * SP + i]);
-    if (i > 0 && r_class[i] == r_class[i - 1] && v != __float_as_uint(m[(size_t)j * SP + i - 1]))
+    const float *m = R + k * S * S;
+    const uint32_t v = __float_as_uint(m[(size_t)i * S + j]);
+    if (j > 0 && r_class[j] == r_class[j - 1] && v != __float_as_uint(m[(size_t)i * S + j - 1]))
       bad = 0x20;
-    if (j > 0 && r_class[j] == r_class[j - 1] && v != __float_as_uint(m[(size_t)(j - 1) * SP + i]))
+    if (i > 0 && r_class[i] == r_class[i - 1] && v != __float_as_uint(m[(size_t)(i - 1) * S + j]))
       bad = 0x20;
   }
   if (bad) atomicOr(status, bad);
+  (void)SP;
 }
 
 // Rc[k][cj][ci] = Rt[k][first strategy of cj][first strategy of ci], +inf for padding classes.
-__global__ __launch_bounds__(256) void k_build_Rc(const float *__restrict__ Rt,
-                                                  const int32_t *__restrict__ cmeta,
-                                                  const int32_t *__restrict__ cstart,
-                                                  float *__restrict__ Rc, int SP, int K, int NC) {
+static __device__ void build_Rc_part(int block, int nblocks, const float *__restrict__ Rt,
+                                     const int32_t *__restrict__ cmeta,
+                                     const int32_t *__restrict__ cstart,
+                                     float *__restrict__ Rc, int SP, int K, int NC) {
   const int nc = cmeta[0];
   const long long total = (long long)K * NC * NC;
-  for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x < total;
-       x += (long long)gridDim.x * blockDim.x) {
+  for (long long x = (long long)block * blockDim.x + threadIdx.x; x < total;
+       x += (long long)nblocks * blockDim.x) {
     const int ci = (int)(x % NC);
     const int cj = (int)((x / NC) % NC);
     const long long k = x / (NC * NC);
@@ -1204,27 +1204,59 @@ __global__ __launch_bounds__(256) void k_build_tables(
             S, K, desc, rmodel, BW, R);
 }
 
-void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
-                    const int32_t *r_index, const int32_t *budget, const Workspace &w,
-                    bool compress_bins, hipStream_t st) {
-  const long long nr = (long long)s.K * s.SP * s.SP + s.SP;
-  const long long waves = (long long)s.B * s.L + (nr + kWave - 1) / kWave + (s.B + kWave - 1) / kWave;
-  hipLaunchKernelGGL(k_prepare, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, T, O, R,
-                     r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.status_acc, s.B,
-                     s.L, s.S, s.M, s.K, s.SP);
-  hipLaunchKernelGGL(k_bin_unit, dim3(s.B), dim3(256), 0, st, w.Oq, w.budget, w.budget0, w.unit,
-                     w.minO, w.lowsum, w.status, w.status_acc, s.L, s.SP, s.M,
-                     compress_bins ? 1 : 0);
+// The two launches that open a solve.  k_prepare: sanitised copies of the tables in its
+// first nb_tables workgroups and, when the caller states transition classes, the check of
+// that promise (against the caller's R) in the others.  k_bin_unit: one workgroup per
+// instance for the bin unit and the least-memory scan, and behind them the workgroups that
+// fill the class table (which needs the run table k_prepare's class part has written).
+__global__ __launch_bounds__(256) void k_prepare(
+    int nb_tables, const float *__restrict__ T, const int32_t *__restrict__ O,
+    const float *__restrict__ R, const int32_t *__restrict__ r_index,
+    const int32_t *__restrict__ budget, float *__restrict__ Tq, int32_t *__restrict__ Oq,
+    float *__restrict__ Rt, int32_t *__restrict__ ridx, int32_t *__restrict__ budq,
+    int32_t *__restrict__ minO, int32_t *__restrict__ status_acc, int B, int L, int S, int M,
+    int K, int SP, const int32_t *__restrict__ r_class, int32_t *__restrict__ cmeta,
+    int32_t *__restrict__ cstart, int32_t *__restrict__ cls, int NC) {
+  const int block = (int)blockIdx.x;
+  if (block < nb_tables)
+    prepare_part(block, T, O, R, r_index, budget, Tq, Oq, Rt, ridx, budq, minO, status_acc, B, L,
+                 S, M, K, SP);
+  else
+    prepare_classes_part(block - nb_tables, (int)gridDim.x - nb_tables, r_class, R, cmeta, cstart,
+                         cls, status_acc, S, SP, K, NC);
 }
 
-void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
-                            hipStream_t st) {
-  const long long total = (long long)s.K * s.S * s.S;
-  hipLaunchKernelGGL(k_prepare_classes, dim3(blocks_for(total, 256, 4096)), dim3(256), 0, st,
-                     r_class, w.Rt, w.cmeta, w.cstart, w.cls, w.status, s.S, s.SP, s.K, s.NC);
-  const long long nrc = (long long)s.K * s.NC * s.NC;
-  hipLaunchKernelGGL(k_build_Rc, dim3(blocks_for(nrc, 256, 4096)), dim3(256), 0, st, w.Rt,
-                     w.cmeta, w.cstart, w.Rc, s.SP, s.K, s.NC);
+__global__ __launch_bounds__(256) void k_bin_unit(
+    int B, int32_t *__restrict__ Oq, int32_t *__restrict__ budget,
+    int32_t *__restrict__ budget0, int32_t *__restrict__ unit, int32_t *__restrict__ minO,
+    int32_t *__restrict__ lowsum, int32_t *__restrict__ status,
+    int32_t *__restrict__ status_acc, int L, int SP, int M, int enable,
+    const float *__restrict__ Rt, const int32_t *__restrict__ cmeta,
+    const int32_t *__restrict__ cstart, float *__restrict__ Rc, int K, int NC) {
+  const int block = (int)blockIdx.x;
+  if (block < B)
+    bin_unit_part(block, Oq, budget, budget0, unit, minO, lowsum, status, status_acc, L, SP, M,
+                  enable);
+  else
+    build_Rc_part(block - B, (int)gridDim.x - B, Rt, cmeta, cstart, Rc, SP, K, NC);
+}
+
+void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
+                    const int32_t *r_index, const int32_t *budget, const int32_t *r_class,
+                    const Workspace &w, bool compress_bins, hipStream_t st) {
+  const long long nr = (long long)s.K * s.SP * s.SP + s.SP;
+  const long long waves = (long long)s.B * s.L + (nr + kWave - 1) / kWave + (s.B + kWave - 1) / kWave;
+  const unsigned nb_tables = (unsigned)((waves + 3) / 4);
+  // r_class: the class promise is checked, and the class table built, in the same launches
+  const unsigned nb_classes = r_class ? blocks_for((long long)s.K * s.S * s.S, 256, 4096) : 0;
+  const unsigned nb_rc = r_class ? blocks_for((long long)s.K * s.NC * s.NC, 256, 4096) : 0;
+  hipLaunchKernelGGL(k_prepare, dim3(nb_tables + nb_classes), dim3(256), 0, st, (int)nb_tables, T,
+                     O, R, r_index, budget, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO,
+                     w.status_acc, s.B, s.L, s.S, s.M, s.K, s.SP, r_class, w.cmeta, w.cstart,
+                     w.cls, s.NC);
+  hipLaunchKernelGGL(k_bin_unit, dim3((unsigned)s.B + nb_rc), dim3(256), 0, st, s.B, w.Oq,
+                     w.budget, w.budget0, w.unit, w.minO, w.lowsum, w.status, w.status_acc, s.L,
+                     s.SP, s.M, compress_bins ? 1 : 0, w.Rt, w.cmeta, w.cstart, w.Rc, s.K, s.NC);
 }
 
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,

@@ -318,11 +318,10 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   else if (c.flags & GSEARCH_FLAG_FORCE_PUSH) which = gs::ForwardKernel::Push;
   else if (c.flags & GSEARCH_FLAG_FORCE_TILE) which = gs::ForwardKernel::Tile;
 
-  gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget, w,
-                     !(c.flags & GSEARCH_FLAG_NO_BIN_UNIT), st);
   // Transition classes: checked whenever the caller states them, exploited by the class
   // kernel when no particular kernel is forced and the shape has a register-tiled size.
-  if (p->r_class && s.L > 1) gs::launch_prepare_classes(s, p->r_class, w, st);
+  gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget,
+                     s.L > 1 ? p->r_class : nullptr, w, !(c.flags & GSEARCH_FLAG_NO_BIN_UNIT), st);
   const bool use_classes =
       p->r_class && s.L > 1 && which == gs::ForwardKernel::Auto && gs::class_path_applies(s);
   // The class kernel works on compact planes (one row per class, at the head of each plane

@@ -69,14 +69,13 @@ inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; 
 inline int class_rows(const Shape &s) { return s.S < s.NC ? s.S : s.NC; }
 
 // ---- launchers (all asynchronous on `st`) -------------------------------------------
+// Sanitised tables, data-status bits, bin units and least-memory sums.  With r_class (may be
+// null) the same two launches also validate r_class and R against each other (status bit on
+// violation) and fill cmeta / cstart / cls / Rc; an invalid partition is replaced by the
+// one-class partition, so that the class kernel stays memory-safe.
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
-                    const int32_t *r_index, const int32_t *budget, const Workspace &w,
-                    bool compress_bins, hipStream_t st);
-// Validates r_class and R against each other (status bit on violation) and fills
-// cmeta / cstart / cls / Rc; with an invalid partition it installs the one-class partition,
-// so that the class kernel stays memory-safe.  Must follow launch_prepare on the stream.
-void launch_prepare_classes(const Shape &s, const int32_t *r_class, const Workspace &w,
-                            hipStream_t st);
+                    const int32_t *r_index, const int32_t *budget, const int32_t *r_class,
+                    const Workspace &w, bool compress_bins, hipStream_t st);
 bool class_path_applies(const Shape &s);
 // One layer front with the class kernel: src and dst are compact planes
 // [B][class_rows][pitch] holding Q[l-1] and Q[l], where
