@@ -516,6 +516,7 @@ __global__ __launch_bounds__(kWave) void k_backtrace_bp_rows(
     const int32_t *__restrict__ instances, int n, int32_t *__restrict__ plan,
     int32_t *__restrict__ mem_used, int B, int L, int S, int SP, int NC, int pitch) {
   const int q = blockIdx.x;
+  if (q >= n) return; // (the grid is n workgroups)
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
   int s = (b >= 0 && b < B) ? ws_s[b] : -1;
@@ -629,6 +630,7 @@ __global__ void k_backtrace_planes(const float *__restrict__ planes,
                                    int32_t *__restrict__ plan, int32_t *__restrict__ mem_used,
                                    int B, int L, int S, int SP, int Sc, int pitch) {
   const int q = blockIdx.x;
+  if (q >= n) return; // (the grid is n workgroups)
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
   int s = (b >= 0 && b < B) ? ws_s[b] : -1;
@@ -692,6 +694,7 @@ __global__ __launch_bounds__(kWave) void k_backtrace_planes_rows(
     int32_t *__restrict__ plan, int32_t *__restrict__ mem_used, int B, int L, int S, int SP,
     int Sc, int M, int pitch) {
   const int q = blockIdx.x;
+  if (q >= n) return; // (the grid is n workgroups)
   const int lane = threadIdx.x;
   const int b = instances ? instances[q] : q;
   int s = (b >= 0 && b < B) ? ws_s[b] : -1;
