@@ -46,6 +46,14 @@ MUTANTS = [(n, DP, a, b) for n, a, b in [
      "                e -= o;\n", ""),
     ("backtrace_forgets_the_first_layer_memory",
      "            used += O[s];\n", ""),
+    ("batch_tie_takes_the_last_instance",
+     "if (best_cost[b] < gbest) { gbest = best_cost[b]; garg = b; }",
+     "if (best_cost[b] <= gbest && best_cost[b] < INFINITY) { gbest = best_cost[b]; garg = b; }"),
+    ("batch_winner_is_the_costliest_instance",
+     "if (best_cost[b] < gbest) { gbest = best_cost[b]; garg = b; }",
+     "if (garg < 0 || (best_cost[b] > gbest && best_cost[b] < INFINITY)) { gbest = best_cost[b]; garg = b; }"),
+    ("batch_reads_the_first_instance_tables",
+     "T + off, O + off, R, r_index + (size_t)b * L,", "T, O, R, r_index,"),
     ("curve_is_a_maximum",
      "if (v < m) m = v;", "if (!(v < m) && v < INFINITY) m = v;"),
     # strategy enumerator and the two table builders

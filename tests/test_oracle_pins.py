@@ -226,13 +226,32 @@ def test_tie_break_is_lowest_index_everywhere(oracle_mod):
 
 
 def test_batch_wrapper_global_min(oracle_mod):
+    """oracle_solve_batch: every instance equals its own single solve, the winner is the
+    lowest-cost instance and, among equal costs, the one with the lowest index."""
     w = random_tables("t", 6, 4, 3, 12, K=2, seed=950, o_hi=5,
                       budget=np.array([12, 2, 9, 12, 5, 7], np.int32))
     res = oracle_mod.solve_batch(w.T, w.O, w.R, w.r_index, w.budget)
     res2 = oracle_mod.solve_batch(w.T, w.O, w.R, w.r_index, w.budget, threads=3)
     for k in ("best_cost", "best_s", "plan", "mem_used", "final_row"):
         assert np.array_equal(res[k], res2[k])
+    for b in range(w.B):
+        one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], int(w.budget[b]))
+        assert np.float32(one["best_cost"]).view(np.uint32) == res["best_cost"][b].view(np.uint32)
+        assert one["best_s"] == res["best_s"][b] and one["mem_used"] == res["mem_used"][b]
+        assert np.array_equal(one["plan"], res["plan"][b])
+        assert np.array_equal(one["final_row"].view(np.uint32), res["final_row"][b].view(np.uint32))
     finite = np.isfinite(res["best_cost"])
     assert not finite[1]                                     # budget 2 < 4 layers * 1 bin
     want = int(np.flatnonzero(res["best_cost"] == res["best_cost"][finite].min())[0])
     assert res["best_instance"] == want == res2["best_instance"]
+    # the winner twice in the batch, behind itself: equal costs, the first copy wins
+    order = np.array([1, want, 2, want, want], np.int64)
+    dup = oracle_mod.solve_batch(w.T[order], w.O[order], w.R, w.r_index[order], w.budget[order])
+    assert dup["best_cost"][1] == dup["best_cost"][3] == dup["best_cost"][4]
+    assert dup["best_instance"] == 1
+    assert oracle_mod.solve_batch(w.T[order], w.O[order], w.R, w.r_index[order],
+                                  w.budget[order], threads=5)["best_instance"] == 1
+    # nothing fits anywhere: no winner
+    none = oracle_mod.solve_batch(w.T[:3], w.O[:3], w.R, w.r_index[:3], np.array([2, 1, 0], np.int32))
+    assert none["best_instance"] == -1 and not np.isfinite(none["best_cost"]).any()
+    assert (none["best_s"] == -1).all() and (none["plan"] == -1).all()
