@@ -183,6 +183,28 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *problem,
 int gsearch_backtrace(gsearch_ctx *ctx, const int32_t *instances, int32_t n, int32_t *plan,
                       int32_t *mem_used, void *stream);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  gsearch_solve_batch followed by gsearch_backtrace of
+ * every instance, with the workspace in a fixed array inside the library's device image
+ * (GSEARCH_NOALLOC_SCRATCH_BYTES per GPU, held until the process ends) instead of a context:
+ * no hipMalloc, hipFree, stream or event creation in this call.  Default mode only (with
+ * backpointers, no flags); one chain of launches on `stream`.
+ *   device       HIP device index whose copy of the array is used (made current for the call)
+ *   problem, result   as for gsearch_solve_batch (device pointers, caller-owned)
+ *   plan         device [B][L] or NULL: plans of all instances (as gsearch_backtrace, NULL ids)
+ *   mem_used     device [B] or NULL
+ *   data_status  device [1] or NULL: the data-status word of this solve (GSEARCH_DATA_* bits)
+ * A shape fits when gsearch_workspace_bytes of a config with exactly its sizes and flags 0 is
+ * at most GSEARCH_NOALLOC_SCRATCH_BYTES; anything larger returns GSEARCH_ERR_CAPACITY and
+ * launches nothing.  All calls on one GPU share the one array, which keeps the last call's
+ * contents (the call clears what it needs cleared): calls that overlap on a GPU, on any
+ * streams, race; order them on one stream or with events.
+ * Errors: INVALID_ARG, CAPACITY, NO_DEVICE, HIP. */
+#define GSEARCH_NOALLOC_SCRATCH_BYTES 16777216u /* 16 MiB */
+int gsearch_solve_batch_noalloc(int32_t device, const gsearch_problem *problem,
+                                const gsearch_result *result, int32_t *plan, int32_t *mem_used,
+                                int32_t *data_status, void *stream);
+
 /* Waits for `stream`, then copies the data-status word of the most recent solve to
  * *host_bits (0 = tables were valid; else GSEARCH_DATA_* bits).  Errors: NOT_SOLVED, HIP. */
 int gsearch_data_status(gsearch_ctx *ctx, void *stream, int32_t *host_bits);

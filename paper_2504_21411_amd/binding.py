@@ -38,6 +38,7 @@ GSEARCH_DATA_BAD_RCLASS = 0x20
 GSEARCH_MAX_CLASSES = 64
 GSEARCH_DEFAULT_CLASSES = 32
 GSEARCH_MAX_S = 1024
+GSEARCH_NOALLOC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = [
     "gsearch_workspace_bytes", "gsearch_create", "gsearch_destroy", "gsearch_solve_batch",
@@ -45,7 +46,7 @@ EXPORTS = [
     "gsearch_enumerate_count", "gsearch_enumerate", "gsearch_build_tables", "gsearch_strerror",
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
     "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
-    "gsearch_instance_groups", "gsearch_layout_classes",
+    "gsearch_instance_groups", "gsearch_layout_classes", "gsearch_solve_batch_noalloc",
 ]
 
 
@@ -112,6 +113,9 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_solve_batch.restype = ctypes.c_int
     lib.gsearch_solve_batch.argtypes = [vp, ctypes.POINTER(gsearch_problem),
                                         ctypes.POINTER(gsearch_result), vp]
+    lib.gsearch_solve_batch_noalloc.restype = ctypes.c_int
+    lib.gsearch_solve_batch_noalloc.argtypes = [i32, ctypes.POINTER(gsearch_problem),
+                                                ctypes.POINTER(gsearch_result), vp, vp, vp, vp]
     lib.gsearch_backtrace.restype = ctypes.c_int
     lib.gsearch_backtrace.argtypes = [vp, vp, i32, vp, vp, vp]
     lib.gsearch_data_status.restype = ctypes.c_int
@@ -252,6 +256,42 @@ def gsearch_build_tables_profiled(desc, layer_type, profile, bandwidth, par, M, 
         _ptr(profile, torch.float64, "profile"), _ptr(bandwidth, torch.float64, "bandwidth"),
         ctypes.byref(pp), _ptr(T), _ptr(O), _stream(stream)), "gsearch_build_tables_profiled")
     return T, O
+
+
+def gsearch_solve_batch_noalloc(T, O, R, r_index, budget, M, r_class=None, r_class_bound=0,
+                                stream=None, out=None):
+    """Solve and backtrace of every instance on the library's fixed scratch array (no context,
+    no allocation inside the library).  Tensors as for GSearch.gsearch_solve_batch; `out` may
+    bring the output tensors (best_cost, best_s, final_row, best_instance, plan, mem_used,
+    data_status), otherwise they are made here, on the caller's side of the boundary."""
+    import torch
+    B, L, S = T.shape
+    K = R.shape[0]
+    if tuple(O.shape) != (B, L, S) or tuple(R.shape) != (K, S, S) or \
+            tuple(r_index.shape) != (B, L) or tuple(budget.shape) != (B,) or \
+            (r_class is not None and tuple(r_class.shape) != (S,)):
+        raise ValueError("table shapes do not agree")
+    dev = T.device
+    if out is None:
+        out = dict(best_cost=torch.empty(B, dtype=torch.float32, device=dev),
+                   best_s=torch.empty(B, dtype=torch.int32, device=dev),
+                   final_row=torch.empty((B, S), dtype=torch.float32, device=dev),
+                   best_instance=torch.empty(1, dtype=torch.int32, device=dev),
+                   plan=torch.empty((B, L), dtype=torch.int32, device=dev),
+                   mem_used=torch.empty(B, dtype=torch.int32, device=dev),
+                   data_status=torch.empty(1, dtype=torch.int32, device=dev))
+    prob = gsearch_problem(B, L, S, int(M), K, _ptr(T, torch.float32, "T"),
+                           _ptr(O, torch.int32, "O"), _ptr(R, torch.float32, "R"),
+                           _ptr(r_index, torch.int32, "r_index"),
+                           _ptr(budget, torch.int32, "budget"),
+                           _ptr(r_class, torch.int32, "r_class"), int(r_class_bound))
+    res = gsearch_result(_ptr(out["best_cost"]), _ptr(out["best_s"]),
+                         _ptr(out.get("final_row")), _ptr(out["best_instance"]))
+    _check(load_library().gsearch_solve_batch_noalloc(
+        dev.index or 0, ctypes.byref(prob), ctypes.byref(res), _ptr(out.get("plan")),
+        _ptr(out.get("mem_used")), _ptr(out.get("data_status")), _stream(stream)),
+        "gsearch_solve_batch_noalloc")
+    return out
 
 
 class GSearch:

@@ -3,6 +3,7 @@
 #include "../../include/gsearch.h"
 
 #include <cstdlib>
+#include <mutex>
 #include <new>
 
 #include "gsearch_internal.h"
@@ -183,88 +184,8 @@ gs::Workspace group_view(const gs::Shape &s, const gs::Workspace &w, int b0) {
   return g;
 }
 
-} // namespace
-
-extern "C" {
-
-const char *gsearch_strerror(int status) {
-  switch (status) {
-    case GSEARCH_OK: return "ok";
-    case GSEARCH_ERR_INVALID_ARG: return "invalid argument";
-    case GSEARCH_ERR_CAPACITY: return "problem exceeds the capacity the context was created with";
-    case GSEARCH_ERR_NO_DEVICE: return "no usable GPU device";
-    case GSEARCH_ERR_HIP: return "HIP runtime error";
-    case GSEARCH_ERR_NOT_SOLVED: return "no solve has been issued on this context";
-    case GSEARCH_ERR_NO_MEMORY: return "out of device or host memory";
-    case GSEARCH_ERR_UNSUPPORTED: return "operation needs a flag the context was not created with";
-    default: return "unknown status";
-  }
-}
-
-size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
-  if (!config_ok(cfg)) return 0;
-  return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
-                     cfg->flags)
-             .total +
-         zero_row_bytes(cfg->max_M);
-}
-
-int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
-  if (!out) return GSEARCH_ERR_INVALID_ARG;
-  *out = nullptr;
-  if (!config_ok(cfg)) return GSEARCH_ERR_INVALID_ARG;
-  int ndev = 0;
-  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1 || cfg->device >= ndev) {
-    (void)hipGetLastError();
-    return GSEARCH_ERR_NO_DEVICE;
-  }
-  DeviceScope scope(cfg->device);
-  if (!scope.ok) return GSEARCH_ERR_NO_DEVICE;
-  gsearch_ctx *ctx = new (std::nothrow) gsearch_ctx;
-  if (!ctx) return GSEARCH_ERR_NO_MEMORY;
-  ctx->cfg = *cfg;
-  ctx->bytes = gsearch_workspace_bytes(cfg);
-  void *p = nullptr;
-  if (hipMalloc(&p, ctx->bytes) != hipSuccess) {
-    (void)hipGetLastError();
-    delete ctx;
-    return GSEARCH_ERR_NO_MEMORY;
-  }
-  ctx->base = static_cast<char *>(p);
-  const size_t zb = zero_row_bytes(cfg->max_M);
-  // (waited for here: solves may run on streams that do not order themselves after it)
-  if (hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) != hipSuccess ||
-      hipStreamSynchronize(nullptr) != hipSuccess) {
-    (void)hipGetLastError();
-    (void)hipFree(p);
-    delete ctx;
-    return GSEARCH_ERR_HIP;
-  }
-  *out = ctx;
-  return GSEARCH_OK;
-}
-
-int gsearch_destroy(gsearch_ctx *ctx) {
-  if (!ctx) return GSEARCH_OK;
-  int rc = GSEARCH_OK;
-  {
-    DeviceScope scope(ctx->cfg.device);
-    if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
-    if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
-    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-    for (int i = 0; i < ctx->n_side; ++i) {
-      (void)hipStreamSynchronize(ctx->side[i]);
-      (void)hipEventDestroy(ctx->ev_join[i]);
-      (void)hipStreamDestroy(ctx->side[i]);
-    }
-    if (ctx->base && hipFree(ctx->base) != hipSuccess) rc = GSEARCH_ERR_HIP;
-  }
-  delete ctx;
-  return rc;
-}
-
-int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result *r,
-                        void *stream) {
+// The solve behind gsearch_solve_batch and gsearch_solve_batch_noalloc.
+int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result *r, void *stream) {
   if (!ctx || !p || !r) return GSEARCH_ERR_INVALID_ARG;
   if (p->B < 1 || p->L < 1 || p->S < 1 || p->M < 1 || p->K < 1 || !p->T || !p->O || !p->R ||
       !p->r_index || !p->budget)
@@ -399,6 +320,172 @@ int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearc
   if (hipGetLastError() != hipSuccess) return GSEARCH_ERR_HIP;
   ctx->solved = true;
   return GSEARCH_OK;
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------
+// Workspace of gsearch_solve_batch_noalloc: a fixed array in the library's device image
+// instead of a hipMalloc'ed block.  Every GPU holds its own copy at its own address; in host
+// code the name only stands for the symbol, so the address is asked for once per device
+// (static_scratch_base) and only that pointer is ever handed to kernels or copies.
+__device__ __align__(256) unsigned char scratch[GSEARCH_NOALLOC_SCRATCH_BYTES];
+
+struct StaticSlot {
+  unsigned char *ptr = nullptr; // device address of `scratch` on this device
+  gsearch_ctx ctx;              // context whose workspace is that array (no streams, no events)
+};
+constexpr int kMaxStaticDevices = 64;
+StaticSlot g_static[kMaxStaticDevices];
+std::mutex g_static_mutex;
+
+// Device address of this device's copy of `scratch` (the device must be current).
+unsigned char *static_scratch_base(int device) {
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  StaticSlot &slot = g_static[device];
+  if (!slot.ptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    slot.ptr = static_cast<unsigned char *>(ptr);
+  }
+  return slot.ptr;
+}
+
+// (a kernel, not hipMemsetAsync: the caller may be capturing the stream into a graph)
+__global__ __launch_bounds__(256) void k_clear_words(uint32_t *__restrict__ p, size_t n) {
+  for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < n; x += (size_t)gridDim.x * 256)
+    p[x] = 0u;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *gsearch_strerror(int status) {
+  switch (status) {
+    case GSEARCH_OK: return "ok";
+    case GSEARCH_ERR_INVALID_ARG: return "invalid argument";
+    case GSEARCH_ERR_CAPACITY: return "problem exceeds the capacity of the context (or of the fixed scratch array)";
+    case GSEARCH_ERR_NO_DEVICE: return "no usable GPU device";
+    case GSEARCH_ERR_HIP: return "HIP runtime error";
+    case GSEARCH_ERR_NOT_SOLVED: return "no solve has been issued on this context";
+    case GSEARCH_ERR_NO_MEMORY: return "out of device or host memory";
+    case GSEARCH_ERR_UNSUPPORTED: return "operation needs a flag the context was not created with";
+    default: return "unknown status";
+  }
+}
+
+size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
+  if (!config_ok(cfg)) return 0;
+  return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
+                     cfg->flags)
+             .total +
+         zero_row_bytes(cfg->max_M);
+}
+
+int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
+  if (!out) return GSEARCH_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!config_ok(cfg)) return GSEARCH_ERR_INVALID_ARG;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1 || cfg->device >= ndev) {
+    (void)hipGetLastError();
+    return GSEARCH_ERR_NO_DEVICE;
+  }
+  DeviceScope scope(cfg->device);
+  if (!scope.ok) return GSEARCH_ERR_NO_DEVICE;
+  gsearch_ctx *ctx = new (std::nothrow) gsearch_ctx;
+  if (!ctx) return GSEARCH_ERR_NO_MEMORY;
+  ctx->cfg = *cfg;
+  ctx->bytes = gsearch_workspace_bytes(cfg);
+  void *p = nullptr;
+  if (hipMalloc(&p, ctx->bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    delete ctx;
+    return GSEARCH_ERR_NO_MEMORY;
+  }
+  ctx->base = static_cast<char *>(p);
+  const size_t zb = zero_row_bytes(cfg->max_M);
+  // (waited for here: solves may run on streams that do not order themselves after it)
+  if (hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) != hipSuccess ||
+      hipStreamSynchronize(nullptr) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(p);
+    delete ctx;
+    return GSEARCH_ERR_HIP;
+  }
+  *out = ctx;
+  return GSEARCH_OK;
+}
+
+int gsearch_destroy(gsearch_ctx *ctx) {
+  if (!ctx) return GSEARCH_OK;
+  int rc = GSEARCH_OK;
+  {
+    DeviceScope scope(ctx->cfg.device);
+    if (ctx->ev_begin) (void)hipEventDestroy(ctx->ev_begin);
+    if (ctx->ev_end) (void)hipEventDestroy(ctx->ev_end);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    for (int i = 0; i < ctx->n_side; ++i) {
+      (void)hipStreamSynchronize(ctx->side[i]);
+      (void)hipEventDestroy(ctx->ev_join[i]);
+      (void)hipStreamDestroy(ctx->side[i]);
+    }
+    if (ctx->base && hipFree(ctx->base) != hipSuccess) rc = GSEARCH_ERR_HIP;
+  }
+  delete ctx;
+  return rc;
+}
+
+int gsearch_solve_batch(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result *r,
+                        void *stream) {
+  return solve_impl(ctx, p, r, stream);
+}
+
+int gsearch_solve_batch_noalloc(int32_t device, const gsearch_problem *p, const gsearch_result *r,
+                                int32_t *plan, int32_t *mem_used, int32_t *data_status,
+                                void *stream) {
+  if (!p || !r || device < 0 || device >= kMaxStaticDevices) return GSEARCH_ERR_INVALID_ARG;
+  if (p->B < 1 || p->L < 1 || p->S < 1 || p->M < 1 || p->K < 1) return GSEARCH_ERR_INVALID_ARG;
+  gsearch_config cfg;
+  cfg.device = device;
+  cfg.max_B = p->B; cfg.max_L = p->L; cfg.max_S = p->S; cfg.max_M = p->M; cfg.max_K = p->K;
+  cfg.flags = 0;
+  if (!config_ok(&cfg)) return GSEARCH_ERR_INVALID_ARG;
+  // the workspace a context of exactly this shape would allocate has to fit the fixed array
+  if (gsearch_workspace_bytes(&cfg) > (size_t)GSEARCH_NOALLOC_SCRATCH_BYTES)
+    return GSEARCH_ERR_CAPACITY;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
+    (void)hipGetLastError();
+    return GSEARCH_ERR_NO_DEVICE;
+  }
+  DeviceScope scope(device);
+  if (!scope.ok) return GSEARCH_ERR_NO_DEVICE;
+  unsigned char *base = static_scratch_base(device);
+  if (!base) return GSEARCH_ERR_HIP;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  gsearch_ctx *ctx = &g_static[device].ctx;
+  ctx->cfg = cfg;
+  ctx->base = reinterpret_cast<char *>(base);
+  ctx->bytes = (size_t)GSEARCH_NOALLOC_SCRATCH_BYTES;
+  ctx->profiling = false;
+  ctx->groups = 1; // one chain of launches on the caller's stream: no streams or events to create
+  // The array keeps whatever the last call left.  What a solve expects to find cleared sits at
+  // the end of the workspace: the row of zeros that stands for Q[0] and the word in which the
+  // data-status bits are collected.  Its place depends on M, so it is cleared on every call.
+  const size_t zb = zero_row_bytes(cfg.max_M);
+  hipLaunchKernelGGL(k_clear_words, dim3((unsigned)((zb / 4 + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<uint32_t *>(base + (ctx->bytes - zb)), zb / 4);
+  const int rc = solve_impl(ctx, p, r, stream);
+  if (rc != GSEARCH_OK) return rc;
+  if (plan) gs::launch_backtrace_bp(ctx->shape, ctx->ws, nullptr, p->B, plan, mem_used, st);
+  if (data_status &&
+      hipMemcpyAsync(data_status, ctx->ws.status, sizeof(int32_t), hipMemcpyDeviceToDevice, st) !=
+          hipSuccess)
+    return GSEARCH_ERR_HIP;
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
 }
 
 int gsearch_backtrace(gsearch_ctx *ctx, const int32_t *instances, int32_t n, int32_t *plan,

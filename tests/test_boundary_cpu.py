@@ -104,6 +104,18 @@ def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.gsearch_layout_classes(dummy, 0, dummy, None, None) == b.GSEARCH_ERR_INVALID_ARG
     assert lib.gsearch_layout_classes(dummy, 1025, dummy, None, None) == b.GSEARCH_ERR_INVALID_ARG
     assert lib.gsearch_forward_kernel(None) == b""
+    # the entry point on the fixed array checks its arguments before it touches a device
+    assert lib.gsearch_solve_batch_noalloc(0, None, None, None, None, None, None) == \
+        b.GSEARCH_ERR_INVALID_ARG
+    prob = b.gsearch_problem(0, 1, 1, 1, 1, None, None, None, None, None, None, 0)
+    res = b.gsearch_result(None, None, None, None)
+    assert lib.gsearch_solve_batch_noalloc(0, ctypes.byref(prob), ctypes.byref(res), None, None,
+                                           None, None) == b.GSEARCH_ERR_INVALID_ARG
+    prob = b.gsearch_problem(8, 128, 96, 16384, 1, None, None, None, None, None, None, 0)
+    assert lib.gsearch_solve_batch_noalloc(0, ctypes.byref(prob), ctypes.byref(res), None, None,
+                                           None, None) == b.GSEARCH_ERR_CAPACITY
+    assert lib.gsearch_solve_batch_noalloc(-1, ctypes.byref(prob), ctypes.byref(res), None, None,
+                                           None, None) == b.GSEARCH_ERR_INVALID_ARG
     # the problem struct carries the optional class promise as its last two fields
     assert [f[0] for f in b.gsearch_problem._fields_][-2:] == ["r_class", "r_class_bound"]
     header = open(os.path.join(ROOT, "include", "gsearch.h")).read()
