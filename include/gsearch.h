@@ -94,6 +94,10 @@ typedef enum {
                                         than announced (r_class_bound) or than
                                         GSEARCH_MAX_CLASSES, or R differs inside one */
 
+#define GSEARCH_DATA_INTERNAL 0x40   /* not about the data: a bounded wait inside the one-launch
+                                        forward kernel gave up, the forward pass is incomplete
+                                        (every instance is reported as infeasible) */
+
 #define GSEARCH_MAX_CLASSES 64 /* transition classes a solve can exploit (see r_class) */
 #define GSEARCH_DEFAULT_CLASSES 32 /* ... unless r_class_bound announces more */
 
@@ -222,6 +226,21 @@ int gsearch_set_instance_groups(gsearch_ctx *ctx, int groups);
  * small instances; 0 before any solve or for a null context). */
 int gsearch_instance_groups(gsearch_ctx *ctx);
 
+/* Tuning knobs: overrides of the launch heuristics, for sweeps and tests; results never depend
+ * on them.  A context takes their initial values from the environment variables
+ * GSEARCH_<NAME IN CAPITALS> when it is created (the library reads the environment nowhere
+ * else) and keeps them per context.  Names: "kernel" (1 push, 2 tile, 3 wide: general forward
+ * kernel), "small" (0/1: one-launch kernel for small instances never / wherever it fits),
+ * "jsplit" (waves per tile), "waves_per_block", "row_groups", "streams" (instance groups),
+ * "chain" (1: the class kernel runs all layer fronts of a solve in one launch wherever it can; it
+ * measured slower than one launch per front and is off otherwise).  0 (or -1 for "small")
+ * restores the heuristic.  gsearch_knob_name lists the names (NULL beyond the last;
+ * host only, needs no GPU).  Errors: INVALID_ARG (null context, unknown name, value outside
+ * [-1, 64], null output). */
+const char *gsearch_knob_name(int index);
+int gsearch_set_knob(gsearch_ctx *ctx, const char *name, int value);
+int gsearch_get_knob(gsearch_ctx *ctx, const char *name, int *value);
+
 /* Measurement aid.  With profiling enabled, every later solve records one HIP event on
  * its stream just before the first forward-DP launch (layer 1) and one just after the
  * last (layer L-1; with instance groups: after the other groups' streams have joined).
@@ -232,7 +251,8 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable);
 int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
 /* Name of the forward kernel the most recent solve launched for its layer fronts
- * ("k_dp_class", "k_dp_tile", "k_dp_wide", "k_dp_push", "k_dp_generic" or "k_dp_small"; "" before any
+ * ("k_dp_class_chain", "k_dp_class", "k_dp_tile", "k_dp_wide", "k_dp_push", "k_dp_generic" or
+ * "k_dp_small"; "" before any
  * solve).  Static string. */
 const char *gsearch_forward_kernel(gsearch_ctx *ctx);
 

@@ -35,6 +35,7 @@ GSEARCH_DATA_BAD_O = 0x4
 GSEARCH_DATA_BAD_BUDGET = 0x8
 GSEARCH_DATA_BAD_RINDEX = 0x10
 GSEARCH_DATA_BAD_RCLASS = 0x20
+GSEARCH_DATA_INTERNAL = 0x40
 GSEARCH_MAX_CLASSES = 64
 GSEARCH_DEFAULT_CLASSES = 32
 GSEARCH_MAX_S = 1024
@@ -47,6 +48,7 @@ EXPORTS = [
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
     "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
     "gsearch_instance_groups", "gsearch_layout_classes", "gsearch_solve_batch_noalloc",
+    "gsearch_knob_name", "gsearch_set_knob", "gsearch_get_knob",
 ]
 
 
@@ -124,6 +126,12 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_set_profiling.argtypes = [vp, ctypes.c_int]
     lib.gsearch_set_instance_groups.restype = ctypes.c_int
     lib.gsearch_set_instance_groups.argtypes = [vp, ctypes.c_int]
+    lib.gsearch_knob_name.restype = ctypes.c_char_p
+    lib.gsearch_knob_name.argtypes = [ctypes.c_int]
+    lib.gsearch_set_knob.restype = ctypes.c_int
+    lib.gsearch_set_knob.argtypes = [vp, ctypes.c_char_p, ctypes.c_int]
+    lib.gsearch_get_knob.restype = ctypes.c_int
+    lib.gsearch_get_knob.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(ctypes.c_int)]
     lib.gsearch_instance_groups.restype = ctypes.c_int
     lib.gsearch_instance_groups.argtypes = [vp]
     lib.gsearch_layout_classes.restype = ctypes.c_int
@@ -182,6 +190,16 @@ def _stream(stream) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
     return stream.cuda_stream or None
+
+
+def gsearch_knob_names() -> list:
+    lib, names, i = load_library(), [], 0
+    while True:
+        n = lib.gsearch_knob_name(i)
+        if n is None:
+            return names
+        names.append(n.decode())
+        i += 1
 
 
 def gsearch_workspace_bytes(max_B, max_L, max_S, max_M, max_K=1, flags=0, device=0) -> int:
@@ -386,6 +404,15 @@ class GSearch:
     def gsearch_set_instance_groups(self, groups: int):
         _check(self._lib.gsearch_set_instance_groups(self._ctx, int(groups)),
                "gsearch_set_instance_groups")
+
+    def gsearch_set_knob(self, name: str, value: int):
+        _check(self._lib.gsearch_set_knob(self._ctx, name.encode(), int(value)), "gsearch_set_knob")
+
+    def gsearch_get_knob(self, name: str) -> int:
+        v = ctypes.c_int(0)
+        _check(self._lib.gsearch_get_knob(self._ctx, name.encode(), ctypes.byref(v)),
+               "gsearch_get_knob")
+        return int(v.value)
 
     def gsearch_instance_groups(self) -> int:
         return int(self._lib.gsearch_instance_groups(self._ctx))

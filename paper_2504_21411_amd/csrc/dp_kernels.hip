@@ -17,8 +17,6 @@
 // Rows e < O[l][sj] of the target cannot hold layer l under sj: they are set to +inf
 // (bp 0) by the wave that owns those rows, so that every row 0..E of the target plane is
 // written exactly once per launch and nothing stale survives from an earlier solve.
-#include <stdlib.h>
-
 #include "gsearch_internal.h"
 
 namespace gs {
@@ -713,43 +711,30 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
 // definition; the tiles wholly below it are not stored, and every reader of a compact plane
 // (the next layer front, the final reductions, the backtrace, the export) applies that bound.
 // ---------------------------------------------------------------------------------------
-template <int SP, int NW, bool WITH_BP, int NC>
-__global__ __launch_bounds__(NW *kWave) void k_dp_class(
+// One 64-row tile of source rows of instance b at layer front l (the work of one workgroup).
+// COHERENT: the plane rows are read with loads that bypass the compute unit's vector cache
+// (agent-scope relaxed atomic loads), for the one-launch form below, in which the rows were
+// written by other workgroups of the same launch.
+// `after_loads` is called by every wave once the tile's rows have arrived and the class minima
+// are formed, before the arithmetic: the one-launch form requests its next item there.
+struct NoHook {
+  __device__ __forceinline__ void operator()() const {}
+};
+template <int SP, int NW, bool WITH_BP, int NC, bool COHERENT, typename Hook = NoHook>
+static __device__ __forceinline__ void class_tile(
     const float *__restrict__ qsrc, float *__restrict__ qdst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
     const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
-    int l, int pitch, int src_pitch, int tiles, unsigned div_magic, int div_shift) {
-  // NC: class capacity (32 or 64): registers for the class minima, rows of the class table
+    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int L, int Sc,
+    int l, int pitch, int src_pitch, int b, int tile_start, float *lds,
+    const Hook &after_loads = Hook()) {
   constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
-  extern __shared__ float lds[];
   float *cmin = lds;                    // [NC][64]  class minima of the tile
   float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
   int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC); // [NC + 1], padded to NC + 32
   float *tile = reinterpret_cast<float *>(cs_lds + NC + 32); // [SP + 3][64], backpointer mode only
-  // Workgroup -> (instance, tile).  The hardware deals consecutive workgroups out to the 8
-  // XCDs in turn, and a tile reads its class rows at many shifts, which the tiles near it in
-  // the same instance read too, so an instance's tiles should share an L2.  With a multiple
-  // of 8 instances a (instances, tiles) grid does that by itself (instance b runs on XCD
-  // b mod 8).  Otherwise (gridDim.y == 1) XCD x gets the x-th eighth of the instance-major
-  // list of tiles as a contiguous run: equal shares for any batch size, and only the two
-  // ends of a run read rows that another XCD reads as well (7 instances of configs[3]'s
-  // shape: 0.188 -> 0.165 ms for 11 fronts).
-  int b, tile_start;
-  if (gridDim.y > 1 || tiles == 1) {
-    b = blockIdx.x;
-    tile_start = (int)blockIdx.y * kWave;
-  } else {
-    const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
-    const unsigned per = gridDim.x >> 3;            // tiles per XCD (the grid is 8 * per)
-    const unsigned item = xcd * per + slot;
-    if (item >= (unsigned)B * (unsigned)tiles) return;
-    // item / tiles by a multiply-high with the host's constant (exact for item < 2^31)
-    b = (int)(__umulhi(item, div_magic) >> div_shift);
-    tile_start = (int)(item - (unsigned)b * (unsigned)tiles) * kWave;
-  }
   const int js = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int bl = b * L + l;
@@ -811,7 +796,9 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
   for (int u = 0; u < PER; ++u) {
     const int cb = c_s[u] * spitch4;         // wave-uniform
     const int t = row4 + (cb - o_s[u] * 4);
-    const float v = *reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb)) + t_s[u];
+    const float *__restrict__ at = reinterpret_cast<const float *>(qsb + (uint32_t)(t > cb ? t : cb));
+    const float v = (COHERENT ? __hip_atomic_load(at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                              : *at) + t_s[u];
     stage[u] = t >= cb + lowq4 ? v : GS_INF; // source row >= lowq (and >= 0), row within budget
   }
   {
@@ -837,6 +824,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
                            __HIP_MEMORY_SCOPE_WORKGROUP);
   }
   __syncthreads();
+  after_loads();
   // every wave keeps all class minima in registers (classes that do not exist hold +inf)
   float cmv[NC];
 #pragma unroll
@@ -892,20 +880,348 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
       const float rr = rc_lds[cj * NC + ca];
       // Four members per round so that their LDS reads are in flight together, highest
       // first.  Past the end of a short class the scan looks at members of the following
-      // classes (or at the rows of slack behind the tile); whatever those match is
-      // overwritten, because class ca attains m and its members come later in the scan.
-      const float *tl = tile + lo * kWave + lane;
+      // classes (or at the padding rows and the slack behind the tile); whatever those match
+      // is overwritten, because class ca attains m and its members come later in the scan.
+      // (a round that would start beyond the last strategy row is read from the last row on,
+      // so the four reads end in the three rows of slack behind the tile at the latest)
+      const int tl = lo * kWave + lane;
+      const int tl_max = (SP - 1) * kWave + lane;
       int rel = 0;
       for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
+        const int at0 = tl + d0 * kWave;
+        const float *tr = tile + (at0 < tl_max ? at0 : tl_max);
         float tv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) tv[u] = tl[(d0 + u) * kWave];
+        for (int u = 0; u < 4; ++u) tv[u] = tr[u * kWave];
 #pragma unroll
         for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? d0 + u : rel;
       }
       arg = lo + rel;
       bpb[at] = (uint8_t)arg;
     }
+  }
+}
+
+template <int SP, int NW, bool WITH_BP, int NC>
+__global__ __launch_bounds__(NW *kWave) void k_dp_class(
+    const float *__restrict__ qsrc, float *__restrict__ qdst, uint8_t *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
+    const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
+    int l, int pitch, int src_pitch, int tiles, unsigned div_magic, int div_shift) {
+  // NC: class capacity (32 or 64): registers for the class minima, rows of the class table
+  extern __shared__ float lds[];
+  // Workgroup -> (instance, tile).  The hardware deals consecutive workgroups out to the 8
+  // XCDs in turn, and a tile reads its class rows at many shifts, which the tiles near it in
+  // the same instance read too, so an instance's tiles should share an L2.  With a multiple
+  // of 8 instances a (instances, tiles) grid does that by itself (instance b runs on XCD
+  // b mod 8).  Otherwise (gridDim.y == 1) XCD x gets the x-th eighth of the instance-major
+  // list of tiles as a contiguous run: equal shares for any batch size, and only the two
+  // ends of a run read rows that another XCD reads as well (7 instances of configs[3]'s
+  // shape: 0.188 -> 0.165 ms for 11 fronts).
+  int b, tile_start;
+  if (gridDim.y > 1 || tiles == 1) {
+    b = blockIdx.x;
+    tile_start = (int)blockIdx.y * kWave;
+  } else {
+    const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+    const unsigned per = gridDim.x >> 3;            // tiles per XCD (the grid is 8 * per)
+    const unsigned item = xcd * per + slot;
+    if (item >= (unsigned)B * (unsigned)tiles) return;
+    // item / tiles by a multiply-high with the host's constant (exact for item < 2^31)
+    b = (int)(__umulhi(item, div_magic) >> div_shift);
+    tile_start = (int)(item - (unsigned)b * (unsigned)tiles) * kWave;
+  }
+  class_tile<SP, NW, WITH_BP, NC, false>(qsrc, qdst, bp, Tq, Oq, Rc, cmeta, cstart, cls, ridx, budget,
+                                         minO, lowsum, L, Sc, l, pitch, src_pitch, b, tile_start,
+                                         lds);
+}
+
+// ---------------------------------------------------------------------------------------
+// The whole forward pass of the class kernel in ONE launch.
+//
+// A layer front of the per-launch form is one short round of workgroups, and between two
+// dependent launches the chip idles for about three microseconds.  Here the (layer, instance,
+// tile) items of all L-1 fronts are handed out from queues, and an item waits only for the
+// tiles of the previous layer it reads (rows r - O[l-1][s], i.e. the tiles at and a little
+// below it), so consecutive fronts overlap and nothing drains between them.
+//
+// Coherence.  The eight XCDs have one L2 each, and those are made coherent with each other
+// only by writing back and invalidating whole caches, which costs far more than the launches
+// it would save.  So an instance is bound to ONE XCD: a workgroup reads the id of the XCD it
+// runs on from the hardware register and serves only that XCD's queue (instances slot,
+// slot + 8, ...).  Within an XCD every compute unit's stores go through to the shared L2
+// (the vector cache is write-through), and a load that bypasses the vector cache (an
+// agent-scope atomic load; see class_tile) reads what sits in that L2.  Producer: stores,
+// wait until they are acknowledged, workgroup barrier, flag.  Consumer: flag seen, workgroup
+// barrier, bypassing loads.
+//
+// Progress.  The items of an XCD form one list in (layer, instance, tile) order, cut into
+// kChainQueues interleaved queues (item i belongs to queue i mod kChainQueues), each with a
+// counter of its own that the workgroups of rank r = q mod kChainQueues pop: an atomic on ONE
+// word takes about half a microsecond and they line up behind each other, which 185 items per
+// front cannot afford, while dealing the items out statically would hang as soon as the
+// chip holds fewer workgroups at once than the launcher believes (the occupancy query was
+// seen to promise seven per compute unit where six ran).  Every dependency of an item
+// precedes it in the list.  Take the lowest unfinished item: everything below it in its own
+// queue is finished, so it has been popped by a running workgroup (and then finishes, its
+// dependencies being done) or is the next one its queue hands out; a queue is served by the
+// first workgroups to arrive on the XCD (a workgroup takes a ticket when it starts and serves
+// queue ticket mod kChainQueues), which are running by definition.  So nothing waits for a
+// workgroup that cannot start, whatever the number of resident workgroups and however the
+// hardware deals them out to the XCDs.  Every wait is bounded all the same; one that gives
+// up raises the internal status bit (the solve then reports every instance as infeasible)
+// and tells the other workgroups to stop.
+//
+// Flags are words holding the number of the solve that set them (a counter the context
+// advances), so they need no clearing between solves.
+//
+// Ping-pong planes: item (l, t) overwrites the rows of Q[l-2] that the items (l-1, t'') up to
+// t'' = (64 t + 63 + largest fitting O[l-2]) / 64 still read, so it waits for those as well.
+// ---------------------------------------------------------------------------------------
+constexpr int kChainQueues = 16;
+struct ChainCtl {
+  unsigned next[8][kChainQueues][16]; // per XCD and queue: pops so far (a cache line each)
+  unsigned arrivals[8][16];           // per XCD: workgroups that have started
+  unsigned total[8];                  // per XCD: number of items
+  unsigned stop;                      // a wait gave up somewhere
+  unsigned pad[7];
+};
+static_assert(sizeof(ChainCtl) <= kChainCtlBytes, "the workspace reserves kChainCtlBytes for it");
+constexpr int kChainSpinMax = 1 << 18; // polls (with a short sleep between them) before a wait gives up
+constexpr int kChainMaxL = 4096;       // an item record keeps the layer in 12 bits
+
+// Queues of one solve, first step.  Block x < 8: the segment table of XCD x, seg[x][q] =
+// number of items before segment q = (l - 1) * nbmax + j (layer l, j-th instance of this XCD);
+// the active tiles of (l, b) are a = lowsum[b][l-1] / 64 .. z = (E_b - minO[b][l]) / 64,
+// exactly those for which class_tile has work.  The other blocks: maxfit[b][l] = largest
+// O[b][l][s] that fits the budget at all (0 if none), one wave per row.  The counters and the
+// stop word are reset here as well.
+__global__ __launch_bounds__(256) void k_chain_plan(
+    const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum,
+    int32_t *__restrict__ maxfit, int32_t *__restrict__ seg, ChainCtl *__restrict__ ctl, int B,
+    int L, int SP, int nbmax) {
+  __shared__ int scan[256];
+  __shared__ int carry;
+  const int nseg = (L - 1) * nbmax;
+  if (blockIdx.x < 8) {
+    const int x = blockIdx.x;
+    int32_t *__restrict__ sg = seg + (size_t)x * (nseg + 1);
+    if (threadIdx.x == 0) carry = 0;
+    if (threadIdx.x < kChainQueues) ctl->next[x][threadIdx.x][0] = 0;
+    if (threadIdx.x == 0) ctl->arrivals[x][0] = 0;
+    if (x == 0 && threadIdx.x == 0) ctl->stop = 0;
+    __syncthreads();
+    for (int q0 = 0; q0 < nseg; q0 += 256) {
+      const int q = q0 + (int)threadIdx.x;
+      int cnt = 0;
+      if (q < nseg) {
+        const int l = 1 + q / nbmax;
+        const int b = x + 8 * (q % nbmax);
+        if (b < B) {
+          const int E = budget[b];
+          const int top = E - minO[(size_t)b * L + l];
+          const int a = lowsum[(size_t)b * L + l - 1] >> 6;
+          const int z = top >= 0 ? top >> 6 : -1;
+          cnt = z >= a ? z - a + 1 : 0;
+        }
+      }
+      scan[threadIdx.x] = cnt;
+      __syncthreads();
+      for (int d = 1; d < 256; d <<= 1) { // inclusive scan of this round
+        const int add = (int)threadIdx.x >= d ? scan[threadIdx.x - d] : 0;
+        __syncthreads();
+        scan[threadIdx.x] += add;
+        __syncthreads();
+      }
+      const int base = carry;
+      if (q < nseg) sg[q] = base + scan[threadIdx.x] - cnt;
+      __syncthreads();
+      if (threadIdx.x == 255) carry = base + scan[255];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+      sg[nseg] = carry;
+      ctl->total[x] = (unsigned)carry;
+    }
+    return;
+  }
+  const int wave = wave_uniform(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int rows = B * L;
+  for (int row = ((int)blockIdx.x - 8) * 4 + wave; row < rows; row += ((int)gridDim.x - 8) * 4) {
+    const int E = budget[row / L];
+    int m = 0;
+    for (int sidx = lane; sidx < SP; sidx += kWave) {
+      const int v = Oq[(size_t)row * SP + sidx];
+      m = (v <= E && v > m) ? v : m;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      const int other = __shfl_xor(m, d, kWave);
+      m = other > m ? other : m;
+    }
+    if (lane == 0) maxfit[row] = m;
+  }
+}
+
+// Second step: one record per item, items[x][i] = (layer | instance << 12, tile, lo, hi): the
+// item's place and the tiles lo..hi of the previous layer whose flags it waits for (lo > hi:
+// none).  It reads the rows r - O[l-1][s] of Q[l-1], i.e. the tiles from
+// (64 t - maxfit[l-1]) / 64 up to its own, and with ping-pong planes it overwrites rows of
+// Q[l-2] that the tiles up to (64 t + 63 + maxfit[l-2]) / 64 of layer l-1 still read; both
+// ranges are cut to the active tiles of layer l-1.  One block per (segment, XCD).
+__global__ __launch_bounds__(256) void k_chain_items(
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
+    const int32_t *__restrict__ seg, uint4 *__restrict__ items, size_t items_per_xcd, int B,
+    int L, int nbmax, int keep) {
+  const int q = blockIdx.x, x = blockIdx.y;
+  const int nseg = (L - 1) * nbmax;
+  const int32_t *__restrict__ sg = seg + (size_t)x * (nseg + 1);
+  const int l = 1 + q / nbmax;
+  const int b = x + 8 * (q % nbmax);
+  if (b >= B) return;
+  const int first = sg[q], cnt = sg[q + 1] - first;
+  if (cnt <= 0) return;
+  const int bl = b * L + l;
+  const int a = lowsum[bl - 1] >> 6;
+  int a1 = 0, z1 = -1, fit1 = 0, fit2 = -1;
+  if (l >= 2) {
+    const int top1 = budget[b] - minO[bl - 1];
+    a1 = lowsum[bl - 2] >> 6;
+    z1 = top1 >= 0 ? top1 >> 6 : -1;
+    fit1 = maxfit[bl - 1];
+    if (!keep && l >= 3) fit2 = maxfit[bl - 2];
+  }
+  uint4 *__restrict__ out = items + (size_t)x * items_per_xcd + first;
+  for (int k = threadIdx.x; k < cnt; k += 256) {
+    const int t = a + k;
+    int lo = 1, hi = 0;
+    if (l >= 2) {
+      lo = 64 * t - fit1;
+      lo = lo > 0 ? lo >> 6 : 0;
+      lo = lo > a1 ? lo : a1;
+      hi = t;
+      if (fit2 >= 0) {
+        const int war = (64 * t + 63 + fit2) >> 6;
+        hi = war > hi ? war : hi;
+      }
+      hi = hi < z1 ? hi : z1;
+    }
+    out[k] = make_uint4((unsigned)l | ((unsigned)b << 12), (unsigned)t, (unsigned)lo, (unsigned)hi);
+  }
+}
+
+template <int SP, int NW, bool WITH_BP, int NC>
+__global__ __launch_bounds__(NW *kWave)
+    __attribute__((amdgpu_waves_per_eu(SP <= 96 && NC == 32 ? 8 : 1))) void k_dp_class_chain(
+    float *__restrict__ planes, size_t plane_elems, int keep, const float *__restrict__ zero_row,
+    uint8_t *__restrict__ bp, size_t bp_layer_bytes, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const float *__restrict__ Rc,
+    const int32_t *__restrict__ cmeta, const int32_t *__restrict__ cstart,
+    const int32_t *__restrict__ cls, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ lowsum, const uint4 *__restrict__ items, size_t items_per_xcd,
+    ChainCtl *__restrict__ ctl, unsigned *__restrict__ flags, unsigned epoch,
+    int32_t *__restrict__ status, int B, int L, int Sc, int pitch, int tiles) {
+  extern __shared__ float lds[];
+  __shared__ int s_ctl[4]; // layer (0: the queue is empty, -1: stop), instance, tile
+  unsigned xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  const int slot = (int)(xcc & 7u); // (the host admits this kernel only where the XCD ids are 0..7)
+  const int wave = wave_uniform(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const uint4 *__restrict__ mine = items + (size_t)slot * items_per_xcd;
+  // Wave 0 runs the queue.  Its branches are wave-uniform except the single-lane atomics, each
+  // closed before the next barrier and none next to the loop's back edge (a lane-0 branch that
+  // spans the back edge lets the compiler move that lane's work behind the next barrier).
+  // The library is built without the compiler's atomic optimiser, so a pop is one plain
+  // instruction whose result is awaited only where it is used.
+  unsigned *__restrict__ myq = nullptr;
+  int qid = 0, total = 0;
+  uint4 rec = make_uint4(0u, 0u, 1u, 0u); // the item to work on next (layer 0: none)
+  if (wave == 0) {
+    unsigned ticket = 0;
+    if (lane == 0)
+      ticket = __hip_atomic_fetch_add(&ctl->arrivals[slot][0], 1u, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT);
+    qid = wave_uniform((int)ticket) % kChainQueues;
+    myq = &ctl->next[slot][qid][0];
+    total = wave_uniform((int)ctl->total[slot]);
+    unsigned got = 0;
+    if (lane == 0)
+      got = __hip_atomic_fetch_add(myq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int i = wave_uniform((int)got) * kChainQueues + qid;
+    if (i < total) rec = mine[i];
+  }
+  for (;;) {
+    unsigned pending = 0; // the pop that fetches the item after this one (wave 0)
+    if (wave == 0) {
+      int l = (int)(rec.x & 0xFFFu);
+      const int b = (int)(rec.x >> 12), t = (int)rec.y, lo = (int)rec.z, hi = (int)rec.w;
+      l = wave_uniform(l);
+      if (l > 0) {
+        const unsigned *__restrict__ fl = flags + ((size_t)(l - 1) * B + wave_uniform(b)) * tiles;
+        int spins = 0;
+        for (int base = wave_uniform(lo); base <= wave_uniform(hi); base += kWave) {
+          for (;;) {
+            const int at = base + lane;
+            unsigned f = epoch;
+            if (at <= hi) f = __hip_atomic_load(&fl[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__builtin_amdgcn_ballot_w64(f != epoch) == 0) break;
+            ++spins;
+            if ((spins & 255) == 0) { // now and then: has somebody given up?
+              const unsigned st = __hip_atomic_load(&ctl->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              if (wave_uniform((int)st) != 0) { l = -1; break; }
+            }
+            if (spins > kChainSpinMax) { // gave up: the forward pass is incomplete
+              __hip_atomic_store(&ctl->stop, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              __hip_atomic_fetch_or(status, 0x40, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              l = -1;
+              break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+          }
+          if (l < 0) break;
+        }
+      }
+      s_ctl[0] = l;
+      s_ctl[1] = b;
+      s_ctl[2] = t;
+    }
+    __syncthreads();
+    const int l = wave_uniform(s_ctl[0]);
+    const int b = wave_uniform(s_ctl[1]);
+    const int t = wave_uniform(s_ctl[2]);
+    if (l <= 0) return;
+    const int srci = keep ? l - 1 : ((l - 1) & 1), dsti = keep ? l : (l & 1);
+    const bool from_zero = !keep && l == 1; // Q[0] = 0 is one shared row of zeros
+    const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
+    float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
+    uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
+    // the pop for the following item travels while this one is computed
+    auto request_next = [&]() {
+      if (threadIdx.x == 0)
+        pending = __hip_atomic_fetch_add(myq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    class_tile<SP, NW, WITH_BP, NC, true>(qsrc, qdst, bp_l, Tq, Oq, Rc, cmeta, cstart, cls, ridx,
+                                          budget, minO, lowsum, L, Sc, l, pitch,
+                                          from_zero ? 0 : pitch, b, t * kWave, lds, request_next);
+    if (wave == 0) { // the record of the following item arrives with the store acknowledgements
+      const int i = wave_uniform((int)pending) * kChainQueues + qid;
+      rec = make_uint4(0u, 0u, 1u, 0u);
+      if (i < total) rec = mine[i];
+    }
+    // the rows are in the XCD's L2 once the stores are acknowledged; then the flag
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads(); // (also: nobody still reads the LDS tile or s_ctl of this item)
+    if (wave == 0)
+      __hip_atomic_store(&flags[((size_t)l * B + b) * tiles + t], epoch, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -1073,12 +1389,9 @@ bool small_path_applies(const Shape &s, bool with_bp) {
   //   tile kernel 1.6 + 0.18 S per launch with backpointers, 1.5 + 0.13 S without
   // e.g. S = 12, M = 256 (per = 4, 15 waves): 62 us against 88 (77 min-only) for 23 fronts;
   // S = 8, M = 512: 66 against 74; S = 24, M = 128: 100 against 123 (100); S = 32, M = 64: 121
-  // against 157 (124); S = 16, M = 512: 185 against 105.  GSEARCH_SMALL = 0 / 1 (tuning)
+  // against 157 (124); S = 16, M = 512: 185 against 105.  The knob "small" = 0 / 1 (tuning)
   // switches the path off / on wherever it fits.
-  static const int forced = [] {
-    const char *e = getenv("GSEARCH_SMALL");
-    return e ? atoi(e) : -1;
-  }();
+  const int forced = s.tune.small;
   if (forced == 0 || forced == 1) return forced == 1;
   const int rows64 = (s.M + 1 + kWave - 1) / kWave * kWave;
   const int groups = s.S < 1024 / rows64 ? s.S : 1024 / rows64;
@@ -1089,15 +1402,19 @@ bool small_path_applies(const Shape &s, bool with_bp) {
   return one_launch <= per_front;
 }
 
-// More than 64 KB of dynamic LDS per workgroup has to be asked for, per kernel and per
-// device: `granted` remembers the largest size already asked for on each device.
-constexpr int kMaxDevices = 64;
-static void lds_opt_in(const void *kernel, size_t lds, size_t (&granted)[kMaxDevices]) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
-  if (lds > granted[dev]) {
-    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    granted[dev] = lds;
+// More than 64 KB of dynamic LDS per workgroup has to be asked for, per kernel: the context's
+// record remembers the largest size already asked for.
+static void lds_opt_in(const void *kernel, size_t lds, LdsGrants *g) {
+  int at = -1;
+  for (int i = 0; g && i < g->n; ++i)
+    if (g->fn[i] == kernel) at = i;
+  if (at >= 0 && lds <= g->bytes[at]) return;
+  (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (!g) return;
+  if (at < 0 && g->n < LdsGrants::kMax) at = g->n++;
+  if (at >= 0) { // (a full record only means asking again next time)
+    g->fn[at] = kernel;
+    g->bytes[at] = lds;
   }
 }
 
@@ -1110,10 +1427,7 @@ void launch_dp_small(const Shape &s, const Workspace &w, bool keep_all, int last
   if (useful < threads) threads = useful;
 #define GS_SMALL(SPV)                                                                     \
   do {                                                                                    \
-    if (lds > 64 * 1024) {                                                                \
-      static size_t granted[kMaxDevices] = {};                                            \
-      lds_opt_in((const void *)k_dp_small<SPV>, lds, granted);                            \
-    }                                                                                     \
+    if (lds > 64 * 1024) lds_opt_in((const void *)k_dp_small<SPV>, lds, s.grants);        \
     hipLaunchKernelGGL((k_dp_small<SPV>), dim3(s.B), dim3(threads), lds, st, w.planes,    \
                        (uint8_t *)w.bp, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, s.B, s.L, s.S, \
                        s.K, s.pitch, keep_all ? 1 : 0, last_plane);                       \
@@ -1148,24 +1462,10 @@ int class_sp_for(int S) {
 // target strategies) pieces, one per wave; slicing the strategies costs a repeated load
 // of the tile's source values but multiplies the number of waves, which is what hides
 // the scalar-load latency when a batch has few tiles (8 instances x 257 tiles fill the
-// 1024 SIMDs only twice).  GSEARCH_JSPLIT / GSEARCH_WAVES_PER_BLOCK override the
+// 1024 SIMDs only twice).  the knobs "jsplit" and "waves_per_block" override the
 // heuristic (debugging and tuning aid).
-struct PushTuning {
-  int jsplit = 0, waves_per_block = 0, kernel = 0, row_groups = 0;
-  PushTuning() {
-    if (const char *e = getenv("GSEARCH_JSPLIT")) jsplit = atoi(e);
-    if (const char *e = getenv("GSEARCH_WAVES_PER_BLOCK")) waves_per_block = atoi(e);
-    if (const char *e = getenv("GSEARCH_KERNEL")) kernel = atoi(e); // 1 = push, 2 = tile, 3 = wide
-    if (const char *e = getenv("GSEARCH_ROW_GROUPS")) row_groups = atoi(e);
-  }
-};
-static const PushTuning &tuning() {
-  static const PushTuning t;
-  return t;
-}
-
 static void push_launch_shape(const Shape &s, int &jsplit, int &wpb) {
-  const PushTuning &tune = tuning();
+  const Tuning &tune = s.tune;
   // tiles of this launch alone, also when other groups of the batch run beside it on
   // parallel streams: measured, the finer split is what lets the groups interleave
   const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.B;
@@ -1238,9 +1538,9 @@ static void launch_push(const Shape &s, const Workspace &w, int l, const float *
   // search batch), where the shared scalar loads and loop overhead are a large part of a
   // short column; the flat argmin is bound by its own instruction count either way and
   // loses occupancy to the extra registers.  Used while the batch still yields at least
-  // eight waves per SIMD.  GSEARCH_ROW_GROUPS overrides.
+  // eight waves per SIMD.  The knob "row_groups" overrides.
   const long long tiles = (long long)((s.M + 1 + kWave - 1) / kWave) * s.Bc * jsplit;
-  int ru = tuning().row_groups;
+  int ru = s.tune.row_groups;
   if (ru < 1) ru = bp_l ? 1 : (tiles >= 4 * 8192 ? 4 : (tiles >= 2 * 8192 ? 2 : 1));
   if constexpr (SP <= 24) {
     if (ru >= 4) return launch_push_ru<SP, 4>(s, w, l, src, dst, bp_l, jsplit, wpb, st);
@@ -1279,10 +1579,8 @@ static void launch_class_nc(const Shape &s, const Workspace &w, int l, const flo
   const dim3 block(NW * kWave);
   const int src_pitch = src == w.zero_row ? 0 : s.pitch; // the shared row of zeros stands for Q[0]
   const size_t lds = sizeof(float) * ((bp_l ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
-  if (lds > 64 * 1024) { // the forms with backpointers from 128 (wide) or 192 strategies up
-    static size_t granted[kMaxDevices] = {};
-    lds_opt_in((const void *)k_dp_class<SP, NW, true, NC>, lds, granted);
-  }
+  // (the forms with backpointers from 128 (wide) or 192 strategies up)
+  if (lds > 64 * 1024) lds_opt_in((const void *)k_dp_class<SP, NW, true, NC>, lds, s.grants);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true, NC>), grid, block, lds, st, src, dst,
                        (uint8_t *)bp_l, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
@@ -1312,9 +1610,9 @@ static void launch_class(const Shape &s, const Workspace &w, int l, const float 
   // a few hundred tiles (pure latency); otherwise eight from 64 padded strategies up with
   // backpointers and at 128 without (a wave's share of the tile is long enough to pay for
   // the per-wave set-up), four below; the min-only pass takes eight at 96 while the batch
-  // is a few thousand tiles and two up to 32 strategies.  GSEARCH_JSPLIT overrides.
+  // is a few thousand tiles and two up to 32 strategies.  The knob "jsplit" overrides.
   const long long tile_inst = (long long)((s.M + kWave) / kWave) * s.Bc;
-  int waves = tuning().jsplit;
+  int waves = s.tune.jsplit;
   if (waves < 1 || waves > 8) {
     if (tile_inst <= 512) waves = 8;
     else if (bp_l) waves = SP >= 64 ? 8 : 4;
@@ -1347,6 +1645,117 @@ const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const flo
   return "k_dp_class";
 }
 
+// Which XCDs workgroups land on: every workgroup ORs the bit of its XCD id into *mask.
+__global__ void k_xcc_probe(unsigned *__restrict__ mask) {
+  unsigned xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  if (threadIdx.x == 0) atomicOr(mask, 1u << (xcc & 15u));
+}
+
+void launch_xcc_probe(unsigned *mask, hipStream_t st) {
+  hipLaunchKernelGGL(k_xcc_probe, dim3(1024), dim3(kWave), 0, st, mask);
+}
+
+size_t chain_seg_entries(const Shape &s) {
+  const int nbmax = (s.B + 7) / 8;
+  return (size_t)8 * ((size_t)(s.L > 1 ? s.L - 1 : 0) * nbmax + 1);
+}
+
+// Upper bound of the items one XCD can be given: every tile of every layer front of its instances.
+size_t chain_items_per_xcd(const Shape &s) {
+  const int nbmax = (s.B + 7) / 8;
+  return (size_t)(s.L > 1 ? s.L - 1 : 0) * nbmax * ((s.M + kWave) / kWave);
+}
+
+bool chain_shape_ok(const Shape &s) { return s.L >= 3 && s.L < kChainMaxL && s.B < (1 << 20); }
+
+template <int SP, int NW, int NC>
+static void launch_chain_nc(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                            size_t plane_elems_all, size_t bp_layer_bytes, int cus,
+                            hipStream_t st) {
+  const int tiles = (s.M + kWave) / kWave;
+  const int nbmax = (s.B + 7) / 8;
+  const size_t lds =
+      sizeof(float) * ((with_bp ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
+  const void *fn = with_bp ? (const void *)k_dp_class_chain<SP, NW, true, NC>
+                           : (const void *)k_dp_class_chain<SP, NW, false, NC>;
+  if (lds > 64 * 1024) lds_opt_in(fn, lds, s.grants);
+  // as many workgroups as the chip holds at once (more would only pop an empty queue)
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, NW * kWave, lds) != hipSuccess ||
+      per_cu < 1)
+    per_cu = 1;
+  const dim3 grid((unsigned)(per_cu * cus + 7) / 8 * 8), block(NW * kWave);
+  const long long rows = (long long)s.B * s.L;
+  const unsigned plan_blocks = 8 + (unsigned)(rows / 4 < 1 ? 1 : (rows / 4 > 1024 ? 1024 : rows / 4));
+  ChainCtl *ctl = static_cast<ChainCtl *>(w.chain_ctl);
+  hipLaunchKernelGGL(k_chain_plan, dim3(plan_blocks), dim3(256), 0, st, w.Oq, w.budget, w.minO,
+                     w.lowsum, w.maxfit, w.seg, ctl, s.B, s.L, s.SP, nbmax);
+  const size_t per_xcd = chain_items_per_xcd(s);
+  uint4 *items = static_cast<uint4 *>(w.chain_items);
+  hipLaunchKernelGGL(k_chain_items, dim3((unsigned)((s.L - 1) * nbmax), 8), dim3(256), 0, st,
+                     w.budget, w.minO, w.lowsum, w.maxfit, w.seg, items, per_xcd, s.B, s.L, nbmax,
+                     keep ? 1 : 0);
+  if (with_bp)
+    hipLaunchKernelGGL((k_dp_class_chain<SP, NW, true, NC>), grid, block, lds, st, w.planes,
+                       plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp, bp_layer_bytes,
+                       w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
+                       w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch, w.status, s.B, s.L,
+                       class_rows(s), s.pitch, tiles);
+  else
+    hipLaunchKernelGGL((k_dp_class_chain<SP, NW, false, NC>), grid, block, lds, st, w.planes,
+                       plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
+                       bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                       w.budget, w.minO, w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch,
+                       w.status, s.B, s.L, class_rows(s), s.pitch, tiles);
+}
+
+template <int SP, int NW>
+static void launch_chain_nw(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                            size_t pe, size_t bpl, int cus, hipStream_t st) {
+  if constexpr (SP >= 48) {
+    if (s.NC > 32) return launch_chain_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, cus, st);
+  }
+  launch_chain_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, cus, st);
+}
+
+template <int SP>
+static void launch_chain(const Shape &s, const Workspace &w, bool keep, bool with_bp, size_t pe,
+                         size_t bpl, int cus, hipStream_t st) {
+  // waves per tile as in the per-launch form, without its one- and two-wave forms
+  int waves = s.tune.jsplit;
+  if (waves < 1 || waves > 8) {
+    if (with_bp) waves = SP >= 64 ? 8 : 4;
+    else waves = SP >= 96 ? 8 : 4;
+  }
+  if constexpr (SP > 128) {
+    launch_chain_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, cus, st);
+  } else {
+    if (waves >= 8) launch_chain_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, cus, st);
+    else launch_chain_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, cus, st);
+  }
+}
+
+// All L-1 layer fronts of the class kernel in one launch (plus the launch that lays out its
+// queues).  plane_elems_all: floats per plane slot; bp_layer_bytes: backpointer bytes per layer.
+const char *launch_dp_class_chain(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                                  size_t plane_elems_all, size_t bp_layer_bytes, int cus,
+                                  hipStream_t st) {
+  switch (s.SP) {
+    case 16: launch_chain<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 24: launch_chain<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 32: launch_chain<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 48: launch_chain<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 64: launch_chain<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 96: launch_chain<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 128: launch_chain<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 192: launch_chain<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 256: launch_chain<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    default: break; // class_path_applies() admits no other pitch
+  }
+  return "k_dp_class_chain";
+}
+
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {
   const size_t n = (size_t)s.B * class_rows(s) * s.pitch;
   const unsigned blocks = (unsigned)((n + 256 * 8 - 1) / (256 * 8));
@@ -1361,10 +1770,8 @@ static void launch_wide_rows(const Shape &s, const Workspace &w, int l, const fl
   const long long tiles = (s.M + 1 + ROWS - 1) / ROWS;
   const dim3 grid((unsigned)(tiles * s.B)), block(NW * kWave);
   const size_t lds = (size_t)s.SP * ROWS * sizeof(float);
-  if (lds > 64 * 1024) {
-    static size_t granted[kMaxDevices] = {};
-    lds_opt_in((const void *)k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>, lds, granted);
-  }
+  if (lds > 64 * 1024)
+    lds_opt_in((const void *)k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>, lds, s.grants);
   hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>), grid, block, lds, st, src, dst,
                      (BPT *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
                      s.S, s.SP, l, s.pitch);
@@ -1399,7 +1806,7 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // from 48 padded strategies up when backpointers are wanted (its argmin costs about 2.3
   // instead of 4 vector instructions per relaxation) and for 48..64 without them; the
   // plain push kernel wins for small S (few chunks, relatively more fixed work per tile)
-  // and for the min-only pass at S >= 96.  The context flags (or GSEARCH_KERNEL=1|2) force one.
+  // and for the min-only pass at S >= 96.  The context flags (or the knob "kernel" = 1 | 2) force one.
   bool use_tile = bp_l ? tsp >= 48 : (tsp >= 48 && tsp <= 64);
   // Small S: the push kernel wins on big batches (outer search: 2048 instances), but while
   // the batch has few tiles a front is bound by the length of one wave's work, and the
@@ -1417,10 +1824,10 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
   // without; S = 96 up to a few thousand tiles: configs[3] 6.9 against 7.3 ms with
   // backpointers, 5.5 against 5.8 without, but 8 K tiles 2.04 against 1.87 and 1.46 against
   // 1.27; S = 64 on a handful of tiles 0.08 against 0.09).
-  // GSEARCH_KERNEL=3 forces it wherever its tile fits.
-  if (which == ForwardKernel::Auto && tsp == s.SP && s.SP % 16 == 0 && tuning().kernel != 1 &&
-      tuning().kernel != 2) {
-    const bool wide = tuning().kernel == 3 || tsp == 128 ||
+  // The knob "kernel" = 3 forces it wherever its tile fits.
+  if (which == ForwardKernel::Auto && tsp == s.SP && s.SP % 16 == 0 && s.tune.kernel != 1 &&
+      s.tune.kernel != 2) {
+    const bool wide = s.tune.kernel == 3 || tsp == 128 ||
                       (tsp == 96 && tile_inst <= 4096) ||
                       (tsp == 64 && tile_inst <= 256);
     if (wide) {
@@ -1428,10 +1835,10 @@ const char *launch_dp_layer(const Shape &s, const Workspace &w, int l, const flo
       return "k_dp_wide";
     }
   }
-  if (tuning().kernel == 1 || which == ForwardKernel::Push) use_tile = false;
-  if (tuning().kernel == 2 || which == ForwardKernel::Tile) use_tile = true;
+  if (s.tune.kernel == 1 || which == ForwardKernel::Push) use_tile = false;
+  if (s.tune.kernel == 2 || which == ForwardKernel::Tile) use_tile = true;
   if (!force_generic && tsp != 0 && tsp == s.SP && !s.bp16 && use_tile) {
-    int waves = tuning().jsplit;
+    int waves = s.tune.jsplit;
     if (waves < 1 || waves > 4) waves = 4;
     if (waves > s.S) waves = s.S;
     switch (tsp) {

@@ -2,7 +2,9 @@
 // sequence of kernel launches.  No arithmetic of the method happens on the host.
 #include "../../include/gsearch.h"
 
+#include <cctype>
 #include <cstdlib>
+#include <cstring>
 #include <mutex>
 #include <new>
 
@@ -12,9 +14,48 @@ namespace {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Names of the tuning knobs, in the order gsearch_knob_name lists them, and where each lives.
+struct KnobDesc {
+  const char *name;
+  int gs::Tuning::*field;
+};
+const KnobDesc kKnobs[] = {
+    {"kernel", &gs::Tuning::kernel},   {"small", &gs::Tuning::small},
+    {"jsplit", &gs::Tuning::jsplit},   {"waves_per_block", &gs::Tuning::waves_per_block},
+    {"row_groups", &gs::Tuning::row_groups}, {"streams", &gs::Tuning::streams},
+    {"chain", &gs::Tuning::chain},
+};
+constexpr int kKnobCount = (int)(sizeof(kKnobs) / sizeof(kKnobs[0]));
+
+int knob_index(const char *name) {
+  if (!name) return -1;
+  for (int i = 0; i < kKnobCount; ++i)
+    if (strcmp(name, kKnobs[i].name) == 0) return i;
+  return -1;
+}
+
+// Initial knob values of a new context: GSEARCH_<NAME IN CAPITALS> in the environment, read
+// here and nowhere else (an unset or non-numeric variable leaves the default).
+gs::Tuning tuning_from_env() {
+  gs::Tuning t;
+  for (int i = 0; i < kKnobCount; ++i) {
+    char var[64] = "GSEARCH_";
+    size_t n = strlen(var);
+    for (const char *c = kKnobs[i].name; *c && n + 1 < sizeof(var); ++c)
+      var[n++] = (char)toupper((unsigned char)*c);
+    var[n] = 0;
+    const char *e = getenv(var);
+    if (!e || !*e) continue;
+    char *end = nullptr;
+    const long v = strtol(e, &end, 10);
+    if (end && *end == 0 && v >= -1 && v <= 64) t.*(kKnobs[i].field) = (int)v;
+  }
+  return t;
+}
+
 struct Layout {
   size_t planes, bp, Tq, Oq, Rt, ridx, budget, budget0, unit, minO, lowsum, best_s, best_cost,
-      status, cmeta, cstart, cls, Rc, total;
+      status, cmeta, cstart, cls, Rc, maxfit, seg, chain_ctl, chain_items, total;
   int nplanes;
 };
 
@@ -27,6 +68,7 @@ gs::Shape make_shape(int B, int L, int S, int M, int K) {
   s.bp16 = S > 256;
   s.Bc = B;
   s.NC = 32;
+  s.grants = nullptr;
   return s;
 }
 
@@ -70,6 +112,11 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   // (more than 32 classes need more than 32 strategies)
   const size_t ncap = s.S > 32 ? gs::kMaxClasses : 32;
   y.Rc = take(sizeof(float) * (size_t)s.K * ncap * ncap);
+  // queues of the one-launch form of the class kernel
+  y.maxfit = take(sizeof(int32_t) * (size_t)s.B * s.L);
+  y.seg = take(sizeof(int32_t) * gs::chain_seg_entries(s));
+  y.chain_ctl = take(gs::kChainCtlBytes);
+  y.chain_items = take((size_t)16 * 8 * gs::chain_items_per_xcd(s));
   y.total = off;
   return y;
 }
@@ -79,6 +126,15 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
 // Its last 256 bytes hold the word in which k_prepare collects data-status bits (zero between solves).
 size_t zero_row_bytes(int max_M) {
   return align_up(((size_t)max_M + 1 + 63) / 64 * 64 * sizeof(float), 256) + 256;
+}
+
+// Before the zero row: the completion flags of the one-launch class kernel, one word per
+// (layer, instance, 64-row tile) of the largest batch, cleared when the context is created
+// (a flag holds the number of the solve that set it, so solves need not clear them).  A batch
+// shape that would need more than 64 M flags gets none and runs one launch per layer front.
+size_t chain_flag_bytes(const gsearch_config *c) {
+  const size_t n = (size_t)c->max_L * (size_t)c->max_B * (((size_t)c->max_M + 64) / 64);
+  return n > ((size_t)64 << 20) ? 0 : align_up(n * sizeof(uint32_t), 256);
 }
 
 bool config_ok(const gsearch_config *c) {
@@ -128,21 +184,25 @@ struct gsearch_ctx {
   int n_side = 0;
   int groups = 0; // 0 = choose from the shape
   int groups_used = 0; // by the most recent solve
+  // One-launch form of the class kernel: needs the chip's XCDs to be numbered 0..7 (looked at
+  // once, when the context is created) and the flag words at the end of the workspace.
+  bool chain_ok = false;
+  int cus = 0;        // compute units of the device
+  uint32_t epoch = 0; // number of the most recent solve that used the flags
+  gs::Tuning tune;      // launch overrides (from the environment at create, gsearch_set_knob)
+  gs::LdsGrants grants; // LDS sizes already asked for, per kernel
 };
 
 namespace {
 
-// Number of instance groups for a batch (GSEARCH_STREAMS overrides).  Measured on MI355X
+// Number of instance groups for a batch (the knob "streams" overrides).  Measured on MI355X
 // over S = 24..128 and fronts of 6e7..2.4e9 relaxations: two groups pay as soon as a layer
 // front is worth about 3e8 relaxations (8 to 35 % on the large batches:
 // a front there is a few rounds of long workgroups, and the second chain fills the tail of
 // each round and the gap between launches) and cost 10 to 40 % below 1.5e8 (fronts of a
 // few microseconds lose to the fork and join); more than two add little.
 int group_count(const gs::Shape &s, int requested, bool class_kernel) {
-  static const int env = [] {
-    const char *e = getenv("GSEARCH_STREAMS");
-    return e ? atoi(e) : 0;
-  }();
+  const int env = s.tune.streams;
   const double front = (double)s.B * (s.M + 1) * s.S * s.S;
   // (the class kernel's launches are one round of short workgroups; a second chain was
   // measured to add its own launch overhead without filling anything)
@@ -184,6 +244,17 @@ gs::Workspace group_view(const gs::Shape &s, const gs::Workspace &w, int b0) {
   return g;
 }
 
+// The one-launch form of the class kernel (every XCD serves the instances b = x, x + 8, ...).
+// Measured on MI355X it does not beat one launch per layer front (configs[3]: 1.93 against
+// 1.67 ms forward, configs[1]: 0.44 against 0.39 ms: a compute unit holds four workgroups of
+// eight waves, and what an item adds to a tile's own latency (waiting for the tiles below it,
+// store acknowledgement, two more barriers) leaves the vector units idle about as long as the
+// launch gaps it removes), so it runs only when the knob "chain" = 1 asks for it.
+bool chain_applies(const gsearch_ctx *ctx, const gs::Shape &s) {
+  if (!ctx->chain_ok || !gs::chain_shape_ok(s)) return false;
+  return ctx->tune.chain == 1;
+}
+
 // The solve behind gsearch_solve_batch and gsearch_solve_batch_noalloc.
 int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result *r, void *stream) {
   if (!ctx || !p || !r) return GSEARCH_ERR_INVALID_ARG;
@@ -198,11 +269,13 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   gs::Shape s = make_shape(p->B, p->L, p->S, p->M, p->K);
+  s.tune = ctx->tune;
+  s.grants = &ctx->grants;
   // class capacity of this solve: the wide form only when the caller announces it
   if (p->r_class && p->r_class_bound > 32 && p->S > 32) s.NC = gs::kMaxClasses;
   const Layout y = make_layout(s, c.flags);
   const size_t zb = zero_row_bytes(c.max_M);
-  if (y.total > ctx->bytes - zb) return GSEARCH_ERR_CAPACITY;
+  if (y.total > ctx->bytes - zb - chain_flag_bytes(&c)) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
   w.by_class = 0;
   char *base = ctx->base;
@@ -227,6 +300,12 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   w.cstart = reinterpret_cast<int32_t *>(base + y.cstart);
   w.cls = reinterpret_cast<int32_t *>(base + y.cls);
   w.Rc = reinterpret_cast<float *>(base + y.Rc);
+  w.maxfit = reinterpret_cast<int32_t *>(base + y.maxfit);
+  w.seg = reinterpret_cast<int32_t *>(base + y.seg);
+  w.chain_ctl = base + y.chain_ctl;
+  w.chain_items = base + y.chain_items;
+  w.chain_flags = reinterpret_cast<unsigned *>(base + (ctx->bytes - zb - chain_flag_bytes(&c)));
+  w.epoch = 0;
   ctx->solved = false;
   ctx->shape = s;
   ctx->ws = w;
@@ -264,6 +343,21 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
     gs::launch_dp_small(s, w, keep, cur, st);
     ctx->forward_kernel = "k_dp_small";
     ctx->groups_used = 1;
+  } else if (use_classes && chain_applies(ctx, s)) {
+    // every layer front in one launch, the instances bound to XCDs (see k_dp_class_chain)
+    if (keep) gs::launch_class_zero(s, w.planes, st);
+    if (++ctx->epoch == 0) { // the counter wrapped: flags of old solves could be mistaken for new
+      if (hipMemsetAsync(w.chain_flags, 0, chain_flag_bytes(&c), st) != hipSuccess)
+        return GSEARCH_ERR_HIP;
+      ctx->epoch = 1;
+    }
+    w.epoch = ctx->epoch;
+    ctx->ws = w;
+    if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
+    ctx->forward_kernel = gs::launch_dp_class_chain(s, w, keep, with_bp, pe, bp_layer_bytes,
+                                                    ctx->cus, st);
+    ctx->groups_used = 1;
+    cur = keep ? s.L - 1 : ((s.L - 1) & 1);
   } else {
     // Q[0] = 0: stored only when the planes are kept (the readers of kept planes read it);
     // otherwise the first front reads the context's row of zeros for every class
@@ -381,7 +475,7 @@ size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
   return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
                      cfg->flags)
              .total +
-         zero_row_bytes(cfg->max_M);
+         chain_flag_bytes(cfg) + zero_row_bytes(cfg->max_M);
 }
 
 int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
@@ -398,6 +492,7 @@ int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
   gsearch_ctx *ctx = new (std::nothrow) gsearch_ctx;
   if (!ctx) return GSEARCH_ERR_NO_MEMORY;
   ctx->cfg = *cfg;
+  ctx->tune = tuning_from_env();
   ctx->bytes = gsearch_workspace_bytes(cfg);
   void *p = nullptr;
   if (hipMalloc(&p, ctx->bytes) != hipSuccess) {
@@ -406,15 +501,25 @@ int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
     return GSEARCH_ERR_NO_MEMORY;
   }
   ctx->base = static_cast<char *>(p);
-  const size_t zb = zero_row_bytes(cfg->max_M);
+  const size_t zb = zero_row_bytes(cfg->max_M) + chain_flag_bytes(cfg);
   // (waited for here: solves may run on streams that do not order themselves after it)
-  if (hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) != hipSuccess ||
-      hipStreamSynchronize(nullptr) != hipSuccess) {
+  unsigned xcds = 0;
+  bool ok = hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) == hipSuccess &&
+            hipMemset(ctx->base, 0, sizeof(unsigned)) == hipSuccess;
+  if (ok) {
+    gs::launch_xcc_probe(reinterpret_cast<unsigned *>(ctx->base), nullptr);
+    ok = hipGetLastError() == hipSuccess && hipStreamSynchronize(nullptr) == hipSuccess &&
+         hipMemcpy(&xcds, ctx->base, sizeof(unsigned), hipMemcpyDeviceToHost) == hipSuccess &&
+         hipDeviceGetAttribute(&ctx->cus, hipDeviceAttributeMultiprocessorCount, cfg->device) ==
+             hipSuccess;
+  }
+  if (!ok) {
     (void)hipGetLastError();
     (void)hipFree(p);
     delete ctx;
     return GSEARCH_ERR_HIP;
   }
+  ctx->chain_ok = xcds == 0xFFu && ctx->cus >= 8 && chain_flag_bytes(cfg) > 0;
   *out = ctx;
   return GSEARCH_OK;
 }
@@ -472,10 +577,12 @@ int gsearch_solve_batch_noalloc(int32_t device, const gsearch_problem *p, const 
   ctx->bytes = (size_t)GSEARCH_NOALLOC_SCRATCH_BYTES;
   ctx->profiling = false;
   ctx->groups = 1; // one chain of launches on the caller's stream: no streams or events to create
+  ctx->chain_ok = false; // (the one-launch class kernel keeps flags across solves: not on this array)
   // The array keeps whatever the last call left.  What a solve expects to find cleared sits at
   // the end of the workspace: the row of zeros that stands for Q[0] and the word in which the
   // data-status bits are collected.  Its place depends on M, so it is cleared on every call.
   const size_t zb = zero_row_bytes(cfg.max_M);
+  // (solve_impl places the zero row at the very end of the workspace)
   hipLaunchKernelGGL(k_clear_words, dim3((unsigned)((zb / 4 + 255) / 256)), dim3(256), 0, st,
                      reinterpret_cast<uint32_t *>(base + (ctx->bytes - zb)), zb / 4);
   const int rc = solve_impl(ctx, p, r, stream);
@@ -522,6 +629,24 @@ const char *gsearch_forward_kernel(gsearch_ctx *ctx) {
 int gsearch_set_instance_groups(gsearch_ctx *ctx, int groups) {
   if (!ctx || groups < 0) return GSEARCH_ERR_INVALID_ARG;
   ctx->groups = groups;
+  return GSEARCH_OK;
+}
+
+const char *gsearch_knob_name(int index) {
+  return (index >= 0 && index < kKnobCount) ? kKnobs[index].name : nullptr;
+}
+
+int gsearch_set_knob(gsearch_ctx *ctx, const char *name, int value) {
+  const int i = knob_index(name);
+  if (!ctx || i < 0 || value < -1 || value > 64) return GSEARCH_ERR_INVALID_ARG;
+  ctx->tune.*(kKnobs[i].field) = value;
+  return GSEARCH_OK;
+}
+
+int gsearch_get_knob(gsearch_ctx *ctx, const char *name, int *value) {
+  const int i = knob_index(name);
+  if (!ctx || i < 0 || !value) return GSEARCH_ERR_INVALID_ARG;
+  *value = ctx->tune.*(kKnobs[i].field);
   return GSEARCH_OK;
 }
 

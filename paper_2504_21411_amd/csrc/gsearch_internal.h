@@ -10,8 +10,31 @@ namespace gs {
 
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kRowsPerBlock = 256; // budget rows handled by one workgroup (4 waves)
+constexpr size_t kChainCtlBytes = 16384; // room for the queue counters of the one-launch class kernel
 constexpr int kMaxClasses = 64;    // most transition classes a solve can exploit (capacity of the
                                    // class kernel's wide variant; the narrow one holds 32)
+
+// Launch-heuristic overrides of one context (sweeps and tests; 0 or -1 = use the heuristic).
+// A context reads them once from the environment when it is created (GSEARCH_<NAME>) and
+// gsearch_set_knob changes them afterwards; nothing in the library reads the environment later.
+struct Tuning {
+  int kernel = 0;          // 1 push, 2 tile, 3 wide: force that general forward kernel
+  int small = -1;          // 0 / 1: the one-launch kernel for small instances never / wherever it fits
+  int jsplit = 0;          // waves per tile
+  int waves_per_block = 0; // push kernel: waves per workgroup (1..4)
+  int row_groups = 0;      // push kernel: 64-row groups per wave
+  int streams = 0;         // instance groups on parallel streams
+  int chain = -1;          // 1: the one-launch class kernel wherever it can run (else never)
+};
+
+// More than 64 KB of dynamic LDS per workgroup has to be asked for once per kernel (and
+// device; a context lives on one device): the largest size already asked for, per kernel.
+struct LdsGrants {
+  static constexpr int kMax = 48;
+  const void *fn[kMax] = {};
+  size_t bytes[kMax] = {};
+  int n = 0;
+};
 
 // Shape of the batch being solved plus the padded pitches of the workspace copies.
 struct Shape {
@@ -24,6 +47,8 @@ struct Shape {
   int NC;    // class capacity of this solve (32, or 64 when the caller announces more than 32
              // classes): row stride of Rc, columns of the per-class backpointers, cap of the
              // compact planes' rows
+  Tuning tune;       // the context's launch overrides
+  LdsGrants *grants; // the context's record of LDS sizes asked for (never null in a solve)
 };
 
 // Device pointers into the context's workspace.
@@ -62,6 +87,14 @@ struct Workspace {
   int32_t *cls;      // [SP]         class of strategy s (0 for the padding)
   float *Rc;         // [K][NC][NC]  Rc[k][cj][ci] = R between the classes'
                      //              first strategies, +inf for padding classes
+  // One-launch form of the class kernel (see k_dp_class_chain):
+  int32_t *maxfit;   // [B][L]       largest O[b][l][s] that fits the budget at all (0: none)
+  int32_t *seg;      // [8][(L-1)*ceil(B/8)+1]  per XCD: items before each (layer, instance) segment
+  void *chain_ctl;   // queue counters of the solve (struct ChainCtl)
+  void *chain_items; // [8][items per XCD] uint4 item records (layer | instance << 12, tile, lo, hi)
+  unsigned *chain_flags; // [L][B][tiles] completion flags; a flag set by solve number n holds n.
+                     //  Sits at a fixed place at the end of the workspace, cleared at create.
+  unsigned epoch;    // number of this solve (never 0)
 };
 
 inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; }
@@ -85,6 +118,14 @@ bool class_path_applies(const Shape &s);
 const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st);
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
+// The whole forward pass of the class kernel in one launch; `cus` = compute units of the device.
+const char *launch_dp_class_chain(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                                  size_t plane_elems_all, size_t bp_layer_bytes, int cus,
+                                  hipStream_t st);
+size_t chain_seg_entries(const Shape &s);          // int32 entries of Workspace::seg
+size_t chain_items_per_xcd(const Shape &s);        // uint4 records per XCD of Workspace::chain_items
+bool chain_shape_ok(const Shape &s);               // the one-launch form can take this shape
+void launch_xcc_probe(unsigned *mask, hipStream_t st); // OR of (1 << XCD id) over a small grid
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
                            hipStream_t st);
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);

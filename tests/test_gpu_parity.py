@@ -169,7 +169,7 @@ def test_uint16_backpointers_above_256_strategies(gs, oracle_mod):
     wc, r_class = workloads.class_tables("wideclass", 2, 3, 300, 90, [6] * 50, seed=33,
                                          budget=np.array([90, 41], np.int32))
     got = runner.solve_workload(wc, 0, r_class=r_class)
-    assert got["forward_kernel"] != "k_dp_class" and got["data_status"] == 0
+    assert not got["forward_kernel"].startswith("k_dp_class") and got["data_status"] == 0
     assert_same(got, oracle_batch(oracle_mod, wc), wc, "300 strategies with classes")
     wc.R[0, 0, 7] += np.float32(1.0)
     got = runner.solve_workload(wc, 0, r_class=r_class)
@@ -334,9 +334,12 @@ def test_config3_large_dense_full_size(gs, oracle_mod):
     dw = runner.DeviceWorkload(w)
     # the three launch configurations bench.py times (class kernel with and without
     # backpointers, general kernel on two instance groups) and the general min-only pass
+    # (and the class kernel as all fronts in one launch, which the knob "chain" asks for)
     for flags, classes, kernel in ((0, True, "k_dp_class"), (0x4, True, "k_dp_class"),
+                                   (0, True, "k_dp_class_chain"), (0x4, True, "k_dp_class_chain"),
                                    (0, False, "k_dp_wide"), (0x4, False, "k_dp_wide")):
         with runner.make_context(w, flags=flags) as ctx:
+            ctx.gsearch_set_knob("chain", 1 if kernel.endswith("chain") else 0)
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=classes))
             got["data_status"] = ctx.gsearch_data_status()
             assert ctx.gsearch_forward_kernel() == kernel
@@ -502,12 +505,14 @@ CLASS_CASES = [
 ]
 
 
+@pytest.mark.parametrize("chain", [0, 1], ids=["per_front", "one_launch"])
 @pytest.mark.parametrize("mode", ["bp", "nobp"])
 @pytest.mark.parametrize("case", CLASS_CASES, ids=lambda c: "S%dnc%dK%d" % (c[0], len(c[1]), c[2]))
-def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode):
+def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode, chain):
     """R constant on (class, class) blocks, stated through r_class: the class kernel must
     give the oracle's bits (the oracle knows nothing of classes), whole planes and
-    backpointers included, also when candidates of one class round to the same sum."""
+    backpointers included, also when candidates of one class round to the same sum.  Both
+    forms: one launch per layer front, and all fronts in one launch."""
     binding, runner = gs
     import torch
     S, sizes, K, M, coarse = case
@@ -519,6 +524,7 @@ def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode):
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
     with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
+        ctx.gsearch_set_knob("chain", chain)
         out = runner.run_step(ctx, dw, backtrace="all", r_class=rc, r_class_bound=len(sizes))
         C, bp = ctx.gsearch_export_planes(want_bp=(mode == "bp"))
         got = runner.to_numpy(out)
@@ -526,7 +532,7 @@ def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode):
         kernel = ctx.gsearch_forward_kernel()
         C = C.cpu().numpy()
         bp = bp.cpu().numpy() if bp is not None else None
-    assert kernel == ("k_dp_class" if S >= 9 else kernel)
+    assert kernel == (("k_dp_class_chain" if chain else "k_dp_class") if S >= 9 else kernel)
     assert_same(got, ref, w, f"classes {mode}")
     for b in range(B):
         E = int(w.budget[b])
@@ -551,6 +557,7 @@ def test_class_kernel_with_instance_groups_and_single_layer(gs, oracle_mod):
         with runner.make_context(w, flags=flags) as ctx:
             for groups in (2, 5, 1, 0):
                 ctx.gsearch_set_instance_groups(groups)
+                ctx.gsearch_set_knob("chain", 0)       # instance groups: one launch per front
                 got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
                 got["data_status"] = ctx.gsearch_data_status()
                 assert ctx.gsearch_forward_kernel() == "k_dp_class"
@@ -604,13 +611,16 @@ def _class_sweep_case(runner, oracle_mod, rng, case):
     flags = 0x4 if case % 3 == 1 else 0
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
+    chain = (case // 2) % 2
     with runner.make_context(w, flags=flags) as ctx:
+        ctx.gsearch_set_knob("chain", chain)
         if case % 6 == 5:
             ctx.gsearch_set_instance_groups(1 + case % 3)
         got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc,
                                               r_class_bound=len(sizes)))
         got["data_status"] = ctx.gsearch_data_status()
-        assert ctx.gsearch_forward_kernel() == "k_dp_class", (case, S)
+        want = "k_dp_class_chain" if chain and L >= 3 else "k_dp_class"
+        assert ctx.gsearch_forward_kernel() == want, (case, S)
     assert_same(got, ref, w, f"class sweep {case} S={S} sizes={sizes} flags={flags}")
 
 
@@ -618,11 +628,62 @@ def test_class_kernel_random_sweep(gs, oracle_mod):
     """Sixty seeded random class-structured workloads: strategy counts around every
     register-tile size, random partitions of 1..64 classes, several matrices, ragged budgets,
     zero-memory and never-fitting strategies, forbidden class transitions, coarse values that
-    make sums collide, memories with a common divisor, both modes, forced instance groups."""
+    make sums collide, memories with a common divisor, both modes, forced instance groups,
+    one launch per front and all fronts in one launch."""
     _, runner = gs
     rng = workloads.SplitMix64(777)
     for case in range(60):
         _class_sweep_case(runner, oracle_mod, rng, case)
+
+
+@pytest.mark.parametrize("mode", ["bp", "nobp", "keep"])
+@pytest.mark.parametrize("shape", [(8, 20, 44, 3000), (16, 9, 96, 1500), (40, 5, 24, 700),
+                                   (9, 6, 44, 900), (64, 12, 16, 260)],
+                         ids=lambda t: "B%dL%dS%dM%d" % t)
+def test_class_kernel_all_fronts_in_one_launch(gs, oracle_mod, shape, mode):
+    """The one-launch form at shapes with many tiles per instance and many layers: the
+    instances are served XCD by XCD, tiles wait for the tiles of the previous layer they read,
+    and with two ping-pong planes (bp, nobp keeps every plane) also for those that still
+    read the rows they overwrite.  Budgets are ragged, one instance fits nothing, memories
+    are small against the tile (64 rows) in some layers and several tiles wide in others."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = shape
+    sizes = [4] * (S // 4)
+    rng = workloads.SplitMix64(B * 1000 + L)
+    budget = rng.randint(M // 2, M, B).astype(np.int32)
+    budget[0] = M
+    budget[B // 2] = 3                               # fits nothing
+    w, r_class = workloads.class_tables("chain", B, L, S, M, sizes, K=2, seed=B + L + S,
+                                        budget=budget, coarse=(L % 2 == 0))
+    w.O[:, 1::3, :] = np.minimum(w.O[:, 1::3, :] * 9, M // 4)     # layers several tiles wide
+    w.O[:, 2::3, :] = np.maximum(w.O[:, 2::3, :] // 8, 1)          # layers of a few bins
+    ref = oracle_batch(oracle_mod, w)
+    flags = {"bp": 0, "nobp": binding.GSEARCH_FLAG_NO_BACKPOINTERS,
+             "keep": binding.GSEARCH_FLAG_KEEP_PLANES}[mode]
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    with runner.make_context(w, flags=flags) as ctx:
+        ctx.gsearch_set_knob("chain", 1)
+        assert ctx.gsearch_get_knob("chain") == 1
+        for rep in range(3):                          # the flags carry over from solve to solve
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == "k_dp_class_chain"
+            assert_same(got, ref, w, f"one launch {mode} rep {rep}")
+        if mode == "keep":
+            C, bp = ctx.gsearch_export_planes(want_bp=True)
+            C, bp = C.cpu().numpy(), bp.cpu().numpy()
+            for b in (0, B - 1):
+                E = int(w.budget[b])
+                one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True)
+                assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), b
+                assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), b
+        ctx.gsearch_set_knob("chain", 0)
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+        got["data_status"] = ctx.gsearch_data_status()
+        assert ctx.gsearch_forward_kernel() == "k_dp_class"
+        assert_same(got, ref, w, f"per front after one launch {mode}")
 
 
 def test_rounding_tie_inside_a_class_keeps_the_lowest_index(gs, oracle_mod):
@@ -645,7 +706,7 @@ def test_rounding_tie_inside_a_class_keeps_the_lowest_index(gs, oracle_mod):
     ref = oracle_mod.solve(T[0], O[0], R, w.r_index[0], M, want_planes=True)
     assert (ref["bp"][1, 2:, :] == 0).all()                   # the oracle takes index 0
     got = runner.solve_workload(w, r_class=r_class)
-    assert got["forward_kernel"] == "k_dp_class" and got["data_status"] == 0
+    assert got["forward_kernel"].startswith("k_dp_class") and got["data_status"] == 0
     assert np.array_equal(got["plan"][0], ref["plan"]) and got["plan"][0][0] == 0
 
 
@@ -671,12 +732,12 @@ def test_bad_transition_classes_are_flagged(gs):
     w3 = copy.deepcopy(w); w3.R = w.R.copy(); w3.R[0, 9, 2] += np.float32(0.5)   # column differs
     cases["column"] = (w3, r_class)
     ok40 = runner.solve_workload(w40, r_class=np.arange(40, dtype=np.int32))   # announced: fine
-    assert ok40["data_status"] == 0 and ok40["forward_kernel"] == "k_dp_class"
+    assert ok40["data_status"] == 0 and ok40["forward_kernel"].startswith("k_dp_class")
     # the bound is an upper bound: larger than the count (even absurdly) is fine, and a
     # negative one means "not announced"
     for bound in (64, 10 ** 6, -5):
         got = runner.solve_workload(w, r_class=r_class, r_class_bound=bound)
-        assert got["data_status"] == 0 and got["forward_kernel"] == "k_dp_class", bound
+        assert got["data_status"] == 0 and got["forward_kernel"].startswith("k_dp_class"), bound
         assert np.array_equal(bits(got["best_cost"]), bits(ok["best_cost"])), bound
         assert np.array_equal(got["plan"], ok["plan"]), bound
     got = runner.solve_workload(w40, r_class=np.arange(40, dtype=np.int32), r_class_bound=10 ** 6)
@@ -720,7 +781,7 @@ def test_model_configs_without_classes_use_the_general_kernels(gs, oracle_mod, i
     ref = oracle_batch(oracle_mod, w, T, O, R)
     a = runner.solve_workload(w, classes=True)
     b = runner.solve_workload(w, classes=False)
-    assert a["forward_kernel"] == "k_dp_class" and b["forward_kernel"] in ("k_dp_tile", "k_dp_wide")
+    assert a["forward_kernel"].startswith("k_dp_class") and b["forward_kernel"] in ("k_dp_tile", "k_dp_wide")
     assert_same(a, ref, w, "classes")
     assert_same(b, ref, w, "general")
 
@@ -777,11 +838,11 @@ def test_strategy_sets_with_more_than_32_layouts(gs, oracle_mod):
         with runner.make_context(w, flags=flags) as ctx:
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
             got["data_status"] = ctx.gsearch_data_status()
-            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+            assert ctx.gsearch_forward_kernel().startswith("k_dp_class")
             assert_same(got, ref, w, f"36 classes, wide class kernel, flags={flags}")
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=False))
             got["data_status"] = ctx.gsearch_data_status()
-            assert ctx.gsearch_forward_kernel() != "k_dp_class"
+            assert not ctx.gsearch_forward_kernel().startswith("k_dp_class")
             assert_same(got, ref, w, f"36 classes withheld, flags={flags}")
             r_class, _ = binding.gsearch_layout_classes(torch.from_numpy(desc).to(dw.device))
             runner.run_step(ctx, dw, backtrace=None, r_class=r_class)       # bound not announced
@@ -795,7 +856,7 @@ def test_strategy_sets_with_more_than_32_layouts(gs, oracle_mod):
     with runner.make_context(w) as ctx:
         got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
         got["data_status"] = ctx.gsearch_data_status()
-        assert ctx.gsearch_forward_kernel() == "k_dp_class"
+        assert ctx.gsearch_forward_kernel().startswith("k_dp_class")
         assert_same(got, oracle_batch(oracle_mod, w, T, O, R), w, "256 devices, 45 classes")
     w = workloads._model_workload("n1024", 1, 3, 300, dict(N=1024), [8192.0], [4096.0], 262144.0,
                                   80.0e9, seed=78, S=242)
@@ -806,7 +867,7 @@ def test_strategy_sets_with_more_than_32_layouts(gs, oracle_mod):
     with runner.make_context(w) as ctx:
         got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
         got["data_status"] = ctx.gsearch_data_status()
-        assert ctx.gsearch_forward_kernel() != "k_dp_class" and "r_class" not in got
+        assert not ctx.gsearch_forward_kernel().startswith("k_dp_class") and "r_class" not in got
         assert_same(got, oracle_batch(oracle_mod, w, T, O, R), w, "66 classes, general kernels")
 
 
@@ -865,7 +926,7 @@ def test_wide_class_kernel_at_large_budgets(gs, oracle_mod, case):
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc,
                                                   r_class_bound=len(sizes)))
             got["data_status"] = ctx.gsearch_data_status()
-            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+            assert ctx.gsearch_forward_kernel().startswith("k_dp_class")
             curve = ctx.gsearch_budget_curve().cpu().numpy()
         assert_same(got, ref, w, f"{case[0]} strategies, {len(sizes)} classes, M={M}, {mode}")
         for b in range(B):
@@ -913,7 +974,7 @@ def test_class_kernel_batch_sizes_that_are_not_a_multiple_of_eight(gs, oracle_mo
         with runner.make_context(w, flags=MODES[mode]) as ctx:
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
             got["data_status"] = ctx.gsearch_data_status()
-            assert ctx.gsearch_forward_kernel() == "k_dp_class"
+            assert ctx.gsearch_forward_kernel().startswith("k_dp_class")
         assert_same(got, ref, w, f"B={B} {mode}")
 
 
@@ -961,7 +1022,7 @@ def test_instances_are_solved_in_their_own_bin_unit(gs, oracle_mod, mode):
         got = runner.solve_workload(w, flags | extra, r_class=rc)
         assert_same(got, ref, w, f"{mode} flags {flags | extra:#x}")
         if rc is not None:
-            assert got["forward_kernel"] == "k_dp_class"
+            assert got["forward_kernel"].startswith("k_dp_class")
     # whole planes, backpointers and curve in the caller's bins
     dw = runner.DeviceWorkload(w)
     rct = None if rc is None else torch.from_numpy(rc).to(dw.device)
