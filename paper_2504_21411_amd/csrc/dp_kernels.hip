@@ -836,6 +836,7 @@ static __device__ __forceinline__ void class_tile(
 #pragma unroll
     for (int x = 0; x < NC / 16; ++x) rv[x] = *reinterpret_cast<const float16_t *>(rc + 16 * x);
     // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
+    // (chunk 0 always exists and starts the scan: "cm < +inf ? cm : +inf" is cm)
     float m = GS_INF;
     int g = 0;
 #pragma unroll
@@ -850,7 +851,8 @@ static __device__ __forceinline__ void class_tile(
 #pragma unroll
           for (int k = 4; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
         }
-        chunk_update<true>(m, g, cm, q);
+        if (q == 0) m = cm;
+        else chunk_update<true>(m, g, cm, q);
       }
     }
     const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
@@ -887,14 +889,23 @@ static __device__ __forceinline__ void class_tile(
       const int tl = lo * kWave + lane;
       const int tl_max = (SP - 1) * kWave + lane;
       int rel = 0;
-      for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
-        const int at0 = tl + d0 * kWave;
-        const float *tr = tile + (at0 < tl_max ? at0 : tl_max);
+      if (maxlen <= 4) { // wave-uniform; the usual case: one round, constant member numbers
+        const float *tr = tile + (tl < tl_max ? tl : tl_max);
         float tv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) tv[u] = tr[u * kWave];
 #pragma unroll
-        for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? d0 + u : rel;
+        for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? u : rel;
+      } else {
+        for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
+          const int at0 = tl + d0 * kWave;
+          const float *tr = tile + (at0 < tl_max ? at0 : tl_max);
+          float tv[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) tv[u] = tr[u * kWave];
+#pragma unroll
+          for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? d0 + u : rel;
+        }
       }
       arg = lo + rel;
       bpb[at] = (uint8_t)arg;
