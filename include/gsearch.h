@@ -256,6 +256,14 @@ int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
  * solve).  Static string. */
 const char *gsearch_forward_kernel(gsearch_ctx *ctx);
 
+/* Measurement aid: LDS traffic of exactly known size, by which the profiler's LDS counters are
+ * scaled (as its HBM counters are by a plain copy).  One launch of 1024 x 256 threads, each
+ * doing `iters` (1 .. 2^20) operations of one kind on a 16 KB table without bank conflicts:
+ * mode 0 four-byte loads, 1 sixteen-byte loads, 2 four-byte stores, 3 float-minimum atomics,
+ * i.e. 262144 x iters x (4 | 16 | 4 | 4) bytes.  sink: device [262144] floats (scratch output).
+ * Asynchronous on `stream`.  Errors: INVALID_ARG, HIP. */
+int gsearch_lds_calibration(int32_t mode, int32_t iters, float *sink, void *stream);
+
 /* Best cost for EVERY budget of the most recent solve (the last plane already holds
  * it): curve[b][e] = min_s C[L-1][e][s] for e <= E_b, +inf for E_b < e <= M.
  * curve is device [B][M+1].  Paper section 1, feature 2 (adapting to hardware

@@ -48,7 +48,7 @@ EXPORTS = [
     "gsearch_set_profiling", "gsearch_forward_ms", "gsearch_forward_kernel",
     "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
     "gsearch_instance_groups", "gsearch_layout_classes", "gsearch_solve_batch_noalloc",
-    "gsearch_knob_name", "gsearch_set_knob", "gsearch_get_knob",
+    "gsearch_knob_name", "gsearch_set_knob", "gsearch_get_knob", "gsearch_lds_calibration",
 ]
 
 
@@ -126,6 +126,8 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_set_profiling.argtypes = [vp, ctypes.c_int]
     lib.gsearch_set_instance_groups.restype = ctypes.c_int
     lib.gsearch_set_instance_groups.argtypes = [vp, ctypes.c_int]
+    lib.gsearch_lds_calibration.restype = ctypes.c_int
+    lib.gsearch_lds_calibration.argtypes = [i32, i32, vp, vp]
     lib.gsearch_knob_name.restype = ctypes.c_char_p
     lib.gsearch_knob_name.argtypes = [ctypes.c_int]
     lib.gsearch_set_knob.restype = ctypes.c_int
@@ -190,6 +192,15 @@ def _stream(stream) -> Optional[int]:
     if stream is None:
         stream = torch.cuda.current_stream()
     return stream.cuda_stream or None
+
+
+def gsearch_lds_calibration(mode: int, iters: int, device="cuda", stream=None) -> int:
+    """One launch of LDS traffic of known size; returns the bytes it moves through LDS."""
+    import torch
+    sink = torch.empty(1024 * 256, dtype=torch.float32, device=device)
+    _check(load_library().gsearch_lds_calibration(int(mode), int(iters), _ptr(sink),
+                                                  _stream(stream)), "gsearch_lds_calibration")
+    return 1024 * 256 * int(iters) * (16 if mode == 1 else 4)
 
 
 def gsearch_knob_names() -> list:

@@ -1393,6 +1393,50 @@ void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hi
                        s.L, s.S, s.SP, class_rows(s), s.NC, s.M, s.pitch);
 }
 
+// ----------------------------------------------------------------------------------------
+// Measurement aid: a kernel whose LDS traffic is known exactly, to scale the profiler's LDS
+// counters by (what a plain copy is to the HBM counters).  Every lane of 1024 x 256 threads
+// performs `iters` operations of one kind on a 16 KB table, conflict-free (consecutive lanes,
+// consecutive words or 16-byte vectors): 0 four-byte loads, 1 sixteen-byte loads, 2 four-byte
+// stores, 3 float-minimum atomics.  The sum that keeps the loads alive goes to `sink`.
+// ----------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256) void k_lds_calibration(float *__restrict__ sink, int iters) {
+  __shared__ float4 tab[1024]; // 16 KB
+  float *f = reinterpret_cast<float *>(tab);
+  for (int i = threadIdx.x; i < 1024; i += 256) tab[i] = make_float4(1.0f, 2.0f, 3.0f, 4.0f);
+  __syncthreads();
+  float acc = 0.0f;
+  unsigned idx = threadIdx.x;
+  for (int i = 0; i < iters; ++i) {
+    if (MODE == 0) {
+      acc += f[idx & 4095];
+    } else if (MODE == 1) {
+      const float4 r = tab[idx & 1023];
+      acc += r.x + r.w;
+    } else if (MODE == 2) {
+      f[idx & 4095] = acc + (float)i;
+    } else {
+      __hip_atomic_fetch_min(&f[idx & 4095], acc - (float)i, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    idx += 256;
+    asm volatile("" : "+v"(acc)); // one LDS instruction per iteration, none merged or hoisted
+  }
+  __syncthreads();
+  sink[blockIdx.x * 256 + threadIdx.x] = acc + f[threadIdx.x];
+}
+
+void launch_lds_calibration(int mode, int iters, float *sink, hipStream_t st) {
+  const dim3 grid(1024), block(256);
+  switch (mode) {
+    case 0: hipLaunchKernelGGL(k_lds_calibration<0>, grid, block, 0, st, sink, iters); break;
+    case 1: hipLaunchKernelGGL(k_lds_calibration<1>, grid, block, 0, st, sink, iters); break;
+    case 2: hipLaunchKernelGGL(k_lds_calibration<2>, grid, block, 0, st, sink, iters); break;
+    default: hipLaunchKernelGGL(k_lds_calibration<3>, grid, block, 0, st, sink, iters); break;
+  }
+}
+
 void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,
                       int32_t *count_out, hipStream_t st) {
   int k = 0;

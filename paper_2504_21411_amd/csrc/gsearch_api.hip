@@ -307,6 +307,7 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   w.chain_flags = reinterpret_cast<unsigned *>(base + (ctx->bytes - zb - chain_flag_bytes(&c)));
   w.epoch = 0;
   ctx->solved = false;
+  ctx->forward_kernel = ""; // (a solve of one layer launches no forward kernel)
   ctx->shape = s;
   ctx->ws = w;
 
@@ -373,14 +374,22 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
     // one instance's share of a plane slot
     const size_t inst_elems = (size_t)(use_classes ? gs::class_rows(s) : s.S) * s.pitch;
     int last = 0;
-    for (int g = groups - 1; g >= 0; --g) { // the caller's stream (group 0) is fed last
+    bool failed = false;
+    bool fed[gsearch_ctx::kMaxSide] = {};    // side stream i may have been given work
+    for (int g = groups - 1; g >= 0 && !failed; --g) { // the caller's stream (group 0) is fed last
       const int b0 = (int)((long long)s.B * g / groups);
       const int b1 = (int)((long long)s.B * (g + 1) / groups);
       gs::Shape sg = s;
       sg.B = b1 - b0;
       const gs::Workspace wg = group_view(s, w, b0);
       hipStream_t sst = g == 0 ? st : ctx->side[g - 1];
-      if (g > 0 && hipStreamWaitEvent(sst, ctx->ev_fork, 0) != hipSuccess) return GSEARCH_ERR_HIP;
+      if (g > 0) {
+        if (hipStreamWaitEvent(sst, ctx->ev_fork, 0) != hipSuccess) {
+          failed = true;
+          break;
+        }
+        fed[g - 1] = true;
+      }
       int c2 = 0;
       for (int l = 1; l < s.L; ++l) {
         const int nxt = keep ? l : (c2 ^ 1);
@@ -396,12 +405,26 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
         c2 = nxt;
       }
       last = c2;
-      if (g > 0) {
-        if (hipEventRecord(ctx->ev_join[g - 1], sst) != hipSuccess) return GSEARCH_ERR_HIP;
+    }
+    // Join: the caller's stream waits for every side stream that was given work, also when a
+    // call above failed (whatever those streams still run must be over before the caller's
+    // next call on this context touches the workspace).  Where even the join cannot be
+    // recorded, the call waits for that stream itself.
+    for (int i = 0; i < groups - 1; ++i) {
+      if (!fed[i]) continue;
+      if (hipEventRecord(ctx->ev_join[i], ctx->side[i]) == hipSuccess &&
+          hipStreamWaitEvent(st, ctx->ev_join[i], 0) == hipSuccess)
+        continue;
+      {
+        failed = true;
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(ctx->side[i]);
       }
     }
-    for (int g = 1; g < groups; ++g)
-      if (hipStreamWaitEvent(st, ctx->ev_join[g - 1], 0) != hipSuccess) return GSEARCH_ERR_HIP;
+    if (failed) {
+      (void)hipGetLastError();
+      return GSEARCH_ERR_HIP;
+    }
     cur = last;
   }
   if (timing) {
@@ -678,6 +701,12 @@ int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms) {
   if (hipEventElapsedTime(host_ms, ctx->ev_begin, ctx->ev_end) != hipSuccess)
     return GSEARCH_ERR_HIP;
   return GSEARCH_OK;
+}
+
+int gsearch_lds_calibration(int32_t mode, int32_t iters, float *sink, void *stream) {
+  if (mode < 0 || mode > 3 || iters < 1 || iters > (1 << 20) || !sink) return GSEARCH_ERR_INVALID_ARG;
+  gs::launch_lds_calibration(mode, iters, sink, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
 }
 
 int gsearch_budget_curve(gsearch_ctx *ctx, float *curve, void *stream) {

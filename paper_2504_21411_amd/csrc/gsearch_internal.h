@@ -152,6 +152,8 @@ void launch_pipeline_reduce(const Shape &s, const Workspace &w, int G, const int
 void launch_budget_curve(const Shape &s, const Workspace &w, const float *last_plane,
                          float *curve, hipStream_t st);
 void launch_export(const Shape &s, const Workspace &w, float *C, int32_t *bp, hipStream_t st);
+// LDS traffic of known size (see k_lds_calibration); sink: 1024 * 256 floats
+void launch_lds_calibration(int mode, int iters, float *sink, hipStream_t st);
 void launch_enumerate(int N, int tp_max, int sp_max, int tpsp_max, int32_t *desc, int cap,
                       int32_t *count_out, hipStream_t st);
 void launch_build_tables_profiled(int B, int L, int S, int M, int Y, int NB, const int32_t *desc,

