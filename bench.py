@@ -314,7 +314,16 @@ def main():
                                 "HIP events over the forward pass (a profiler serialises them: "
                                 "see frac_single_chain)")
         if prof.get("avg_us") is not None:
+            # the same algorithmic work per launch over the kernel-trace average of the
+            # profile (dispatches serialised, about a microsecond of tracing each): the figure
+            # that profiles/ alone reproduces
             roof["profiled_kernel_avg_us"] = prof["avg_us"]
+            if roof["bound"] == "alu":
+                roof["frac_at_profiled_duration"] = ops / (prof["avg_us"] * 1e-6) / 1e12 \
+                    / ALU_PEAK_TLANEOPS
+            else:
+                roof["frac_at_profiled_duration"] = front_bytes / groups / (prof["avg_us"] * 1e-6) \
+                    / 1e9 / HBM_PEAK_GBS
         res = {"mode": mode, "ms_per_step": ms_step, "forward_ms": fwd_ms,
                "grelax_per_s": relax / (ms_step * 1e-3) / 1e9,
                "forward_grelax_per_s": relax / (fwd_ms * 1e-3) / 1e9,
@@ -330,6 +339,8 @@ def main():
             roof["single_chain_forward_ms"] = one["forward_ms"]
             roof["single_chain_profiled_kernel_avg_us"] = \
                 one["roofline"].get("profiled_kernel_avg_us")
+            roof["frac_single_chain_at_profiled_duration"] = \
+                one["roofline"].get("frac_at_profiled_duration")
         return res
 
     w = workloads.get_config(args.config)
