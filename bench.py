@@ -226,34 +226,40 @@ def main():
                 extras["pipeline_reduce_ms"] = (time.perf_counter() - t1) * 1e3 / 5
                 extras["pipeline_candidates"] = int(gk.numel())
             # Share of the (layer, budget row) pairs the forward kernels really computed:
-            # rows below the prefix sum of the per-layer minimum memory are filled with
-            # +inf without being computed (64-row tile granularity).  Reporting only.
+            # source rows below the prefix sum of the per-layer minimum memory hold +inf and
+            # are filled without being computed (64-row tile granularity); source rows above
+            # E minus the suffix sum of the remaining layers' minimum memory lead to no
+            # complete plan within the budget and are skipped.  Reporting only.
             O = (out["O"] if "O" in out else dw.O).cpu().numpy().astype(np.int64)
-            low = np.minimum(np.cumsum(np.minimum(O.min(axis=2), w.M + 1), axis=1), w.M + 1)
+            mo = np.minimum(O.min(axis=2), w.M + 1)
+            low = np.minimum(np.cumsum(mo, axis=1), w.M + 1)
+            top = np.minimum(np.cumsum(mo[:, ::-1], axis=1)[:, ::-1], w.M + 1)  # layers l..L-1
             rows = w.budget.astype(np.int64)[:, None] + 1
             skipped = np.minimum(low[:, :-1] // 64 * 64, rows)
-            executed = float((rows - skipped).sum()) / float((rows * (w.L - 1)).sum())
+            upper = np.maximum(rows - top[:, 1:], 0)          # useful source rows of front l
+            active = np.maximum(upper - np.minimum(skipped, upper), 0)
+            executed = float(active.sum()) / float((rows * (w.L - 1)).sum())
             if not kernel.startswith(("k_dp_push", "k_dp_tile", "k_dp_wide", "k_dp_class")):
                 executed = 1.0
             n_class = int(out["n_class"].cpu()[0]) if "n_class" in out else None
-            computed = float((rows - skipped).sum()) / (w.L - 1)
+            computed = float(active.sum()) / (w.L - 1)
             if kernel.startswith("k_dp_class"):
                 # Compact planes: a front reads and writes one float per computed source
-                # row and CLASS (plus one backpointer byte); rows above E - min_s O[l][s]
-                # have no target within the budget and are not touched.
+                # row and CLASS (plus one backpointer byte).
                 rc = out["r_class"].cpu().numpy()
                 max_len = int(np.bincount(rc).max())
-                upper = np.maximum(rows - np.minimum(O.min(axis=2), w.M + 1)[:, 1:], 0)
-                class_rows = float(np.maximum(upper - np.minimum(skipped, upper), 0).sum()) \
-                    / (w.L - 1)
+                class_rows = computed
                 front_bytes = class_rows * n_class * (8.0 if nobp else 9.0)
             else:
                 # algorithmic HBM bytes of one layer front: every computed source row is
-                # read once (4 B per state) and every target row 0..E written once (4 B per
-                # state); backpointers: 1 B per target state
-                front_bytes = (computed * 4.0 + float(rows.sum()) * 4.0) * w.S
+                # read once (4 B per state) and every useful target row (those the next front,
+                # or the result, reads) written once (4 B per state); backpointers: 1 B per
+                # target state
+                nxt = np.concatenate([top[:, 2:], np.zeros((top.shape[0], 1), np.int64)], axis=1)
+                targets = float(np.maximum(rows - nxt, 0).sum()) / (w.L - 1)
+                front_bytes = (computed * 4.0 + targets * 4.0) * w.S
                 if not nobp:
-                    front_bytes += float(rows.sum()) * w.S
+                    front_bytes += targets * w.S
             if kernel == "k_dp_small":
                 front_bytes = 0.0 if nobp else float(rows.sum()) * w.S   # planes stay in LDS
         ms_step = dt * 1e3 / steps

@@ -125,9 +125,9 @@ static __device__ void bin_unit_part(int b, int32_t *__restrict__ Oq,
                                      int32_t *__restrict__ budget,
                                      int32_t *__restrict__ budget0, int32_t *__restrict__ unit,
                                      int32_t *__restrict__ minO, int32_t *__restrict__ lowsum,
-                                     int32_t *__restrict__ status,
+                                     int32_t *__restrict__ topsum, int32_t *__restrict__ status,
                                      int32_t *__restrict__ status_acc, int L, int SP, int M,
-                                     int enable) {
+                                     int enable, int all_rows) {
   __shared__ int red[4];
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int lane = threadIdx.x & 63;
@@ -198,6 +198,26 @@ static __device__ void bin_unit_part(int b, int32_t *__restrict__ Oq,
     }
     v = (v + carry > M + 1) ? M + 1 : v + carry;
     if (l < L) lowsum[(size_t)b * L + l] = v;
+    carry = __shfl(v, kWave - 1, kWave);
+  }
+  // The same from the other end: topsum[b][l] = min(M+1, sum_{l' >= l} min_s O[l'][s]), the
+  // least memory layers l..L-1 still need.  A state (l-1, r) with r > E - topsum[l] cannot be
+  // completed within the budget, so no result reads it (final row, budget curve and every
+  // plan pass through states below that bound only): the forward kernels skip the tiles of
+  // source rows above it.  With all_rows (kept planes are exported whole) the bound is the
+  // layer's own least memory, beyond which a source row has no target row at all.
+  carry = 0;
+  for (int k0 = 0; k0 < L; k0 += kWave) {
+    const int l = L - 1 - (k0 + lane);
+    int v = l >= 0 ? minO[(size_t)b * L + l] : 0;
+    const int own = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int up = __shfl_up(v, d, kWave);
+      if (lane >= d) v = (v + up > M + 1) ? M + 1 : v + up;
+    }
+    v = (v + carry > M + 1) ? M + 1 : v + carry;
+    if (l >= 0) topsum[(size_t)b * L + l] = all_rows ? own : v;
     carry = __shfl(v, kWave - 1, kWave);
   }
 }
@@ -1232,21 +1252,21 @@ __global__ __launch_bounds__(256) void k_prepare(
 __global__ __launch_bounds__(256) void k_bin_unit(
     int B, int32_t *__restrict__ Oq, int32_t *__restrict__ budget,
     int32_t *__restrict__ budget0, int32_t *__restrict__ unit, int32_t *__restrict__ minO,
-    int32_t *__restrict__ lowsum, int32_t *__restrict__ status,
-    int32_t *__restrict__ status_acc, int L, int SP, int M, int enable,
+    int32_t *__restrict__ lowsum, int32_t *__restrict__ topsum, int32_t *__restrict__ status,
+    int32_t *__restrict__ status_acc, int L, int SP, int M, int enable, int all_rows,
     const float *__restrict__ Rt, const int32_t *__restrict__ cmeta,
     const int32_t *__restrict__ cstart, float *__restrict__ Rc, int K, int NC) {
   const int block = (int)blockIdx.x;
   if (block < B)
-    bin_unit_part(block, Oq, budget, budget0, unit, minO, lowsum, status, status_acc, L, SP, M,
-                  enable);
+    bin_unit_part(block, Oq, budget, budget0, unit, minO, lowsum, topsum, status, status_acc, L,
+                  SP, M, enable, all_rows);
   else
     build_Rc_part(block - B, (int)gridDim.x - B, Rt, cmeta, cstart, Rc, SP, K, NC);
 }
 
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
                     const int32_t *r_index, const int32_t *budget, const int32_t *r_class,
-                    const Workspace &w, bool compress_bins, hipStream_t st) {
+                    const Workspace &w, bool compress_bins, bool all_rows, hipStream_t st) {
   const long long nr = (long long)s.K * s.SP * s.SP + s.SP;
   const long long waves = (long long)s.B * s.L + (nr + kWave - 1) / kWave + (s.B + kWave - 1) / kWave;
   const unsigned nb_tables = (unsigned)((waves + 3) / 4);
@@ -1258,8 +1278,9 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
                      w.status_acc, s.B, s.L, s.S, s.M, s.K, s.SP, r_class, w.cmeta, w.cstart,
                      w.cls, s.NC);
   hipLaunchKernelGGL(k_bin_unit, dim3((unsigned)s.B + nb_rc), dim3(256), 0, st, s.B, w.Oq,
-                     w.budget, w.budget0, w.unit, w.minO, w.lowsum, w.status, w.status_acc, s.L,
-                     s.SP, s.M, compress_bins ? 1 : 0, w.Rt, w.cmeta, w.cstart, w.Rc, s.K, s.NC);
+                     w.budget, w.budget0, w.unit, w.minO, w.lowsum, w.topsum, w.status,
+                     w.status_acc, s.L, s.SP, s.M, compress_bins ? 1 : 0, all_rows ? 1 : 0, w.Rt,
+                     w.cmeta, w.cstart, w.Rc, s.K, s.NC);
 }
 
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,

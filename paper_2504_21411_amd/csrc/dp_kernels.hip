@@ -257,7 +257,7 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
     const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
     const int32_t *__restrict__ lowsum, int B, int L, int S,
     int l, int pitch, int jsplit, int nblk) {
   // Work item p = row_block * B + b (nblk of them): consecutive items belong to different
@@ -284,11 +284,11 @@ __global__ __launch_bounds__(kRowsPerBlock) void k_dp_push(
 
   const int row0 = tile_start + lane;
   const int bl = b * L + l;
-  // source rows above E - min_s O[l][s] feed no target row; source rows below `low`, the
+  // source rows above E - topsum[l] (the least memory layers l.. still need) feed no result; source rows below `low`, the
   // least memory any plan of layers 0..l-1 needs, hold +inf only, so their targets are
   // filled with +inf by the row owners below instead of being computed
   const int low = lowsum[bl - 1];
-  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave * RU > low;
+  const bool compute = tile_start <= E - topsum[bl] && tile_start + kWave * RU > low;
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
@@ -390,7 +390,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
     const float *__restrict__ src, float *__restrict__ dst, uint8_t *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
     const int32_t *__restrict__ lowsum, int B, int L, int S,
     int l, int pitch) {
   extern __shared__ float tile[]; // [SP][64]
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_tile(
   const bool valid = row <= E;
   const int bl = b * L + l;
   const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
-  const bool compute = tile_start <= E - minO[bl] && tile_start + kWave > low; // uniform
+  const bool compute = tile_start <= E - topsum[bl] && tile_start + kWave > low; // uniform
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
@@ -516,7 +516,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
     const float *__restrict__ src, float *__restrict__ dst, BPT *__restrict__ bp,
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const float *__restrict__ Rt, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
     const int32_t *__restrict__ lowsum, int B, int L, int S, int SP, int l, int pitch) {
   // ROWS: budget rows per tile, 64, or 32 when S x 64 floats would not fit LDS (then the
   // upper half of every wave repeats the lower half's rows and stores nothing)
@@ -533,7 +533,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
   const bool valid = row <= E && act;
   const int bl = b * L + l;
   const int low = lowsum[bl - 1]; // rows below it are +inf in the previous plane
-  const bool compute = tile_start <= E - minO[bl] && tile_start + ROWS > low; // uniform
+  const bool compute = tile_start <= E - topsum[bl] && tile_start + ROWS > low; // uniform
   const size_t plane_off = (size_t)b * S * pitch;
   const float *__restrict__ srcb = src + plane_off;
   float *__restrict__ dstb = dst + plane_off;
@@ -727,7 +727,7 @@ static __device__ __forceinline__ void class_tile(
     const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
     const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int L, int Sc,
+    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum, int L, int Sc,
     int l, int pitch, int src_pitch, int b, int tile_start, float *lds,
     const Hook &after_loads = Hook()) {
   constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
@@ -747,7 +747,7 @@ static __device__ __forceinline__ void class_tile(
   // Those rows are not stored anywhere: every reader of a compact plane applies this bound.
   int lowq = lowsum[bl - (l >= 2 ? 2 : 1)];
   lowq = l >= 2 ? lowq : 0;
-  int mo = minO[bl];
+  int mo = topsum[bl];
   int kr = ridx[bl];
   int nc = cmeta[0];
   int maxlen = cmeta[1];
@@ -920,7 +920,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
     const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
     const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
+    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum, int B, int L, int Sc,
     int l, int pitch, int src_pitch, int tiles, unsigned div_magic, int div_shift) {
   // NC: class capacity (32 or 64): registers for the class minima, rows of the class table
   extern __shared__ float lds[];
@@ -946,7 +946,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     tile_start = (int)(item - (unsigned)b * (unsigned)tiles) * kWave;
   }
   class_tile<SP, NW, WITH_BP, NC, false>(qsrc, qdst, bp, Tq, Oq, Rc, cmeta, cstart, cls, ridx, budget,
-                                         minO, lowsum, L, Sc, l, pitch, src_pitch, b, tile_start,
+                                         topsum, lowsum, L, Sc, l, pitch, src_pitch, b, tile_start,
                                          lds);
 }
 
@@ -1006,13 +1006,13 @@ constexpr int kChainMaxL = 4096;       // an item record keeps the layer in 12 b
 
 // Queues of one solve, first step.  Block x < 8: the segment table of XCD x, seg[x][q] =
 // number of items before segment q = (l - 1) * nbmax + j (layer l, j-th instance of this XCD);
-// the active tiles of (l, b) are a = lowsum[b][l-1] / 64 .. z = (E_b - minO[b][l]) / 64,
+// the active tiles of (l, b) are a = lowsum[b][l-1] / 64 .. z = (E_b - topsum[b][l]) / 64,
 // exactly those for which class_tile has work.  The other blocks: maxfit[b][l] = largest
 // O[b][l][s] that fits the budget at all (0 if none), one wave per row.  The counters and the
 // stop word are reset here as well.
 __global__ __launch_bounds__(256) void k_chain_plan(
     const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ minO, const int32_t *__restrict__ lowsum,
+    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum,
     int32_t *__restrict__ maxfit, int32_t *__restrict__ seg, ChainCtl *__restrict__ ctl, int B,
     int L, int SP, int nbmax) {
   __shared__ int scan[256];
@@ -1034,7 +1034,7 @@ __global__ __launch_bounds__(256) void k_chain_plan(
         const int b = x + 8 * (q % nbmax);
         if (b < B) {
           const int E = budget[b];
-          const int top = E - minO[(size_t)b * L + l];
+          const int top = E - topsum[(size_t)b * L + l];
           const int a = lowsum[(size_t)b * L + l - 1] >> 6;
           const int z = top >= 0 ? top >> 6 : -1;
           cnt = z >= a ? z - a + 1 : 0;
@@ -1086,7 +1086,7 @@ __global__ __launch_bounds__(256) void k_chain_plan(
 // Q[l-2] that the tiles up to (64 t + 63 + maxfit[l-2]) / 64 of layer l-1 still read; both
 // ranges are cut to the active tiles of layer l-1.  One block per (segment, XCD).
 __global__ __launch_bounds__(256) void k_chain_items(
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
     const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
     const int32_t *__restrict__ seg, uint4 *__restrict__ items, size_t items_per_xcd, int B,
     int L, int nbmax, int keep) {
@@ -1102,7 +1102,7 @@ __global__ __launch_bounds__(256) void k_chain_items(
   const int a = lowsum[bl - 1] >> 6;
   int a1 = 0, z1 = -1, fit1 = 0, fit2 = -1;
   if (l >= 2) {
-    const int top1 = budget[b] - minO[bl - 1];
+    const int top1 = budget[b] - topsum[bl - 1];
     a1 = lowsum[bl - 2] >> 6;
     z1 = top1 >= 0 ? top1 >> 6 : -1;
     fit1 = maxfit[bl - 1];
@@ -1135,7 +1135,7 @@ __global__ __launch_bounds__(NW *kWave)
     const int32_t *__restrict__ Oq, const float *__restrict__ Rc,
     const int32_t *__restrict__ cmeta, const int32_t *__restrict__ cstart,
     const int32_t *__restrict__ cls, const int32_t *__restrict__ ridx,
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ minO,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
     const int32_t *__restrict__ lowsum, const uint4 *__restrict__ items, size_t items_per_xcd,
     ChainCtl *__restrict__ ctl, unsigned *__restrict__ flags, unsigned epoch,
     int32_t *__restrict__ status, int B, int L, int Sc, int pitch, int tiles) {
@@ -1220,7 +1220,7 @@ __global__ __launch_bounds__(NW *kWave)
         pending = __hip_atomic_fetch_add(myq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     class_tile<SP, NW, WITH_BP, NC, true>(qsrc, qdst, bp_l, Tq, Oq, Rc, cmeta, cstart, cls, ridx,
-                                          budget, minO, lowsum, L, Sc, l, pitch,
+                                          budget, topsum, lowsum, L, Sc, l, pitch,
                                           from_zero ? 0 : pitch, b, t * kWave, lds, request_next);
     if (wave == 0) { // the record of the following item arrives with the store acknowledgements
       const int i = wave_uniform((int)pending) * kChainQueues + qid;
@@ -1497,11 +1497,11 @@ static void launch_tile_sa(const Shape &s, const Workspace &w, int l, const floa
   const size_t lds = sizeof(float) * SP * kWave;
   if (bp_l)
     hipLaunchKernelGGL((k_dp_tile<SP, NW, true, SA>), grid, block, lds, st, src, dst,
-                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
+                       (uint8_t *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.topsum, w.lowsum, s.B, s.L,
                        s.S, l, s.pitch);
   else
     hipLaunchKernelGGL((k_dp_tile<SP, NW, false, SA>), grid, block, lds, st, src, dst,
-                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.topsum, w.lowsum, s.B,
                        s.L, s.S, l, s.pitch);
 }
 
@@ -1532,11 +1532,11 @@ static void launch_push_ru(const Shape &s, const Workspace &w, int l, const floa
   const dim3 grid((unsigned)((nblk + 7) / 8 * 8 * jsplit)), block(wpb * kWave);
   if (bp_l)
     hipLaunchKernelGGL((k_dp_push<SP, RU, true>), grid, block, 0, st, src, dst, (uint8_t *)bp_l,
-                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L, s.S, l, s.pitch,
+                       w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.topsum, w.lowsum, s.B, s.L, s.S, l, s.pitch,
                        jsplit, (int)nblk);
   else
     hipLaunchKernelGGL((k_dp_push<SP, RU, false>), grid, block, 0, st, src, dst,
-                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B,
+                       (uint8_t *)nullptr, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.topsum, w.lowsum, s.B,
                        s.L, s.S, l, s.pitch, jsplit, (int)nblk);
 }
 
@@ -1595,12 +1595,12 @@ static void launch_class_nc(const Shape &s, const Workspace &w, int l, const flo
   if (bp_l)
     hipLaunchKernelGGL((k_dp_class<SP, NW, true, NC>), grid, block, lds, st, src, dst,
                        (uint8_t *)bp_l, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, src_pitch, (int)tiles,
+                       w.budget, w.topsum, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, src_pitch, (int)tiles,
                        div_magic, div_shift);
   else
     hipLaunchKernelGGL((k_dp_class<SP, NW, false, NC>), grid, block, lds, st, src, dst,
                        (uint8_t *)nullptr, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.minO, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, src_pitch, (int)tiles,
+                       w.budget, w.topsum, w.lowsum, s.B, s.L, class_rows(s), l, s.pitch, src_pitch, (int)tiles,
                        div_magic, div_shift);
 }
 
@@ -1700,24 +1700,24 @@ static void launch_chain_nc(const Shape &s, const Workspace &w, bool keep, bool 
   const long long rows = (long long)s.B * s.L;
   const unsigned plan_blocks = 8 + (unsigned)(rows / 4 < 1 ? 1 : (rows / 4 > 1024 ? 1024 : rows / 4));
   ChainCtl *ctl = static_cast<ChainCtl *>(w.chain_ctl);
-  hipLaunchKernelGGL(k_chain_plan, dim3(plan_blocks), dim3(256), 0, st, w.Oq, w.budget, w.minO,
+  hipLaunchKernelGGL(k_chain_plan, dim3(plan_blocks), dim3(256), 0, st, w.Oq, w.budget, w.topsum,
                      w.lowsum, w.maxfit, w.seg, ctl, s.B, s.L, s.SP, nbmax);
   const size_t per_xcd = chain_items_per_xcd(s);
   uint4 *items = static_cast<uint4 *>(w.chain_items);
   hipLaunchKernelGGL(k_chain_items, dim3((unsigned)((s.L - 1) * nbmax), 8), dim3(256), 0, st,
-                     w.budget, w.minO, w.lowsum, w.maxfit, w.seg, items, per_xcd, s.B, s.L, nbmax,
+                     w.budget, w.topsum, w.lowsum, w.maxfit, w.seg, items, per_xcd, s.B, s.L, nbmax,
                      keep ? 1 : 0);
   if (with_bp)
     hipLaunchKernelGGL((k_dp_class_chain<SP, NW, true, NC>), grid, block, lds, st, w.planes,
                        plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp, bp_layer_bytes,
-                       w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.minO,
+                       w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.topsum,
                        w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch, w.status, s.B, s.L,
                        class_rows(s), s.pitch, tiles);
   else
     hipLaunchKernelGGL((k_dp_class_chain<SP, NW, false, NC>), grid, block, lds, st, w.planes,
                        plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
                        bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.minO, w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch,
+                       w.budget, w.topsum, w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch,
                        w.status, s.B, s.L, class_rows(s), s.pitch, tiles);
 }
 
@@ -1784,7 +1784,7 @@ static void launch_wide_rows(const Shape &s, const Workspace &w, int l, const fl
   if (lds > 64 * 1024)
     lds_opt_in((const void *)k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>, lds, s.grants);
   hipLaunchKernelGGL((k_dp_wide<BPT, NW, WITH_BP, JB, ROWS>), grid, block, lds, st, src, dst,
-                     (BPT *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.minO, w.lowsum, s.B, s.L,
+                     (BPT *)bp_l, w.Tq, w.Oq, w.Rt, w.ridx, w.budget, w.topsum, w.lowsum, s.B, s.L,
                      s.S, s.SP, l, s.pitch);
 }
 

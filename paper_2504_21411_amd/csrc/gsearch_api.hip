@@ -54,7 +54,7 @@ gs::Tuning tuning_from_env() {
 }
 
 struct Layout {
-  size_t planes, bp, Tq, Oq, Rt, ridx, budget, budget0, unit, minO, lowsum, best_s, best_cost,
+  size_t planes, bp, Tq, Oq, Rt, ridx, budget, budget0, unit, minO, lowsum, topsum, best_s, best_cost,
       status, cmeta, cstart, cls, Rc, maxfit, seg, chain_ctl, chain_items, total;
   int nplanes;
 };
@@ -103,6 +103,7 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.unit = take(sizeof(int32_t) * (size_t)s.B);
   y.minO = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.lowsum = take(sizeof(int32_t) * (size_t)s.B * s.L);
+  y.topsum = take(sizeof(int32_t) * (size_t)s.B * s.L);
   y.best_s = take(sizeof(int32_t) * (size_t)s.B);
   y.best_cost = take(sizeof(float) * (size_t)s.B);
   y.status = take(sizeof(int32_t));
@@ -241,6 +242,7 @@ gs::Workspace group_view(const gs::Shape &s, const gs::Workspace &w, int b0) {
   g.unit = w.unit + b0;
   g.minO = w.minO + (size_t)b0 * s.L;
   g.lowsum = w.lowsum + (size_t)b0 * s.L;
+  g.topsum = w.topsum + (size_t)b0 * s.L;
   return g;
 }
 
@@ -293,6 +295,7 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   w.unit = reinterpret_cast<int32_t *>(base + y.unit);
   w.minO = reinterpret_cast<int32_t *>(base + y.minO);
   w.lowsum = reinterpret_cast<int32_t *>(base + y.lowsum);
+  w.topsum = reinterpret_cast<int32_t *>(base + y.topsum);
   w.best_s = reinterpret_cast<int32_t *>(base + y.best_s);
   w.best_cost = reinterpret_cast<float *>(base + y.best_cost);
   w.status = reinterpret_cast<int32_t *>(base + y.status);
@@ -322,7 +325,9 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   // Transition classes: checked whenever the caller states them, exploited by the class
   // kernel when no particular kernel is forced and the shape has a register-tiled size.
   gs::launch_prepare(s, p->T, p->O, p->R, p->r_index, p->budget,
-                     s.L > 1 ? p->r_class : nullptr, w, !(c.flags & GSEARCH_FLAG_NO_BIN_UNIT), st);
+                     s.L > 1 ? p->r_class : nullptr, w, !(c.flags & GSEARCH_FLAG_NO_BIN_UNIT),
+                     // kept planes are exported whole: no skipping of rows that lead nowhere
+                     (c.flags & GSEARCH_FLAG_KEEP_PLANES) != 0, st);
   const bool use_classes =
       p->r_class && s.L > 1 && which == gs::ForwardKernel::Auto && gs::class_path_applies(s);
   // The class kernel works on compact planes (one row per class, at the head of each plane

@@ -74,6 +74,9 @@ struct Workspace {
   int32_t *unit;     // [B]          bin unit g of the instance (see k_bin_unit): Oq, minO,
                      //              lowsum, budget and every plane row count multiples of g
   int32_t *minO;     // [B][L]       min_s Oq
+  int32_t *topsum;   // [B][L]       sum over layers l..L-1 of minO, clamped to M+1: a source row
+                     //              r of front l above E - topsum[l] leads to no result and is
+                     //              skipped (the layer's own minO when every row is wanted)
   int32_t *lowsum;   // [B][L]       sum over layers 0..l of minO, clamped to M+1: budget rows
                      //              below it cannot hold any plan of layers 0..l (all +inf)
   int32_t *best_s;   // [B]          result of the final reduction (kept for backtrace)
@@ -108,7 +111,7 @@ inline int class_rows(const Shape &s) { return s.S < s.NC ? s.S : s.NC; }
 // one-class partition, so that the class kernel stays memory-safe.
 void launch_prepare(const Shape &s, const float *T, const int32_t *O, const float *R,
                     const int32_t *r_index, const int32_t *budget, const int32_t *r_class,
-                    const Workspace &w, bool compress_bins, hipStream_t st);
+                    const Workspace &w, bool compress_bins, bool all_rows, hipStream_t st);
 bool class_path_applies(const Shape &s);
 // One layer front with the class kernel: src and dst are compact planes
 // [B][class_rows][pitch] holding Q[l-1] and Q[l], where

@@ -4,6 +4,7 @@ Costs, final rows, argmins, plans, memory use and the best instance must be iden
 with kept planes the whole C and backpointer tables are compared too.  All inputs are
 seeded and synthetic.
 """
+import dataclasses
 import os
 
 import numpy as np
@@ -41,6 +42,15 @@ def assert_same(got, ref, w, what=""):
     if "plan" in got and got["plan"].shape == ref["plan"].shape:
         assert np.array_equal(got["plan"], ref["plan"]), tag
         assert np.array_equal(got["mem_used"], ref["mem_used"]), tag
+
+
+def assert_curve(oracle_mod, curve, w, what=""):
+    """Best cost for every budget 0..E of every instance, and +inf beyond E."""
+    for b in range(w.B):
+        E = int(w.budget[b])
+        one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_curve=True)
+        assert np.array_equal(bits(curve[b, :E + 1]), bits(one["curve"])), (w.name, what, b)
+        assert np.isinf(curve[b, E + 1:]).all(), (w.name, what, b)
 
 
 def oracle_batch(oracle_mod, w, T=None, O=None, R=None):
@@ -621,7 +631,10 @@ def _class_sweep_case(runner, oracle_mod, rng, case):
         got["data_status"] = ctx.gsearch_data_status()
         want = "k_dp_class_chain" if chain and L >= 3 else "k_dp_class"
         assert ctx.gsearch_forward_kernel() == want, (case, S)
+        curve = ctx.gsearch_budget_curve().cpu().numpy() if case % 4 == 1 else None
     assert_same(got, ref, w, f"class sweep {case} S={S} sizes={sizes} flags={flags}")
+    if curve is not None:
+        assert_curve(oracle_mod, curve, w, f"class sweep {case}")
 
 
 def test_class_kernel_random_sweep(gs, oracle_mod):
@@ -684,6 +697,53 @@ def test_class_kernel_all_fronts_in_one_launch(gs, oracle_mod, shape, mode):
         got["data_status"] = ctx.gsearch_data_status()
         assert ctx.gsearch_forward_kernel() == "k_dp_class"
         assert_same(got, ref, w, f"per front after one launch {mode}")
+
+
+@pytest.mark.parametrize("mode", ["bp", "nobp", "bp_push", "bp_tile", "nobp_tile", "generic",
+                                  "class_bp", "class_nobp", "class_chain"])
+def test_rows_that_no_plan_can_use_are_skipped_exactly(gs, oracle_mod, mode):
+    """Every strategy of every layer needs a good share of the budget, so most rows of the
+    early layers cannot be completed to a plan within the budget and the forward kernels
+    leave them out (unless the planes are kept for export).  What the results are read from
+    must not change: costs, final rows, plans of every instance, the budget curve; twice on
+    one context, the second time after a solve with kept-planes semantics off and other
+    budgets has left other values in the planes."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = 5, 9, 24, 1800
+    budget = np.array([M, M - 1, 1300, 1230, 700], np.int32)
+    if mode.startswith("class"):
+        sizes = [4] * (S // 4)
+        w, r_class = workloads.class_tables("topcut", B, L, S, M, sizes, K=2, seed=91,
+                                            budget=budget, coarse=True)
+    else:
+        w, r_class = random_tables("topcut", B, L, S, M, K=2, seed=91, budget=budget), None
+    # layer minima between 64 and 200 bins: the budgets of the last two instances fit no
+    # plan or only the leanest ones, and the rows cut off span many 64-row tiles
+    rng = workloads.SplitMix64(5)
+    floor = 64 + rng.randint(0, 136, L)
+    w.O[:] = np.minimum(w.O % 90 + floor[None, :, None], M + 1).astype(w.O.dtype)
+    ref = oracle_batch(oracle_mod, w)
+    assert np.isfinite(ref["best_cost"][:4]).all() and not np.isfinite(ref["best_cost"][4])
+    flags = {"class_bp": 0, "class_nobp": 0x4, "class_chain": 0}.get(mode, MODES.get(mode, 0))
+    dw = runner.DeviceWorkload(w)
+    kw = {}
+    if r_class is not None:
+        kw = dict(r_class=torch.from_numpy(r_class).to(dw.device), r_class_bound=S // 4)
+    other = dataclasses.replace(w, budget=(w.budget[::-1] // 2).astype(np.int32))
+    dother = runner.DeviceWorkload(other)
+    with runner.make_context(w, flags=flags) as ctx:
+        if mode == "class_chain":
+            ctx.gsearch_set_knob("chain", 1)
+        for rep in range(2):
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", **kw))
+            got["data_status"] = ctx.gsearch_data_status()
+            curve = ctx.gsearch_budget_curve().cpu().numpy()
+            assert_same(got, ref, w, f"{mode} rep {rep}")
+            assert_curve(oracle_mod, curve, w, f"{mode} rep {rep}")
+            if r_class is not None:
+                assert ctx.gsearch_forward_kernel().startswith("k_dp_class")
+            runner.run_step(ctx, dother, backtrace="all", **kw)
 
 
 def test_rounding_tie_inside_a_class_keeps_the_lowest_index(gs, oracle_mod):
@@ -1149,4 +1209,7 @@ def test_general_kernels_random_sweep(gs, oracle_mod):
                     ctx.gsearch_set_instance_groups(g)
                 got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all"))
                 got["data_status"] = ctx.gsearch_data_status()
+                curve = ctx.gsearch_budget_curve().cpu().numpy() if case % 4 == 1 else None
             assert_same(got, ref, w, f"sweep {case} S={S} flags={flags:#x} groups={g}")
+            if curve is not None:
+                assert_curve(oracle_mod, curve, w, f"sweep {case} flags={flags:#x}")
