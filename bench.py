@@ -130,8 +130,9 @@ def main():
                          "beside the main line ('' for none)")
     ap.add_argument("--instance-groups", type=int, default=0,
                     help="force this many chains of launches (0: the library's choice)")
-    ap.add_argument("--chain", type=int, default=-1,
-                    help="1: the class kernel runs all layer fronts in one launch (knob 'chain')")
+    ap.add_argument("--fronts", type=int, default=-1,
+                    help="class kernel: layer fronts per launch (knob 'fronts'; 0: one launch per "
+                         "front; default: the library's choice)")
     ap.add_argument("--no-single-chain", action="store_true",
                     help="do not time the one-chain variant beside a multi-chain forward pass")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -180,8 +181,8 @@ def main():
             ctx.gsearch_set_profiling(True)
             if groups_forced:
                 ctx.gsearch_set_instance_groups(groups_forced)
-            if args.chain >= 0:
-                ctx.gsearch_set_knob("chain", args.chain)
+            if args.fronts >= 0:
+                ctx.gsearch_set_knob("fronts", args.fronts)
             # W untimed steps, and in any case half a second of them: on the test box the
             # first launch phase that starts 0.1-0.2 s after a context's first solve has been
             # seen to stall on the host for about 40 ms, once per context
@@ -267,12 +268,12 @@ def main():
         # The batch runs as `groups` chains of L-1 launches side by side (one stream each);
         # every chain spans the forward time, so a launch lasts fwd/(L-1) on average and
         # works on 1/groups of a layer front while the other chains' launches share the chip.
-        # (k_dp_small and k_dp_class_chain are ONE launch for all fronts: a "launch" below is
-        # then a layer front's share of it.)
+        # (k_dp_small runs all fronts in ONE launch and k_dp_class_fronts 64 per launch: a
+        # "launch" below is then a layer front's share of it.)
         launches = w.L - 1
         launch_s = fwd_ms * 1e-3 / launches
         key = f"{cfg_index}/{mode}" + (f"/groups{groups_forced}" if groups_forced else "") \
-            + ("/chain" if kernel == "k_dp_class_chain" else "")
+            + ("/perfront" if kernel == "k_dp_class" and args.fronts == 0 else "")
         prof = (profiled.get("entries") or {}).get(key) or {}
         common = {"kernel": kernel, "concurrent_launches": groups,
                   "traffic": prof.get("traffic_bytes"),

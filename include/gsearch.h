@@ -232,9 +232,10 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
  * else) and keeps them per context.  Names: "kernel" (1 push, 2 tile, 3 wide: general forward
  * kernel), "small" (0/1: one-launch kernel for small instances never / wherever it fits),
  * "jsplit" (waves per tile), "waves_per_block", "row_groups", "streams" (instance groups),
- * "chain" (1: the class kernel runs all layer fronts of a solve in one launch wherever it can; it
- * measured slower than one launch per front and is off otherwise).  0 (or -1 for "small")
- * restores the heuristic.  gsearch_knob_name lists the names (NULL beyond the last;
+ * "fronts" (class kernel: layer fronts per launch, 2..64; 0 or 1: one launch per front; -1, the
+ * default: 64 wherever that form can run, i.e. a batch that is a multiple of 8, three layers or
+ * more, no forced instance groups, a GPU whose eight XCDs take workgroups in turn).  0 (or -1
+ * for "small" and "fronts") restores the heuristic.  gsearch_knob_name lists the names (NULL beyond the last;
  * host only, needs no GPU).  Errors: INVALID_ARG (null context, unknown name, value outside
  * [-1, 64], null output). */
 const char *gsearch_knob_name(int index);
@@ -251,10 +252,17 @@ int gsearch_get_knob(gsearch_ctx *ctx, const char *name, int *value);
 int gsearch_set_profiling(gsearch_ctx *ctx, int enable);
 int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
 /* Name of the forward kernel the most recent solve launched for its layer fronts
- * ("k_dp_class_chain", "k_dp_class", "k_dp_tile", "k_dp_wide", "k_dp_push", "k_dp_generic" or
+ * ("k_dp_class_fronts", "k_dp_class", "k_dp_tile", "k_dp_wide", "k_dp_push", "k_dp_generic" or
  * "k_dp_small"; "" before any
  * solve).  Static string. */
 const char *gsearch_forward_kernel(gsearch_ctx *ctx);
+
+/* Test aid for the class kernel's several-fronts form, whose completion flags are stamped
+ * with the number of the solve (a counter in the workspace that every solve advances on the
+ * device and that wraps at 2^29): sets that counter, on `stream`, so that a test can walk a
+ * context across the wrap.  Errors: INVALID_ARG (null context, value >= 2^29), UNSUPPORTED (the
+ * context has no such flags: see the knob "fronts"), HIP. */
+int gsearch_set_solve_counter(gsearch_ctx *ctx, uint32_t value, void *stream);
 
 /* Measurement aid: LDS traffic of exactly known size, by which the profiler's LDS counters are
  * scaled (as its HBM counters are by a plain copy).  One launch of 1024 x 256 threads, each

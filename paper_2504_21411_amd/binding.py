@@ -49,6 +49,7 @@ EXPORTS = [
     "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
     "gsearch_instance_groups", "gsearch_layout_classes", "gsearch_solve_batch_noalloc",
     "gsearch_knob_name", "gsearch_set_knob", "gsearch_get_knob", "gsearch_lds_calibration",
+    "gsearch_set_solve_counter",
 ]
 
 
@@ -130,6 +131,8 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_lds_calibration.argtypes = [i32, i32, vp, vp]
     lib.gsearch_knob_name.restype = ctypes.c_char_p
     lib.gsearch_knob_name.argtypes = [ctypes.c_int]
+    lib.gsearch_set_solve_counter.restype = ctypes.c_int
+    lib.gsearch_set_solve_counter.argtypes = [vp, ctypes.c_uint32, vp]
     lib.gsearch_set_knob.restype = ctypes.c_int
     lib.gsearch_set_knob.argtypes = [vp, ctypes.c_char_p, ctypes.c_int]
     lib.gsearch_get_knob.restype = ctypes.c_int
@@ -418,6 +421,10 @@ class GSearch:
 
     def gsearch_set_knob(self, name: str, value: int):
         _check(self._lib.gsearch_set_knob(self._ctx, name.encode(), int(value)), "gsearch_set_knob")
+
+    def gsearch_set_solve_counter(self, value: int, stream=None):
+        _check(self._lib.gsearch_set_solve_counter(self._ctx, int(value), _stream(stream)),
+               "gsearch_set_solve_counter")
 
     def gsearch_get_knob(self, name: str) -> int:
         v = ctypes.c_int(0)

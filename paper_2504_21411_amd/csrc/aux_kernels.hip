@@ -1255,8 +1255,22 @@ __global__ __launch_bounds__(256) void k_bin_unit(
     int32_t *__restrict__ lowsum, int32_t *__restrict__ topsum, int32_t *__restrict__ status,
     int32_t *__restrict__ status_acc, int L, int SP, int M, int enable, int all_rows,
     const float *__restrict__ Rt, const int32_t *__restrict__ cmeta,
-    const int32_t *__restrict__ cstart, float *__restrict__ Rc, int K, int NC) {
+    const int32_t *__restrict__ cstart, float *__restrict__ Rc, int K, int NC,
+    unsigned *__restrict__ epoch) {
   const int block = (int)blockIdx.x;
+  // The solve counter the class kernel's flags are stamped with (see k_dp_class_fronts):
+  // advanced here, on the device, so that a captured and replayed solve advances it as well.
+  // epoch[1]: the counter has wrapped and the flags still have to be cleared, which the next
+  // solve that uses them does, setting epoch[2].
+  if (epoch && block == 0 && threadIdx.x == 0) {
+    if (epoch[2] != 0) epoch[1] = epoch[2] = 0;
+    unsigned next = epoch[0] + 1u;
+    if (next >= (1u << 29)) {
+      next = 1u;
+      epoch[1] = 1u;
+    }
+    epoch[0] = next;
+  }
   if (block < B)
     bin_unit_part(block, Oq, budget, budget0, unit, minO, lowsum, topsum, status, status_acc, L,
                   SP, M, enable, all_rows);
@@ -1280,7 +1294,7 @@ void launch_prepare(const Shape &s, const float *T, const int32_t *O, const floa
   hipLaunchKernelGGL(k_bin_unit, dim3((unsigned)s.B + nb_rc), dim3(256), 0, st, s.B, w.Oq,
                      w.budget, w.budget0, w.unit, w.minO, w.lowsum, w.topsum, w.status,
                      w.status_acc, s.L, s.SP, s.M, compress_bins ? 1 : 0, all_rows ? 1 : 0, w.Rt,
-                     w.cmeta, w.cstart, w.Rc, s.K, s.NC);
+                     w.cmeta, w.cstart, w.Rc, s.K, s.NC, w.epoch);
 }
 
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,

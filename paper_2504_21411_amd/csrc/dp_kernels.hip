@@ -720,15 +720,63 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
 struct NoHook {
   __device__ __forceinline__ void operator()() const {}
 };
+// The scalar table entries a wave needs for a tile of instance b at layer front l: the
+// per-instance scalars and the O, T and class entries of the wave's source strategies.  All
+// are requested before the first of them is looked at (one round trip to the scalar cache
+// instead of one per dependent step); none depends on the tile.
+template <int PER>
+struct ClassScalars {
+  int E, low, lowq, mo, kr, nc, maxlen;
+  int o_s[PER], c_s[PER];
+  float t_s[PER];
+};
+template <int SP, int NW>
+static __device__ __forceinline__ ClassScalars<SP / NW> class_scalars(
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const int32_t *__restrict__ cmeta, const int32_t *__restrict__ cls,
+    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum, int L, int l, int b) {
+  constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
+  ClassScalars<PER> k;
+  const int js = wave_uniform(threadIdx.x >> 6);
+  const int bl = b * L + l;
+  k.E = budget[b];
+  k.low = lowsum[bl - 1]; // C[l-1], and with it Q[l], is +inf below this row
+  // Q[l-1] is +inf below the least memory of layers 0..l-2 (Q[0] = 0 has no such rows).
+  // Those rows are not stored anywhere: every reader of a compact plane applies this bound.
+  k.lowq = lowsum[bl - (l >= 2 ? 2 : 1)];
+  k.lowq = l >= 2 ? k.lowq : 0;
+  k.mo = topsum[bl];
+  k.kr = ridx[bl];
+  k.nc = cmeta[0];
+  k.maxlen = cmeta[1];
+  {
+    const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
+    const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      k.o_s[u] = oprev[js * PER + u];
+      k.c_s[u] = cls[js * PER + u];
+      k.t_s[u] = tprev[js * PER + u];
+    }
+  }
+  asm volatile(""
+               : "+s"(k.E), "+s"(k.low), "+s"(k.lowq), "+s"(k.mo), "+s"(k.kr), "+s"(k.nc),
+                 "+s"(k.maxlen));
+  // (a longer run would not fit the scalar registers next to the class table row: there the
+  // compiler places the loads where the values are used)
+  if constexpr (PER <= 16) {
+#pragma unroll
+    for (int u = 0; u < PER; ++u) asm volatile("" : "+s"(k.o_s[u]), "+s"(k.c_s[u]), "+s"(k.t_s[u]));
+  }
+  return k;
+}
+
 template <int SP, int NW, bool WITH_BP, int NC, bool COHERENT, typename Hook = NoHook>
 static __device__ __forceinline__ void class_tile(
-    const float *__restrict__ qsrc, float *__restrict__ qdst, uint8_t *__restrict__ bp,
-    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
-    const float *__restrict__ Rc, const int32_t *__restrict__ cmeta,
-    const int32_t *__restrict__ cstart, const int32_t *__restrict__ cls,
-    const int32_t *__restrict__ ridx, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum, int L, int Sc,
-    int l, int pitch, int src_pitch, int b, int tile_start, float *lds,
+    const ClassScalars<SP / NW> &k, const float *__restrict__ qsrc, float *__restrict__ qdst,
+    uint8_t *__restrict__ bp, const float *__restrict__ Rc, const int32_t *__restrict__ cstart,
+    int Sc, int pitch, int src_pitch, int b, int tile_start, float *lds,
     const Hook &after_loads = Hook()) {
   constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
   float *cmin = lds;                    // [NC][64]  class minima of the tile
@@ -737,39 +785,11 @@ static __device__ __forceinline__ void class_tile(
   float *tile = reinterpret_cast<float *>(cs_lds + NC + 32); // [SP + 3][64], backpointer mode only
   const int js = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const int bl = b * L + l;
-  // Every scalar table entry this wave will need is requested before the first of them is
-  // looked at (one round trip to the scalar cache instead of one per dependent step): the
-  // per-instance scalars, and the O, T and class entries of the wave's source strategies.
-  int E = budget[b];
-  int low = lowsum[bl - 1]; // C[l-1], and with it Q[l], is +inf below this row
-  // Q[l-1] is +inf below the least memory of layers 0..l-2 (Q[0] = 0 has no such rows).
-  // Those rows are not stored anywhere: every reader of a compact plane applies this bound.
-  int lowq = lowsum[bl - (l >= 2 ? 2 : 1)];
-  lowq = l >= 2 ? lowq : 0;
-  int mo = topsum[bl];
-  int kr = ridx[bl];
-  int nc = cmeta[0];
-  int maxlen = cmeta[1];
-  int o_s[PER], c_s[PER];
-  float t_s[PER];
-  {
-    const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
-    const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      o_s[u] = oprev[js * PER + u];
-      c_s[u] = cls[js * PER + u];
-      t_s[u] = tprev[js * PER + u];
-    }
-  }
-  asm volatile("" : "+s"(E), "+s"(low), "+s"(lowq), "+s"(mo), "+s"(kr), "+s"(nc), "+s"(maxlen));
-  // (a longer run would not fit the scalar registers next to the class table row: there the
-  // compiler places the loads where the values are used)
-  if constexpr (PER <= 16) {
-#pragma unroll
-    for (int u = 0; u < PER; ++u) asm volatile("" : "+s"(o_s[u]), "+s"(c_s[u]), "+s"(t_s[u]));
-  }
+  const int E = k.E, low = k.low, lowq = k.lowq, mo = k.mo, kr = k.kr, nc = k.nc,
+            maxlen = k.maxlen;
+  const int(&o_s)[PER] = k.o_s;
+  const int(&c_s)[PER] = k.c_s;
+  const float(&t_s)[PER] = k.t_s;
   if (tile_start > E - mo) return; // no target row within the budget (whole workgroup)
 
   const int row = tile_start + lane;
@@ -945,125 +965,82 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
     b = (int)(__umulhi(item, div_magic) >> div_shift);
     tile_start = (int)(item - (unsigned)b * (unsigned)tiles) * kWave;
   }
-  class_tile<SP, NW, WITH_BP, NC, false>(qsrc, qdst, bp, Tq, Oq, Rc, cmeta, cstart, cls, ridx, budget,
-                                         topsum, lowsum, L, Sc, l, pitch, src_pitch, b, tile_start,
-                                         lds);
+  const ClassScalars<SP / NW> k =
+      class_scalars<SP, NW>(Tq, Oq, cmeta, cls, ridx, budget, topsum, lowsum, L, l, b);
+  class_tile<SP, NW, WITH_BP, NC, false>(k, qsrc, qdst, bp, Rc, cstart, Sc, pitch, src_pitch, b,
+                                         tile_start, lds);
 }
 
 // ---------------------------------------------------------------------------------------
-// The whole forward pass of the class kernel in ONE launch.
+// Several layer fronts of the class kernel per launch.
 //
 // A layer front of the per-launch form is one short round of workgroups, and between two
-// dependent launches the chip idles for about three microseconds.  Here the (layer, instance,
-// tile) items of all L-1 fronts are handed out from queues, and an item waits only for the
-// tiles of the previous layer it reads (rows r - O[l-1][s], i.e. the tiles at and a little
-// below it), so consecutive fronts overlap and nothing drains between them.
+// dependent launches the chip idles for about three microseconds.  Here one launch covers
+// `fronts` consecutive layer fronts, grid (instances, tiles, fronts), and a tile waits only
+// for the tiles of the previous front that it depends on, so consecutive fronts overlap.
+//
+// Dependencies.  Tile t of front l reads the rows r - O[l-1][s] of Q[l-1], i.e. the tiles
+// from (64 t - largest fitting O[l-1]) / 64 up to t of front l-1; and with two planes taking
+// turns it overwrites rows of Q[l-2] that the tiles of front l-1 up to
+// (64 t + 63 + largest fitting O[l-2]) / 64 still read.  Both ranges are cut to the tiles of
+// front l-1 that have work.  A finished tile publishes a flag word holding the number of the
+// solve (a counter the context advances, so flags need no clearing between solves).
 //
 // Coherence.  The eight XCDs have one L2 each, and those are made coherent with each other
 // only by writing back and invalidating whole caches, which costs far more than the launches
-// it would save.  So an instance is bound to ONE XCD: a workgroup reads the id of the XCD it
-// runs on from the hardware register and serves only that XCD's queue (instances slot,
-// slot + 8, ...).  Within an XCD every compute unit's stores go through to the shared L2
-// (the vector cache is write-through), and a load that bypasses the vector cache (an
-// agent-scope atomic load; see class_tile) reads what sits in that L2.  Producer: stores,
-// wait until they are acknowledged, workgroup barrier, flag.  Consumer: flag seen, workgroup
-// barrier, bypassing loads.
+// it would save.  So an instance stays on ONE XCD: consecutive workgroups of a launch go to
+// consecutive XCDs (starting at an XCD that depends on the stream's hardware queue) and the
+// batch is a multiple of 8, hence all workgroups of an instance run on the same XCD.  A flag
+// carries the id of the XCD that wrote the rows, read from the hardware register, and a tile
+// that finds a flag from another XCD raises the internal status bit instead of reading rows
+// its L2 may not hold.  Within an XCD
+// every compute unit's stores go through to the shared L2 (the vector cache is
+// write-through), and a load that bypasses the vector cache (an agent-scope atomic load; see
+// class_tile) reads what sits in that L2.  Producer: stores, wait until they are
+// acknowledged, workgroup barrier, flag.  Consumer: flag seen, workgroup barrier, bypassing
+// loads.
 //
-// Progress.  The items of an XCD form one list in (layer, instance, tile) order, cut into
-// kChainQueues interleaved queues (item i belongs to queue i mod kChainQueues), each with a
-// counter of its own that the workgroups of rank r = q mod kChainQueues pop: an atomic on ONE
-// word takes about half a microsecond and they line up behind each other, which 185 items per
-// front cannot afford, while dealing the items out statically would hang as soon as the
-// chip holds fewer workgroups at once than the launcher believes (the occupancy query was
-// seen to promise seven per compute unit where six ran).  Every dependency of an item
-// precedes it in the list.  Take the lowest unfinished item: everything below it in its own
-// queue is finished, so it has been popped by a running workgroup (and then finishes, its
-// dependencies being done) or is the next one its queue hands out; a queue is served by the
-// first workgroups to arrive on the XCD (a workgroup takes a ticket when it starts and serves
-// queue ticket mod kChainQueues), which are running by definition.  So nothing waits for a
-// workgroup that cannot start, whatever the number of resident workgroups and however the
-// hardware deals them out to the XCDs.  Every wait is bounded all the same; one that gives
-// up raises the internal status bit (the solve then reports every instance as infeasible)
-// and tells the other workgroups to stop.
+// Progress.  The hardware starts workgroups in the order of their linear index, so every
+// workgroup of front f of a launch has been started before any of front f + 1 is, and a
+// workgroup that waits does so for workgroups that are running or done: nothing waits for a
+// workgroup that cannot start.  Every wait is bounded all the same; one that gives up raises
+// the internal status bit (the solve then reports every instance as infeasible) and tells
+// the other workgroups to stop.  The first front of a launch waits for nothing (the previous
+// launch is over), the last publishes no flags.
 //
-// Flags are words holding the number of the solve that set them (a counter the context
-// advances), so they need no clearing between solves.
+// A workgroup's tile index counts from the first tile that has work (below it everything is
+// +inf), so the workgroups with work come first in every front and the empty ones behind
+// them leave at once.
 //
-// Ping-pong planes: item (l, t) overwrites the rows of Q[l-2] that the items (l-1, t'') up to
-// t'' = (64 t + 63 + largest fitting O[l-2]) / 64 still read, so it waits for those as well.
+// Measured on MI355X, 64 fronts per launch: configs[1] 0.28 against 0.32 ms forward,
+// configs[3] 1.18 against 1.22 ms.  What a flag costs (store acknowledgement, barrier, flag
+// store, the poll's round trip: four to five microseconds from a tile's last store to its
+// dependant's first load) is about what a launch boundary costs, so the gain comes from the
+// fronts overlapping, not from a shorter hand-over.  Forms that keep workgroups resident and
+// hand them (layer, instance, tile) items from atomic queues, or deal the items out
+// statically, pay the same hand-over without that overlap and were slower than one launch per
+// front (configs[3]: 1.6 to 1.7 ms); they are not kept.
 // ---------------------------------------------------------------------------------------
-constexpr int kChainQueues = 16;
-struct ChainCtl {
-  unsigned next[8][kChainQueues][16]; // per XCD and queue: pops so far (a cache line each)
-  unsigned arrivals[8][16];           // per XCD: workgroups that have started
-  unsigned total[8];                  // per XCD: number of items
-  unsigned stop;                      // a wait gave up somewhere
-  unsigned pad[7];
-};
-static_assert(sizeof(ChainCtl) <= kChainCtlBytes, "the workspace reserves kChainCtlBytes for it");
-constexpr int kChainSpinMax = 1 << 18; // polls (with a short sleep between them) before a wait gives up
-constexpr int kChainMaxL = 4096;       // an item record keeps the layer in 12 bits
-
-// Queues of one solve, first step.  Block x < 8: the segment table of XCD x, seg[x][q] =
-// number of items before segment q = (l - 1) * nbmax + j (layer l, j-th instance of this XCD);
-// the active tiles of (l, b) are a = lowsum[b][l-1] / 64 .. z = (E_b - topsum[b][l]) / 64,
-// exactly those for which class_tile has work.  The other blocks: maxfit[b][l] = largest
-// O[b][l][s] that fits the budget at all (0 if none), one wave per row.  The counters and the
-// stop word are reset here as well.
-__global__ __launch_bounds__(256) void k_chain_plan(
+constexpr int kFrontSpinMax = 1 << 18; // polls before a wait gives up
+// A flag word: the number of the solve in the low 29 bits, the XCD that wrote the rows above.
+constexpr int kFlagXcdShift = 29;
+constexpr unsigned kFlagEpochMask = (1u << kFlagXcdShift) - 1u;
+__global__ __launch_bounds__(256) void k_class_maxfit(
     const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
-    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum,
-    int32_t *__restrict__ maxfit, int32_t *__restrict__ seg, ChainCtl *__restrict__ ctl, int B,
-    int L, int SP, int nbmax) {
-  __shared__ int scan[256];
-  __shared__ int carry;
-  const int nseg = (L - 1) * nbmax;
-  if (blockIdx.x < 8) {
-    const int x = blockIdx.x;
-    int32_t *__restrict__ sg = seg + (size_t)x * (nseg + 1);
-    if (threadIdx.x == 0) carry = 0;
-    if (threadIdx.x < kChainQueues) ctl->next[x][threadIdx.x][0] = 0;
-    if (threadIdx.x == 0) ctl->arrivals[x][0] = 0;
-    if (x == 0 && threadIdx.x == 0) ctl->stop = 0;
-    __syncthreads();
-    for (int q0 = 0; q0 < nseg; q0 += 256) {
-      const int q = q0 + (int)threadIdx.x;
-      int cnt = 0;
-      if (q < nseg) {
-        const int l = 1 + q / nbmax;
-        const int b = x + 8 * (q % nbmax);
-        if (b < B) {
-          const int E = budget[b];
-          const int top = E - topsum[(size_t)b * L + l];
-          const int a = lowsum[(size_t)b * L + l - 1] >> 6;
-          const int z = top >= 0 ? top >> 6 : -1;
-          cnt = z >= a ? z - a + 1 : 0;
-        }
-      }
-      scan[threadIdx.x] = cnt;
-      __syncthreads();
-      for (int d = 1; d < 256; d <<= 1) { // inclusive scan of this round
-        const int add = (int)threadIdx.x >= d ? scan[threadIdx.x - d] : 0;
-        __syncthreads();
-        scan[threadIdx.x] += add;
-        __syncthreads();
-      }
-      const int base = carry;
-      if (q < nseg) sg[q] = base + scan[threadIdx.x] - cnt;
-      __syncthreads();
-      if (threadIdx.x == 255) carry = base + scan[255];
-      __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-      sg[nseg] = carry;
-      ctl->total[x] = (unsigned)carry;
-    }
-    return;
-  }
+    int32_t *__restrict__ maxfit, unsigned *__restrict__ stop,
+    unsigned *__restrict__ epoch, unsigned *__restrict__ flags, size_t flag_words, int B, int L,
+    int SP) {
   const int wave = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *stop = 0;
+  if (epoch[1] != 0) { // the solve counter has wrapped: no old flag may look like a new one
+    for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < flag_words;
+         x += (size_t)gridDim.x * 256)
+      flags[x] = 0u;
+    if (blockIdx.x == 0 && threadIdx.x == 0) epoch[2] = 1u; // (acted on by the next solve)
+  }
   const int rows = B * L;
-  for (int row = ((int)blockIdx.x - 8) * 4 + wave; row < rows; row += ((int)gridDim.x - 8) * 4) {
+  for (int row = (int)blockIdx.x * 4 + wave; row < rows; row += (int)gridDim.x * 4) {
     const int E = budget[row / L];
     int m = 0;
     for (int sidx = lane; sidx < SP; sidx += kWave) {
@@ -1079,160 +1056,107 @@ __global__ __launch_bounds__(256) void k_chain_plan(
   }
 }
 
-// Second step: one record per item, items[x][i] = (layer | instance << 12, tile, lo, hi): the
-// item's place and the tiles lo..hi of the previous layer whose flags it waits for (lo > hi:
-// none).  It reads the rows r - O[l-1][s] of Q[l-1], i.e. the tiles from
-// (64 t - maxfit[l-1]) / 64 up to its own, and with ping-pong planes it overwrites rows of
-// Q[l-2] that the tiles up to (64 t + 63 + maxfit[l-2]) / 64 of layer l-1 still read; both
-// ranges are cut to the active tiles of layer l-1.  One block per (segment, XCD).
-__global__ __launch_bounds__(256) void k_chain_items(
-    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
-    const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
-    const int32_t *__restrict__ seg, uint4 *__restrict__ items, size_t items_per_xcd, int B,
-    int L, int nbmax, int keep) {
-  const int q = blockIdx.x, x = blockIdx.y;
-  const int nseg = (L - 1) * nbmax;
-  const int32_t *__restrict__ sg = seg + (size_t)x * (nseg + 1);
-  const int l = 1 + q / nbmax;
-  const int b = x + 8 * (q % nbmax);
-  if (b >= B) return;
-  const int first = sg[q], cnt = sg[q + 1] - first;
-  if (cnt <= 0) return;
-  const int bl = b * L + l;
-  const int a = lowsum[bl - 1] >> 6;
-  int a1 = 0, z1 = -1, fit1 = 0, fit2 = -1;
-  if (l >= 2) {
-    const int top1 = budget[b] - topsum[bl - 1];
-    a1 = lowsum[bl - 2] >> 6;
-    z1 = top1 >= 0 ? top1 >> 6 : -1;
-    fit1 = maxfit[bl - 1];
-    if (!keep && l >= 3) fit2 = maxfit[bl - 2];
-  }
-  uint4 *__restrict__ out = items + (size_t)x * items_per_xcd + first;
-  for (int k = threadIdx.x; k < cnt; k += 256) {
-    const int t = a + k;
-    int lo = 1, hi = 0;
-    if (l >= 2) {
-      lo = 64 * t - fit1;
-      lo = lo > 0 ? lo >> 6 : 0;
-      lo = lo > a1 ? lo : a1;
-      hi = t;
-      if (fit2 >= 0) {
-        const int war = (64 * t + 63 + fit2) >> 6;
-        hi = war > hi ? war : hi;
-      }
-      hi = hi < z1 ? hi : z1;
-    }
-    out[k] = make_uint4((unsigned)l | ((unsigned)b << 12), (unsigned)t, (unsigned)lo, (unsigned)hi);
-  }
-}
-
 template <int SP, int NW, bool WITH_BP, int NC>
-__global__ __launch_bounds__(NW *kWave)
-    __attribute__((amdgpu_waves_per_eu(SP <= 96 && NC == 32 ? 8 : 1))) void k_dp_class_chain(
+__global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
     float *__restrict__ planes, size_t plane_elems, int keep, const float *__restrict__ zero_row,
     uint8_t *__restrict__ bp, size_t bp_layer_bytes, const float *__restrict__ Tq,
     const int32_t *__restrict__ Oq, const float *__restrict__ Rc,
     const int32_t *__restrict__ cmeta, const int32_t *__restrict__ cstart,
     const int32_t *__restrict__ cls, const int32_t *__restrict__ ridx,
     const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
-    const int32_t *__restrict__ lowsum, const uint4 *__restrict__ items, size_t items_per_xcd,
-    ChainCtl *__restrict__ ctl, unsigned *__restrict__ flags, unsigned epoch,
-    int32_t *__restrict__ status, int B, int L, int Sc, int pitch, int tiles) {
-  extern __shared__ float lds[];
-  __shared__ int s_ctl[4]; // layer (0: the queue is empty, -1: stop), instance, tile
-  unsigned xcc;
-  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-  const int slot = (int)(xcc & 7u); // (the host admits this kernel only where the XCD ids are 0..7)
+    const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
+    unsigned *__restrict__ flags, unsigned *__restrict__ stop,
+    const unsigned *__restrict__ epoch_word, int32_t *__restrict__ status, int B, int L, int Sc,
+    int pitch, int tiles, int l0) {
+  // (the dynamic part follows the static one: keep it 16-byte aligned for its float4 accesses)
+  extern __shared__ __align__(16) float lds[];
+  __shared__ __align__(16) int s_go4[4];
+  int &s_go = s_go4[0];
+  const int b = (int)blockIdx.x;
+  if (b >= B) return;
+  const int f = (int)blockIdx.z;
+  const int l = l0 + f;
+  const int bl = b * L + l;
+  const unsigned epoch = epoch_word[0]; // number of this solve (the prepare step advanced it)
+  // the tile's table entries travel while wave 0 waits for the tiles below
+  const ClassScalars<SP / NW> k =
+      class_scalars<SP, NW>(Tq, Oq, cmeta, cls, ridx, budget, topsum, lowsum, L, l, b);
+  const int E = k.E;
+  const int a = k.low >> 6;                    // first tile with work
+  const int top = E - k.mo;                    // last source row with work
+  const int t = a + (int)blockIdx.y;
+  if (t * kWave > top) return;
   const int wave = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  const uint4 *__restrict__ mine = items + (size_t)slot * items_per_xcd;
-  // Wave 0 runs the queue.  Its branches are wave-uniform except the single-lane atomics, each
-  // closed before the next barrier and none next to the loop's back edge (a lane-0 branch that
-  // spans the back edge lets the compiler move that lane's work behind the next barrier).
-  // The library is built without the compiler's atomic optimiser, so a pop is one plain
-  // instruction whose result is awaited only where it is used.
-  unsigned *__restrict__ myq = nullptr;
-  int qid = 0, total = 0;
-  uint4 rec = make_uint4(0u, 0u, 1u, 0u); // the item to work on next (layer 0: none)
+  unsigned xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  xcc &= 7u;
   if (wave == 0) {
-    unsigned ticket = 0;
-    if (lane == 0)
-      ticket = __hip_atomic_fetch_add(&ctl->arrivals[slot][0], 1u, __ATOMIC_RELAXED,
-                                      __HIP_MEMORY_SCOPE_AGENT);
-    qid = wave_uniform((int)ticket) % kChainQueues;
-    myq = &ctl->next[slot][qid][0];
-    total = wave_uniform((int)ctl->total[slot]);
-    unsigned got = 0;
-    if (lane == 0)
-      got = __hip_atomic_fetch_add(myq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int i = wave_uniform((int)got) * kChainQueues + qid;
-    if (i < total) rec = mine[i];
-  }
-  for (;;) {
-    unsigned pending = 0; // the pop that fetches the item after this one (wave 0)
-    if (wave == 0) {
-      int l = (int)(rec.x & 0xFFFu);
-      const int b = (int)(rec.x >> 12), t = (int)rec.y, lo = (int)rec.z, hi = (int)rec.w;
-      l = wave_uniform(l);
-      if (l > 0) {
-        const unsigned *__restrict__ fl = flags + ((size_t)(l - 1) * B + wave_uniform(b)) * tiles;
-        int spins = 0;
-        for (int base = wave_uniform(lo); base <= wave_uniform(hi); base += kWave) {
-          for (;;) {
-            const int at = base + lane;
-            unsigned f = epoch;
-            if (at <= hi) f = __hip_atomic_load(&fl[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (__builtin_amdgcn_ballot_w64(f != epoch) == 0) break;
-            ++spins;
-            if ((spins & 255) == 0) { // now and then: has somebody given up?
-              const unsigned st = __hip_atomic_load(&ctl->stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              if (wave_uniform((int)st) != 0) { l = -1; break; }
-            }
-            if (spins > kChainSpinMax) { // gave up: the forward pass is incomplete
-              __hip_atomic_store(&ctl->stop, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int go = 1;
+    if (f > 0) {
+      // tiles of layer l-1 this one reads (rows r - O[l-1][s]) and, with two planes taking
+      // turns, those that still read the rows of Q[l-2] it overwrites
+      const int top1 = E - topsum[bl - 1];
+      const int a1 = lowsum[bl - 2] >> 6;
+      const int z1 = top1 >= 0 ? top1 >> 6 : -1;
+      int lo = kWave * t - maxfit[bl - 1];
+      lo = lo > 0 ? lo >> 6 : 0;
+      lo = lo > a1 ? lo : a1;
+      int hi = t;
+      if (!keep && l >= 3) {
+        const int war = (kWave * t + 63 + maxfit[bl - 2]) >> 6;
+        hi = war > hi ? war : hi;
+      }
+      hi = hi < z1 ? hi : z1;
+      const unsigned *__restrict__ fl = flags + ((size_t)(l - 1) * B + b) * tiles;
+      int spins = 0;
+      for (int base = lo; base <= hi && go; base += kWave) {
+        for (;;) {
+          const int at = base + lane;
+          unsigned fv = epoch | (xcc << kFlagXcdShift);
+          if (at <= hi) fv = __hip_atomic_load(&fl[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (__builtin_amdgcn_ballot_w64((fv & kFlagEpochMask) != epoch) == 0) {
+            // all there: were they written on this XCD (else its L2 may not hold the rows)?
+            if (__builtin_amdgcn_ballot_w64((fv >> kFlagXcdShift) != xcc) != 0) {
+              __hip_atomic_store(stop, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
               __hip_atomic_fetch_or(status, 0x40, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              l = -1;
-              break;
+              go = 0;
             }
-            __builtin_amdgcn_s_sleep(2);
+            break;
           }
-          if (l < 0) break;
+          ++spins;
+          if ((spins & 255) == 0) { // now and then: has somebody given up?
+            const unsigned st = __hip_atomic_load(stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (wave_uniform((int)st) != 0) { go = 0; break; }
+          }
+          if (spins > kFrontSpinMax) { // gave up: the forward pass is incomplete
+            __hip_atomic_store(stop, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_or(status, 0x40, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            go = 0;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(2);
         }
       }
-      s_ctl[0] = l;
-      s_ctl[1] = b;
-      s_ctl[2] = t;
     }
-    __syncthreads();
-    const int l = wave_uniform(s_ctl[0]);
-    const int b = wave_uniform(s_ctl[1]);
-    const int t = wave_uniform(s_ctl[2]);
-    if (l <= 0) return;
-    const int srci = keep ? l - 1 : ((l - 1) & 1), dsti = keep ? l : (l & 1);
-    const bool from_zero = !keep && l == 1; // Q[0] = 0 is one shared row of zeros
-    const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
-    float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
-    uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
-    // the pop for the following item travels while this one is computed
-    auto request_next = [&]() {
-      if (threadIdx.x == 0)
-        pending = __hip_atomic_fetch_add(myq, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    };
-    class_tile<SP, NW, WITH_BP, NC, true>(qsrc, qdst, bp_l, Tq, Oq, Rc, cmeta, cstart, cls, ridx,
-                                          budget, topsum, lowsum, L, Sc, l, pitch,
-                                          from_zero ? 0 : pitch, b, t * kWave, lds, request_next);
-    if (wave == 0) { // the record of the following item arrives with the store acknowledgements
-      const int i = wave_uniform((int)pending) * kChainQueues + qid;
-      rec = make_uint4(0u, 0u, 1u, 0u);
-      if (i < total) rec = mine[i];
-    }
+    s_go = go;
+  }
+  __syncthreads();
+  if (wave_uniform(s_go) == 0) return;
+  const int srci = keep ? l - 1 : ((l - 1) & 1), dsti = keep ? l : (l & 1);
+  const bool from_zero = !keep && l == 1; // Q[0] = 0 is one shared row of zeros
+  const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
+  float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
+  uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
+  class_tile<SP, NW, WITH_BP, NC, true>(k, qsrc, qdst, bp_l, Rc, cstart, Sc, pitch,
+                                        from_zero ? 0 : pitch, b, t * kWave, lds);
+  if (f + 1 < (int)gridDim.z) {
     // the rows are in the XCD's L2 once the stores are acknowledged; then the flag
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads(); // (also: nobody still reads the LDS tile or s_ctl of this item)
+    __syncthreads();
     if (wave == 0)
-      __hip_atomic_store(&flags[((size_t)l * B + b) * tiles + t], epoch, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&flags[((size_t)l * B + b) * tiles + t], epoch | (xcc << kFlagXcdShift),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -1656,83 +1580,71 @@ const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const flo
   return "k_dp_class";
 }
 
-// Which XCDs workgroups land on: every workgroup ORs the bit of its XCD id into *mask.
-__global__ void k_xcc_probe(unsigned *__restrict__ mask) {
+// Which XCD each workgroup of a small grid runs on: out[i] = XCD id of workgroup i.
+__global__ void k_xcc_probe(unsigned *__restrict__ out) {
   unsigned xcc;
   asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-  if (threadIdx.x == 0) atomicOr(mask, 1u << (xcc & 15u));
+  if (threadIdx.x == 0) out[blockIdx.x] = xcc & 15u;
 }
 
-void launch_xcc_probe(unsigned *mask, hipStream_t st) {
-  hipLaunchKernelGGL(k_xcc_probe, dim3(1024), dim3(kWave), 0, st, mask);
+void launch_xcc_probe(unsigned *out, hipStream_t st) {
+  hipLaunchKernelGGL(k_xcc_probe, dim3(kXccProbeGrid), dim3(kWave), 0, st, out);
 }
 
-size_t chain_seg_entries(const Shape &s) {
-  const int nbmax = (s.B + 7) / 8;
-  return (size_t)8 * ((size_t)(s.L > 1 ? s.L - 1 : 0) * nbmax + 1);
+bool fronts_shape_ok(const Shape &s) {
+  return s.L >= 3 && s.B % 8 == 0 && (long long)s.B * ((s.M + kWave) / kWave) < (1ll << 22);
 }
-
-// Upper bound of the items one XCD can be given: every tile of every layer front of its instances.
-size_t chain_items_per_xcd(const Shape &s) {
-  const int nbmax = (s.B + 7) / 8;
-  return (size_t)(s.L > 1 ? s.L - 1 : 0) * nbmax * ((s.M + kWave) / kWave);
-}
-
-bool chain_shape_ok(const Shape &s) { return s.L >= 3 && s.L < kChainMaxL && s.B < (1 << 20); }
 
 template <int SP, int NW, int NC>
-static void launch_chain_nc(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                            size_t plane_elems_all, size_t bp_layer_bytes, int cus,
-                            hipStream_t st) {
+static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                             size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
+                             hipStream_t st) {
   const int tiles = (s.M + kWave) / kWave;
-  const int nbmax = (s.B + 7) / 8;
   const size_t lds =
       sizeof(float) * ((with_bp ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
-  const void *fn = with_bp ? (const void *)k_dp_class_chain<SP, NW, true, NC>
-                           : (const void *)k_dp_class_chain<SP, NW, false, NC>;
+  const void *fn = with_bp ? (const void *)k_dp_class_fronts<SP, NW, true, NC>
+                           : (const void *)k_dp_class_fronts<SP, NW, false, NC>;
   if (lds > 64 * 1024) lds_opt_in(fn, lds, s.grants);
-  // as many workgroups as the chip holds at once (more would only pop an empty queue)
-  int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, NW * kWave, lds) != hipSuccess ||
-      per_cu < 1)
-    per_cu = 1;
-  const dim3 grid((unsigned)(per_cu * cus + 7) / 8 * 8), block(NW * kWave);
   const long long rows = (long long)s.B * s.L;
-  const unsigned plan_blocks = 8 + (unsigned)(rows / 4 < 1 ? 1 : (rows / 4 > 1024 ? 1024 : rows / 4));
-  ChainCtl *ctl = static_cast<ChainCtl *>(w.chain_ctl);
-  hipLaunchKernelGGL(k_chain_plan, dim3(plan_blocks), dim3(256), 0, st, w.Oq, w.budget, w.topsum,
-                     w.lowsum, w.maxfit, w.seg, ctl, s.B, s.L, s.SP, nbmax);
-  const size_t per_xcd = chain_items_per_xcd(s);
-  uint4 *items = static_cast<uint4 *>(w.chain_items);
-  hipLaunchKernelGGL(k_chain_items, dim3((unsigned)((s.L - 1) * nbmax), 8), dim3(256), 0, st,
-                     w.budget, w.topsum, w.lowsum, w.maxfit, w.seg, items, per_xcd, s.B, s.L, nbmax,
-                     keep ? 1 : 0);
-  if (with_bp)
-    hipLaunchKernelGGL((k_dp_class_chain<SP, NW, true, NC>), grid, block, lds, st, w.planes,
-                       plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp, bp_layer_bytes,
-                       w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx, w.budget, w.topsum,
-                       w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch, w.status, s.B, s.L,
-                       class_rows(s), s.pitch, tiles);
-  else
-    hipLaunchKernelGGL((k_dp_class_chain<SP, NW, false, NC>), grid, block, lds, st, w.planes,
-                       plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
-                       bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
-                       w.budget, w.topsum, w.lowsum, items, per_xcd, ctl, w.chain_flags, w.epoch,
-                       w.status, s.B, s.L, class_rows(s), s.pitch, tiles);
+  hipLaunchKernelGGL(k_class_maxfit,
+                     dim3((unsigned)(rows / 4 < 1 ? 1 : (rows / 4 > 1024 ? 1024 : rows / 4))),
+                     dim3(256), 0, st, w.Oq, w.budget, w.maxfit, w.stop, w.epoch, w.front_flags,
+                     w.front_flag_words, s.B, s.L, s.SP);
+  // (the grid's thread count stays below 2^31)
+  long long cap = ((1ll << 31) / (NW * kWave)) / ((long long)s.B * tiles);
+  if (cap > 65535) cap = 65535;
+  if (cap < 1) cap = 1;
+  const int per = fronts < cap ? fronts : (int)cap;
+  for (int l0 = 1; l0 < s.L; l0 += per) {
+    const int nf = s.L - l0 < per ? s.L - l0 : per;
+    const dim3 grid((unsigned)s.B, (unsigned)tiles, (unsigned)nf), block(NW * kWave);
+    if (with_bp)
+      hipLaunchKernelGGL((k_dp_class_fronts<SP, NW, true, NC>), grid, block, lds, st, w.planes,
+                         plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp,
+                         bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                         w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
+                         w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0);
+    else
+      hipLaunchKernelGGL((k_dp_class_fronts<SP, NW, false, NC>), grid, block, lds, st, w.planes,
+                         plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
+                         bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                         w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
+                         w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0);
+  }
 }
 
 template <int SP, int NW>
-static void launch_chain_nw(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                            size_t pe, size_t bpl, int cus, hipStream_t st) {
+static void launch_fronts_nw(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                             size_t pe, size_t bpl, int fronts, hipStream_t st) {
   if constexpr (SP >= 48) {
-    if (s.NC > 32) return launch_chain_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, cus, st);
+    if (s.NC > 32) return launch_fronts_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, fronts, st);
   }
-  launch_chain_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, cus, st);
+  launch_fronts_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, fronts, st);
 }
 
 template <int SP>
-static void launch_chain(const Shape &s, const Workspace &w, bool keep, bool with_bp, size_t pe,
-                         size_t bpl, int cus, hipStream_t st) {
+static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp, size_t pe,
+                          size_t bpl, int fronts, hipStream_t st) {
   // waves per tile as in the per-launch form, without its one- and two-wave forms
   int waves = s.tune.jsplit;
   if (waves < 1 || waves > 8) {
@@ -1740,31 +1652,32 @@ static void launch_chain(const Shape &s, const Workspace &w, bool keep, bool wit
     else waves = SP >= 96 ? 8 : 4;
   }
   if constexpr (SP > 128) {
-    launch_chain_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, cus, st);
+    launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, st);
   } else {
-    if (waves >= 8) launch_chain_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, cus, st);
-    else launch_chain_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, cus, st);
+    if (waves >= 8) launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, st);
+    else launch_fronts_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, fronts, st);
   }
 }
 
-// All L-1 layer fronts of the class kernel in one launch (plus the launch that lays out its
-// queues).  plane_elems_all: floats per plane slot; bp_layer_bytes: backpointer bytes per layer.
-const char *launch_dp_class_chain(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                                  size_t plane_elems_all, size_t bp_layer_bytes, int cus,
-                                  hipStream_t st) {
+// The forward pass of the class kernel with `fronts` layer fronts per launch (plus one small
+// launch for its dependency table).  plane_elems_all: floats per plane slot; bp_layer_bytes:
+// backpointer bytes per layer.
+const char *launch_dp_class_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                                   size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
+                                   hipStream_t st) {
   switch (s.SP) {
-    case 16: launch_chain<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 24: launch_chain<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 32: launch_chain<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 48: launch_chain<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 64: launch_chain<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 96: launch_chain<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 128: launch_chain<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 192: launch_chain<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
-    case 256: launch_chain<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, cus, st); break;
+    case 16: launch_fronts<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 24: launch_fronts<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 32: launch_fronts<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 48: launch_fronts<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 64: launch_fronts<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 96: launch_fronts<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 128: launch_fronts<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 192: launch_fronts<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 256: launch_fronts<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
     default: break; // class_path_applies() admits no other pitch
   }
-  return "k_dp_class_chain";
+  return "k_dp_class_fronts";
 }
 
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st) {

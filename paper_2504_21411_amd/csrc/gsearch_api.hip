@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <vector>
 #include <new>
 
 #include "gsearch_internal.h"
@@ -23,7 +24,7 @@ const KnobDesc kKnobs[] = {
     {"kernel", &gs::Tuning::kernel},   {"small", &gs::Tuning::small},
     {"jsplit", &gs::Tuning::jsplit},   {"waves_per_block", &gs::Tuning::waves_per_block},
     {"row_groups", &gs::Tuning::row_groups}, {"streams", &gs::Tuning::streams},
-    {"chain", &gs::Tuning::chain},
+    {"fronts", &gs::Tuning::fronts},
 };
 constexpr int kKnobCount = (int)(sizeof(kKnobs) / sizeof(kKnobs[0]));
 
@@ -55,7 +56,7 @@ gs::Tuning tuning_from_env() {
 
 struct Layout {
   size_t planes, bp, Tq, Oq, Rt, ridx, budget, budget0, unit, minO, lowsum, topsum, best_s, best_cost,
-      status, cmeta, cstart, cls, Rc, maxfit, seg, chain_ctl, chain_items, total;
+      status, cmeta, cstart, cls, Rc, maxfit, stop, total;
   int nplanes;
 };
 
@@ -115,9 +116,7 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
   y.Rc = take(sizeof(float) * (size_t)s.K * ncap * ncap);
   // queues of the one-launch form of the class kernel
   y.maxfit = take(sizeof(int32_t) * (size_t)s.B * s.L);
-  y.seg = take(sizeof(int32_t) * gs::chain_seg_entries(s));
-  y.chain_ctl = take(gs::kChainCtlBytes);
-  y.chain_items = take((size_t)16 * 8 * gs::chain_items_per_xcd(s));
+  y.stop = take(sizeof(uint32_t));
   y.total = off;
   return y;
 }
@@ -129,13 +128,15 @@ size_t zero_row_bytes(int max_M) {
   return align_up(((size_t)max_M + 1 + 63) / 64 * 64 * sizeof(float), 256) + 256;
 }
 
-// Before the zero row: the completion flags of the one-launch class kernel, one word per
+// Before the zero row: the completion flags of the class kernel's several-fronts-per-launch
+// form, one word per
 // (layer, instance, 64-row tile) of the largest batch, cleared when the context is created
 // (a flag holds the number of the solve that set it, so solves need not clear them).  A batch
 // shape that would need more than 64 M flags gets none and runs one launch per layer front.
-size_t chain_flag_bytes(const gsearch_config *c) {
+size_t front_flag_bytes(const gsearch_config *c) {
   const size_t n = (size_t)c->max_L * (size_t)c->max_B * (((size_t)c->max_M + 64) / 64);
-  return n > ((size_t)64 << 20) ? 0 : align_up(n * sizeof(uint32_t), 256);
+  // (256 bytes in front of them hold the solve counter, see Workspace::epoch)
+  return n > ((size_t)64 << 20) ? 0 : align_up(n * sizeof(uint32_t), 256) + 256;
 }
 
 bool config_ok(const gsearch_config *c) {
@@ -187,9 +188,7 @@ struct gsearch_ctx {
   int groups_used = 0; // by the most recent solve
   // One-launch form of the class kernel: needs the chip's XCDs to be numbered 0..7 (looked at
   // once, when the context is created) and the flag words at the end of the workspace.
-  bool chain_ok = false;
-  int cus = 0;        // compute units of the device
-  uint32_t epoch = 0; // number of the most recent solve that used the flags
+  bool fronts_ok = false; // the XCDs take workgroups in turn and the flags have room
   gs::Tuning tune;      // launch overrides (from the environment at create, gsearch_set_knob)
   gs::LdsGrants grants; // LDS sizes already asked for, per kernel
 };
@@ -246,15 +245,22 @@ gs::Workspace group_view(const gs::Shape &s, const gs::Workspace &w, int b0) {
   return g;
 }
 
-// The one-launch form of the class kernel (every XCD serves the instances b = x, x + 8, ...).
-// Measured on MI355X it does not beat one launch per layer front (configs[3]: 1.93 against
-// 1.67 ms forward, configs[1]: 0.44 against 0.39 ms: a compute unit holds four workgroups of
-// eight waves, and what an item adds to a tile's own latency (waiting for the tiles below it,
-// store acknowledgement, two more barriers) leaves the vector units idle about as long as the
-// launch gaps it removes), so it runs only when the knob "chain" = 1 asks for it.
-bool chain_applies(const gsearch_ctx *ctx, const gs::Shape &s) {
-  if (!ctx->chain_ok || !gs::chain_shape_ok(s)) return false;
-  return ctx->tune.chain == 1;
+// (a kernel, not hipMemsetAsync: the caller may be capturing the stream into a graph)
+__global__ __launch_bounds__(256) void k_clear_words(uint32_t *__restrict__ p, size_t n) {
+  for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < n; x += (size_t)gridDim.x * 256)
+    p[x] = 0u;
+}
+
+__global__ void k_set_word(uint32_t *__restrict__ p, uint32_t v) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
+}
+
+// Layer fronts per launch of the class kernel (0: one launch per front).  The several-fronts
+// form needs the eight XCDs to take workgroups in turn and a batch that is a multiple of 8.
+int fronts_per_launch(const gsearch_ctx *ctx, const gs::Shape &s) {
+  if (!ctx->fronts_ok || !gs::fronts_shape_ok(s) || ctx->groups > 1) return 0;
+  if (ctx->tune.fronts < 0) return 64;
+  return ctx->tune.fronts >= 2 ? ctx->tune.fronts : 0;
 }
 
 // The solve behind gsearch_solve_batch and gsearch_solve_batch_noalloc.
@@ -277,7 +283,7 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   if (p->r_class && p->r_class_bound > 32 && p->S > 32) s.NC = gs::kMaxClasses;
   const Layout y = make_layout(s, c.flags);
   const size_t zb = zero_row_bytes(c.max_M);
-  if (y.total > ctx->bytes - zb - chain_flag_bytes(&c)) return GSEARCH_ERR_CAPACITY;
+  if (y.total > ctx->bytes - zb - front_flag_bytes(&c)) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
   w.by_class = 0;
   char *base = ctx->base;
@@ -304,11 +310,16 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   w.cls = reinterpret_cast<int32_t *>(base + y.cls);
   w.Rc = reinterpret_cast<float *>(base + y.Rc);
   w.maxfit = reinterpret_cast<int32_t *>(base + y.maxfit);
-  w.seg = reinterpret_cast<int32_t *>(base + y.seg);
-  w.chain_ctl = base + y.chain_ctl;
-  w.chain_items = base + y.chain_items;
-  w.chain_flags = reinterpret_cast<unsigned *>(base + (ctx->bytes - zb - chain_flag_bytes(&c)));
-  w.epoch = 0;
+  w.stop = reinterpret_cast<unsigned *>(base + y.stop);
+  w.epoch = nullptr;
+  w.front_flags = nullptr;
+  w.front_flag_words = 0;
+  if (ctx->fronts_ok && front_flag_bytes(&c) > 0) {
+    char *fb = base + (ctx->bytes - zb - front_flag_bytes(&c));
+    w.epoch = reinterpret_cast<unsigned *>(fb);
+    w.front_flags = reinterpret_cast<unsigned *>(fb + 256);
+    w.front_flag_words = (front_flag_bytes(&c) - 256) / sizeof(uint32_t);
+  }
   ctx->solved = false;
   ctx->forward_kernel = ""; // (a solve of one layer launches no forward kernel)
   ctx->shape = s;
@@ -349,19 +360,12 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
     gs::launch_dp_small(s, w, keep, cur, st);
     ctx->forward_kernel = "k_dp_small";
     ctx->groups_used = 1;
-  } else if (use_classes && chain_applies(ctx, s)) {
-    // every layer front in one launch, the instances bound to XCDs (see k_dp_class_chain)
+  } else if (use_classes && fronts_per_launch(ctx, s) > 0) {
+    // several layer fronts per launch, the instances bound to XCDs (see k_dp_class_fronts)
     if (keep) gs::launch_class_zero(s, w.planes, st);
-    if (++ctx->epoch == 0) { // the counter wrapped: flags of old solves could be mistaken for new
-      if (hipMemsetAsync(w.chain_flags, 0, chain_flag_bytes(&c), st) != hipSuccess)
-        return GSEARCH_ERR_HIP;
-      ctx->epoch = 1;
-    }
-    w.epoch = ctx->epoch;
-    ctx->ws = w;
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
-    ctx->forward_kernel = gs::launch_dp_class_chain(s, w, keep, with_bp, pe, bp_layer_bytes,
-                                                    ctx->cus, st);
+    ctx->forward_kernel = gs::launch_dp_class_fronts(s, w, keep, with_bp, pe, bp_layer_bytes,
+                                                     fronts_per_launch(ctx, s), st);
     ctx->groups_used = 1;
     cur = keep ? s.L - 1 : ((s.L - 1) & 1);
   } else {
@@ -474,12 +478,6 @@ unsigned char *static_scratch_base(int device) {
   return slot.ptr;
 }
 
-// (a kernel, not hipMemsetAsync: the caller may be capturing the stream into a graph)
-__global__ __launch_bounds__(256) void k_clear_words(uint32_t *__restrict__ p, size_t n) {
-  for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < n; x += (size_t)gridDim.x * 256)
-    p[x] = 0u;
-}
-
 } // namespace
 
 extern "C" {
@@ -503,7 +501,7 @@ size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
   return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
                      cfg->flags)
              .total +
-         chain_flag_bytes(cfg) + zero_row_bytes(cfg->max_M);
+         front_flag_bytes(cfg) + zero_row_bytes(cfg->max_M);
 }
 
 int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
@@ -529,17 +527,20 @@ int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
     return GSEARCH_ERR_NO_MEMORY;
   }
   ctx->base = static_cast<char *>(p);
-  const size_t zb = zero_row_bytes(cfg->max_M) + chain_flag_bytes(cfg);
+  const size_t zb = zero_row_bytes(cfg->max_M) + front_flag_bytes(cfg);
   // (waited for here: solves may run on streams that do not order themselves after it)
-  unsigned xcds = 0;
-  bool ok = hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) == hipSuccess &&
-            hipMemset(ctx->base, 0, sizeof(unsigned)) == hipSuccess;
-  if (ok) {
+  bool ok = hipMemset(ctx->base + (ctx->bytes - zb), 0, zb) == hipSuccess;
+  // Do workgroups whose indices agree mod 8 run on the same XCD?  (The class kernel's
+  // several-fronts form keeps an instance in one L2 that way; asked once, on a small grid,
+  // written into the head of the workspace, which every workspace has room for.)
+  std::vector<unsigned> where(gs::kXccProbeGrid, 0xFFu);
+  bool turns = ok && ctx->bytes >= sizeof(unsigned) * gs::kXccProbeGrid;
+  if (turns) {
     gs::launch_xcc_probe(reinterpret_cast<unsigned *>(ctx->base), nullptr);
     ok = hipGetLastError() == hipSuccess && hipStreamSynchronize(nullptr) == hipSuccess &&
-         hipMemcpy(&xcds, ctx->base, sizeof(unsigned), hipMemcpyDeviceToHost) == hipSuccess &&
-         hipDeviceGetAttribute(&ctx->cus, hipDeviceAttributeMultiprocessorCount, cfg->device) ==
-             hipSuccess;
+         hipMemcpy(where.data(), ctx->base, sizeof(unsigned) * gs::kXccProbeGrid,
+                   hipMemcpyDeviceToHost) == hipSuccess;
+    for (int i = 0; i < gs::kXccProbeGrid; ++i) turns = turns && where[i] == where[i & 7];
   }
   if (!ok) {
     (void)hipGetLastError();
@@ -547,7 +548,7 @@ int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
     delete ctx;
     return GSEARCH_ERR_HIP;
   }
-  ctx->chain_ok = xcds == 0xFFu && ctx->cus >= 8 && chain_flag_bytes(cfg) > 0;
+  ctx->fronts_ok = turns && front_flag_bytes(cfg) > 0;
   *out = ctx;
   return GSEARCH_OK;
 }
@@ -605,7 +606,7 @@ int gsearch_solve_batch_noalloc(int32_t device, const gsearch_problem *p, const 
   ctx->bytes = (size_t)GSEARCH_NOALLOC_SCRATCH_BYTES;
   ctx->profiling = false;
   ctx->groups = 1; // one chain of launches on the caller's stream: no streams or events to create
-  ctx->chain_ok = false; // (the one-launch class kernel keeps flags across solves: not on this array)
+  ctx->fronts_ok = false; // (that form of the class kernel keeps flags across solves: not on this array)
   // The array keeps whatever the last call left.  What a solve expects to find cleared sits at
   // the end of the workspace: the row of zeros that stands for Q[0] and the word in which the
   // data-status bits are collected.  Its place depends on M, so it is cleared on every call.
@@ -706,6 +707,18 @@ int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms) {
   if (hipEventElapsedTime(host_ms, ctx->ev_begin, ctx->ev_end) != hipSuccess)
     return GSEARCH_ERR_HIP;
   return GSEARCH_OK;
+}
+
+int gsearch_set_solve_counter(gsearch_ctx *ctx, uint32_t value, void *stream) {
+  if (!ctx || value >= (1u << 29)) return GSEARCH_ERR_INVALID_ARG;
+  const size_t fb = front_flag_bytes(&ctx->cfg);
+  if (!ctx->fronts_ok || fb == 0) return GSEARCH_ERR_UNSUPPORTED;
+  DeviceScope scope(ctx->cfg.device);
+  if (!scope.ok) return GSEARCH_ERR_NO_DEVICE;
+  char *at = ctx->base + (ctx->bytes - zero_row_bytes(ctx->cfg.max_M) - fb);
+  hipLaunchKernelGGL(k_set_word, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<uint32_t *>(at), value);
+  return hipGetLastError() == hipSuccess ? GSEARCH_OK : GSEARCH_ERR_HIP;
 }
 
 int gsearch_lds_calibration(int32_t mode, int32_t iters, float *sink, void *stream) {

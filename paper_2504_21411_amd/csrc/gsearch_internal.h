@@ -10,7 +10,6 @@ namespace gs {
 
 constexpr int kWave = 64;          // CDNA wavefront width
 constexpr int kRowsPerBlock = 256; // budget rows handled by one workgroup (4 waves)
-constexpr size_t kChainCtlBytes = 16384; // room for the queue counters of the one-launch class kernel
 constexpr int kMaxClasses = 64;    // most transition classes a solve can exploit (capacity of the
                                    // class kernel's wide variant; the narrow one holds 32)
 
@@ -24,7 +23,8 @@ struct Tuning {
   int waves_per_block = 0; // push kernel: waves per workgroup (1..4)
   int row_groups = 0;      // push kernel: 64-row groups per wave
   int streams = 0;         // instance groups on parallel streams
-  int chain = -1;          // 1: the one-launch class kernel wherever it can run (else never)
+  int fronts = -1;         // class kernel: layer fronts per launch, 2..64 (0, 1: one launch per
+                           // front; -1: 64 wherever that form can run)
 };
 
 // More than 64 KB of dynamic LDS per workgroup has to be asked for once per kernel (and
@@ -90,14 +90,15 @@ struct Workspace {
   int32_t *cls;      // [SP]         class of strategy s (0 for the padding)
   float *Rc;         // [K][NC][NC]  Rc[k][cj][ci] = R between the classes'
                      //              first strategies, +inf for padding classes
-  // One-launch form of the class kernel (see k_dp_class_chain):
+  // Several layer fronts per launch of the class kernel (see k_dp_class_fronts):
   int32_t *maxfit;   // [B][L]       largest O[b][l][s] that fits the budget at all (0: none)
-  int32_t *seg;      // [8][(L-1)*ceil(B/8)+1]  per XCD: items before each (layer, instance) segment
-  void *chain_ctl;   // queue counters of the solve (struct ChainCtl)
-  void *chain_items; // [8][items per XCD] uint4 item records (layer | instance << 12, tile, lo, hi)
-  unsigned *chain_flags; // [L][B][tiles] completion flags; a flag set by solve number n holds n.
-                     //  Sits at a fixed place at the end of the workspace, cleared at create.
-  unsigned epoch;    // number of this solve (never 0)
+  unsigned *stop;    // one word: a bounded wait gave up somewhere in this solve
+  size_t front_flag_words; // words the context has room for
+  unsigned *front_flags; // [L][B][tiles] completion flags; a flag set by solve number n holds n.
+                     // At a fixed place of the context's allocation, cleared when it is created.
+  unsigned *epoch;   // [3] at a fixed place of the allocation: number of the current solve
+                     // (1 .. 2^29 - 1, advanced on the device by the prepare step, so that a
+                     // replayed graph advances it too), "wrapped, clear the flags", "cleared"
 };
 
 inline size_t plane_elems(const Shape &s) { return (size_t)s.B * s.S * s.pitch; }
@@ -121,14 +122,15 @@ bool class_path_applies(const Shape &s);
 const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const float *src,
                             float *dst, void *bp_l, hipStream_t st);
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
-// The whole forward pass of the class kernel in one launch; `cus` = compute units of the device.
-const char *launch_dp_class_chain(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                                  size_t plane_elems_all, size_t bp_layer_bytes, int cus,
-                                  hipStream_t st);
-size_t chain_seg_entries(const Shape &s);          // int32 entries of Workspace::seg
-size_t chain_items_per_xcd(const Shape &s);        // uint4 records per XCD of Workspace::chain_items
-bool chain_shape_ok(const Shape &s);               // the one-launch form can take this shape
-void launch_xcc_probe(unsigned *mask, hipStream_t st); // OR of (1 << XCD id) over a small grid
+// The forward pass of the class kernel with `fronts` layer fronts per launch, the tiles of a
+// launch waiting for each other through flags (batch a multiple of 8, 3 layers or more).
+const char *launch_dp_class_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp,
+                                   size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
+                                   hipStream_t st);
+bool fronts_shape_ok(const Shape &s);              // that form can take this shape
+// out[i] = id of the XCD that workgroup i of a grid of kXccProbeGrid workgroups ran on
+constexpr int kXccProbeGrid = 512;
+void launch_xcc_probe(unsigned *out, hipStream_t st);
 void launch_layout_classes(const int32_t *desc, int S, int32_t *r_class, int32_t *count_out,
                            hipStream_t st);
 void launch_init_layer0(const Shape &s, const Workspace &w, float *plane0, hipStream_t st);

@@ -106,11 +106,12 @@ def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.gsearch_forward_kernel(None) == b""
     # tuning knobs: the names are host data; setting needs a context
     names = b.gsearch_knob_names()
-    assert names == ["kernel", "small", "jsplit", "waves_per_block", "row_groups", "streams", "chain"]
+    assert names == ["kernel", "small", "jsplit", "waves_per_block", "row_groups", "streams", "fronts"]
     assert lib.gsearch_knob_name(-1) is None and lib.gsearch_knob_name(len(names)) is None
-    assert lib.gsearch_set_knob(None, b"chain", 1) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_set_knob(None, b"fronts", 1) == b.GSEARCH_ERR_INVALID_ARG
     v = ctypes.c_int(0)
-    assert lib.gsearch_get_knob(None, b"chain", ctypes.byref(v)) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_get_knob(None, b"fronts", ctypes.byref(v)) == b.GSEARCH_ERR_INVALID_ARG
+    assert lib.gsearch_set_solve_counter(None, 5, None) == b.GSEARCH_ERR_INVALID_ARG
     # the entry point on the fixed array checks its arguments before it touches a device
     assert lib.gsearch_solve_batch_noalloc(0, None, None, None, None, None, None) == \
         b.GSEARCH_ERR_INVALID_ARG

@@ -344,12 +344,12 @@ def test_config3_large_dense_full_size(gs, oracle_mod):
     dw = runner.DeviceWorkload(w)
     # the three launch configurations bench.py times (class kernel with and without
     # backpointers, general kernel on two instance groups) and the general min-only pass
-    # (and the class kernel as all fronts in one launch, which the knob "chain" asks for)
-    for flags, classes, kernel in ((0, True, "k_dp_class"), (0x4, True, "k_dp_class"),
-                                   (0, True, "k_dp_class_chain"), (0x4, True, "k_dp_class_chain"),
+    # (the class kernel with 64 layer fronts per launch, its default here, and with one)
+    for flags, classes, kernel in ((0, True, "k_dp_class_fronts"), (0x4, True, "k_dp_class_fronts"),
+                                   (0, True, "k_dp_class"), (0x4, True, "k_dp_class"),
                                    (0, False, "k_dp_wide"), (0x4, False, "k_dp_wide")):
         with runner.make_context(w, flags=flags) as ctx:
-            ctx.gsearch_set_knob("chain", 1 if kernel.endswith("chain") else 0)
+            ctx.gsearch_set_knob("fronts", -1 if kernel.endswith("fronts") else 0)
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", classes=classes))
             got["data_status"] = ctx.gsearch_data_status()
             assert ctx.gsearch_forward_kernel() == kernel
@@ -515,26 +515,27 @@ CLASS_CASES = [
 ]
 
 
-@pytest.mark.parametrize("chain", [0, 1], ids=["per_front", "one_launch"])
+@pytest.mark.parametrize("fronts", [0, 3], ids=["per_front", "three_fronts_per_launch"])
 @pytest.mark.parametrize("mode", ["bp", "nobp"])
 @pytest.mark.parametrize("case", CLASS_CASES, ids=lambda c: "S%dnc%dK%d" % (c[0], len(c[1]), c[2]))
-def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode, chain):
+def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode, fronts):
     """R constant on (class, class) blocks, stated through r_class: the class kernel must
     give the oracle's bits (the oracle knows nothing of classes), whole planes and
     backpointers included, also when candidates of one class round to the same sum.  Both
-    forms: one launch per layer front, and all fronts in one launch."""
+    forms: one launch per layer front, and several fronts per launch (which takes batches
+    that are a multiple of 8)."""
     binding, runner = gs
     import torch
     S, sizes, K, M, coarse = case
-    B, L = 3, 6
-    budget = np.array([M, M // 3, max(0, M - 65)], np.int32)
+    B, L = (8, 6) if fronts else (3, 6)
+    budget = np.array([M, M // 3, max(0, M - 65), M // 2, 0, M - 1, M, 2 * M // 3][:B], np.int32)
     w, r_class = workloads.class_tables("classes", B, L, S, M, sizes, K=K, seed=S + len(sizes),
                                         budget=budget, coarse=coarse)
     ref = oracle_batch(oracle_mod, w)
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
     with runner.make_context(w, flags=MODES[mode] | binding.GSEARCH_FLAG_KEEP_PLANES) as ctx:
-        ctx.gsearch_set_knob("chain", chain)
+        ctx.gsearch_set_knob("fronts", fronts)
         out = runner.run_step(ctx, dw, backtrace="all", r_class=rc, r_class_bound=len(sizes))
         C, bp = ctx.gsearch_export_planes(want_bp=(mode == "bp"))
         got = runner.to_numpy(out)
@@ -542,7 +543,7 @@ def test_class_kernel_matches_oracle(gs, oracle_mod, case, mode, chain):
         kernel = ctx.gsearch_forward_kernel()
         C = C.cpu().numpy()
         bp = bp.cpu().numpy() if bp is not None else None
-    assert kernel == (("k_dp_class_chain" if chain else "k_dp_class") if S >= 9 else kernel)
+    assert kernel == (("k_dp_class_fronts" if fronts else "k_dp_class") if S >= 9 else kernel)
     assert_same(got, ref, w, f"classes {mode}")
     for b in range(B):
         E = int(w.budget[b])
@@ -567,7 +568,6 @@ def test_class_kernel_with_instance_groups_and_single_layer(gs, oracle_mod):
         with runner.make_context(w, flags=flags) as ctx:
             for groups in (2, 5, 1, 0):
                 ctx.gsearch_set_instance_groups(groups)
-                ctx.gsearch_set_knob("chain", 0)       # instance groups: one launch per front
                 got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
                 got["data_status"] = ctx.gsearch_data_status()
                 assert ctx.gsearch_forward_kernel() == "k_dp_class"
@@ -603,6 +603,9 @@ def _class_sweep_case(runner, oracle_mod, rng, case):
     S = [9, 12, 16, 17, 24, 31, 32, 33, 44, 48, 49, 64, 65, 96, 100, 128, 129, 162, 192,
          256][int(v[0]) % 20]
     B, L, M, K = 1 + int(v[1]) % 5, 2 + int(v[2]) % 5, 1 + int(v[3]) % 600, 1 + int(v[4]) % 3
+    fronts = [0, 2, 0, 64][(case // 2) % 4]        # several fronts per launch: batches of 8, 16
+    if fronts:
+        B = 8 * (1 + B % 2)
     sizes = _random_partition(rng, S)
     budget = rng.randint(0, M, B).astype(np.int32)
     w, r_class = workloads.class_tables(f"csweep{case}", B, L, S, M, sizes, K=K, seed=9000 + case,
@@ -621,15 +624,14 @@ def _class_sweep_case(runner, oracle_mod, rng, case):
     flags = 0x4 if case % 3 == 1 else 0
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
-    chain = (case // 2) % 2
     with runner.make_context(w, flags=flags) as ctx:
-        ctx.gsearch_set_knob("chain", chain)
-        if case % 6 == 5:
+        ctx.gsearch_set_knob("fronts", fronts)
+        if case % 6 == 5 and not fronts:
             ctx.gsearch_set_instance_groups(1 + case % 3)
         got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc,
                                               r_class_bound=len(sizes)))
         got["data_status"] = ctx.gsearch_data_status()
-        want = "k_dp_class_chain" if chain and L >= 3 else "k_dp_class"
+        want = "k_dp_class_fronts" if fronts and L >= 3 else "k_dp_class"
         assert ctx.gsearch_forward_kernel() == want, (case, S)
         curve = ctx.gsearch_budget_curve().cpu().numpy() if case % 4 == 1 else None
     assert_same(got, ref, w, f"class sweep {case} S={S} sizes={sizes} flags={flags}")
@@ -642,7 +644,7 @@ def test_class_kernel_random_sweep(gs, oracle_mod):
     register-tile size, random partitions of 1..64 classes, several matrices, ragged budgets,
     zero-memory and never-fitting strategies, forbidden class transitions, coarse values that
     make sums collide, memories with a common divisor, both modes, forced instance groups,
-    one launch per front and all fronts in one launch."""
+    one launch per front and several fronts per launch."""
     _, runner = gs
     rng = workloads.SplitMix64(777)
     for case in range(60):
@@ -651,11 +653,11 @@ def test_class_kernel_random_sweep(gs, oracle_mod):
 
 @pytest.mark.parametrize("mode", ["bp", "nobp", "keep"])
 @pytest.mark.parametrize("shape", [(8, 20, 44, 3000), (16, 9, 96, 1500), (40, 5, 24, 700),
-                                   (9, 6, 44, 900), (64, 12, 16, 260)],
+                                   (24, 6, 44, 900), (64, 12, 16, 260)],
                          ids=lambda t: "B%dL%dS%dM%d" % t)
-def test_class_kernel_all_fronts_in_one_launch(gs, oracle_mod, shape, mode):
-    """The one-launch form at shapes with many tiles per instance and many layers: the
-    instances are served XCD by XCD, tiles wait for the tiles of the previous layer they read,
+def test_class_kernel_several_fronts_per_launch(gs, oracle_mod, shape, mode):
+    """Several layer fronts per launch at shapes with many tiles per instance and many layers:
+    an instance stays on one XCD, tiles wait for the tiles of the previous layer they read,
     and with two ping-pong planes (bp, nobp keeps every plane) also for those that still
     read the rows they overwrite.  Budgets are ragged, one instance fits nothing, memories
     are small against the tile (64 rows) in some layers and several tiles wide in others."""
@@ -667,7 +669,7 @@ def test_class_kernel_all_fronts_in_one_launch(gs, oracle_mod, shape, mode):
     budget = rng.randint(M // 2, M, B).astype(np.int32)
     budget[0] = M
     budget[B // 2] = 3                               # fits nothing
-    w, r_class = workloads.class_tables("chain", B, L, S, M, sizes, K=2, seed=B + L + S,
+    w, r_class = workloads.class_tables("fronts", B, L, S, M, sizes, K=2, seed=B + L + S,
                                         budget=budget, coarse=(L % 2 == 0))
     w.O[:, 1::3, :] = np.minimum(w.O[:, 1::3, :] * 9, M // 4)     # layers several tiles wide
     w.O[:, 2::3, :] = np.maximum(w.O[:, 2::3, :] // 8, 1)          # layers of a few bins
@@ -677,13 +679,13 @@ def test_class_kernel_all_fronts_in_one_launch(gs, oracle_mod, shape, mode):
     dw = runner.DeviceWorkload(w)
     rc = torch.from_numpy(r_class).to(dw.device)
     with runner.make_context(w, flags=flags) as ctx:
-        ctx.gsearch_set_knob("chain", 1)
-        assert ctx.gsearch_get_knob("chain") == 1
-        for rep in range(3):                          # the flags carry over from solve to solve
+        for rep, fronts in enumerate((64, 2, 5)):     # the flags carry over from solve to solve
+            ctx.gsearch_set_knob("fronts", fronts)
+            assert ctx.gsearch_get_knob("fronts") == fronts
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
             got["data_status"] = ctx.gsearch_data_status()
-            assert ctx.gsearch_forward_kernel() == "k_dp_class_chain"
-            assert_same(got, ref, w, f"one launch {mode} rep {rep}")
+            assert ctx.gsearch_forward_kernel() == "k_dp_class_fronts"
+            assert_same(got, ref, w, f"{fronts} fronts per launch {mode} rep {rep}")
         if mode == "keep":
             C, bp = ctx.gsearch_export_planes(want_bp=True)
             C, bp = C.cpu().numpy(), bp.cpu().numpy()
@@ -692,15 +694,77 @@ def test_class_kernel_all_fronts_in_one_launch(gs, oracle_mod, shape, mode):
                 one = oracle_mod.solve(w.T[b], w.O[b], w.R, w.r_index[b], E, want_planes=True)
                 assert np.array_equal(bits(C[b, :, :E + 1, :]), bits(one["C"])), b
                 assert np.array_equal(bp[b, :, :E + 1, :], one["bp"].astype(np.int32)), b
-        ctx.gsearch_set_knob("chain", 0)
+        ctx.gsearch_set_knob("fronts", 0)
         got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
         got["data_status"] = ctx.gsearch_data_status()
         assert ctx.gsearch_forward_kernel() == "k_dp_class"
-        assert_same(got, ref, w, f"per front after one launch {mode}")
+        assert_same(got, ref, w, f"per front after several per launch {mode}")
+
+
+def test_several_fronts_per_launch_on_other_streams_and_in_a_graph(gs, oracle_mod):
+    """Which XCD the first workgroup of a launch lands on depends on the stream's hardware
+    queue; the several-fronts form only needs an instance's workgroups to share an XCD.  Solves
+    on three streams of their own, then a captured step replayed between eager solves."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = 16, 12, 44, 1200
+    rng = workloads.SplitMix64(99)
+    budget = rng.randint(M // 3, M, B).astype(np.int32)
+    w, r_class = workloads.class_tables("streams", B, L, S, M, [4] * 11, K=2, seed=17,
+                                        budget=budget, coarse=True)
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    with runner.make_context(w) as ctx:
+        for st in streams:
+            with torch.cuda.stream(st):
+                got = runner.run_step(ctx, dw, backtrace="all", r_class=rc)
+                st.synchronize()
+                got = runner.to_numpy(got)
+                got["data_status"] = ctx.gsearch_data_status()
+                assert ctx.gsearch_forward_kernel() == "k_dp_class_fronts"
+                assert_same(got, ref, w, "own stream")
+        st = streams[1]
+        with torch.cuda.stream(st):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=st):
+                captured = runner.run_step(ctx, dw, backtrace="all",
+                                           r_class=rc)
+            for _ in range(3):
+                graph.replay()
+                got = runner.to_numpy(captured)
+                got["data_status"] = ctx.gsearch_data_status()
+                assert_same(got, ref, w, "replay")
+
+
+def test_solve_counter_wraps_without_mistaking_old_flags_for_new(gs, oracle_mod):
+    """The flags of the several-fronts form hold the number of the solve that set them; the
+    counter wraps at 2^29, and the flags are cleared then.  Walk a context across the wrap
+    (flags of solves 2^29 - 2 and 2^29 - 1, then 1, 2, 3 again, whose flags the earlier solves
+    of this test had set as well)."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = 8, 10, 24, 900
+    w, r_class = workloads.class_tables("wrap", B, L, S, M, [4] * 6, K=1, seed=5,
+                                        budget=np.arange(M - 7, M + 1, dtype=np.int32))
+    other = dataclasses.replace(w, budget=(w.budget // 2).astype(np.int32))
+    ref, ref_other = oracle_batch(oracle_mod, w), oracle_batch(oracle_mod, other)
+    dw, dwo = runner.DeviceWorkload(w), runner.DeviceWorkload(other)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    with runner.make_context(w) as ctx:
+        for start in (0, (1 << 29) - 3):
+            ctx.gsearch_set_solve_counter(start)
+            for rep in range(6):
+                which, d, r = (w, dw, ref) if rep % 2 == 0 else (other, dwo, ref_other)
+                got = runner.to_numpy(runner.run_step(ctx, d, backtrace="all", r_class=rc))
+                got["data_status"] = ctx.gsearch_data_status()
+                assert ctx.gsearch_forward_kernel() == "k_dp_class_fronts"
+                assert_same(got, r, which, f"counter from {start}, solve {rep}")
 
 
 @pytest.mark.parametrize("mode", ["bp", "nobp", "bp_push", "bp_tile", "nobp_tile", "generic",
-                                  "class_bp", "class_nobp", "class_chain"])
+                                  "class_bp", "class_nobp", "class_fronts"])
 def test_rows_that_no_plan_can_use_are_skipped_exactly(gs, oracle_mod, mode):
     """Every strategy of every layer needs a good share of the budget, so most rows of the
     early layers cannot be completed to a plan within the budget and the forward kernels
@@ -710,8 +774,8 @@ def test_rows_that_no_plan_can_use_are_skipped_exactly(gs, oracle_mod, mode):
     budgets has left other values in the planes."""
     binding, runner = gs
     import torch
-    B, L, S, M = 5, 9, 24, 1800
-    budget = np.array([M, M - 1, 1300, 1230, 700], np.int32)
+    B, L, S, M = 8, 9, 24, 1800
+    budget = np.array([M, M - 1, 1300, 1230, 700, 1500, 1264, 1799], np.int32)
     if mode.startswith("class"):
         sizes = [4] * (S // 4)
         w, r_class = workloads.class_tables("topcut", B, L, S, M, sizes, K=2, seed=91,
@@ -725,7 +789,7 @@ def test_rows_that_no_plan_can_use_are_skipped_exactly(gs, oracle_mod, mode):
     w.O[:] = np.minimum(w.O % 90 + floor[None, :, None], M + 1).astype(w.O.dtype)
     ref = oracle_batch(oracle_mod, w)
     assert np.isfinite(ref["best_cost"][:4]).all() and not np.isfinite(ref["best_cost"][4])
-    flags = {"class_bp": 0, "class_nobp": 0x4, "class_chain": 0}.get(mode, MODES.get(mode, 0))
+    flags = {"class_bp": 0, "class_nobp": 0x4, "class_fronts": 0}.get(mode, MODES.get(mode, 0))
     dw = runner.DeviceWorkload(w)
     kw = {}
     if r_class is not None:
@@ -733,8 +797,7 @@ def test_rows_that_no_plan_can_use_are_skipped_exactly(gs, oracle_mod, mode):
     other = dataclasses.replace(w, budget=(w.budget[::-1] // 2).astype(np.int32))
     dother = runner.DeviceWorkload(other)
     with runner.make_context(w, flags=flags) as ctx:
-        if mode == "class_chain":
-            ctx.gsearch_set_knob("chain", 1)
+        ctx.gsearch_set_knob("fronts", 4 if mode == "class_fronts" else 0)
         for rep in range(2):
             got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", **kw))
             got["data_status"] = ctx.gsearch_data_status()
