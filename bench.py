@@ -274,8 +274,17 @@ def main():
         launch_s = fwd_ms * 1e-3 / launches
         key = f"{cfg_index}/{mode}" + (f"/groups{groups_forced}" if groups_forced else "") \
             + ("/perfront" if kernel == "k_dp_class" and args.fronts == 0 else "")
-        prof = (profiled.get("entries") or {}).get(key) or {}
+        prof = dict((profiled.get("entries") or {}).get(key) or {})
+        fronts_per_launch = 1.0
+        if kernel == "k_dp_class_fronts" and prof.get("calls") and prof.get("solves"):
+            # a launch of this kernel covers up to 64 layer fronts: the profile's per-dispatch
+            # figures are brought to one layer front (dispatches per solve / (L - 1))
+            fronts_per_launch = (w.L - 1) / (prof["calls"] / prof["solves"])
+            for name in ("avg_us", "traffic_bytes", "lds_bytes", "fetch_bytes", "write_bytes"):
+                if prof.get(name) is not None:
+                    prof[name] = prof[name] / fronts_per_launch
         common = {"kernel": kernel, "concurrent_launches": groups,
+                  "layer_fronts_per_launch": fronts_per_launch,
                   "traffic": prof.get("traffic_bytes"),
                   "traffic_profiled_kernel": prof.get("kernel")}
         if kernel.startswith("k_dp_class"):

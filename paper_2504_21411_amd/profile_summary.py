@@ -1,7 +1,9 @@
 """Turns rocprofv3 result databases of bench.py runs into profiles/traffic.json.
 
     python -m paper_2504_21411_amd.profile_summary --root <dir> --commit <hash> \
-        [--out profiles/traffic.json] [--text profiles/summary.md]
+        [--out profiles/traffic.json] [--markdown-dir profiles] [--notes profiles/notes.json]
+    python -m paper_2504_21411_amd.profile_summary --from-json profiles/traffic.json \
+        --markdown-dir profiles [--notes profiles/notes.json]
 
 <dir> holds one folder per measured run, named like the key bench.py looks up
 ("3_bp", "3_bp-general_groups1", "1_bp", ...: configuration, mode, forced instance groups), and
@@ -84,13 +86,97 @@ def forward_kernel(times):
     return best
 
 
+NAMES = {"0": "cfg0_single_decoder", "1": "cfg1_batch_decoder", "2": "cfg2_hetero_encdec",
+         "3": "cfg3_large_dense", "4": "cfg4_outer_search"}
+SHAPES = {"0": "B=1, L=24, S=12, M=256", "1": "B=64, L=48, S=44, M=2048", "2": "B=256, L=32, S=44, M=4096, K=4",
+          "3": "B=8, L=128, S=96, M=16384", "4": "B=2048, L=32, S=24, M=2048"}
+SQ = "SQ_WAVES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_INSTS_VALU SQ_INSTS_SALU SQ_WAIT_INST_ANY SQ_INSTS_SMEM SQ_INSTS_LDS"
+LDS = "SQ_INSTS_LDS_LOAD SQ_INSTS_LDS_STORE SQ_INSTS_LDS_ATOMIC SQ_INSTS_LDS_LOAD_BANDWIDTH SQ_INSTS_LDS_STORE_BANDWIDTH SQ_INSTS_LDS_ATOMIC_BANDWIDTH SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS"
+
+
+def write_markdown(d, folder, notes):
+    """One short summary per kernel and workload, written from the same document as
+    traffic.json; older *.md files in the folder are removed."""
+    commit = d["commit"]
+    cal = d["calibration"]
+    for old in os.listdir(folder):
+        if old.endswith(".md"):
+            os.remove(os.path.join(folder, old))
+    groups = {}
+    for key, e in d["entries"].items():
+        cfg = key.split("/")[0]
+        kern = e["kernel"].replace("void ", "").split("<")[0]
+        groups.setdefault((kern, cfg), []).append((key, e))
+    for (kern, cfg), items in sorted(groups.items()):
+        path = os.path.join(folder, f"{kern}_{NAMES[cfg]}.md")
+        out = []
+        out.append(f"# {kern} on configs[{cfg}] ({SHAPES[cfg]}) — rocprofv3 summary, MI355X\n")
+        out.append(f"Measured at commit `{commit}` ({d['written']}); figures per dispatch of the forward kernel, "
+                   f"averaged over the run. Written from `profiles/traffic.json` "
+                   f"(`python -m paper_2504_21411_amd.profile_summary`).\n")
+        out.append("Commands (from /tmp with TMPDIR=/tmp; `bench.py` is the repository's; `<B>` below):\n")
+        for key, e in items:
+            parts = key.split("/")
+            extra = " --instance-groups 1" if "groups1" in parts else (" --fronts 0" if "perfront" in parts else "")
+            out.append(f"    <B {key}> = python3 bench.py --config {parts[0]} --mode {parts[1]} --also= --also-configs= "
+                       f"--no-cpu-baseline --no-single-chain --min-warmup-seconds 0 --warmup 1{extra}")
+        out.append("")
+        out.append("    rocprofv3 --kernel-trace --stats -d <dir>/kt -o r -- <B> --steps 5")
+        out.append("    rocprofv3 --pmc FETCH_SIZE -d <dir>/fetch -o r -- <B> --steps 3")
+        out.append("    rocprofv3 --pmc WRITE_SIZE -d <dir>/write -o r -- <B> --steps 3")
+        out.append(f"    rocprofv3 --pmc {SQ} -d <dir>/sq -o r -- <B> --steps 3")
+        out.append(f"    rocprofv3 --pmc {LDS} -d <dir>/lds -o r -- <B> --steps 3")
+        out.append("    rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) -d <dir>/calib/copy_fetch -o c -- python3 bench.py --copy-calibration")
+        out.append(f"    rocprofv3 --pmc <the LDS set> -d <dir>/calib/lds -o c -- python3 bench.py --lds-calibration\n")
+        out.append("| run | kernel | calls | avg µs | min | max | HBM fetch MB | write MB | total MB | LDS MB | VALU wave-insts | SALU | SMEM | LDS insts | waves |")
+        out.append("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+        for key, e in items:
+            c = e["counters"]
+            g = lambda k: f"{c[k] / 1e6:.2f} M" if k in c else "-"
+            out.append(f"| {key} | `{e['kernel'].replace('void ', '')}` | {e['calls']} | {e['avg_us']:.2f} | {e['min_us']:.2f} | {e['max_us']:.2f} | "
+                       f"{e.get('fetch_bytes', 0) / 1e6:.2f} | {e.get('write_bytes', 0) / 1e6:.2f} | {e.get('traffic_bytes', 0) / 1e6:.2f} | "
+                       f"{e.get('lds_bytes', 0) / 1e6:.1f} | {g('SQ_INSTS_VALU')} | {g('SQ_INSTS_SALU')} | {g('SQ_INSTS_SMEM')} | {g('SQ_INSTS_LDS')} | {int(c.get('SQ_WAVES', 0))} |")
+        out.append("")
+        out.append(f"Calibration: a 1 GiB device copy reads FETCH_SIZE = {cal['FETCH_SIZE_of_a_1GiB_copy']:.0f} and "
+                   f"WRITE_SIZE = {cal['WRITE_SIZE_of_a_1GiB_copy']:.0f} per dispatch, so one unit is "
+                   f"{cal['FETCH_SIZE_bytes_per_unit']:.0f} and {cal['WRITE_SIZE_bytes_per_unit']:.0f} bytes. LDS bytes = "
+                   f"LOAD / STORE / ATOMIC_BANDWIDTH units x {cal['lds_load_b32_bytes_per_unit']:.0f} / "
+                   f"{cal['lds_store_b32_bytes_per_unit']:.0f} / {cal['lds_atomic_b32_bytes_per_unit']:.0f} bytes (what the counters "
+                   f"read for 2^30 four-byte loads, stores and float-minimum atomics of `gsearch_lds_calibration`; a sixteen-byte "
+                   f"load reads {cal['lds_load_b128_bytes_per_unit']:.0f} bytes per unit, so kernels with wide LDS loads move up to "
+                   f"twice the LDS bytes listed).\n")
+        for key, e in items:
+            if "k_dp_class_fronts" in e["kernel"] and e.get("solves"):
+                out.append(f"Run {key}: one dispatch of this kernel covers up to 64 layer fronts "
+                           f"({e['calls']} dispatches in {e['solves']} solves); divide the per-dispatch "
+                           f"figures by the fronts per dispatch for one front.")
+        for key, e in items:
+            ok = e.get("other_kernels", [])[:6]
+            out.append(f"Other kernels of run {key}: " + ", ".join(f"`{o['kernel'].replace('void ', '')}` {o['calls']} x {o['avg_us']:.1f} µs" for o in ok) + ".")
+        note = notes.get(f"{kern}|{cfg}")
+        if note:
+            out.append("")
+            out.append(note)
+        open(path, "w").write("\n".join(out) + "\n")
+        print(path, os.path.getsize(path))
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--root", required=True)
-    ap.add_argument("--commit", required=True)
+    ap.add_argument("--root", default=None)
+    ap.add_argument("--commit", default="unknown")
     ap.add_argument("--out", default=os.path.join("profiles", "traffic.json"))
     ap.add_argument("--text", default=None)
+    ap.add_argument("--from-json", default=None,
+                    help="skip the databases: rewrite the *.md summaries from this traffic.json")
+    ap.add_argument("--markdown-dir", default=None, help="write one *.md summary per kernel here")
+    ap.add_argument("--notes", default=None,
+                    help="JSON {\"<kernel>|<config>\": \"remark\"} appended to the summaries")
     args = ap.parse_args()
+    notes = json.load(open(args.notes)) if args.notes else {}
+    if args.from_json:
+        write_markdown(json.load(open(args.from_json)), args.markdown_dir or "profiles", notes)
+        return
 
     calib = {}
     cdir = os.path.join(args.root, "calib")
@@ -130,6 +216,10 @@ def main():
             continue
         e = {"kernel": short(fk), "calls": times[fk][0], "avg_us": times[fk][1],
              "min_us": times[fk][2], "max_us": times[fk][3]}
+        # solves of the kernel-trace pass: every solve launches the prepare kernel once
+        solves = [t[0] for n, t in times.items() if "k_bin_unit" in n]
+        if solves:
+            e["solves"] = solves[0]
         merged = {}
         for sub in ("fetch", "write", "sq", "lds"):
             c = counters(os.path.join(folder, sub))
@@ -173,6 +263,8 @@ def main():
         with open(args.text, "w") as f:
             f.write("\n".join(text) + "\n")
     print("\n".join(text))
+    if args.markdown_dir:
+        write_markdown(doc, args.markdown_dir, notes)
 
 
 if __name__ == "__main__":
