@@ -18,10 +18,6 @@ LIB = os.path.join(HERE, "libgsearch.so")
 SOURCES = ["gsearch_api.hip", "dp_kernels.hip", "aux_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # atomics stay single instructions (the one-launch class kernel requests its next
-         # item with one and awaits the answer much later; the optimiser's wave scan would
-         # wait on the spot)
-         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
