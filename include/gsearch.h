@@ -233,8 +233,8 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
  * kernel), "small" (0/1: one-launch kernel for small instances never / wherever it fits),
  * "jsplit" (waves per tile), "waves_per_block", "row_groups", "streams" (instance groups),
  * "fronts" (class kernel: layer fronts per launch, 2..64; 0 or 1: one launch per front; -1, the
- * default: 64 wherever that form can run, i.e. a batch that is a multiple of 8, three layers or
- * more, no forced instance groups, a GPU whose eight XCDs take workgroups in turn).  0 (or -1
+ * default: 64 wherever that form can run, i.e. a batch that is a multiple of 8 or has 64 instances
+ * or more, three layers or more, no forced instance groups, a GPU whose eight XCDs take workgroups in turn).  0 (or -1
  * for "small" and "fronts") restores the heuristic.  gsearch_knob_name lists the names (NULL beyond the last;
  * host only, needs no GPU).  Errors: INVALID_ARG (null context, unknown name, value outside
  * [-1, 64], null output). */

@@ -990,7 +990,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
 // only by writing back and invalidating whole caches, which costs far more than the launches
 // it would save.  So an instance stays on ONE XCD: consecutive workgroups of a launch go to
 // consecutive XCDs (starting at an XCD that depends on the stream's hardware queue) and the
-// batch is a multiple of 8, hence all workgroups of an instance run on the same XCD.  A flag
+// grid's first dimension is the batch rounded up to a multiple of 8, hence all workgroups of
+// an instance run on the same XCD.  A flag
 // carries the id of the XCD that wrote the rows, read from the hardware register, and a tile
 // that finds a flag from another XCD raises the internal status bit instead of reading rows
 // its L2 may not hold.  Within an XCD
@@ -1591,8 +1592,11 @@ void launch_xcc_probe(unsigned *out, hipStream_t st) {
   hipLaunchKernelGGL(k_xcc_probe, dim3(kXccProbeGrid), dim3(kWave), 0, st, out);
 }
 
+// (a batch that is not a multiple of 8 leaves some XCDs one instance short: taken from 64
+// instances up, where that is at most an eighth)
 bool fronts_shape_ok(const Shape &s) {
-  return s.L >= 3 && s.B % 8 == 0 && (long long)s.B * ((s.M + kWave) / kWave) < (1ll << 22);
+  return s.L >= 3 && (s.B % 8 == 0 || s.B >= 64) &&
+         (long long)(s.B + 7) * ((s.M + kWave) / kWave) < (1ll << 22);
 }
 
 template <int SP, int NW, int NC>
@@ -1611,13 +1615,14 @@ static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool
                      dim3(256), 0, st, w.Oq, w.budget, w.maxfit, w.stop, w.epoch, w.front_flags,
                      w.front_flag_words, s.B, s.L, s.SP);
   // (the grid's thread count stays below 2^31)
-  long long cap = ((1ll << 31) / (NW * kWave)) / ((long long)s.B * tiles);
+  const unsigned bx = (unsigned)((s.B + 7) / 8 * 8); // workgroups b >= B leave at once
+  long long cap = ((1ll << 31) / (NW * kWave)) / ((long long)bx * tiles);
   if (cap > 65535) cap = 65535;
   if (cap < 1) cap = 1;
   const int per = fronts < cap ? fronts : (int)cap;
   for (int l0 = 1; l0 < s.L; l0 += per) {
     const int nf = s.L - l0 < per ? s.L - l0 : per;
-    const dim3 grid((unsigned)s.B, (unsigned)tiles, (unsigned)nf), block(NW * kWave);
+    const dim3 grid(bx, (unsigned)tiles, (unsigned)nf), block(NW * kWave);
     if (with_bp)
       hipLaunchKernelGGL((k_dp_class_fronts<SP, NW, true, NC>), grid, block, lds, st, w.planes,
                          plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp,

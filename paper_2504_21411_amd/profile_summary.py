@@ -119,9 +119,9 @@ def write_markdown(d, folder, notes):
             parts = key.split("/")
             extra = " --instance-groups 1" if "groups1" in parts else (" --fronts 0" if "perfront" in parts else "")
             out.append(f"    <B {key}> = python3 bench.py --config {parts[0]} --mode {parts[1]} --also= --also-configs= "
-                       f"--no-cpu-baseline --no-single-chain --min-warmup-seconds 0 --warmup 1{extra}")
+                       f"--no-cpu-baseline --no-single-chain --min-warmup-seconds 0.3 --warmup 3{extra}")
         out.append("")
-        out.append("    rocprofv3 --kernel-trace --stats -d <dir>/kt -o r -- <B> --steps 5")
+        out.append("    rocprofv3 --kernel-trace --stats -d <dir>/kt -o r -- <B> --steps 8")
         out.append("    rocprofv3 --pmc FETCH_SIZE -d <dir>/fetch -o r -- <B> --steps 3")
         out.append("    rocprofv3 --pmc WRITE_SIZE -d <dir>/write -o r -- <B> --steps 3")
         out.append(f"    rocprofv3 --pmc {SQ} -d <dir>/sq -o r -- <B> --steps 3")

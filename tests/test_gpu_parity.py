@@ -653,7 +653,7 @@ def test_class_kernel_random_sweep(gs, oracle_mod):
 
 @pytest.mark.parametrize("mode", ["bp", "nobp", "keep"])
 @pytest.mark.parametrize("shape", [(8, 20, 44, 3000), (16, 9, 96, 1500), (40, 5, 24, 700),
-                                   (24, 6, 44, 900), (64, 12, 16, 260)],
+                                   (24, 6, 44, 900), (64, 12, 16, 260), (67, 5, 24, 300)],
                          ids=lambda t: "B%dL%dS%dM%d" % t)
 def test_class_kernel_several_fronts_per_launch(gs, oracle_mod, shape, mode):
     """Several layer fronts per launch at shapes with many tiles per instance and many layers:
