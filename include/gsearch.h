@@ -94,9 +94,11 @@ typedef enum {
                                         than announced (r_class_bound) or than
                                         GSEARCH_MAX_CLASSES, or R differs inside one */
 
-#define GSEARCH_DATA_INTERNAL 0x40   /* not about the data: a bounded wait inside the one-launch
-                                        forward kernel gave up, the forward pass is incomplete
-                                        (every instance is reported as infeasible) */
+#define GSEARCH_DATA_INTERNAL 0x40   /* not about the data: a bounded wait inside the class
+                                        kernel's several-fronts-per-launch form gave up, or a
+                                        tile found rows written on another XCD; the forward
+                                        pass is incomplete (every instance is reported as
+                                        infeasible) */
 
 #define GSEARCH_MAX_CLASSES 64 /* transition classes a solve can exploit (see r_class) */
 #define GSEARCH_DEFAULT_CLASSES 32 /* ... unless r_class_bound announces more */

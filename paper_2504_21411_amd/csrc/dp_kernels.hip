@@ -1068,7 +1068,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
     const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
     unsigned *__restrict__ flags, unsigned *__restrict__ stop,
     const unsigned *__restrict__ epoch_word, int32_t *__restrict__ status, int B, int L, int Sc,
-    int pitch, int tiles, int l0) {
+    int pitch, int tiles, int l0, int spin_max, int publish) {
   // (the dynamic part follows the static one: keep it 16-byte aligned for its float4 accesses)
   extern __shared__ __align__(16) float lds[];
   __shared__ __align__(16) int s_go4[4];
@@ -1130,7 +1130,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
             const unsigned st = __hip_atomic_load(stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (wave_uniform((int)st) != 0) { go = 0; break; }
           }
-          if (spins > kFrontSpinMax) { // gave up: the forward pass is incomplete
+          if (spins > spin_max) { // gave up: the forward pass is incomplete
             __hip_atomic_store(stop, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_fetch_or(status, 0x40, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             go = 0;
@@ -1151,7 +1151,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
   class_tile<SP, NW, WITH_BP, NC, true>(k, qsrc, qdst, bp_l, Rc, cstart, Sc, pitch,
                                         from_zero ? 0 : pitch, b, t * kWave, lds);
-  if (f + 1 < (int)gridDim.z) {
+  if (f + 1 < (int)gridDim.z && publish) {
     // the rows are in the XCD's L2 once the stores are acknowledged; then the flag
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -1616,6 +1616,7 @@ static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool
                      w.front_flag_words, s.B, s.L, s.SP);
   // (the grid's thread count stays below 2^31)
   const unsigned bx = (unsigned)((s.B + 7) / 8 * 8); // workgroups b >= B leave at once
+  const int spin_max = s.tune.spin_limit >= 1 ? s.tune.spin_limit : kFrontSpinMax;
   long long cap = ((1ll << 31) / (NW * kWave)) / ((long long)bx * tiles);
   if (cap > 65535) cap = 65535;
   if (cap < 1) cap = 1;
@@ -1628,13 +1629,15 @@ static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool
                          plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp,
                          bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
                          w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
-                         w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0);
+                         w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0, spin_max,
+                         s.tune.hold_flags == 1 ? 0 : 1);
     else
       hipLaunchKernelGGL((k_dp_class_fronts<SP, NW, false, NC>), grid, block, lds, st, w.planes,
                          plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
                          bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
                          w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
-                         w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0);
+                         w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0, spin_max,
+                         s.tune.hold_flags == 1 ? 0 : 1);
   }
 }
 

@@ -25,6 +25,9 @@ struct Tuning {
   int streams = 0;         // instance groups on parallel streams
   int fronts = -1;         // class kernel: layer fronts per launch, 2..64 (0, 1: one launch per
                            // front; -1: 64 wherever that form can run)
+  int spin_limit = 0;      // that form: polls before a wait gives up (0: the default, 2^18)
+  int hold_flags = 0;      // that form, tests only: 1 = finished tiles publish no flags, so that
+                           // every wait runs into its limit (the error path, with no fault)
 };
 
 // More than 64 KB of dynamic LDS per workgroup has to be asked for once per kernel (and

@@ -738,6 +738,34 @@ def test_several_fronts_per_launch_on_other_streams_and_in_a_graph(gs, oracle_mo
                 assert_same(got, ref, w, "replay")
 
 
+def test_a_wait_that_gives_up_ends_the_solve_with_the_internal_status(gs, oracle_mod):
+    """The error path of the several-fronts form, forced from the host: with the completion
+    flags held back and a spin limit of a few polls every wait gives up, every kernel still
+    ends normally, the status word says so, every instance is reported as infeasible, and the
+    next solve on the same context is right again."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = 8, 8, 24, 700
+    w, r_class = workloads.class_tables("giveup", B, L, S, M, [4] * 6, K=1, seed=12,
+                                        budget=np.arange(M - 7, M + 1, dtype=np.int32))
+    ref = oracle_batch(oracle_mod, w)
+    dw = runner.DeviceWorkload(w)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    with runner.make_context(w) as ctx:
+        ctx.gsearch_set_knob("spin_limit", 4)
+        ctx.gsearch_set_knob("hold_flags", 1)
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+        assert ctx.gsearch_forward_kernel() == "k_dp_class_fronts"
+        assert ctx.gsearch_data_status() == binding.GSEARCH_DATA_INTERNAL
+        assert np.isinf(got["best_cost"]).all() and int(got["best_instance"][0]) == -1
+        assert (got["plan"] == -1).all()
+        ctx.gsearch_set_knob("spin_limit", 0)
+        ctx.gsearch_set_knob("hold_flags", 0)
+        got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+        got["data_status"] = ctx.gsearch_data_status()
+        assert_same(got, ref, w, "after a solve that gave up")
+
+
 def test_solve_counter_wraps_without_mistaking_old_flags_for_new(gs, oracle_mod):
     """The flags of the several-fronts form hold the number of the solve that set them; the
     counter wraps at 2^29, and the flags are cleared then.  Walk a context across the wrap
