@@ -772,7 +772,31 @@ static __device__ __forceinline__ ClassScalars<SP / NW> class_scalars(
   return k;
 }
 
-template <int SP, int NW, bool WITH_BP, int NC, bool COHERENT, typename Hook = NoHook>
+// What a tile needs in LDS before its rows arrive: class minima at +inf and, for the argmin
+// levels, the layer's class table and the run table.  class_tile does this itself unless the
+// caller has done it (and a workgroup barrier) already: PREPPED.
+template <int SP, int NW, bool WITH_BP, int NC>
+static __device__ __forceinline__ void class_tile_prepare(const float *__restrict__ Rc,
+                                                          const int32_t *__restrict__ cstart,
+                                                          int kr, float *lds) {
+  float *cmin = lds;
+  float *rc_lds = cmin + NC * kWave;
+  int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC);
+  const float4 inf4 = {GS_INF, GS_INF, GS_INF, GS_INF};
+  for (int x = threadIdx.x; x < NC * kWave / 4; x += NW * kWave)
+    reinterpret_cast<float4 *>(cmin)[x] = inf4;
+  if (WITH_BP) {
+    // (the per-lane gathers of the argmin levels read the class table and the run table
+    // from LDS; the min-only pass takes both as scalar operands only)
+    const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
+    for (int x = threadIdx.x; x < NC * NC / 4; x += NW * kWave)
+      reinterpret_cast<float4 *>(rc_lds)[x] = reinterpret_cast<const float4 *>(rck)[x];
+    if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+  }
+}
+
+template <int SP, int NW, bool WITH_BP, int NC, bool COHERENT, typename Hook = NoHook,
+          bool PREPPED = false>
 static __device__ __forceinline__ void class_tile(
     const ClassScalars<SP / NW> &k, const float *__restrict__ qsrc, float *__restrict__ qdst,
     uint8_t *__restrict__ bp, const float *__restrict__ Rc, const int32_t *__restrict__ cstart,
@@ -821,22 +845,13 @@ static __device__ __forceinline__ void class_tile(
                               : *at) + t_s[u];
     stage[u] = t >= cb + lowq4 ? v : GS_INF; // source row >= lowq (and >= 0), row within budget
   }
-  {
-    const float4 inf4 = {GS_INF, GS_INF, GS_INF, GS_INF};
-    for (int x = threadIdx.x; x < NC * kWave / 4; x += NW * kWave)
-      reinterpret_cast<float4 *>(cmin)[x] = inf4;
-  }
+  if (!PREPPED) class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, kr, lds);
   if (WITH_BP) {
-    // (the per-lane gathers of the argmin levels read the class table and the run table
-    // from LDS; the min-only pass takes both as scalar operands only)
-    for (int x = threadIdx.x; x < NC * NC / 4; x += NW * kWave)
-      reinterpret_cast<float4 *>(rc_lds)[x] = reinterpret_cast<const float4 *>(rck)[x];
-    if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
     float *tw = tile + (js * PER) * kWave + lane;
 #pragma unroll
     for (int u = 0; u < PER; ++u) tw[u * kWave] = stage[u];
   }
-  __syncthreads();
+  if (!PREPPED) __syncthreads();
 #pragma unroll
   for (int u = 0; u < PER; ++u) {
     const int c = c_s[u]; // wave-uniform
@@ -1092,6 +1107,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   unsigned xcc;
   asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
   xcc &= 7u;
+  // (what the tile needs in LDS beside its rows is laid out while wave 0 waits)
+  class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, k.kr, lds);
   if (wave == 0) {
     int go = 1;
     if (f > 0) {
@@ -1149,8 +1166,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
   float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
   uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
-  class_tile<SP, NW, WITH_BP, NC, true>(k, qsrc, qdst, bp_l, Rc, cstart, Sc, pitch,
-                                        from_zero ? 0 : pitch, b, t * kWave, lds);
+  class_tile<SP, NW, WITH_BP, NC, true, NoHook, true>(k, qsrc, qdst, bp_l, Rc, cstart, Sc, pitch,
+                                                      from_zero ? 0 : pitch, b, t * kWave, lds);
   if (f + 1 < (int)gridDim.z && publish) {
     // the rows are in the XCD's L2 once the stores are acknowledged; then the flag
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
