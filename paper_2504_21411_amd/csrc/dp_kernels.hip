@@ -706,8 +706,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_wide(
 // strategies.  The class minima are formed by LDS float-minimum atomics (cmin[class][lane]),
 // then every wave keeps all of them in registers and takes every NW-th target class.
 //
-// Rows above E - min_s O[l][s] have no target within the budget and are neither computed
-// nor read by anyone.  Rows of Q[l] below the least memory of layers 0..l-1 are +inf by
+// Rows above E - topsum[l] (the least memory that layers l.. still need) cannot be completed
+// to a plan within the budget and are neither computed nor read by anyone.  Rows of Q[l] below the least memory of layers 0..l-1 are +inf by
 // definition; the tiles wholly below it are not stored, and every reader of a compact plane
 // (the next layer front, the final reductions, the backtrace, the export) applies that bound.
 // ---------------------------------------------------------------------------------------
@@ -814,7 +814,7 @@ static __device__ __forceinline__ void class_tile(
   const int(&o_s)[PER] = k.o_s;
   const int(&c_s)[PER] = k.c_s;
   const float(&t_s)[PER] = k.t_s;
-  if (tile_start > E - mo) return; // no target row within the budget (whole workgroup)
+  if (tile_start > E - mo) return; // no row here can reach a plan within the budget (whole workgroup)
 
   const int row = tile_start + lane;
   const size_t inst = (size_t)b * Sc * pitch;
