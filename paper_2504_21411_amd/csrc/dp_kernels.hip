@@ -19,6 +19,8 @@
 // written exactly once per launch and nothing stale survives from an earlier solve.
 #include "gsearch_internal.h"
 
+#include <type_traits>
+
 namespace gs {
 
 #define GS_INF __builtin_huge_valf()
@@ -796,12 +798,12 @@ static __device__ __forceinline__ void class_tile_prepare(const float *__restric
 }
 
 template <int SP, int NW, bool WITH_BP, int NC, bool COHERENT, typename Hook = NoHook,
-          bool PREPPED = false>
+          bool PREPPED = false, typename Hook2 = NoHook>
 static __device__ __forceinline__ void class_tile(
     const ClassScalars<SP / NW> &k, const float *__restrict__ qsrc, float *__restrict__ qdst,
     uint8_t *__restrict__ bp, const float *__restrict__ Rc, const int32_t *__restrict__ cstart,
     int Sc, int pitch, int src_pitch, int b, int tile_start, float *lds,
-    const Hook &after_loads = Hook()) {
+    const Hook &after_loads = Hook(), const Hook2 &minima_stored = Hook2()) {
   constexpr int PER = SP / NW; // source strategies per wave (a contiguous run)
   float *cmin = lds;                    // [NC][64]  class minima of the tile
   float *rc_lds = cmin + NC * kWave;    // [NC][NC]  this layer's class table
@@ -865,15 +867,16 @@ static __device__ __forceinline__ void class_tile(
 #pragma unroll
   for (int k = 0; k < NC; ++k) cmv[k] = cmin[k * kWave + lane];
 
-  for (int cj = js; cj < nc; cj += NW) {
+  // One target class: the minimum over the source classes (level 1: per chunk of eight classes,
+  // first chunk attaining the minimum), stored as Q[l][cj][row]; returns it and the chunk.
+  auto minimum_of = [&](int cj, float &m, int &g) {
     const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
     float16_t rv[NC / 16];
 #pragma unroll
     for (int x = 0; x < NC / 16; ++x) rv[x] = *reinterpret_cast<const float16_t *>(rc + 16 * x);
-    // level 1: minimum per chunk of eight classes, first chunk attaining the minimum
     // (chunk 0 always exists and starts the scan: "cm < +inf ? cm : +inf" is cm)
-    float m = GS_INF;
-    int g = 0;
+    m = GS_INF;
+    g = 0;
 #pragma unroll
     for (int q = 0; q < NC / 8; ++q) {
       if (8 * q < nc) {
@@ -892,59 +895,84 @@ static __device__ __forceinline__ void class_tile(
     }
     const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
     *reinterpret_cast<float *>(reinterpret_cast<char *>(qd) + (at << 2)) = m;
-    if (WITH_BP) {
-      // level 1b: first class of chunk g attaining it (operands re-read from LDS: g varies
-      // from lane to lane)
-      int ca = 8 * g;
-      {
-        const float *cg = cmin + (8 * g) * kWave + lane;
-        const float *rg = rc_lds + cj * NC + 8 * g;
-        const float4 ra = *reinterpret_cast<const float4 *>(rg);
-        const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
-        const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
-        int kk = 0;
+  };
+  // Its argmin, from the minimum m and the chunk g: stored as one backpointer per (target
+  // class, source row).
+  auto argmin_of = [&](int cj, float m, int g) {
+    // level 1b: first class of chunk g attaining it (operands re-read from LDS: g varies
+    // from lane to lane)
+    int ca = 8 * g;
+    {
+      const float *cg = cmin + (8 * g) * kWave + lane;
+      const float *rg = rc_lds + cj * NC + 8 * g;
+      const float4 ra = *reinterpret_cast<const float4 *>(rg);
+      const float4 rb = *reinterpret_cast<const float4 *>(rg + 4);
+      const float rr[8] = {ra.x, ra.y, ra.z, ra.w, rb.x, rb.y, rb.z, rb.w};
+      int kk = 0;
 #pragma unroll
-        for (int k = 7; k >= 0; --k) { // descending: the lowest matching class wins
-          const float v = cg[k * kWave] + rr[k];
-          kk = (v == m) ? k : kk;
-        }
-        ca += kk;
+      for (int k = 7; k >= 0; --k) { // descending: the lowest matching class wins
+        const float v = cg[k * kWave] + rr[k];
+        kk = (v == m) ? k : kk;
       }
-      // level 2: lowest member of class ca whose sum equals m (descending scan, last hit
-      // wins); several members can round to the same sum
-      int arg = 0;
-      const int lo = cs_lds[ca];
-      const float rr = rc_lds[cj * NC + ca];
-      // Four members per round so that their LDS reads are in flight together, highest
-      // first.  Past the end of a short class the scan looks at members of the following
-      // classes (or at the padding rows and the slack behind the tile); whatever those match
-      // is overwritten, because class ca attains m and its members come later in the scan.
-      // (a round that would start beyond the last strategy row is read from the last row on,
-      // so the four reads end in the three rows of slack behind the tile at the latest)
-      const int tl = lo * kWave + lane;
-      const int tl_max = (SP - 1) * kWave + lane;
-      int rel = 0;
-      if (maxlen <= 4) { // wave-uniform; the usual case: one round, constant member numbers
-        const float *tr = tile + (tl < tl_max ? tl : tl_max);
+      ca += kk;
+    }
+    // level 2: lowest member of class ca whose sum equals m (descending scan, last hit
+    // wins); several members can round to the same sum
+    const int lo = cs_lds[ca];
+    const float rr = rc_lds[cj * NC + ca];
+    // Four members per round so that their LDS reads are in flight together, highest
+    // first.  Past the end of a short class the scan looks at members of the following
+    // classes (or at the padding rows and the slack behind the tile); whatever those match
+    // is overwritten, because class ca attains m and its members come later in the scan.
+    // (a round that would start beyond the last strategy row is read from the last row on,
+    // so the four reads end in the three rows of slack behind the tile at the latest)
+    const int tl = lo * kWave + lane;
+    const int tl_max = (SP - 1) * kWave + lane;
+    int rel = 0;
+    if (maxlen <= 4) { // wave-uniform; the usual case: one round, constant member numbers
+      const float *tr = tile + (tl < tl_max ? tl : tl_max);
+      float tv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) tv[u] = tr[u * kWave];
+#pragma unroll
+      for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? u : rel;
+    } else {
+      for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
+        const int at0 = tl + d0 * kWave;
+        const float *tr = tile + (at0 < tl_max ? at0 : tl_max);
         float tv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) tv[u] = tr[u * kWave];
 #pragma unroll
-        for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? u : rel;
-      } else {
-        for (int d0 = ((maxlen + 3) & ~3) - 4; d0 >= 0; d0 -= 4) {
-          const int at0 = tl + d0 * kWave;
-          const float *tr = tile + (at0 < tl_max ? at0 : tl_max);
-          float tv[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) tv[u] = tr[u * kWave];
-#pragma unroll
-          for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? d0 + u : rel;
-        }
+        for (int u = 3; u >= 0; --u) rel = (tv[u] + rr == m) ? d0 + u : rel;
       }
-      arg = lo + rel;
-      bpb[at] = (uint8_t)arg;
     }
+    const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
+    bpb[at] = (uint8_t)(lo + rel);
+  };
+  constexpr bool kMinimaFirst = WITH_BP && !std::is_same<Hook2, NoHook>::value;
+  if constexpr (kMinimaFirst) {
+    // All minima first: once they are stored the next layer front can go ahead (the caller's
+    // `minima_stored` publishes that); the argmins, which only the backtrace reads, follow
+    // from the minimum and the chunk kept per target class.
+    constexpr int MAXIT = (NC + NW - 1) / NW;
+    float m_it[MAXIT];
+    int g_it[MAXIT];
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it)
+      if (js + it * NW < nc) minimum_of(js + it * NW, m_it[it], g_it[it]);
+    minima_stored();
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it)
+      if (js + it * NW < nc) argmin_of(js + it * NW, m_it[it], g_it[it]);
+  } else {
+    for (int cj = js; cj < nc; cj += NW) {
+      float m;
+      int g;
+      minimum_of(cj, m, g);
+      if (WITH_BP) argmin_of(cj, m, g);
+    }
+    minima_stored();
   }
 }
 
@@ -1166,16 +1194,23 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
   float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
   uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
+  // As soon as the tile's rows of Q[l] are stored (before its backpointers are worked out) the
+  // tiles of the next front that depend on it may go ahead.
+  const bool announce = f + 1 < (int)gridDim.z && publish;
+  auto publish_flag = [&]() {
+    if (announce) {
+      // the rows are in the XCD's L2 once the stores are acknowledged; then the flag
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (wave == 0)
+        __hip_atomic_store(&flags[((size_t)l * B + b) * tiles + t],
+                           epoch | (xcc << kFlagXcdShift), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+  };
   class_tile<SP, NW, WITH_BP, NC, true, NoHook, true>(k, qsrc, qdst, bp_l, Rc, cstart, Sc, pitch,
-                                                      from_zero ? 0 : pitch, b, t * kWave, lds);
-  if (f + 1 < (int)gridDim.z && publish) {
-    // the rows are in the XCD's L2 once the stores are acknowledged; then the flag
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (wave == 0)
-      __hip_atomic_store(&flags[((size_t)l * B + b) * tiles + t], epoch | (xcc << kFlagXcdShift),
-                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+                                                      from_zero ? 0 : pitch, b, t * kWave, lds,
+                                                      NoHook(), publish_flag);
 }
 
 __global__ __launch_bounds__(256) void k_zero_plane(float *__restrict__ q, size_t n) {
