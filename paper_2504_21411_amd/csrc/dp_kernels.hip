@@ -1056,8 +1056,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
 // +inf), so the workgroups with work come first in every front and the empty ones behind
 // them leave at once.
 //
-// Measured on MI355X, 64 fronts per launch: configs[1] 0.24 against 0.32 ms forward,
-// configs[3] 1.14 against 1.22 ms.  What a flag costs (store acknowledgement, barrier, flag
+// Measured on MI355X, 64 fronts per launch: configs[1] 0.20 against 0.32 ms forward,
+// configs[3] 1.04 against 1.22 ms.  What a flag costs (store acknowledgement, barrier, flag
 // store, the poll's round trip: four to five microseconds from a tile's last store to its
 // dependant's first load) is about what a launch boundary costs, so the gain comes from the
 // fronts overlapping, not from a shorter hand-over.  Forms that keep workgroups resident and
