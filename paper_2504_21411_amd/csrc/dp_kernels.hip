@@ -780,20 +780,21 @@ static __device__ __forceinline__ ClassScalars<SP / NW> class_scalars(
 template <int SP, int NW, bool WITH_BP, int NC>
 static __device__ __forceinline__ void class_tile_prepare(const float *__restrict__ Rc,
                                                           const int32_t *__restrict__ cstart,
-                                                          int kr, float *lds) {
+                                                          int kr, float *lds, int tid,
+                                                          int nthreads) {
+  // (tid, nthreads: the threads that share this work, numbered from 0)
   float *cmin = lds;
   float *rc_lds = cmin + NC * kWave;
   int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC);
   const float4 inf4 = {GS_INF, GS_INF, GS_INF, GS_INF};
-  for (int x = threadIdx.x; x < NC * kWave / 4; x += NW * kWave)
-    reinterpret_cast<float4 *>(cmin)[x] = inf4;
+  for (int x = tid; x < NC * kWave / 4; x += nthreads) reinterpret_cast<float4 *>(cmin)[x] = inf4;
   if (WITH_BP) {
     // (the per-lane gathers of the argmin levels read the class table and the run table
     // from LDS; the min-only pass takes both as scalar operands only)
     const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
-    for (int x = threadIdx.x; x < NC * NC / 4; x += NW * kWave)
+    for (int x = tid; x < NC * NC / 4; x += nthreads)
       reinterpret_cast<float4 *>(rc_lds)[x] = reinterpret_cast<const float4 *>(rck)[x];
-    if (threadIdx.x <= NC) cs_lds[threadIdx.x] = cstart[threadIdx.x];
+    for (int x = tid; x <= NC; x += nthreads) cs_lds[x] = cstart[x];
   }
 }
 
@@ -847,7 +848,8 @@ static __device__ __forceinline__ void class_tile(
                               : *at) + t_s[u];
     stage[u] = t >= cb + lowq4 ? v : GS_INF; // source row >= lowq (and >= 0), row within budget
   }
-  if (!PREPPED) class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, kr, lds);
+  if (!PREPPED)
+    class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, kr, lds, (int)threadIdx.x, NW * kWave);
   if (WITH_BP) {
     float *tw = tile + (js * PER) * kWave + lane;
 #pragma unroll
@@ -1135,8 +1137,16 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   unsigned xcc;
   asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
   xcc &= 7u;
-  // (what the tile needs in LDS beside its rows is laid out while wave 0 waits)
-  class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, k.kr, lds);
+  // (what the tile needs in LDS beside its rows is laid out while wave 0 waits; with eight
+  // waves the other seven do it and wave 0 polls at once, with four it takes its share first:
+  // measured both ways)
+  if constexpr (NW >= 8) {
+    if (wave != 0)
+      class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, k.kr, lds, (int)threadIdx.x - kWave,
+                                              (NW - 1) * kWave);
+  } else {
+    class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, k.kr, lds, (int)threadIdx.x, NW * kWave);
+  }
   if (wave == 0) {
     int go = 1;
     if (f > 0) {
