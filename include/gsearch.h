@@ -101,7 +101,8 @@ typedef enum {
                                         infeasible) */
 
 #define GSEARCH_MAX_CLASSES 64 /* transition classes a solve can exploit (see r_class) */
-#define GSEARCH_DEFAULT_CLASSES 32 /* ... unless r_class_bound announces more */
+#define GSEARCH_DEFAULT_CLASSES 32 /* ... unless r_class_bound announces more (a bound of 16 or
+                                      less selects a leaner form of the same kernel) */
 
 #define GSEARCH_MAX_S 1024 /* strategies per layer (bp is uint8 up to 256, uint16 above) */
 

@@ -1598,6 +1598,7 @@ static void launch_class_nw(const Shape &s, const Workspace &w, int l, const flo
   if constexpr (SP >= 48) {
     if (s.NC > 32) return launch_class_nc<SP, NW, 64>(s, w, l, src, dst, bp_l, st);
   }
+  if (s.NC <= 16) return launch_class_nc<SP, NW, 16>(s, w, l, src, dst, bp_l, st);
   launch_class_nc<SP, NW, 32>(s, w, l, src, dst, bp_l, st);
 }
 
@@ -1709,6 +1710,7 @@ static void launch_fronts_nw(const Shape &s, const Workspace &w, bool keep, bool
   if constexpr (SP >= 48) {
     if (s.NC > 32) return launch_fronts_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, fronts, st);
   }
+  if (s.NC <= 16) return launch_fronts_nc<SP, NW, 16>(s, w, keep, with_bp, pe, bpl, fronts, st);
   launch_fronts_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, fronts, st);
 }
 

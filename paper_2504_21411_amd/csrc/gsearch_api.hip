@@ -280,8 +280,11 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   gs::Shape s = make_shape(p->B, p->L, p->S, p->M, p->K);
   s.tune = ctx->tune;
   s.grants = &ctx->grants;
-  // class capacity of this solve: the wide form only when the caller announces it
+  // class capacity of this solve: the wide form only when the caller announces it, the
+  // narrow one (half the LDS and registers for the class minima, so more workgroups per
+  // compute unit) when it announces sixteen classes at most
   if (p->r_class && p->r_class_bound > 32 && p->S > 32) s.NC = gs::kMaxClasses;
+  else if (p->r_class && p->r_class_bound >= 1 && p->r_class_bound <= 16) s.NC = 16;
   const Layout y = make_layout(s, c.flags);
   const size_t zb = zero_row_bytes(c.max_M);
   if (y.total > ctx->bytes - zb - front_flag_bytes(&c)) return GSEARCH_ERR_CAPACITY;
