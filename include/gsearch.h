@@ -242,6 +242,10 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
  * host only, needs no GPU).  Errors: INVALID_ARG (null context, unknown name, value outside
  * [-1, 64], null output). */
 const char *gsearch_knob_name(int index);
+/* The value a context created now would start the knob with: its default, or what the
+ * environment variable GSEARCH_<NAME IN CAPITALS> says (a decimal integer in [-1, 64]; anything
+ * else is ignored).  Host only, needs no GPU.  Errors: INVALID_ARG (unknown name, null output). */
+int gsearch_knob_initial(const char *name, int *value);
 int gsearch_set_knob(gsearch_ctx *ctx, const char *name, int value);
 int gsearch_get_knob(gsearch_ctx *ctx, const char *name, int *value);
 

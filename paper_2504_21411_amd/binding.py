@@ -49,7 +49,7 @@ EXPORTS = [
     "gsearch_pipeline_reduce", "gsearch_build_tables_profiled", "gsearch_set_instance_groups",
     "gsearch_instance_groups", "gsearch_layout_classes", "gsearch_solve_batch_noalloc",
     "gsearch_knob_name", "gsearch_set_knob", "gsearch_get_knob", "gsearch_lds_calibration",
-    "gsearch_set_solve_counter",
+    "gsearch_set_solve_counter", "gsearch_knob_initial",
 ]
 
 
@@ -133,6 +133,8 @@ def load_library() -> ctypes.CDLL:
     lib.gsearch_knob_name.argtypes = [ctypes.c_int]
     lib.gsearch_set_solve_counter.restype = ctypes.c_int
     lib.gsearch_set_solve_counter.argtypes = [vp, ctypes.c_uint32, vp]
+    lib.gsearch_knob_initial.restype = ctypes.c_int
+    lib.gsearch_knob_initial.argtypes = [ctypes.c_char_p, ctypes.POINTER(ctypes.c_int)]
     lib.gsearch_set_knob.restype = ctypes.c_int
     lib.gsearch_set_knob.argtypes = [vp, ctypes.c_char_p, ctypes.c_int]
     lib.gsearch_get_knob.restype = ctypes.c_int
@@ -204,6 +206,14 @@ def gsearch_lds_calibration(mode: int, iters: int, device="cuda", stream=None) -
     _check(load_library().gsearch_lds_calibration(int(mode), int(iters), _ptr(sink),
                                                   _stream(stream)), "gsearch_lds_calibration")
     return 1024 * 256 * int(iters) * (16 if mode == 1 else 4)
+
+
+def gsearch_knob_initial(name: str) -> int:
+    """Value a new context would start the knob with (default or GSEARCH_<NAME>); host only."""
+    v = ctypes.c_int(0)
+    _check(load_library().gsearch_knob_initial(name.encode(), ctypes.byref(v)),
+           "gsearch_knob_initial")
+    return int(v.value)
 
 
 def gsearch_knob_names() -> list:

@@ -669,6 +669,14 @@ const char *gsearch_knob_name(int index) {
   return (index >= 0 && index < kKnobCount) ? kKnobs[index].name : nullptr;
 }
 
+int gsearch_knob_initial(const char *name, int *value) {
+  const int i = knob_index(name);
+  if (i < 0 || !value) return GSEARCH_ERR_INVALID_ARG;
+  const gs::Tuning t = tuning_from_env();
+  *value = t.*(kKnobs[i].field);
+  return GSEARCH_OK;
+}
+
 int gsearch_set_knob(gsearch_ctx *ctx, const char *name, int value) {
   const int i = knob_index(name);
   if (!ctx || i < 0 || value < -1 || value > 64) return GSEARCH_ERR_INVALID_ARG;

@@ -112,6 +112,31 @@ def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
     v = ctypes.c_int(0)
     assert lib.gsearch_get_knob(None, b"fronts", ctypes.byref(v)) == b.GSEARCH_ERR_INVALID_ARG
     assert lib.gsearch_set_solve_counter(None, 5, None) == b.GSEARCH_ERR_INVALID_ARG
+
+
+def test_knobs_take_their_initial_values_from_the_environment(lib, monkeypatch):
+    """GSEARCH_<NAME> is read when a context is created and nowhere else; what a new context
+    would start with can be asked without a GPU.  Numbers in [-1, 64] count, anything else is
+    ignored."""
+    from paper_2504_21411_amd import binding as b
+    for name in b.gsearch_knob_names():
+        monkeypatch.delenv("GSEARCH_" + name.upper(), raising=False)
+    defaults = {name: b.gsearch_knob_initial(name) for name in b.gsearch_knob_names()}
+    assert defaults["fronts"] == -1 and defaults["small"] == -1 and defaults["jsplit"] == 0
+    assert defaults["spin_limit"] == 0 and defaults["hold_flags"] == 0
+    monkeypatch.setenv("GSEARCH_FRONTS", "5")
+    monkeypatch.setenv("GSEARCH_JSPLIT", "8")
+    monkeypatch.setenv("GSEARCH_STREAMS", "-1")
+    assert b.gsearch_knob_initial("fronts") == 5 and b.gsearch_knob_initial("jsplit") == 8
+    assert b.gsearch_knob_initial("streams") == -1
+    for bad in ("65", "-2", "4x", "", " 3", "1e1", "0x10"):
+        monkeypatch.setenv("GSEARCH_FRONTS", bad)
+        assert b.gsearch_knob_initial("fronts") == defaults["fronts"], bad
+    monkeypatch.setenv("GSEARCH_FRONTS", "0")
+    assert b.gsearch_knob_initial("fronts") == 0
+    assert b.gsearch_knob_initial("kernel") == defaults["kernel"]      # others untouched
+    with pytest.raises(b.GSearchError):
+        b.gsearch_knob_initial("no_such_knob")
     # the entry point on the fixed array checks its arguments before it touches a device
     assert lib.gsearch_solve_batch_noalloc(0, None, None, None, None, None, None) == \
         b.GSEARCH_ERR_INVALID_ARG
