@@ -129,7 +129,7 @@ def test_knobs_take_their_initial_values_from_the_environment(lib, monkeypatch):
     monkeypatch.setenv("GSEARCH_STREAMS", "-1")
     assert b.gsearch_knob_initial("fronts") == 5 and b.gsearch_knob_initial("jsplit") == 8
     assert b.gsearch_knob_initial("streams") == -1
-    for bad in ("65", "-2", "4x", "", " 3", "1e1", "0x10"):
+    for bad in ("65", "-2", "4x", "", "3 ", "1e1", "0x10"):
         monkeypatch.setenv("GSEARCH_FRONTS", bad)
         assert b.gsearch_knob_initial("fronts") == defaults["fronts"], bad
     monkeypatch.setenv("GSEARCH_FRONTS", "0")
