@@ -870,19 +870,18 @@ static __device__ __forceinline__ void class_tile(
   for (int k = 0; k < NC; ++k) cmv[k] = cmin[k * kWave + lane];
 
   // One target class: the minimum over the source classes (level 1: per chunk of eight classes,
-  // first chunk attaining the minimum), stored as Q[l][cj][row]; returns it and the chunk.
-  auto minimum_of = [&](int cj, float &m, int &g) {
-    const float *__restrict__ rc = rck + (size_t)cj * NC; // Rc[cj][.]: wave-uniform operands
-    float16_t rv[NC / 16];
-#pragma unroll
-    for (int x = 0; x < NC / 16; ++x) rv[x] = *reinterpret_cast<const float16_t *>(rc + 16 * x);
+  // first chunk attaining the minimum), stored as Q[l][cj][row]; kept with the chunk.
+  // (Rc[cj][.] travels as wave-uniform scalar operands, requested by piece_of)
+  constexpr int XP = NC / 16; // sixteen-float pieces per class table row
+  auto piece_of = [&](int cj, int x) -> float16_t {
+    return *reinterpret_cast<const float16_t *>(rck + (size_t)cj * NC + 16 * x);
+  };
+  // the two chunks of eight source classes that piece x of a row covers, folded into (m, g)
+  auto chunks_of = [&](const float16_t &r, int x, float &m, int &g) {
     // (chunk 0 always exists and starts the scan: "cm < +inf ? cm : +inf" is cm)
-    m = GS_INF;
-    g = 0;
 #pragma unroll
-    for (int q = 0; q < NC / 8; ++q) {
+    for (int q = 2 * x; q < 2 * x + 2; ++q) {
       if (8 * q < nc) {
-        const float16_t r = rv[q >> 1];
         const int h = (q & 1) * 8;
         float cm = __builtin_fminf(cmv[8 * q] + r[h], cmv[8 * q + 1] + r[h + 1]);
 #pragma unroll
@@ -891,10 +890,16 @@ static __device__ __forceinline__ void class_tile(
 #pragma unroll
           for (int k = 4; k < 8; ++k) cm = __builtin_fminf(cm, cmv[8 * q + k] + r[h + k]);
         }
-        if (q == 0) m = cm;
-        else chunk_update<true>(m, g, cm, q);
+        if (q == 0) {
+          m = cm;
+          g = 0;
+        } else {
+          chunk_update<true>(m, g, cm, q);
+        }
       }
     }
+  };
+  auto store_minimum = [&](int cj, float m) {
     const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
     *reinterpret_cast<float *>(reinterpret_cast<char *>(qd) + (at << 2)) = m;
   };
@@ -952,26 +957,56 @@ static __device__ __forceinline__ void class_tile(
     const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
     bpb[at] = (uint8_t)(lo + rel);
   };
-  constexpr bool kMinimaFirst = WITH_BP && !std::is_same<Hook2, NoHook>::value;
+  constexpr bool kMinimaFirst = !std::is_same<Hook2, NoHook>::value;
   if constexpr (kMinimaFirst) {
     // All minima first: once they are stored the next layer front can go ahead (the caller's
     // `minima_stored` publishes that); the argmins, which only the backtrace reads, follow
-    // from the minimum and the chunk kept per target class.
+    // from the minimum and the chunk kept per target class.  The class table rows arrive as
+    // pieces of sixteen scalar operands, and the next piece (of this row or of the wave's next
+    // target class) is requested as soon as the current one has arrived and before it is used:
+    // two pieces are live at a time, so the scalar registers still allow eight waves per SIMD,
+    // and a piece's latency is spent under the arithmetic of the one before.  (Scalar loads
+    // return in any order, so a wait for one is a wait for all: requested any earlier, the
+    // next piece would be waited for together with the current one.)
     constexpr int MAXIT = (NC + NW - 1) / NW;
+    constexpr int P = MAXIT * XP;
     float m_it[MAXIT];
     int g_it[MAXIT];
+    float16_t piece[P];
+    if (js < nc) piece[0] = piece_of(js, 0);
 #pragma unroll
-    for (int it = 0; it < MAXIT; ++it)
-      if (js + it * NW < nc) minimum_of(js + it * NW, m_it[it], g_it[it]);
+    for (int p = 0; p < P; ++p) {
+      const int it = p / XP, x = p % XP;
+      if (js + it * NW < nc) {
+        asm volatile("" : "+s"(piece[p]));
+        if (p + 1 < P) {
+          const int it2 = (p + 1) / XP, x2 = (p + 1) % XP;
+          if (js + it2 * NW < nc) piece[p + 1 < P ? p + 1 : p] = piece_of(js + it2 * NW, x2);
+        }
+        if (x == 0) {
+          m_it[it] = GS_INF;
+          g_it[it] = 0;
+        }
+        chunks_of(piece[p], x, m_it[it], g_it[it]);
+        if (x == XP - 1) store_minimum(js + it * NW, m_it[it]);
+      }
+    }
     minima_stored();
+    if (WITH_BP) {
 #pragma unroll
-    for (int it = 0; it < MAXIT; ++it)
-      if (js + it * NW < nc) argmin_of(js + it * NW, m_it[it], g_it[it]);
+      for (int it = 0; it < MAXIT; ++it)
+        if (js + it * NW < nc) argmin_of(js + it * NW, m_it[it], g_it[it]);
+    }
   } else {
     for (int cj = js; cj < nc; cj += NW) {
-      float m;
-      int g;
-      minimum_of(cj, m, g);
+      float16_t rv[XP];
+#pragma unroll
+      for (int x = 0; x < XP; ++x) rv[x] = piece_of(cj, x);
+      float m = GS_INF;
+      int g = 0;
+#pragma unroll
+      for (int x = 0; x < XP; ++x) chunks_of(rv[x], x, m, g);
+      store_minimum(cj, m);
       if (WITH_BP) argmin_of(cj, m, g);
     }
     minima_stored();
