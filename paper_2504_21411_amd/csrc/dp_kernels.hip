@@ -730,9 +730,9 @@ template <int PER>
 struct ClassScalars {
   int E, low, lowq, mo, kr, nc, maxlen;
   int o_s[PER], c_s[PER];
-  float t_s[PER];
+  float t_s[PER]; // in vector registers where VEC_T says so (every lane holds the same value)
 };
-template <int SP, int NW>
+template <int SP, int NW, bool VEC_T = false>
 static __device__ __forceinline__ ClassScalars<SP / NW> class_scalars(
     const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
     const int32_t *__restrict__ cmeta, const int32_t *__restrict__ cls,
@@ -755,11 +755,16 @@ static __device__ __forceinline__ ClassScalars<SP / NW> class_scalars(
   {
     const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
     const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
+    // VEC_T: the T entries come through vector loads of one address per load (the index passes
+    // through an empty asm as a vector value), so that they take vector registers, of which
+    // the kernel has some to spare, and leave twelve scalar ones to the caller.
+    int first = js * PER;
+    if (VEC_T) asm volatile("" : "+v"(first));
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
       k.o_s[u] = oprev[js * PER + u];
       k.c_s[u] = cls[js * PER + u];
-      k.t_s[u] = tprev[js * PER + u];
+      k.t_s[u] = tprev[(VEC_T ? first : js * PER) + u];
     }
   }
   asm volatile(""
@@ -769,7 +774,10 @@ static __device__ __forceinline__ ClassScalars<SP / NW> class_scalars(
   // compiler places the loads where the values are used)
   if constexpr (PER <= 16) {
 #pragma unroll
-    for (int u = 0; u < PER; ++u) asm volatile("" : "+s"(k.o_s[u]), "+s"(k.c_s[u]), "+s"(k.t_s[u]));
+    for (int u = 0; u < PER; ++u) {
+      asm volatile("" : "+s"(k.o_s[u]), "+s"(k.c_s[u]));
+      if (!VEC_T) asm volatile("" : "+s"(k.t_s[u]));
+    }
   }
   return k;
 }
@@ -1148,7 +1156,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
     const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
     unsigned *__restrict__ flags, unsigned *__restrict__ stop,
     const unsigned *__restrict__ epoch_word, int32_t *__restrict__ status, int B, int L, int Sc,
-    int pitch, int tiles, int l0, int spin_max, int publish) {
+    int pitch, int tiles, int l0, int spin_max, int publish, int ring) {
   // (the dynamic part follows the static one: keep it 16-byte aligned for its float4 accesses)
   extern __shared__ __align__(16) float lds[];
   __shared__ __align__(16) int s_go4[4];
@@ -1161,7 +1169,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   const unsigned epoch = epoch_word[0]; // number of this solve (the prepare step advanced it)
   // the tile's table entries travel while wave 0 waits for the tiles below
   const ClassScalars<SP / NW> k =
-      class_scalars<SP, NW>(Tq, Oq, cmeta, cls, ridx, budget, topsum, lowsum, L, l, b);
+      class_scalars<SP, NW, ((WITH_BP || SP / NW > 12) && SP / NW <= 16)>(Tq, Oq, cmeta, cls, ridx,
+                                                                       budget, topsum, lowsum, L, l, b);
   const int E = k.E;
   const int a = k.low >> 6;                    // first tile with work
   const int top = E - k.mo;                    // last source row with work
@@ -1185,27 +1194,38 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   if (wave == 0) {
     int go = 1;
     if (f > 0) {
-      // tiles of layer l-1 this one reads (rows r - O[l-1][s]) and, with two planes taking
-      // turns, those that still read the rows of Q[l-2] it overwrites
+      // Tiles of front l-1 that this one reads (rows r - O[l-1][s]), up to its own index.
+      // And with `ring` planes taking turns it overwrites rows of Q[l-ring], which the tiles
+      // above it of front l-ring+1 may still be reading (up to the largest shift O[l-ring][s]
+      // that fits): it waits for those as well, unless that front belongs to an earlier
+      // launch.  With four planes that front is three behind and long done; with two it is
+      // the front before, whose upper tiles start late.
       const int top1 = E - topsum[bl - 1];
       const int a1 = lowsum[bl - 2] >> 6;
       const int z1 = top1 >= 0 ? top1 >> 6 : -1;
       int lo = kWave * t - maxfit[bl - 1];
       lo = lo > 0 ? lo >> 6 : 0;
       lo = lo > a1 ? lo : a1;
-      int hi = t;
-      if (!keep && l >= 3) {
-        const int war = (kWave * t + 63 + maxfit[bl - 2]) >> 6;
-        hi = war > hi ? war : hi;
+      const int hi1 = t < z1 ? t : z1;
+      int hiw = -1;
+      const int lw = l - ring + 1; // the front that reads the plane this one overwrites
+      if (!keep && lw >= 2 && f >= ring - 1) {
+        const int war = (kWave * t + 63 + maxfit[bl - ring]) >> 6;
+        const int topw = E - topsum[bl - ring + 1];
+        const int zw = topw >= 0 ? topw >> 6 : -1;
+        hiw = war < zw ? war : zw;
       }
-      hi = hi < z1 ? hi : z1;
-      const unsigned *__restrict__ fl = flags + ((size_t)(l - 1) * B + b) * tiles;
+      const int hi = hi1 > hiw ? hi1 : hiw;
+      // (flag words are counted in 32 bits: there are fewer than 2^26 of them)
+      const int row1 = ((l - 1) * B + b) * tiles, roww = (lw * B + b) * tiles;
       int spins = 0;
       for (int base = lo; base <= hi && go; base += kWave) {
         for (;;) {
           const int at = base + lane;
           unsigned fv = epoch | (xcc << kFlagXcdShift);
-          if (at <= hi) fv = __hip_atomic_load(&fl[at], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int word = at <= hi1 ? row1 + at : (at > t && at <= hiw ? roww + at : -1);
+          if (word >= 0)
+            fv = __hip_atomic_load(&flags[word], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           if (__builtin_amdgcn_ballot_w64((fv & kFlagEpochMask) != epoch) == 0) {
             // all there: were they written on this XCD (else its L2 may not hold the rows)?
             if (__builtin_amdgcn_ballot_w64((fv >> kFlagXcdShift) != xcc) != 0) {
@@ -1234,7 +1254,7 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   }
   __syncthreads();
   if (wave_uniform(s_go) == 0) return;
-  const int srci = keep ? l - 1 : ((l - 1) & 1), dsti = keep ? l : (l & 1);
+  const int srci = keep ? l - 1 : ((l - 1) & (ring - 1)), dsti = keep ? l : (l & (ring - 1));
   const bool from_zero = !keep && l == 1; // Q[0] = 0 is one shared row of zeros
   const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
   float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
@@ -1699,7 +1719,7 @@ bool fronts_shape_ok(const Shape &s) {
 
 template <int SP, int NW, int NC>
 static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                             size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
+                             size_t plane_elems_all, size_t bp_layer_bytes, int fronts, int ring,
                              hipStream_t st) {
   const int tiles = (s.M + kWave) / kWave;
   const size_t lds =
@@ -1728,30 +1748,30 @@ static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool
                          bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
                          w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
                          w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0, spin_max,
-                         s.tune.hold_flags == 1 ? 0 : 1);
+                         s.tune.hold_flags == 1 ? 0 : 1, ring);
     else
       hipLaunchKernelGGL((k_dp_class_fronts<SP, NW, false, NC>), grid, block, lds, st, w.planes,
                          plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
                          bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
                          w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
                          w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0, spin_max,
-                         s.tune.hold_flags == 1 ? 0 : 1);
+                         s.tune.hold_flags == 1 ? 0 : 1, ring);
   }
 }
 
 template <int SP, int NW>
 static void launch_fronts_nw(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                             size_t pe, size_t bpl, int fronts, hipStream_t st) {
+                             size_t pe, size_t bpl, int fronts, int ring, hipStream_t st) {
   if constexpr (SP >= 48) {
-    if (s.NC > 32) return launch_fronts_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, fronts, st);
+    if (s.NC > 32) return launch_fronts_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
   }
-  if (s.NC <= 16) return launch_fronts_nc<SP, NW, 16>(s, w, keep, with_bp, pe, bpl, fronts, st);
-  launch_fronts_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, fronts, st);
+  if (s.NC <= 16) return launch_fronts_nc<SP, NW, 16>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
+  launch_fronts_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
 }
 
 template <int SP>
 static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp, size_t pe,
-                          size_t bpl, int fronts, hipStream_t st) {
+                          size_t bpl, int fronts, int ring, hipStream_t st) {
   // waves per tile as in the per-launch form, without its one- and two-wave forms
   int waves = s.tune.jsplit;
   if (waves < 1 || waves > 8) {
@@ -1759,10 +1779,10 @@ static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool wi
     else waves = SP >= 96 ? 8 : 4;
   }
   if constexpr (SP > 128) {
-    launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, st);
+    launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
   } else {
-    if (waves >= 8) launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, st);
-    else launch_fronts_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, fronts, st);
+    if (waves >= 8) launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
+    else launch_fronts_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
   }
 }
 
@@ -1771,17 +1791,17 @@ static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool wi
 // backpointer bytes per layer.
 const char *launch_dp_class_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp,
                                    size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
-                                   hipStream_t st) {
+                                   int ring, hipStream_t st) {
   switch (s.SP) {
-    case 16: launch_fronts<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 24: launch_fronts<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 32: launch_fronts<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 48: launch_fronts<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 64: launch_fronts<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 96: launch_fronts<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 128: launch_fronts<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 192: launch_fronts<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
-    case 256: launch_fronts<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, st); break;
+    case 16: launch_fronts<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 24: launch_fronts<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 32: launch_fronts<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 48: launch_fronts<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 64: launch_fronts<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 96: launch_fronts<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 128: launch_fronts<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 192: launch_fronts<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 256: launch_fronts<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
     default: break; // class_path_applies() admits no other pitch
   }
   return "k_dp_class_fronts";

@@ -25,7 +25,7 @@ const KnobDesc kKnobs[] = {
     {"jsplit", &gs::Tuning::jsplit},   {"waves_per_block", &gs::Tuning::waves_per_block},
     {"row_groups", &gs::Tuning::row_groups}, {"streams", &gs::Tuning::streams},
     {"fronts", &gs::Tuning::fronts},   {"spin_limit", &gs::Tuning::spin_limit},
-    {"hold_flags", &gs::Tuning::hold_flags},
+    {"hold_flags", &gs::Tuning::hold_flags}, {"front_tiles", &gs::Tuning::front_tiles},
 };
 constexpr int kKnobCount = (int)(sizeof(kKnobs) / sizeof(kKnobs[0]));
 
@@ -78,7 +78,10 @@ bool keeps_all_planes(uint32_t flags) {
   return (flags & (GSEARCH_FLAG_KEEP_PLANES | GSEARCH_FLAG_NO_BACKPOINTERS)) != 0;
 }
 
-Layout make_layout(const gs::Shape &s, uint32_t flags) {
+// ring: the several-fronts form of the class kernel may run, which rotates kFrontRing plane
+// slots instead of two (the other kernels use the first two).
+constexpr int kFrontRing = 4;
+Layout make_layout(const gs::Shape &s, uint32_t flags, bool ring) {
   Layout y;
   size_t off = 0;
   auto take = [&off](size_t bytes) {
@@ -86,7 +89,8 @@ Layout make_layout(const gs::Shape &s, uint32_t flags) {
     off = align_up(off + bytes, 256);
     return at;
   };
-  y.nplanes = keeps_all_planes(flags) ? s.L : (s.L < 2 ? s.L : 2);
+  const int slots = ring ? kFrontRing : 2;
+  y.nplanes = keeps_all_planes(flags) ? s.L : (s.L < slots ? s.L : slots);
   // The class kernel keeps compact planes (one row per class) at the head of the slots.
   // Behind the last slot, slack of one padded instance row block: the tile kernel reads
   // (and discards) the strategy rows S..SP-1 of an instance without clamping the address.
@@ -285,7 +289,7 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
   // compute unit) when it announces sixteen classes at most
   if (p->r_class && p->r_class_bound > 32 && p->S > 32) s.NC = gs::kMaxClasses;
   else if (p->r_class && p->r_class_bound >= 1 && p->r_class_bound <= 16) s.NC = 16;
-  const Layout y = make_layout(s, c.flags);
+  const Layout y = make_layout(s, c.flags, ctx->fronts_ok);
   const size_t zb = zero_row_bytes(c.max_M);
   if (y.total > ctx->bytes - zb - front_flag_bytes(&c)) return GSEARCH_ERR_CAPACITY;
   gs::Workspace w;
@@ -368,10 +372,12 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
     // several layer fronts per launch, the instances bound to XCDs (see k_dp_class_fronts)
     if (keep) gs::launch_class_zero(s, w.planes, st);
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
+    // (a power of two; not used when the planes are kept)
+    const int ring = y.nplanes < kFrontRing ? 2 : kFrontRing;
     ctx->forward_kernel = gs::launch_dp_class_fronts(s, w, keep, with_bp, pe, bp_layer_bytes,
-                                                     fronts_per_launch(ctx, s), st);
+                                                     fronts_per_launch(ctx, s), ring, st);
     ctx->groups_used = 1;
-    cur = keep ? s.L - 1 : ((s.L - 1) & 1);
+    cur = keep ? s.L - 1 : ((s.L - 1) & (ring - 1));
   } else {
     // Q[0] = 0: stored only when the planes are kept (the readers of kept planes read it);
     // otherwise the first front reads the context's row of zeros for every class
@@ -503,7 +509,7 @@ const char *gsearch_strerror(int status) {
 size_t gsearch_workspace_bytes(const gsearch_config *cfg) {
   if (!config_ok(cfg)) return 0;
   return make_layout(make_shape(cfg->max_B, cfg->max_L, cfg->max_S, cfg->max_M, cfg->max_K),
-                     cfg->flags)
+                     cfg->flags, front_flag_bytes(cfg) > 0)
              .total +
          front_flag_bytes(cfg) + zero_row_bytes(cfg->max_M);
 }

@@ -25,6 +25,8 @@ struct Tuning {
   int streams = 0;         // instance groups on parallel streams
   int fronts = -1;         // class kernel: layer fronts per launch, 2..64 (0, 1: one launch per
                            // front; -1: 64 wherever that form can run)
+  int front_tiles = 0;     // that form: workgroups per instance and front that take one tile
+                           // each, in eights (0: 128); the tiles beyond them go 32 to a workgroup
   int spin_limit = 0;      // that form: polls before a wait gives up (0: the default, 2^18)
   int hold_flags = 0;      // that form, tests only: 1 = finished tiles publish no flags, so that
                            // every wait runs into its limit (the error path, with no fault)
@@ -127,9 +129,10 @@ const char *launch_dp_class(const Shape &s, const Workspace &w, int l, const flo
 void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
 // The forward pass of the class kernel with `fronts` layer fronts per launch, the tiles of a
 // launch waiting for each other through flags (batch a multiple of 8, 3 layers or more).
+// Unless the planes are kept, Q[l] goes to plane slot l % ring (ring = 2 or 4 slots are there).
 const char *launch_dp_class_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp,
                                    size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
-                                   hipStream_t st);
+                                   int ring, hipStream_t st);
 bool fronts_shape_ok(const Shape &s);              // that form can take this shape
 // out[i] = id of the XCD that workgroup i of a grid of kXccProbeGrid workgroups ran on
 constexpr int kXccProbeGrid = 512;
