@@ -25,7 +25,7 @@ const KnobDesc kKnobs[] = {
     {"jsplit", &gs::Tuning::jsplit},   {"waves_per_block", &gs::Tuning::waves_per_block},
     {"row_groups", &gs::Tuning::row_groups}, {"streams", &gs::Tuning::streams},
     {"fronts", &gs::Tuning::fronts},   {"spin_limit", &gs::Tuning::spin_limit},
-    {"hold_flags", &gs::Tuning::hold_flags}, {"front_tiles", &gs::Tuning::front_tiles},
+    {"hold_flags", &gs::Tuning::hold_flags},
 };
 constexpr int kKnobCount = (int)(sizeof(kKnobs) / sizeof(kKnobs[0]));
 

@@ -25,8 +25,6 @@ struct Tuning {
   int streams = 0;         // instance groups on parallel streams
   int fronts = -1;         // class kernel: layer fronts per launch, 2..64 (0, 1: one launch per
                            // front; -1: 64 wherever that form can run)
-  int front_tiles = 0;     // that form: workgroups per instance and front that take one tile
-                           // each, in eights (0: 128); the tiles beyond them go 32 to a workgroup
   int spin_limit = 0;      // that form: polls before a wait gives up (0: the default, 2^18)
   int hold_flags = 0;      // that form, tests only: 1 = finished tiles publish no flags, so that
                            // every wait runs into its limit (the error path, with no fault)
