@@ -1059,6 +1059,77 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class(
                                          tile_start, lds);
 }
 
+// One tile of a front the plain way: the same results as class_tile (the same single
+// additions, minima and first-index rules), with every table entry read through vector loads
+// and all loops rolled, so that it needs few registers of either kind.  For the workgroups of
+// k_dp_class_fronts that take the tiles behind the first y0 of a front: there it runs in a
+// loop, where class_tile's scalar operands would have to be held or fetched again per tile,
+// and that loop must not cost the straight-line path registers.  Many times slower per tile.
+// Expects what class_tile_prepare lays out (and a barrier after it); ends with the rows of
+// Q[l] and the backpointers stored, before any flag.
+template <int SP, int NW, bool WITH_BP, int NC>
+static __device__ __forceinline__ void class_tile_plain(
+    const float *__restrict__ qsrc, float *__restrict__ qdst, uint8_t *__restrict__ bp,
+    const float *__restrict__ Tq, const int32_t *__restrict__ Oq,
+    const int32_t *__restrict__ cls, const float *__restrict__ Rc, int bl, int kr, int nc, int E,
+    int lowq, int Sc, int pitch, int src_pitch, int b, int tile_start, float *lds) {
+  float *cmin = lds;
+  float *rc_lds = cmin + NC * kWave;
+  int *cs_lds = reinterpret_cast<int *>(rc_lds + NC * NC);
+  float *tile = reinterpret_cast<float *>(cs_lds + NC + 32);
+  const int wave = (int)threadIdx.x >> 6, lane = (int)threadIdx.x & 63;
+  const int row = tile_start + lane;
+  const size_t inst = (size_t)b * Sc * pitch;
+  const float *__restrict__ qs = src_pitch ? qsrc + inst : qsrc;
+  float *__restrict__ qd = qdst + inst;
+  uint8_t *__restrict__ bpb = WITH_BP ? bp + (size_t)b * NC * pitch : nullptr;
+  const float *__restrict__ tprev = Tq + (size_t)(bl - 1) * SP;
+  const int32_t *__restrict__ oprev = Oq + (size_t)(bl - 1) * SP;
+#pragma unroll 1
+  for (int sidx = wave; sidx < SP; sidx += NW) {
+    const int o = oprev[sidx], c = cls[sidx];
+    const int r = row - o;
+    float v = GS_INF;
+    if (row <= E && r >= lowq && r >= 0)
+      v = __hip_atomic_load(&qs[(size_t)c * src_pitch + r], __ATOMIC_RELAXED,
+                            __HIP_MEMORY_SCOPE_AGENT) + tprev[sidx];
+    if (WITH_BP) tile[sidx * kWave + lane] = v;
+    __hip_atomic_fetch_min(&cmin[c * kWave + lane], v, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_WORKGROUP);
+  }
+  __syncthreads();
+  const float *__restrict__ rck = Rc + (size_t)kr * NC * NC;
+#pragma unroll 1
+  for (int cj = wave; cj < nc; cj += NW) {
+    const float *__restrict__ rc = rck + (size_t)cj * NC;
+    float m = GS_INF;
+    int g = 0;
+#pragma unroll 1
+    for (int q = 0; 8 * q < nc; ++q) {
+      float cm = GS_INF;
+#pragma unroll 1
+      for (int ci = 8 * q; ci < 8 * q + 8 && ci < nc; ++ci)
+        cm = __builtin_fminf(cm, cmin[ci * kWave + lane] + rc[ci]);
+      chunk_update<true>(m, g, cm, q);
+    }
+    const uint32_t at = (uint32_t)cj * (uint32_t)pitch + (uint32_t)row;
+    qd[at] = m;
+    if (WITH_BP) {
+      int ca = 8 * g; // first class of chunk g that attains m (the padding classes hold +inf)
+#pragma unroll 1
+      for (int k2 = 7; k2 >= 0; --k2)
+        if (cmin[(8 * g + k2) * kWave + lane] + rc_lds[cj * NC + 8 * g + k2] == m) ca = 8 * g + k2;
+      const int lo = cs_lds[ca], len = cs_lds[ca + 1] - lo;
+      const float rr = rc_lds[cj * NC + ca];
+      int rel = 0; // lowest member of class ca whose sum equals m
+#pragma unroll 1
+      for (int d = len - 1; d >= 0; --d)
+        if (tile[(lo + d) * kWave + lane] + rr == m) rel = d;
+      bpb[at] = (uint8_t)(lo + rel);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Several layer fronts of the class kernel per launch.
 //
@@ -1114,11 +1185,18 @@ constexpr int kFrontSpinMax = 1 << 18; // polls before a wait gives up
 // A flag word: the number of the solve in the low 29 bits, the XCD that wrote the rows above.
 constexpr int kFlagXcdShift = 29;
 constexpr unsigned kFlagEpochMask = (1u << kFlagXcdShift) - 1u;
+// Words of the solve counter's 256 bytes that the several-fronts form uses beside the counter
+// (see Workspace::epoch): [kOverflowWord] holds the number of a solve in which some front has
+// more tiles with work than the launch has workgroups for (y0 per instance and front),
+// [kNeedWord] the most tiles with work of any instance and front since it was last fetched,
+// [kNeedWord + 1] the count that was last handed to the host.
+constexpr int kOverflowWord = 4, kNeedWord = 6;
 __global__ __launch_bounds__(256) void k_class_maxfit(
     const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
+    const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum,
     int32_t *__restrict__ maxfit, unsigned *__restrict__ stop,
     unsigned *__restrict__ epoch, unsigned *__restrict__ flags, size_t flag_words, int B, int L,
-    int SP) {
+    int SP, int y0) {
   const int wave = wave_uniform(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (blockIdx.x == 0 && threadIdx.x == 0) *stop = 0;
@@ -1141,7 +1219,20 @@ __global__ __launch_bounds__(256) void k_class_maxfit(
       const int other = __shfl_xor(m, d, kWave);
       m = other > m ? other : m;
     }
-    if (lane == 0) maxfit[row] = m;
+    if (lane == 0) {
+      maxfit[row] = m;
+      const int l = row % L;
+      if (l >= 1) { // tiles with work of front l: see k_dp_class_fronts
+        const int top = E - topsum[row];
+        const int active = top >= 0 ? (top >> 6) - (lowsum[row - 1] >> 6) + 1 : 0;
+        // (a thousand atomics on one word take tens of microseconds: only counts above the
+        // one the host already has are collected, and every 64th solve all of them, so that
+        // the host's count can come down again)
+        const unsigned known = (epoch[0] & 63u) == 0u ? 0u : epoch[kNeedWord + 1];
+        if (active > 0 && (unsigned)active > known) atomicMax(&epoch[kNeedWord], (unsigned)active);
+        if (active > y0) epoch[kOverflowWord] = epoch[0];
+      }
+    }
   }
 }
 
@@ -1167,6 +1258,8 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   const int l = l0 + f;
   const int bl = b * L + l;
   const unsigned epoch = epoch_word[0]; // number of this solve (the prepare step advanced it)
+  // (some front has more tiles with work than gridDim.y: k_dp_class_fronts_plain takes the solve)
+  if (epoch_word[kOverflowWord] == epoch) return;
   // the tile's table entries travel while wave 0 waits for the tiles below
   const ClassScalars<SP / NW> k =
       class_scalars<SP, NW, ((WITH_BP || SP / NW > 12) && SP / NW <= 16)>(Tq, Oq, cmeta, cls, ridx,
@@ -1276,6 +1369,126 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts(
   class_tile<SP, NW, WITH_BP, NC, true, NoHook, true>(k, qsrc, qdst, bp_l, Rc, cstart, Sc, pitch,
                                                       from_zero ? 0 : pitch, b, t * kWave, lds,
                                                       NoHook(), publish_flag);
+}
+
+// The same forward pass the plain way, for the rare solve in which a front has more tiles with
+// work than k_dp_class_fronts was given workgroups for (that kernel's workgroups then leave at
+// once; the host sizes its grid by what earlier solves needed, and must not wait to learn what
+// this one needs).  One launch for all fronts: gridDim.y workgroups per instance, all of them
+// resident at once (the launcher sees to that), each taking every gridDim.y-th tile of front
+// 1, then of front 2, and so on, with the same flags between dependent tiles.  Many times
+// slower; the next solve of the context has a grid that fits.  Always launched: its first
+// thread hands the host the most tiles any front of this solve needed (`hint`, in host memory
+// that the device can write) and clears the count.
+template <int SP, int NW, bool WITH_BP, int NC>
+__global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts_plain(
+    float *__restrict__ planes, size_t plane_elems, int keep, const float *__restrict__ zero_row,
+    uint8_t *__restrict__ bp, size_t bp_layer_bytes, const float *__restrict__ Tq,
+    const int32_t *__restrict__ Oq, const float *__restrict__ Rc,
+    const int32_t *__restrict__ cmeta, const int32_t *__restrict__ cstart,
+    const int32_t *__restrict__ cls, const int32_t *__restrict__ ridx,
+    const int32_t *__restrict__ budget, const int32_t *__restrict__ topsum,
+    const int32_t *__restrict__ lowsum, const int32_t *__restrict__ maxfit,
+    unsigned *__restrict__ flags, unsigned *__restrict__ stop, unsigned *__restrict__ epoch_word,
+    int32_t *__restrict__ status, unsigned *__restrict__ hint, int B, int L, int Sc, int pitch,
+    int tiles, int spin_max, int ring) {
+  extern __shared__ __align__(16) float lds[];
+  __shared__ __align__(16) int s_go4[4];
+  int &s_go = s_go4[0];
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+    // (k_class_maxfit collects the counts above the one handed over last, and all of them
+    // every 64th solve: see there)
+    const unsigned need = epoch_word[kNeedWord], known = epoch_word[kNeedWord + 1];
+    const bool all = (epoch_word[0] & 63u) == 0u;
+    if (hint && need != 0u && (all ? need != known : need > known)) {
+      *hint = need;
+      epoch_word[kNeedWord + 1] = need;
+    }
+    epoch_word[kNeedWord] = 0u;
+  }
+  const int b = (int)blockIdx.x;
+  if (b >= B) return;
+  const unsigned epoch = epoch_word[0];
+  if (epoch_word[kOverflowWord] != epoch) return;
+  const int wave = wave_uniform(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  unsigned xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  xcc &= 7u;
+  const unsigned want = epoch | (xcc << kFlagXcdShift);
+  const int E = budget[b];
+  const int nc = cmeta[0];
+#pragma unroll 1
+  for (int l = 1; l < L; ++l) {
+    const int bl = b * L + l;
+    const int low = lowsum[bl - 1], lowq = l >= 2 ? lowsum[bl - 2] : 0;
+    const int top = E - topsum[bl];
+    const int kr = ridx[bl];
+    const int srci = keep ? l - 1 : ((l - 1) & (ring - 1)), dsti = keep ? l : (l & (ring - 1));
+    const bool from_zero = !keep && l == 1;
+    const float *__restrict__ qsrc = from_zero ? zero_row : planes + (size_t)srci * plane_elems;
+    float *__restrict__ qdst = planes + (size_t)dsti * plane_elems;
+    uint8_t *__restrict__ bp_l = WITH_BP ? bp + (size_t)(l - 1) * bp_layer_bytes : nullptr;
+#pragma unroll 1
+    for (int t = (low >> 6) + (int)blockIdx.y; t * kWave <= top; t += (int)gridDim.y) {
+      class_tile_prepare<SP, NW, WITH_BP, NC>(Rc, cstart, kr, lds, (int)threadIdx.x, NW * kWave);
+      if (wave == 0) {
+        int go = 1;
+        if (l >= 2) { // (the same two ranges of tiles as in k_dp_class_fronts)
+          const int top1 = E - topsum[bl - 1];
+          const int a1 = lowsum[bl - 2] >> 6;
+          const int z1 = top1 >= 0 ? top1 >> 6 : -1;
+          int lo = kWave * t - maxfit[bl - 1];
+          lo = lo > 0 ? lo >> 6 : 0;
+          lo = lo > a1 ? lo : a1;
+          const int hi1 = t < z1 ? t : z1;
+          int hiw = -1;
+          const int lw = l - ring + 1;
+          if (!keep && lw >= 2) {
+            const int war = (kWave * t + 63 + maxfit[bl - ring]) >> 6;
+            const int topw = E - topsum[bl - ring + 1];
+            const int zw = topw >= 0 ? topw >> 6 : -1;
+            hiw = war < zw ? war : zw;
+          }
+          const int hi = hi1 > hiw ? hi1 : hiw;
+          const int row1 = ((l - 1) * B + b) * tiles, roww = (lw * B + b) * tiles;
+          int spins = 0;
+          for (int base = lo; base <= hi && go; base += kWave) {
+            for (;;) {
+              const int at = base + lane;
+              unsigned fv = want;
+              const int word = at <= hi1 ? row1 + at : (at > t && at <= hiw ? roww + at : -1);
+              if (word >= 0)
+                fv = __hip_atomic_load(&flags[word], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              if (__builtin_amdgcn_ballot_w64(fv != want) == 0) break;
+              ++spins;
+              if ((spins & 255) == 0) {
+                const unsigned st = __hip_atomic_load(stop, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (wave_uniform((int)st) != 0) { go = 0; break; }
+              }
+              if (spins > spin_max) { // gave up (also: a flag from another XCD never matches)
+                __hip_atomic_store(stop, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_fetch_or(status, 0x40, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                go = 0;
+                break;
+              }
+              __builtin_amdgcn_s_sleep(2);
+            }
+          }
+        }
+        s_go = go;
+      }
+      __syncthreads();
+      if (wave_uniform(s_go) == 0) return;
+      class_tile_plain<SP, NW, WITH_BP, NC>(qsrc, qdst, bp_l, Tq, Oq, cls, Rc, bl, kr, nc, E, lowq,
+                                            Sc, pitch, from_zero ? 0 : pitch, b, t * kWave, lds);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads(); // (also: the next tile reuses the LDS)
+      if (threadIdx.x == 0)
+        __hip_atomic_store(&flags[((size_t)l * B + b) * tiles + t], want, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 }
 
 __global__ __launch_bounds__(256) void k_zero_plane(float *__restrict__ q, size_t n) {
@@ -1720,7 +1933,7 @@ bool fronts_shape_ok(const Shape &s) {
 template <int SP, int NW, int NC>
 static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool with_bp,
                              size_t plane_elems_all, size_t bp_layer_bytes, int fronts, int ring,
-                             hipStream_t st) {
+                             int front_y0, unsigned *hint, int resident_wgs, hipStream_t st) {
   const int tiles = (s.M + kWave) / kWave;
   const size_t lds =
       sizeof(float) * ((with_bp ? (SP + 3) * kWave : 0) + NC * kWave + NC * NC + NC + 32);
@@ -1728,20 +1941,27 @@ static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool
                            : (const void *)k_dp_class_fronts<SP, NW, false, NC>;
   if (lds > 64 * 1024) lds_opt_in(fn, lds, s.grants);
   const long long rows = (long long)s.B * s.L;
+  // Workgroups per instance and front: one per tile that earlier solves of the context found
+  // with work (front_y0, 0 when nothing is known), all tiles at most.  Most tiles of a front
+  // can be without work (rows that lead nowhere), and a workgroup that finds none still has
+  // to be started, in order, before the next front's can be: with one workgroup per tile of
+  // configs[3]'s shape (257 tiles, 113 with work) that took 2.4 of a front's 7.7 us.
+  int y0 = s.tune.front_tiles >= 1 ? s.tune.front_tiles * 8 : front_y0;
+  if (y0 > tiles || y0 < 1) y0 = tiles;
   hipLaunchKernelGGL(k_class_maxfit,
                      dim3((unsigned)(rows / 4 < 1 ? 1 : (rows / 4 > 1024 ? 1024 : rows / 4))),
-                     dim3(256), 0, st, w.Oq, w.budget, w.maxfit, w.stop, w.epoch, w.front_flags,
-                     w.front_flag_words, s.B, s.L, s.SP);
+                     dim3(256), 0, st, w.Oq, w.budget, w.topsum, w.lowsum, w.maxfit, w.stop,
+                     w.epoch, w.front_flags, w.front_flag_words, s.B, s.L, s.SP, y0);
   // (the grid's thread count stays below 2^31)
   const unsigned bx = (unsigned)((s.B + 7) / 8 * 8); // workgroups b >= B leave at once
   const int spin_max = s.tune.spin_limit >= 1 ? s.tune.spin_limit : kFrontSpinMax;
-  long long cap = ((1ll << 31) / (NW * kWave)) / ((long long)bx * tiles);
+  long long cap = ((1ll << 31) / (NW * kWave)) / ((long long)bx * y0);
   if (cap > 65535) cap = 65535;
   if (cap < 1) cap = 1;
   const int per = fronts < cap ? fronts : (int)cap;
   for (int l0 = 1; l0 < s.L; l0 += per) {
     const int nf = s.L - l0 < per ? s.L - l0 : per;
-    const dim3 grid(bx, (unsigned)tiles, (unsigned)nf), block(NW * kWave);
+    const dim3 grid(bx, (unsigned)y0, (unsigned)nf), block(NW * kWave);
     if (with_bp)
       hipLaunchKernelGGL((k_dp_class_fronts<SP, NW, true, NC>), grid, block, lds, st, w.planes,
                          plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp,
@@ -1757,21 +1977,47 @@ static void launch_fronts_nc(const Shape &s, const Workspace &w, bool keep, bool
                          w.status, s.B, s.L, class_rows(s), s.pitch, tiles, l0, spin_max,
                          s.tune.hold_flags == 1 ? 0 : 1, ring);
   }
+  // The plain form behind it: leaves at once unless a front needed more than y0 workgroups.
+  // All its workgroups have to be resident together when an instance has several of them:
+  // one per compute unit is taken for granted, and an instance gets what that allows.
+  {
+    const void *fp = with_bp ? (const void *)k_dp_class_fronts_plain<SP, NW, true, NC>
+                             : (const void *)k_dp_class_fronts_plain<SP, NW, false, NC>;
+    if (lds > 64 * 1024) lds_opt_in(fp, lds, s.grants);
+    int gy = resident_wgs / (int)bx;
+    gy = gy > 32 ? 32 : gy;
+    if (gy < 1) gy = 1; // (one workgroup per instance waits for nobody)
+    if (gy > tiles) gy = tiles;
+    const dim3 grid(bx, (unsigned)gy, 1), block(NW * kWave);
+    if (with_bp)
+      hipLaunchKernelGGL((k_dp_class_fronts_plain<SP, NW, true, NC>), grid, block, lds, st,
+                         w.planes, plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)w.bp,
+                         bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                         w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
+                         w.status, hint, s.B, s.L, class_rows(s), s.pitch, tiles, spin_max, ring);
+    else
+      hipLaunchKernelGGL((k_dp_class_fronts_plain<SP, NW, false, NC>), grid, block, lds, st,
+                         w.planes, plane_elems_all, keep ? 1 : 0, w.zero_row, (uint8_t *)nullptr,
+                         bp_layer_bytes, w.Tq, w.Oq, w.Rc, w.cmeta, w.cstart, w.cls, w.ridx,
+                         w.budget, w.topsum, w.lowsum, w.maxfit, w.front_flags, w.stop, w.epoch,
+                         w.status, hint, s.B, s.L, class_rows(s), s.pitch, tiles, spin_max, ring);
+  }
 }
-
 template <int SP, int NW>
 static void launch_fronts_nw(const Shape &s, const Workspace &w, bool keep, bool with_bp,
-                             size_t pe, size_t bpl, int fronts, int ring, hipStream_t st) {
+                             size_t pe, size_t bpl, int fronts, int ring, int y0, unsigned *hint,
+                             int res, hipStream_t st) {
   if constexpr (SP >= 48) {
-    if (s.NC > 32) return launch_fronts_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
+    if (s.NC > 32) return launch_fronts_nc<SP, NW, 64>(s, w, keep, with_bp, pe, bpl, fronts, ring, y0, hint, res, st);
   }
-  if (s.NC <= 16) return launch_fronts_nc<SP, NW, 16>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
-  launch_fronts_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
+  if (s.NC <= 16) return launch_fronts_nc<SP, NW, 16>(s, w, keep, with_bp, pe, bpl, fronts, ring, y0, hint, res, st);
+  launch_fronts_nc<SP, NW, 32>(s, w, keep, with_bp, pe, bpl, fronts, ring, y0, hint, res, st);
 }
 
 template <int SP>
 static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp, size_t pe,
-                          size_t bpl, int fronts, int ring, hipStream_t st) {
+                          size_t bpl, int fronts, int ring, int y0, unsigned *hint, int res,
+                          hipStream_t st) {
   // waves per tile as in the per-launch form, without its one- and two-wave forms
   int waves = s.tune.jsplit;
   if (waves < 1 || waves > 8) {
@@ -1779,10 +2025,10 @@ static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool wi
     else waves = SP >= 96 ? 8 : 4;
   }
   if constexpr (SP > 128) {
-    launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
+    launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, ring, y0, hint, res, st);
   } else {
-    if (waves >= 8) launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
-    else launch_fronts_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, fronts, ring, st);
+    if (waves >= 8) launch_fronts_nw<SP, 8>(s, w, keep, with_bp, pe, bpl, fronts, ring, y0, hint, res, st);
+    else launch_fronts_nw<SP, 4>(s, w, keep, with_bp, pe, bpl, fronts, ring, y0, hint, res, st);
   }
 }
 
@@ -1791,17 +2037,18 @@ static void launch_fronts(const Shape &s, const Workspace &w, bool keep, bool wi
 // backpointer bytes per layer.
 const char *launch_dp_class_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp,
                                    size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
-                                   int ring, hipStream_t st) {
+                                   int ring, int y0, unsigned *hint, int resident_wgs,
+                                   hipStream_t st) {
   switch (s.SP) {
-    case 16: launch_fronts<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 24: launch_fronts<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 32: launch_fronts<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 48: launch_fronts<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 64: launch_fronts<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 96: launch_fronts<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 128: launch_fronts<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 192: launch_fronts<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
-    case 256: launch_fronts<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, st); break;
+    case 16: launch_fronts<16>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 24: launch_fronts<24>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 32: launch_fronts<32>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 48: launch_fronts<48>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 64: launch_fronts<64>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 96: launch_fronts<96>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 128: launch_fronts<128>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 192: launch_fronts<192>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
+    case 256: launch_fronts<256>(s, w, keep, with_bp, plane_elems_all, bp_layer_bytes, fronts, ring, y0, hint, resident_wgs, st); break;
     default: break; // class_path_applies() admits no other pitch
   }
   return "k_dp_class_fronts";

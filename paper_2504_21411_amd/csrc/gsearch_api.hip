@@ -25,7 +25,7 @@ const KnobDesc kKnobs[] = {
     {"jsplit", &gs::Tuning::jsplit},   {"waves_per_block", &gs::Tuning::waves_per_block},
     {"row_groups", &gs::Tuning::row_groups}, {"streams", &gs::Tuning::streams},
     {"fronts", &gs::Tuning::fronts},   {"spin_limit", &gs::Tuning::spin_limit},
-    {"hold_flags", &gs::Tuning::hold_flags},
+    {"hold_flags", &gs::Tuning::hold_flags}, {"front_tiles", &gs::Tuning::front_tiles},
 };
 constexpr int kKnobCount = (int)(sizeof(kKnobs) / sizeof(kKnobs[0]));
 
@@ -194,6 +194,12 @@ struct gsearch_ctx {
   // One-launch form of the class kernel: needs the chip's XCDs to be numbered 0..7 (looked at
   // once, when the context is created) and the flag words at the end of the workspace.
   bool fronts_ok = false; // the XCDs take workgroups in turn and the flags have room
+  // That form sizes its grid by the most tiles with work that a front of an earlier solve of
+  // this context had: the device writes that count here when a solve ends (host memory that
+  // it can reach), and the next call reads whatever has arrived, without waiting.  A count
+  // that is out of date costs time, never results (see k_dp_class_fronts_plain).
+  unsigned *front_hint = nullptr;
+  int resident_wgs = 0; // workgroups of 512 threads the GPU surely holds at once
   gs::Tuning tune;      // launch overrides (from the environment at create, gsearch_set_knob)
   gs::LdsGrants grants; // LDS sizes already asked for, per kernel
 };
@@ -374,8 +380,16 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
     // (a power of two; not used when the planes are kept)
     const int ring = y.nplanes < kFrontRing ? 2 : kFrontRing;
+    // workgroups per instance and front: what the fronts of an earlier solve needed and a few
+    // more, in eights; all tiles while nothing is known, and where no row is left out
+    int y0 = 0;
+    if (ctx->front_hint && !(c.flags & GSEARCH_FLAG_KEEP_PLANES)) {
+      const unsigned seen = *static_cast<volatile unsigned *>(ctx->front_hint);
+      if (seen >= 1u && seen < (1u << 24)) y0 = ((int)seen + 4 + 7) / 8 * 8;
+    }
     ctx->forward_kernel = gs::launch_dp_class_fronts(s, w, keep, with_bp, pe, bp_layer_bytes,
-                                                     fronts_per_launch(ctx, s), ring, st);
+                                                     fronts_per_launch(ctx, s), ring, y0,
+                                                     ctx->front_hint, ctx->resident_wgs, st);
     ctx->groups_used = 1;
     cur = keep ? s.L - 1 : ((s.L - 1) & (ring - 1));
   } else {
@@ -559,6 +573,18 @@ int gsearch_create(const gsearch_config *cfg, gsearch_ctx **out) {
     return GSEARCH_ERR_HIP;
   }
   ctx->fronts_ok = turns && front_flag_bytes(cfg) > 0;
+  if (ctx->fronts_ok) {
+    hipDeviceProp_t prop;
+    void *hp = nullptr;
+    if (hipGetDeviceProperties(&prop, cfg->device) == hipSuccess)
+      ctx->resident_wgs = prop.multiProcessorCount; // (one per compute unit, whatever else runs)
+    if (hipHostMalloc(&hp, 64, hipHostMallocMapped) == hipSuccess && hp) {
+      ctx->front_hint = static_cast<unsigned *>(hp);
+      *ctx->front_hint = 0u;
+    } else {
+      (void)hipGetLastError(); // (without it the grid keeps one workgroup per tile)
+    }
+  }
   *out = ctx;
   return GSEARCH_OK;
 }
@@ -577,6 +603,8 @@ int gsearch_destroy(gsearch_ctx *ctx) {
       (void)hipStreamDestroy(ctx->side[i]);
     }
     if (ctx->base && hipFree(ctx->base) != hipSuccess) rc = GSEARCH_ERR_HIP;
+    // (after the free above, which waits for whatever may still write the word)
+    if (ctx->front_hint && hipHostFree(ctx->front_hint) != hipSuccess) rc = GSEARCH_ERR_HIP;
   }
   delete ctx;
   return rc;

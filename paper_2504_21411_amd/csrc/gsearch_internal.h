@@ -25,6 +25,8 @@ struct Tuning {
   int streams = 0;         // instance groups on parallel streams
   int fronts = -1;         // class kernel: layer fronts per launch, 2..64 (0, 1: one launch per
                            // front; -1: 64 wherever that form can run)
+  int front_tiles = 0;     // that form: workgroups per instance and front, in eights (0: what
+                           // earlier solves of the context needed, all tiles at first)
   int spin_limit = 0;      // that form: polls before a wait gives up (0: the default, 2^18)
   int hold_flags = 0;      // that form, tests only: 1 = finished tiles publish no flags, so that
                            // every wait runs into its limit (the error path, with no fault)
@@ -128,9 +130,14 @@ void launch_class_zero(const Shape &s, float *q0, hipStream_t st);
 // The forward pass of the class kernel with `fronts` layer fronts per launch, the tiles of a
 // launch waiting for each other through flags (batch a multiple of 8, 3 layers or more).
 // Unless the planes are kept, Q[l] goes to plane slot l % ring (ring = 2 or 4 slots are there).
+// y0: workgroups per instance and front (0: one per tile of the budget); a solve in which a
+// front has more tiles with work than that is redone by a slow launch behind the fast ones.
+// hint (host memory that the device can write, or null): receives the most tiles with work of
+// any front.  resident_wgs: workgroups of 512 threads the GPU surely holds at once.
 const char *launch_dp_class_fronts(const Shape &s, const Workspace &w, bool keep, bool with_bp,
                                    size_t plane_elems_all, size_t bp_layer_bytes, int fronts,
-                                   int ring, hipStream_t st);
+                                   int ring, int y0, unsigned *hint, int resident_wgs,
+                                   hipStream_t st);
 bool fronts_shape_ok(const Shape &s);              // that form can take this shape
 // out[i] = id of the XCD that workgroup i of a grid of kXccProbeGrid workgroups ran on
 constexpr int kXccProbeGrid = 512;

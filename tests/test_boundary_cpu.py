@@ -108,7 +108,7 @@ def test_new_entry_points_reject_bad_arguments_without_a_gpu(lib):
     assert lib.gsearch_forward_kernel(None) == b""
     # tuning knobs: the names are host data; setting needs a context
     names = b.gsearch_knob_names()
-    assert names == ["kernel", "small", "jsplit", "waves_per_block", "row_groups", "streams", "fronts", "spin_limit", "hold_flags"]
+    assert names == ["kernel", "small", "jsplit", "waves_per_block", "row_groups", "streams", "fronts", "spin_limit", "hold_flags", "front_tiles"]
     assert lib.gsearch_knob_name(-1) is None and lib.gsearch_knob_name(len(names)) is None
     assert lib.gsearch_set_knob(None, b"fronts", 1) == b.GSEARCH_ERR_INVALID_ARG
     v = ctypes.c_int(0)

@@ -738,6 +738,67 @@ def test_several_fronts_per_launch_on_other_streams_and_in_a_graph(gs, oracle_mo
                 assert_same(got, ref, w, "replay")
 
 
+@pytest.mark.parametrize("mode", ["bp", "nobp"])
+@pytest.mark.parametrize("shape", [(8, 11, 44, 3000), (16, 7, 96, 1500), (67, 5, 24, 600),
+                                   (264, 4, 16, 2000)],
+                         ids=lambda t: "B%dL%dS%dM%d" % t)
+def test_a_front_with_more_tiles_than_workgroups_is_redone_the_plain_way(gs, oracle_mod, shape,
+                                                                        mode):
+    """The several-fronts form sizes its grid by the tiles with work that the fronts of earlier
+    solves of the context had.  When a solve needs more (here: the knob asks for eight
+    workgroups per front, and then a context that has only seen tight budgets is given loose
+    ones), the fast launches leave at once and one slow launch does the forward pass with the
+    same results; the solve after it has a grid that fits.  264 instances: more workgroups
+    than are surely resident together, so an instance gets one."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = shape
+    sizes = [4] * (S // 4)
+    rng = workloads.SplitMix64(B * 77 + L)
+    loose = rng.randint(3 * M // 4, M, B).astype(np.int32)
+    loose[0] = M
+    tight = np.maximum(loose // 6, 70).astype(np.int32)
+    flags = {"bp": 0, "nobp": binding.GSEARCH_FLAG_NO_BACKPOINTERS}[mode]
+    cases = {}
+    for name, budget in (("loose", loose), ("tight", tight)):
+        w, r_class = workloads.class_tables("plain", B, L, S, M, sizes, K=2, seed=B + L + S,
+                                            budget=budget, coarse=(L % 2 == 0))
+        w.O[:, 1::2, :] = np.maximum(w.O[:, 1::2, :] // 6, 1)     # leaves slack: many tiles with work
+        cases[name] = (w, r_class, oracle_batch(oracle_mod, w))
+    def most_tiles_with_work(w):
+        # tiles of 64 rows between the least memory of the layers before a front and the budget
+        # less the least memory of the layers from it on (memories as given: no common divisor)
+        mo = np.minimum(w.O.min(axis=2).astype(np.int64), w.M + 1)
+        low = np.cumsum(mo, axis=1)
+        top = w.budget.astype(np.int64)[:, None] - np.cumsum(mo[:, ::-1], axis=1)[:, ::-1]
+        active = np.where(top[:, 1:] >= 0, (top[:, 1:] >> 6) - (low[:, :-1] >> 6) + 1, 0)
+        return int(active.max())
+    assert np.gcd.reduce(cases["loose"][0].O.ravel()) == 1
+    need_loose, need_tight = (most_tiles_with_work(cases[n][0]) for n in ("loose", "tight"))
+    # (what the test is about: eight workgroups are too few for the loose budgets, and so is
+    # the grid that the tight budgets leave behind)
+    assert need_loose > 8 and need_loose > (need_tight + 4 + 7) // 8 * 8, (need_loose, need_tight)
+    w0 = cases["loose"][0]
+    with runner.make_context(w0, flags=flags) as ctx:
+        def solve(name, what):
+            w, r_class, ref = cases[name]
+            dw = runner.DeviceWorkload(w)
+            rc = torch.from_numpy(r_class).to(dw.device)
+            got = runner.to_numpy(runner.run_step(ctx, dw, backtrace="all", r_class=rc))
+            got["data_status"] = ctx.gsearch_data_status()
+            assert ctx.gsearch_forward_kernel() == "k_dp_class_fronts"
+            assert_same(got, ref, w, f"{what} {mode}")
+        ctx.gsearch_set_knob("front_tiles", 1)          # eight workgroups per instance and front
+        solve("loose", "eight workgroups per front")
+        solve("loose", "eight workgroups per front, again")
+        ctx.gsearch_set_knob("front_tiles", 0)
+        for rep in range(3):                              # the context learns the tight need
+            solve("tight", f"tight budgets {rep}")
+        solve("loose", "loose budgets after tight ones")  # more tiles than the grid has
+        solve("loose", "loose budgets, second solve")
+        solve("tight", "tight again")
+
+
 def test_a_wait_that_gives_up_ends_the_solve_with_the_internal_status(gs, oracle_mod):
     """The error path of the several-fronts form, forced from the host: with the completion
     flags held back and a spin limit of a few polls every wait gives up, every kernel still
