@@ -237,7 +237,14 @@ int gsearch_instance_groups(gsearch_ctx *ctx);
  * "jsplit" (waves per tile), "waves_per_block", "row_groups", "streams" (instance groups),
  * "fronts" (class kernel: layer fronts per launch, 2..64; 0 or 1: one launch per front; -1, the
  * default: 64 wherever that form can run, i.e. a batch that is a multiple of 8 or has 64 instances
- * or more, three layers or more, no forced instance groups, a GPU whose eight XCDs take workgroups in turn).  0 (or -1
+ * or more, three layers or more, no forced instance groups, a GPU whose eight XCDs take workgroups in turn),
+ * "front_tiles" (that form: workgroups per instance and layer front, in eights; 0, the default: as
+ * many as the fronts of earlier solves of the context had 64-row tiles with work, one per tile of
+ * the budget at first.  Whatever the number, the results are the same: a solve whose fronts need
+ * more is redone by a slow launch of k_dp_class_fronts_plain behind the fast ones),
+ * "spin_limit" and "hold_flags" (that form, tests of its error path: polls before a wait between
+ * dependent tiles gives up, default 2^18; 1 = finished tiles publish no flags, so that every wait
+ * gives up, every kernel still ends normally and the solve reports GSEARCH_DATA_INTERNAL).  0 (or -1
  * for "small" and "fronts") restores the heuristic.  gsearch_knob_name lists the names (NULL beyond the last;
  * host only, needs no GPU).  Errors: INVALID_ARG (null context, unknown name, value outside
  * [-1, 64], null output). */
@@ -261,7 +268,8 @@ int gsearch_forward_ms(gsearch_ctx *ctx, float *host_ms);
 /* Name of the forward kernel the most recent solve launched for its layer fronts
  * ("k_dp_class_fronts", "k_dp_class", "k_dp_tile", "k_dp_wide", "k_dp_push", "k_dp_generic" or
  * "k_dp_small"; "" before any
- * solve).  Static string. */
+ * solve; "k_dp_class_fronts" also when its slow stand-in did the work, which only the device
+ * knows).  Static string. */
 const char *gsearch_forward_kernel(gsearch_ctx *ctx);
 
 /* Test aid for the class kernel's several-fronts form, whose completion flags are stamped

@@ -1139,10 +1139,10 @@ static __device__ __forceinline__ void class_tile_plain(
 // for the tiles of the previous front that it depends on, so consecutive fronts overlap.
 //
 // Dependencies.  Tile t of front l reads the rows r - O[l-1][s] of Q[l-1], i.e. the tiles
-// from (64 t - largest fitting O[l-1]) / 64 up to t of front l-1; and with two planes taking
-// turns it overwrites rows of Q[l-2] that the tiles of front l-1 up to
-// (64 t + 63 + largest fitting O[l-2]) / 64 still read.  Both ranges are cut to the tiles of
-// front l-1 that have work.  A finished tile publishes a flag word holding the number of the
+// from (64 t - largest fitting O[l-1]) / 64 up to t of front l-1; and with `ring` plane slots
+// taking turns (four; two when the problem has fewer than four planes) it overwrites rows of
+// Q[l-ring] that the tiles of front l-ring+1 up to (64 t + 63 + largest fitting O[l-ring]) / 64
+// still read.  Both ranges are cut to the tiles of their front that have work.  A finished tile publishes a flag word holding the number of the
 // solve (a counter the context advances, so flags need no clearing between solves).
 //
 // Coherence.  The eight XCDs have one L2 each, and those are made coherent with each other
@@ -1170,10 +1170,15 @@ static __device__ __forceinline__ void class_tile_plain(
 //
 // A workgroup's tile index counts from the first tile that has work (below it everything is
 // +inf), so the workgroups with work come first in every front and the empty ones behind
-// them leave at once.
+// them leave at once.  Empty ones still cost: each has to be started, in order, before the
+// next front's workgroups can be (16 ns apiece, 2.4 of a front's 7.7 us on configs[3], where
+// 113 of the 257 tiles of the budget have work).  So the grid's second dimension is not the
+// number of tiles but what the fronts of earlier solves of the context needed (the host
+// cannot look at this solve's tables); when that is too few for some front of this solve, all
+// workgroups leave at once and k_dp_class_fronts_plain does the solve (see there).
 //
-// Measured on MI355X, 64 fronts per launch: configs[1] 0.20 against 0.32 ms forward,
-// configs[3] 1.04 against 1.22 ms.  What a flag costs (store acknowledgement, barrier, flag
+// Measured on MI355X, 64 fronts per launch: configs[1] 0.18 against 0.29 ms forward,
+// configs[3] 0.90 against 1.22 ms.  What a flag costs (store acknowledgement, barrier, flag
 // store, the poll's round trip: four to five microseconds from a tile's last store to its
 // dependant's first load) is about what a launch boundary costs, so the gain comes from the
 // fronts overlapping, not from a shorter hand-over.  Forms that keep workgroups resident and
