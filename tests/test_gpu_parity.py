@@ -658,8 +658,9 @@ def test_class_kernel_random_sweep(gs, oracle_mod):
 def test_class_kernel_several_fronts_per_launch(gs, oracle_mod, shape, mode):
     """Several layer fronts per launch at shapes with many tiles per instance and many layers:
     an instance stays on one XCD, tiles wait for the tiles of the previous layer they read,
-    and with two ping-pong planes (bp, nobp keeps every plane) also for those that still
-    read the rows they overwrite.  Budgets are ragged, one instance fits nothing, memories
+    and with plane slots taking turns (bp: four, two for three layers; nobp keeps every plane)
+    also for those that still read the rows they overwrite.  From the second solve of a context
+    on the grid has as many workgroups per front as the solves before found tiles with work.  Budgets are ragged, one instance fits nothing, memories
     are small against the tile (64 rows) in some layers and several tiles wide in others."""
     binding, runner = gs
     import torch
