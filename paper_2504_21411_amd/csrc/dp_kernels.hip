@@ -1196,6 +1196,7 @@ constexpr unsigned kFlagEpochMask = (1u << kFlagXcdShift) - 1u;
 // [kNeedWord] the most tiles with work of any instance and front since it was last fetched,
 // [kNeedWord + 1] the count that was last handed to the host.
 constexpr int kOverflowWord = 4, kNeedWord = 6;
+constexpr unsigned kNeedAllTiles = 1u << 23; // stands for "one workgroup per tile"
 __global__ __launch_bounds__(256) void k_class_maxfit(
     const int32_t *__restrict__ Oq, const int32_t *__restrict__ budget,
     const int32_t *__restrict__ topsum, const int32_t *__restrict__ lowsum,
@@ -1403,8 +1404,13 @@ __global__ __launch_bounds__(NW *kWave) void k_dp_class_fronts_plain(
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
     // (k_class_maxfit collects the counts above the one handed over last, and all of them
     // every 64th solve: see there)
-    const unsigned need = epoch_word[kNeedWord], known = epoch_word[kNeedWord + 1];
+    // A solve that did not fit sends the host back to one workgroup per tile (a count beyond
+    // any number of tiles) until the next solve in which all counts are collected: at most one
+    // slow solve in 64, however the budgets move.
+    unsigned need = epoch_word[kNeedWord];
+    const unsigned known = epoch_word[kNeedWord + 1];
     const bool all = (epoch_word[0] & 63u) == 0u;
+    if (epoch_word[kOverflowWord] == epoch_word[0]) need = kNeedAllTiles;
     if (hint && need != 0u && (all ? need != known : need > known)) {
       *hint = need;
       epoch_word[kNeedWord + 1] = need;

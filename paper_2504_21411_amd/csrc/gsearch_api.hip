@@ -380,12 +380,14 @@ int solve_impl(gsearch_ctx *ctx, const gsearch_problem *p, const gsearch_result 
     if (timing && hipEventRecord(ctx->ev_begin, st) != hipSuccess) return GSEARCH_ERR_HIP;
     // (a power of two; not used when the planes are kept)
     const int ring = y.nplanes < kFrontRing ? 2 : kFrontRing;
-    // workgroups per instance and front: what the fronts of an earlier solve needed and a few
-    // more, in eights; all tiles while nothing is known, and where no row is left out
+    // workgroups per instance and front: what the fronts of earlier solves needed and a
+    // sixteenth more (four at least); all tiles while nothing is known, after a solve that
+    // did not fit, and where no row is left out
     int y0 = 0;
     if (ctx->front_hint && !(c.flags & GSEARCH_FLAG_KEEP_PLANES)) {
       const unsigned seen = *static_cast<volatile unsigned *>(ctx->front_hint);
-      if (seen >= 1u && seen < (1u << 24)) y0 = ((int)seen + 4 + 7) / 8 * 8;
+      if (seen >= 1u && seen < (1u << 22))
+        y0 = (int)seen + ((int)seen / 16 > 4 ? (int)seen / 16 : 4);
     }
     ctx->forward_kernel = gs::launch_dp_class_fronts(s, w, keep, with_bp, pe, bp_layer_bytes,
                                                      fronts_per_launch(ctx, s), ring, y0,
