@@ -739,6 +739,17 @@ def test_several_fronts_per_launch_on_other_streams_and_in_a_graph(gs, oracle_mo
                 assert_same(got, ref, w, "replay")
 
 
+def most_tiles_with_work(w):
+    """Most 64-row tiles with work of any instance and layer front: between the least memory of
+    the layers before the front and the budget less the least memory of the layers from it on
+    (memories as given: for tables without a common divisor)."""
+    mo = np.minimum(w.O.min(axis=2).astype(np.int64), w.M + 1)
+    low = np.cumsum(mo, axis=1)
+    top = w.budget.astype(np.int64)[:, None] - np.cumsum(mo[:, ::-1], axis=1)[:, ::-1]
+    active = np.where(top[:, 1:] >= 0, (top[:, 1:] >> 6) - (low[:, :-1] >> 6) + 1, 0)
+    return int(active.max())
+
+
 @pytest.mark.parametrize("mode", ["bp", "nobp"])
 @pytest.mark.parametrize("shape", [(8, 11, 44, 3000), (16, 7, 96, 1500), (67, 5, 24, 2000),
                                    (264, 4, 16, 2000)],
@@ -766,14 +777,6 @@ def test_a_front_with_more_tiles_than_workgroups_is_redone_the_plain_way(gs, ora
                                             budget=budget, coarse=(L % 2 == 0))
         w.O[:, 1::2, :] = np.maximum(w.O[:, 1::2, :] // 6, 1)     # leaves slack: many tiles with work
         cases[name] = (w, r_class, oracle_batch(oracle_mod, w))
-    def most_tiles_with_work(w):
-        # tiles of 64 rows between the least memory of the layers before a front and the budget
-        # less the least memory of the layers from it on (memories as given: no common divisor)
-        mo = np.minimum(w.O.min(axis=2).astype(np.int64), w.M + 1)
-        low = np.cumsum(mo, axis=1)
-        top = w.budget.astype(np.int64)[:, None] - np.cumsum(mo[:, ::-1], axis=1)[:, ::-1]
-        active = np.where(top[:, 1:] >= 0, (top[:, 1:] >> 6) - (low[:, :-1] >> 6) + 1, 0)
-        return int(active.max())
     assert np.gcd.reduce(cases["loose"][0].O.ravel()) == 1
     need_loose, need_tight = (most_tiles_with_work(cases[n][0]) for n in ("loose", "tight"))
     # (what the test is about: eight workgroups are too few for the loose budgets, and so is
@@ -799,6 +802,53 @@ def test_a_front_with_more_tiles_than_workgroups_is_redone_the_plain_way(gs, ora
         solve("loose", "loose budgets after tight ones")  # more tiles than the grid has
         solve("loose", "loose budgets, second solve")
         solve("tight", "tight again")
+
+
+def test_a_captured_solve_stays_right_when_its_inputs_come_to_need_a_larger_grid(gs, oracle_mod):
+    """A captured solve keeps the grid it was captured with.  Captured after solves with tight
+    budgets, then replayed on loose budgets written into the same device buffers: the fronts
+    need more workgroups than the graph's launches have, and every replay still gives the
+    loose budgets' results (the slow launch is part of the graph)."""
+    binding, runner = gs
+    import torch
+    B, L, S, M = 8, 9, 44, 3000
+    sizes = [4] * (S // 4)
+    rng = workloads.SplitMix64(4242)
+    loose = rng.randint(3 * M // 4, M, B).astype(np.int32)
+    tight = np.maximum(loose // 6, 70).astype(np.int32)
+    made = {}
+    for name, budget in (("loose", loose), ("tight", tight)):
+        w, r_class = workloads.class_tables("graph", B, L, S, M, sizes, K=2, seed=5, budget=budget)
+        w.O[:, 1::2, :] = np.maximum(w.O[:, 1::2, :] // 6, 1)
+        made[name] = (w, r_class, oracle_batch(oracle_mod, w))
+    w_t, r_class, ref_t = made["tight"]
+    w_l, _, ref_l = made["loose"]
+    assert np.array_equal(w_t.O, w_l.O) and np.array_equal(w_t.T, w_l.T)   # only the budgets differ
+    need_t, need_l = most_tiles_with_work(w_t), most_tiles_with_work(w_l)
+    assert np.gcd.reduce(w_l.O.ravel()) == 1 and need_l > need_t + max(4, need_t // 16)
+    dw = runner.DeviceWorkload(w_t)
+    rc = torch.from_numpy(r_class).to(dw.device)
+    st = torch.cuda.Stream()
+    with runner.make_context(w_t) as ctx, torch.cuda.stream(st):
+        for _ in range(3):
+            got = runner.run_step(ctx, dw, backtrace="all", r_class=rc)
+            st.synchronize()
+        got = runner.to_numpy(got)
+        got["data_status"] = ctx.gsearch_data_status()
+        assert_same(got, ref_t, w_t, "tight, eager")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            captured = runner.run_step(ctx, dw, backtrace="all", r_class=rc)
+        graph.replay()
+        got = runner.to_numpy(captured)
+        got["data_status"] = ctx.gsearch_data_status()
+        assert_same(got, ref_t, w_t, "tight, replay")
+        dw.budget.copy_(torch.from_numpy(loose).to(dw.device))
+        for rep in range(2):
+            graph.replay()
+            got = runner.to_numpy(captured)
+            got["data_status"] = ctx.gsearch_data_status()
+            assert_same(got, ref_l, w_l, f"loose, replay {rep}")
 
 
 def test_a_wait_that_gives_up_ends_the_solve_with_the_internal_status(gs, oracle_mod):
