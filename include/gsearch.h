@@ -62,7 +62,9 @@ typedef enum {
 
 /* gsearch_config.flags */
 #define GSEARCH_FLAG_KEEP_PLANES 0x1u    /* keep every C plane (needed by export / curve of
-                                            any layer); default keeps two ping-pong planes.
+                                            any layer); default keeps two plane slots that
+                                            take turns (four where the class kernel's
+                                            several-fronts form can run).
                                             (With r_class the planes are kept in a compact
                                             form, one row per class, from which C is rebuilt
                                             wherever it is read.)                          */
